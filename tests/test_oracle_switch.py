@@ -1,0 +1,217 @@
+"""Pins for oracle.switch_step / gated_lowrank_sum / switch_magnitude.
+
+Nothing numeric is printed in the paper for Sec. 3.3, so the oracle is pinned to
+  * exact rational brute force on tiny inputs (tests/exact_rational.py),
+  * hand-derived single-element rounding cases (tests/golden/rne_cases.txt),
+  * the textbook LoRA merge W + B@A as the k=1, g=1 special case (Eq. 4),
+  * the algebraic identities of Eq. 7, Eq. 8 and Eq. 10.
+A planted mistake (dropped term, wrong sign, transposed operand, wrong expert
+index) fails at least one of them; test_planted_mistakes_are_caught shows it.
+"""
+import numpy as np
+import pytest
+
+from oracle import lsw_oracle as O
+from oracle import compare as C
+from paper_2405_17741_amd import inputs as I
+from tests.exact_rational import exact_switch
+from tests.golden_cases import load_rne_cases
+
+
+def _tiny(seed, out=5, inn=7, E=4, r=2, w_std=0.02, a_std=0.3, b_std=0.05):
+    rng = np.random.default_rng(seed)
+    return I.host_linear(rng, out, inn, E, r, w_std, a_std, b_std)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_exact_rational_bruteforce(seed):
+    out, inn, E, r = [(5, 7, 4, 2), (8, 8, 4, 2), (3, 4, 3, 1), (8, 5, 4, 2), (6, 8, 2, 2), (4, 4, 4, 1)][seed]
+    W, A, B = _tiny(seed, out, inn, E, r)
+    rng = np.random.default_rng(100 + seed)
+    old_ids = rng.choice(E, size=min(2, E), replace=False)
+    new_ids = rng.choice(E, size=min(2, E), replace=False)
+    og = rng.random(len(old_ids)).astype(np.float32)
+    ng = rng.random(len(new_ids)).astype(np.float32)
+    scale = [1.0, 1.0, 0.25, 2.0, 1.0, 0.5][seed]
+    got = O.switch_step(W, A, B, old_ids, og, new_ids, ng, scale)
+    want = exact_switch(W.tolist(), A.tolist(), B.tolist(),
+                        list(zip(old_ids.tolist(), og.tolist())),
+                        list(zip(new_ids.tolist(), ng.tolist())), scale)
+    assert got.tolist() == want
+
+
+def test_exact_rational_with_heavy_cancellation():
+    # W_prev already holds the old expert; removing it cancels most of the magnitude.
+    rng = np.random.default_rng(11)
+    W0, A, B = _tiny(11, 6, 6, 3, 2, w_std=1e-4, a_std=1.0, b_std=1.0)
+    g = np.array([0.75], dtype=np.float32)
+    W1 = O.switch_step(W0, A, B, [], [], [1], g)
+    got = O.switch_step(W1, A, B, [1], g, [2], np.array([1e-3], dtype=np.float32))
+    want = exact_switch(W1.tolist(), A.tolist(), B.tolist(), [(1, float(g[0]))], [(2, float(np.float32(1e-3)))])
+    assert got.tolist() == want
+
+
+def test_golden_rounding_cases():
+    for c in load_rne_cases():
+        W = np.array([[c["w"]]], dtype=np.uint16)
+        A = np.array([[[c["a"]]]], dtype=np.float32)
+        B = np.array([[[c["b"]]]], dtype=np.float32)
+        assert float(A[0, 0, 0]) == c["a"] and float(B[0, 0, 0]) == c["b"], "fixture values must be exact fp32"
+        g = np.array([c["gate"]], dtype=np.float32)
+        if c["side"] == "new":
+            got = O.switch_step(W, A, B, [], [], [0], g)
+            ex = exact_switch([[c["w"]]], A.tolist(), B.tolist(), [], [(0, c["gate"])])
+        else:
+            got = O.switch_step(W, A, B, [0], g, [], [])
+            ex = exact_switch([[c["w"]]], A.tolist(), B.tolist(), [(0, c["gate"])], [])
+        assert int(got[0, 0]) == c["expect"], c
+        assert ex[0][0] == c["expect"], c
+
+
+def test_single_expert_unit_gate_is_plain_lora_merge():
+    # Eq. 4 with k = 1, G = softmax of one logit = 1: W + B @ A, the ordinary LoRA merge.
+    W, A, B = _tiny(3, 16, 24, 4, 4, a_std=1 / 8, b_std=0.01)
+    ids, gates = O.route(np.array([0.1, 2.0, -1.0, 0.3], dtype=np.float32), 1)
+    assert ids.tolist() == [1] and gates.tolist() == [1.0]
+    got = O.switch_step(W, A, B, [], [], ids, gates)
+    # independent evaluation: einsum over explicit index letters i (out), p (rank), j (in)
+    delta = np.einsum("ip,pj->ij", B[1].astype(np.float64), A[1].astype(np.float64))
+    wide = O.bf16_bits_to_f64(W) + delta
+    # nearest bf16 by searching the two neighbours around a truncated fp32 cast
+    lo = (wide.astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    cand = np.stack([lo - 1, lo, lo + 1]).astype(np.uint16)
+    err = np.abs(O.bf16_bits_to_f64(cand) - wide)
+    best = np.take_along_axis(cand, err.argmin(0)[None], 0)[0]
+    ties = (np.sort(err, 0)[0] == np.sort(err, 0)[1])
+    assert not ties.any()
+    assert (got == best).all()
+    # shape/transposition: a non-square case must give [out, in]
+    assert got.shape == (16, 24)
+
+
+def test_no_experts_is_identity():
+    W, A, B = _tiny(4)
+    assert (O.switch_step(W, A, B, [], [], [], []) == W).all()
+
+
+def test_same_set_is_identity():
+    W, A, B = _tiny(5, 32, 32, 4, 2)
+    g = np.array([0.6, 0.4], dtype=np.float32)
+    got = O.switch_step(W, A, B, [2, 0], g, [2, 0], g)
+    assert (got == W).all()
+    # also when the pairs are listed in a different order
+    got = O.switch_step(W, A, B, [2, 0], g, [0, 2], g[::-1])
+    assert (got == W).all()
+
+
+def test_permutation_of_pairs_changes_nothing():
+    W, A, B = _tiny(6, 16, 16, 4, 2)
+    og = np.array([0.7, 0.3], dtype=np.float32)
+    ng = np.array([0.55, 0.45], dtype=np.float32)
+    a = O.switch_step(W, A, B, [0, 1], og, [2, 3], ng)
+    b = O.switch_step(W, A, B, [1, 0], og[::-1], [3, 2], ng[::-1])
+    # float64 addition of two terms commutes exactly
+    assert (a == b).all()
+
+
+def test_merge_then_unmerge_returns_within_one_ulp_of_larger_magnitude():
+    # Eq. 7 made precise: W2 = rne(rne(W0 + d) - d) differs from W0 by at most one
+    # bf16 ulp at max(|W0|, |W1|), and is exact where ulp(W1) <= ulp(W0) barring ties.
+    W0, A, B = _tiny(7, 64, 64, 8, 8, a_std=1 / 16, b_std=0.01)
+    g = np.array([0.6, 0.4], dtype=np.float32)
+    W1 = O.switch_step(W0, A, B, [], [], [3, 5], g)
+    W2 = O.switch_step(W1, A, B, [3, 5], g, [], [])
+    w0, w1, w2 = (O.bf16_bits_to_f64(x) for x in (W0, W1, W2))
+    bound = C.bf16_ulp_at(np.maximum(np.abs(w0), np.abs(w1)))
+    assert (np.abs(w2 - w0) <= bound).all()
+    # where W1 is not coarser than W0 the rounding error of the merge is at most half an
+    # ulp of W0, so the unmerge lands back on W0 -- except on an exact tie, or when W0 is a
+    # power of two (the spacing below it is half as wide).
+    same_or_finer = C.bf16_ulp_at(np.abs(w1)) <= C.bf16_ulp_at(np.abs(w0))
+    not_pow2 = (W0 & 0x7F) != 0
+    sel = same_or_finer & not_pow2
+    assert sel.sum() > 1000
+    assert (W2 == W0)[sel].mean() > 0.9995
+    assert (W2 == W0)[same_or_finer].mean() > 0.99
+    assert (W1 != W0).mean() > 0.5     # the merge really changed most weights
+
+
+def test_fused_switch_equals_unmerge_then_merge_up_to_one_rounding():
+    # Eq. 8 (one rounding) versus Eq. 7 followed by Eq. 6 (two roundings).
+    W0, A, B = _tiny(8, 48, 40, 8, 4, a_std=1 / 8, b_std=0.01)
+    og = np.array([0.5, 0.5], dtype=np.float32)
+    ng = np.array([0.8, 0.2], dtype=np.float32)
+    Wm = O.switch_step(W0, A, B, [], [], [1, 2], og)
+    fused = O.switch_step(Wm, A, B, [1, 2], og, [4, 7], ng)
+    mid = O.switch_step(Wm, A, B, [1, 2], og, [], [])
+    two = O.switch_step(mid, A, B, [], [], [4, 7], ng)
+    # the two-step path carries the rounding error of the intermediate (at most half an ulp
+    # of it) into the second rounding; measured at the larger magnitude that is one ulp
+    f, t, m = (O.bf16_bits_to_f64(x) for x in (fused, two, mid))
+    assert (np.abs(f - t) <= C.bf16_ulp_at(np.maximum(np.abs(m), np.abs(f)))).all()
+    assert (fused == two).mean() > 0.5
+
+
+def test_switch_is_linear_in_the_gates():
+    # doubling every gate doubles delta exactly (power of two): check through magnitudes
+    W, A, B = _tiny(9, 8, 8, 4, 2)
+    g = np.array([0.25, 0.5], dtype=np.float32)
+    d1 = O.gated_lowrank_sum(A, B, [0, 3], g)
+    d2 = O.gated_lowrank_sum(A, B, [0, 3], 2 * g)
+    assert (d2 == 2 * d1).all()
+    d3 = O.gated_lowrank_sum(A, B, [0, 3], g, scale=4.0)
+    assert (d3 == 4 * d1).all()
+
+
+def test_rows_argument_selects_rows():
+    W, A, B = _tiny(10, 20, 12, 4, 2)
+    g = np.array([0.3, 0.7], dtype=np.float32)
+    full = O.switch_step(W, A, B, [0, 1], g, [2, 3], g)
+    rows = np.array([0, 3, 19])
+    part = O.switch_step(W[rows], A, B, [0, 1], g, [2, 3], g, rows=rows)
+    assert (part == full[rows]).all()
+    S = O.switch_magnitude(A, B, [0, 1], g, [2, 3], g)
+    assert (O.switch_magnitude(A, B, [0, 1], g, [2, 3], g, rows=rows) == S[rows]).all()
+
+
+def test_switch_magnitude_bruteforce():
+    W, A, B = _tiny(12, 3, 4, 3, 2)
+    og = np.array([0.5], dtype=np.float32)
+    ng = np.array([0.25, 0.75], dtype=np.float32)
+    S = O.switch_magnitude(A, B, [1], og, [0, 2], ng, scale=-2.0)
+    for i in range(3):
+        for j in range(4):
+            s = 0.0
+            for e, g in [(1, 0.5), (0, 0.25), (2, 0.75)]:
+                s += 2.0 * g * sum(abs(float(B[e, i, p])) * abs(float(A[e, p, j])) for p in range(2))
+            assert S[i, j] == pytest.approx(s, rel=1e-14)
+    d = np.abs(O.gated_lowrank_sum(A, B, [0, 2], ng, -2.0) - O.gated_lowrank_sum(A, B, [1], og, -2.0))
+    assert (d <= S * (1 + 1e-12)).all()
+
+
+def test_planted_mistakes_are_caught():
+    """Each plausible bug, planted in a copy of the definition, disagrees with the exact pin."""
+    W, A, B = _tiny(13, 5, 7, 4, 2)
+    old = [(0, 0.375)]
+    new = [(1, 0.5), (3, 0.25)]
+    want = np.array(exact_switch(W.tolist(), A.tolist(), B.tolist(), old, new), dtype=np.uint16)
+
+    def variant(sign_old=-1.0, drop_last=False, swap_expert=False, fp32_stop=False):
+        w = O.bf16_bits_to_f64(W)
+        d = np.zeros_like(w)
+        nn = new[:-1] if drop_last else new
+        for e, g in nn:
+            ee = (e + 1) % 4 if swap_expert else e
+            d += g * (B[ee].astype(np.float64) @ A[e].astype(np.float64))
+        for e, g in old:
+            d += sign_old * g * (B[e].astype(np.float64) @ A[e].astype(np.float64))
+        v = w + d
+        if fp32_stop:
+            v = v.astype(np.float32).astype(np.float64)
+        return O.f64_to_bf16_bits(v)
+
+    assert (variant() == want).all()
+    assert (variant(sign_old=+1.0) != want).any()
+    assert (variant(drop_last=True) != want).any()
+    assert (variant(swap_expert=True) != want).any()
+    assert (O.switch_step(W, A, B, [0], [0.375], [1, 3], [0.5, 0.25]) == want).all()

@@ -1,0 +1,180 @@
+/*
+ * lsw.h -- C ABI of the per-token LoRA expert switch for AMD MI355X (gfx950).
+ *
+ * The operation is the fused adapter switch of LoRA-Switch (arXiv 2405.17741,
+ * Sec. 3.3): every adapted backbone weight holds, merged in place, the top-k
+ * LoRA experts the router chose for the previous token; for the next token the
+ * previous experts are removed (Eq. 7) and the newly routed ones are added
+ * (Eq. 4) in ONE pass over the weight (Eq. 8, rewritten as Eq. 10), for every
+ * adapted linear of every layer in ONE kernel launch (Sec. 3.4, Eq. 11):
+ *
+ *     W[i,j] <- rne_bf16( W[i,j] + sum_{c in new} s*g_c * (B_{e_c} A_{e_c})[i,j]
+ *                                - sum_{c in old} s*g_c * (B_{e_c} A_{e_c})[i,j] )
+ *
+ * Conventions
+ *   - W is bf16 [out, in] row-major.  A = LoRA_DOWN is fp32 [E, r, in],
+ *     B = LoRA_UP is fp32 [E, out, r]; one expert's update is B_e @ A_e.
+ *   - One (ids, gates) pair per token drives all layers (Sec. 3.2, Eq. 2: the
+ *     single router G^1 gates every layer's adapters).
+ *   - Accumulation is at least fp32 and there is one round-to-nearest-even to
+ *     bf16 per element per switch.
+ *   - Every call returns a status and never throws or aborts.  Arguments are
+ *     validated before anything is launched: on an error no weight is touched.
+ *   - Pointers marked DEVICE must be device memory of the current HIP device;
+ *     pointers marked HOST are ordinary host memory.  Nothing here takes
+ *     ownership of caller memory.
+ *   - Calls on one context are not thread-safe; work is ordered by the stream.
+ *     Two switches in flight on different streams over the same weights race.
+ */
+#ifndef LSW_H
+#define LSW_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lsw_ctx lsw_ctx;          /* opaque, owned by the library */
+
+typedef enum lsw_status {
+  LSW_OK = 0,
+  LSW_ERR_ARG = 1,      /* null pointer, id out of range, duplicate id, k too large, non-finite gate ... */
+  LSW_ERR_SHAPE = 2,    /* unsupported shape or misaligned pointer */
+  LSW_ERR_STATE = 3,    /* `old` does not match what the context knows to be merged (strict mode only) */
+  LSW_ERR_NOMEM = 4,    /* host or device allocation failed */
+  LSW_ERR_DEVICE = 5    /* no usable HIP device, or a HIP call failed */
+} lsw_status;
+
+enum { LSW_MAX_K = 8 };  /* largest top-k per list (old or new) */
+
+/* One adapted linear.  All three tensors are BORROWED and must outlive the context. */
+typedef struct lsw_linear {
+  void*        W;      /* DEVICE bf16 [out, in] row-major, 16-byte aligned; updated in place by lsw_switch */
+  const float* A;      /* DEVICE fp32 [E, r, in]  (LoRA_DOWN), 16-byte aligned; read at create time (see below) */
+  const float* B;      /* DEVICE fp32 [E, out, r] (LoRA_UP),   16-byte aligned; read by every switch */
+  int32_t      out;    /* rows of W, >= 1 */
+  int32_t      in;     /* columns of W, a positive multiple of 8 (rows stay 16-byte aligned) */
+  int32_t      layer;  /* layer number >= 0; several linears share one layer */
+  int32_t      kind;   /* informational: 0..6 = q,k,v,o,gate,up,down */
+} lsw_linear;
+
+/*
+ * Register a stack of adapted linears (the pointer-and-shape arrays that Sec. 3.4
+ * gives the fused kernel) and build the static launch metadata: a descriptor per
+ * linear and the work decomposition over (layer, linear, tile).
+ *
+ *   lin, n_lin  HOST array of descriptors, n_lin >= 1.
+ *   E, r        experts per linear (1..4096) and LoRA rank (1..512), the same for every linear.
+ *   scale       multiplied into every gate (alpha/r of the LoRA recipe; 1.0 if gates are used as is).
+ *   out         receives the context; destroy with lsw_destroy.
+ *
+ * When r is a multiple of 8 the library also keeps its OWN re-laid-out copy of every A
+ * (k-contiguous, split into bf16 high and low parts for the matrix cores, E*r*in*4 bytes
+ * per linear): A is read once here and must be re-registered if it changes; B is read
+ * from the caller's tensor at every switch.  Nothing is merged by this call: the context
+ * starts in the state "no expert merged".
+ *
+ * Errors: LSW_ERR_ARG (null, n_lin < 1, E/r out of range, non-finite scale, layer < 0),
+ * LSW_ERR_SHAPE (out < 1, in not a positive multiple of 8, pointer not 16-byte aligned),
+ * LSW_ERR_NOMEM, LSW_ERR_DEVICE (also when no GPU is present; validation comes first).
+ */
+lsw_status lsw_create_adapters(const lsw_linear* lin, int32_t n_lin, int32_t E, int32_t r,
+                               float scale, lsw_ctx** out);
+
+/*
+ * The fused switch (Alg. 1 steps 2-4; Eq. 8 == Eq. 10; one launch as in Eq. 11).
+ *
+ *   layers, n_layers   HOST list of distinct layer numbers to switch; NULL, 0 = every layer.
+ *   old_ids/old_gates  HOST, k_old entries: the experts merged now (Eq. 7 removes them).  k_old = 0: none.
+ *   new_ids/new_gates  HOST, k_new entries: the experts to merge (Eq. 4).  k_new = 0: restore the base weights.
+ *   hip_stream         hipStream_t (NULL = default stream).  The call is asynchronous on it.
+ *
+ * An expert listed in both sets is applied once with the coefficient s*g_new - s*g_old and
+ * skipped when that is zero; if nothing remains nothing is launched and W is untouched.
+ * Errors (nothing launched): LSW_ERR_ARG for a null list with k > 0, k outside 0..LSW_MAX_K or
+ * above E, id outside [0,E), duplicate id inside one list, non-finite gate, unknown or
+ * duplicate layer; LSW_ERR_STATE in strict mode (see lsw_set_option); LSW_ERR_DEVICE.
+ */
+lsw_status lsw_switch(lsw_ctx* ctx, const int32_t* layers, int32_t n_layers,
+                      const int32_t* old_ids, const float* old_gates, int32_t k_old,
+                      const int32_t* new_ids, const float* new_gates, int32_t k_new,
+                      void* hip_stream);
+
+/*
+ * Decode through one merged linear (Eq. 3: the backbone runs as if it had no adapters):
+ * y[i] = sum_j W[i,j] * x[j], fp32 accumulation.
+ *
+ *   lin_index  index into the array given to lsw_create_adapters.
+ *   x_bf16     DEVICE bf16 [in], 16-byte aligned.      y_fp32  DEVICE fp32 [out].
+ * Asynchronous on hip_stream.  Errors: LSW_ERR_ARG, LSW_ERR_SHAPE (misaligned x), LSW_ERR_DEVICE.
+ */
+lsw_status lsw_merged_gemv(lsw_ctx* ctx, int32_t lin_index, const void* x_bf16, float* y_fp32,
+                           void* hip_stream);
+
+/*
+ * Router on given logits: G = Softmax(TopK(logits)) (definition of G under Eq. 1, used by the
+ * single token-wise router of Eq. 2).  Host helper, touches no device.
+ *
+ *   logits HOST fp32 [E];  ids HOST int32 [k] and gates HOST fp32 [k] receive the selection in
+ *   descending logit order (equal logits: lower index first; +0 equals -0); the softmax runs over
+ *   the k selected logits only, in double precision, rounded once to fp32.
+ * Errors: LSW_ERR_ARG (null, E < 1, k outside 0..E, NaN logit).
+ */
+lsw_status lsw_route(const float* logits, int32_t E, int32_t k, int32_t* ids, float* gates);
+
+/*
+ * The signed coefficient list one switch applies (Alg. 1 steps 2-3 without moving any tensor:
+ * Eq. 5 puts the gate on one factor, Eq. 9 negates the previous set): new experts with
+ * +scale*g, old experts with -scale*g, an expert in both with scale*g_new - scale*g_old,
+ * zero coefficients dropped.  Host helper; lsw_switch uses exactly this.
+ *
+ *   terms_ids / terms_coeff  HOST arrays with room for k_old + k_new entries; n_terms receives the count.
+ * Errors: as the list checks of lsw_switch (LSW_ERR_ARG).
+ */
+lsw_status lsw_build_terms(const int32_t* old_ids, const float* old_gates, int32_t k_old,
+                           const int32_t* new_ids, const float* new_gates, int32_t k_new,
+                           int32_t E, float scale,
+                           int32_t* terms_ids, float* terms_coeff, int32_t* n_terms);
+
+/*
+ * What the context believes is merged in `layer` now (the pair Eq. 7 needs for the next
+ * switch).  ids/gates HOST arrays with room for LSW_MAX_K entries; k receives the count.
+ */
+lsw_status lsw_get_state(const lsw_ctx* ctx, int32_t layer, int32_t* ids, float* gates, int32_t* k);
+
+/* Options (lsw_set_option) and queries (lsw_query). */
+enum {
+  LSW_OPT_KERNEL = 1,        /* 0 = automatic, 1 = fp32 vector-ALU kernel, 2 = matrix-core kernel (needs r % 8 == 0) */
+  LSW_OPT_STRICT_STATE = 2,  /* 1: lsw_switch rejects an `old` that differs from the tracked state of a layer */
+  LSW_OPT_GRID = 3           /* workgroups per launch; 0 = automatic (fills the device once) */
+};
+enum {
+  LSW_Q_N_LINEARS = 1, LSW_Q_N_LAYERS = 2,
+  LSW_Q_LAST_KERNEL = 3,     /* kernel the last lsw_switch launched: 0 none, 1 vector-ALU, 2 matrix-core */
+  LSW_Q_LAST_ITEMS = 4,      /* work items of the last launch */
+  LSW_Q_LAST_GRID = 5,       /* workgroups of the last launch */
+  LSW_Q_PACKED_BYTES = 6     /* bytes of device memory the context owns */
+};
+lsw_status lsw_set_option(lsw_ctx* ctx, int32_t option, int64_t value);
+int64_t    lsw_query(const lsw_ctx* ctx, int32_t what);   /* -1 on a bad argument */
+
+/*
+ * The work decomposition of one launch (the tiles Sec. 3.4 hands to thread blocks), as a pure
+ * function of the shapes: linear p is cut into ceil(out/tile_rows) x ceil(in/tile_cols) items,
+ * numbered linear by linear, rows outermost.  Host helpers, no device.  The kernels decode an
+ * item number with the same routine.
+ */
+int64_t    lsw_worklist_size(const int32_t* out, const int32_t* in, int32_t n_lin,
+                             int32_t tile_rows, int32_t tile_cols);            /* -1 on a bad argument */
+lsw_status lsw_worklist_item(const int32_t* out, const int32_t* in, int32_t n_lin,
+                             int32_t tile_rows, int32_t tile_cols, int64_t item,
+                             int32_t* lin, int32_t* row0, int32_t* n_rows, int32_t* col0, int32_t* n_cols);
+
+void        lsw_destroy(lsw_ctx* ctx);       /* frees what the library owns; NULL is allowed */
+const char* lsw_last_error(void);            /* message of the last failing call on this thread */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LSW_H */

@@ -1,0 +1,196 @@
+"""ctypes binding of liblsw.so: same names as include/lsw.h, argument marshalling only.
+
+Every step of the switch runs inside the library's kernels; nothing here computes.
+The library must have been built (python -m paper_2405_17741_amd.build); loading fails
+loudly otherwise -- there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+LSW_OK, LSW_ERR_ARG, LSW_ERR_SHAPE, LSW_ERR_STATE, LSW_ERR_NOMEM, LSW_ERR_DEVICE = range(6)
+LSW_MAX_K = 8
+LSW_OPT_KERNEL, LSW_OPT_STRICT_STATE, LSW_OPT_GRID = 1, 2, 3
+LSW_Q_N_LINEARS, LSW_Q_N_LAYERS, LSW_Q_LAST_KERNEL, LSW_Q_LAST_ITEMS, LSW_Q_LAST_GRID, LSW_Q_PACKED_BYTES = range(1, 7)
+KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
+
+EXPORTS = (
+    "lsw_create_adapters", "lsw_switch", "lsw_merged_gemv", "lsw_route", "lsw_build_terms",
+    "lsw_get_state", "lsw_set_option", "lsw_query", "lsw_worklist_size", "lsw_worklist_item",
+    "lsw_destroy", "lsw_last_error",
+)
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblsw.so")
+_lib = None
+
+
+class LswError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"lsw status {status}: {message}")
+        self.status = status
+
+
+class lsw_linear(C.Structure):
+    _fields_ = [("W", C.c_void_p), ("A", C.c_void_p), ("B", C.c_void_p),
+                ("out", C.c_int32), ("in_", C.c_int32), ("layer", C.c_int32), ("kind", C.c_int32)]
+
+
+_i32p = C.POINTER(C.c_int32)
+_f32p = C.POINTER(C.c_float)
+
+
+def lib() -> C.CDLL:
+    """Load liblsw.so once; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2405_17741_amd.build`")
+        L = C.CDLL(_LIB_PATH)
+        L.lsw_create_adapters.argtypes = [C.POINTER(lsw_linear), C.c_int32, C.c_int32, C.c_int32, C.c_float,
+                                          C.POINTER(C.c_void_p)]
+        L.lsw_switch.argtypes = [C.c_void_p, _i32p, C.c_int32, _i32p, _f32p, C.c_int32, _i32p, _f32p, C.c_int32,
+                                 C.c_void_p]
+        L.lsw_merged_gemv.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.lsw_route.argtypes = [_f32p, C.c_int32, C.c_int32, _i32p, _f32p]
+        L.lsw_build_terms.argtypes = [_i32p, _f32p, C.c_int32, _i32p, _f32p, C.c_int32, C.c_int32, C.c_float,
+                                      _i32p, _f32p, _i32p]
+        L.lsw_get_state.argtypes = [C.c_void_p, C.c_int32, _i32p, _f32p, _i32p]
+        L.lsw_set_option.argtypes = [C.c_void_p, C.c_int32, C.c_int64]
+        L.lsw_query.argtypes = [C.c_void_p, C.c_int32]
+        L.lsw_query.restype = C.c_int64
+        L.lsw_worklist_size.argtypes = [_i32p, _i32p, C.c_int32, C.c_int32, C.c_int32]
+        L.lsw_worklist_size.restype = C.c_int64
+        L.lsw_worklist_item.argtypes = [_i32p, _i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int64,
+                                        _i32p, _i32p, _i32p, _i32p, _i32p]
+        L.lsw_destroy.argtypes = [C.c_void_p]
+        L.lsw_destroy.restype = None
+        L.lsw_last_error.restype = C.c_char_p
+        for name in EXPORTS:
+            if name not in ("lsw_query", "lsw_worklist_size", "lsw_destroy", "lsw_last_error"):
+                getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def lsw_last_error() -> str:
+    return lib().lsw_last_error().decode()
+
+
+def _check(status: int):
+    if status != LSW_OK:
+        raise LswError(status, lsw_last_error())
+
+
+def _i32(a):
+    if a is None:
+        return None, None, 0
+    arr = np.ascontiguousarray(a, dtype=np.int32).reshape(-1)
+    return arr, arr.ctypes.data_as(_i32p), arr.size
+
+
+def _f32(a):
+    if a is None:
+        return None, None, 0
+    arr = np.ascontiguousarray(a, dtype=np.float32).reshape(-1)
+    return arr, arr.ctypes.data_as(_f32p), arr.size
+
+
+def lsw_create_adapters(linears, E: int, r: int, scale: float = 1.0) -> int:
+    """linears: iterable of (W_ptr, A_ptr, B_ptr, out, in, layer, kind) with device addresses as ints.
+
+    Returns the opaque context handle (an int); release it with lsw_destroy.
+    """
+    linears = list(linears)
+    arr = (lsw_linear * max(len(linears), 1))()
+    for i, (w, a, b, o, n, layer, kind) in enumerate(linears):
+        arr[i] = lsw_linear(w, a, b, o, n, layer, kind)
+    ctx = C.c_void_p()
+    _check(lib().lsw_create_adapters(arr if linears else None, len(linears), E, r, scale, C.byref(ctx)))
+    return ctx.value
+
+
+def lsw_switch(ctx: int, old_ids, old_gates, new_ids, new_gates, layers=None, stream: int = 0) -> None:
+    _, lp, nl = _i32(layers)
+    ko, oi, k_old = _i32(old_ids)
+    kg, og, n_og = _f32(old_gates)
+    kn, ni, k_new = _i32(new_ids)
+    kh, ng, n_ng = _f32(new_gates)
+    if n_og != k_old or n_ng != k_new:
+        raise LswError(LSW_ERR_ARG, "ids and gates differ in length")
+    _check(lib().lsw_switch(ctx, lp, nl, oi, og, k_old, ni, ng, k_new, C.c_void_p(stream)))
+
+
+def lsw_merged_gemv(ctx: int, lin_index: int, x_ptr: int, y_ptr: int, stream: int = 0) -> None:
+    _check(lib().lsw_merged_gemv(ctx, lin_index, C.c_void_p(x_ptr), C.c_void_p(y_ptr), C.c_void_p(stream)))
+
+
+def lsw_route(logits, k: int):
+    la, lp, E = _f32(logits)
+    ids = np.zeros(max(k, 1), dtype=np.int32)
+    gates = np.zeros(max(k, 1), dtype=np.float32)
+    _check(lib().lsw_route(lp, E, k, ids.ctypes.data_as(_i32p), gates.ctypes.data_as(_f32p)))
+    return ids[:k].copy(), gates[:k].copy()
+
+
+def lsw_build_terms(old_ids, old_gates, new_ids, new_gates, E: int, scale: float = 1.0):
+    ko, oi, k_old = _i32(old_ids)
+    kg, og, _ = _f32(old_gates)
+    kn, ni, k_new = _i32(new_ids)
+    kh, ng, _ = _f32(new_gates)
+    ids = np.zeros(max(k_old + k_new, 1), dtype=np.int32)
+    coeff = np.zeros(max(k_old + k_new, 1), dtype=np.float32)
+    n = C.c_int32(0)
+    _check(lib().lsw_build_terms(oi, og, k_old, ni, ng, k_new, E, scale,
+                                 ids.ctypes.data_as(_i32p), coeff.ctypes.data_as(_f32p), C.byref(n)))
+    return ids[: n.value].copy(), coeff[: n.value].copy()
+
+
+def lsw_get_state(ctx: int, layer: int):
+    ids = np.zeros(LSW_MAX_K, dtype=np.int32)
+    gates = np.zeros(LSW_MAX_K, dtype=np.float32)
+    k = C.c_int32(0)
+    _check(lib().lsw_get_state(ctx, layer, ids.ctypes.data_as(_i32p), gates.ctypes.data_as(_f32p), C.byref(k)))
+    return ids[: k.value].copy(), gates[: k.value].copy()
+
+
+def lsw_set_option(ctx: int, option: int, value: int) -> None:
+    _check(lib().lsw_set_option(ctx, option, value))
+
+
+def lsw_query(ctx: int, what: int) -> int:
+    return int(lib().lsw_query(ctx, what))
+
+
+def lsw_worklist_size(out, inn, tile_rows: int, tile_cols: int) -> int:
+    oa, op, n = _i32(out)
+    ia, ip, _ = _i32(inn)
+    return int(lib().lsw_worklist_size(op, ip, n, tile_rows, tile_cols))
+
+
+def lsw_worklist_item(out, inn, tile_rows: int, tile_cols: int, item: int):
+    oa, op, n = _i32(out)
+    ia, ip, _ = _i32(inn)
+    v = [C.c_int32(0) for _ in range(5)]
+    _check(lib().lsw_worklist_item(op, ip, n, tile_rows, tile_cols, item, *[C.byref(x) for x in v]))
+    return tuple(x.value for x in v)   # lin, row0, n_rows, col0, n_cols
+
+
+def lsw_destroy(ctx: int) -> None:
+    lib().lsw_destroy(ctx)
+
+
+# ---------------------------------------------------------------------------
+# convenience for torch users: tensors -> device addresses (still marshalling only)
+# ---------------------------------------------------------------------------
+def create_from_tensors(stack, shapes, E: int, r: int, scale: float = 1.0) -> int:
+    """stack: [(W bf16 [out,in], A fp32 [E,r,in], B fp32 [E,out,r])] torch CUDA tensors;
+    shapes: [(layer, kind, out, in)] as produced by inputs.Workload.linear_shapes()."""
+    lin = []
+    for (W, A, B), (layer, kind, o, n) in zip(stack, shapes):
+        assert W.is_contiguous() and A.is_contiguous() and B.is_contiguous()
+        assert tuple(W.shape) == (o, n) and tuple(A.shape) == (E, r, n) and tuple(B.shape) == (E, o, r)
+        lin.append((W.data_ptr(), A.data_ptr(), B.data_ptr(), o, n, layer, kind))
+    return lsw_create_adapters(lin, E, r, scale)

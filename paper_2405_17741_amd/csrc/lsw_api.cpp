@@ -1,0 +1,477 @@
+// Host side of liblsw: argument checks, the signed term list of a switch, the
+// Softmax(TopK) router, the work decomposition, context state and kernel dispatch.
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <memory>
+#include <new>
+#include <vector>
+
+#include "lsw_internal.h"
+
+using namespace lsw;
+
+// ---------------------------------------------------------------------------
+// error reporting
+// ---------------------------------------------------------------------------
+static thread_local char g_err[512] = "";
+
+static lsw_status fail(lsw_status st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+#define LSW_HIP(call)                                                                     \
+  do {                                                                                    \
+    hipError_t e_ = (call);                                                               \
+    if (e_ != hipSuccess) {                                                               \
+      lsw_status st_ = (e_ == hipErrorOutOfMemory) ? LSW_ERR_NOMEM : LSW_ERR_DEVICE;      \
+      return fail(st_, "%s failed: %s", #call, hipGetErrorString(e_));                    \
+    }                                                                                     \
+  } while (0)
+
+extern "C" const char* lsw_last_error(void) { return g_err; }
+
+// ---------------------------------------------------------------------------
+// context
+// ---------------------------------------------------------------------------
+struct PlanKey {
+  int kernel;                 // 1 vector-ALU, 2 matrix-core
+  std::vector<int32_t> layers;  // empty = all
+  bool operator<(const PlanKey& o) const {
+    if (kernel != o.kernel) return kernel < o.kernel;
+    return layers < o.layers;
+  }
+};
+
+struct DevicePlan {
+  int32_t* d_sel = nullptr;   // one allocation: sel[n_sel] followed by first[n_sel+1]
+  int32_t n_sel = 0;
+  int32_t n_items = 0;
+};
+
+struct LayerState {
+  int32_t k = 0;
+  int32_t ids[LSW_MAX_K];
+  float gates[LSW_MAX_K];
+};
+
+struct lsw_ctx {
+  std::vector<lsw_linear> lin;
+  std::vector<int32_t> layer_ids;            // sorted distinct layer numbers
+  std::vector<LayerState> state;             // parallel to layer_ids
+  int32_t E = 0, r = 0;
+  float scale = 1.0f;
+  int device = 0;
+  int n_cu = 0;
+  LinDesc* d_lin = nullptr;
+  uint16_t* d_apk = nullptr;                 // packed A of all linears (r % 8 == 0 only)
+  int64_t owned_bytes = 0;
+  std::map<PlanKey, DevicePlan> plans;
+  int opt_kernel = 0, opt_strict = 0, opt_grid = 0;
+  int last_kernel = 0, last_items = 0, last_grid = 0;
+};
+
+static int layer_slot(const lsw_ctx* c, int32_t layer) {
+  auto it = std::lower_bound(c->layer_ids.begin(), c->layer_ids.end(), layer);
+  if (it == c->layer_ids.end() || *it != layer) return -1;
+  return int(it - c->layer_ids.begin());
+}
+
+// ---------------------------------------------------------------------------
+// step a1: router
+// ---------------------------------------------------------------------------
+extern "C" lsw_status lsw_route(const float* logits, int32_t E, int32_t k, int32_t* ids, float* gates) {
+  if (!logits || E < 1) return fail(LSW_ERR_ARG, "lsw_route: logits null or E < 1");
+  if (k < 0 || k > E) return fail(LSW_ERR_ARG, "lsw_route: k=%d outside 0..E=%d", k, E);
+  if (k > 0 && (!ids || !gates)) return fail(LSW_ERR_ARG, "lsw_route: null output");
+  for (int32_t i = 0; i < E; ++i)
+    if (std::isnan(logits[i])) return fail(LSW_ERR_ARG, "lsw_route: logit %d is NaN", i);
+  // selection: k passes, each taking the largest remaining logit; `>` keeps the lowest index on ties
+  std::vector<char> taken(size_t(E), 0);
+  for (int32_t c = 0; c < k; ++c) {
+    int32_t best = -1;
+    for (int32_t i = 0; i < E; ++i) {
+      if (taken[i]) continue;
+      if (best < 0 || logits[i] > logits[best]) best = i;
+    }
+    taken[best] = 1;
+    ids[c] = best;
+  }
+  if (k == 0) return LSW_OK;
+  const double top = double(logits[ids[0]]);
+  std::vector<double> ex(size_t(k), 0.0);
+  double sum = 0.0;
+  for (int32_t c = 0; c < k; ++c) {
+    ex[c] = std::exp(double(logits[ids[c]]) - top);
+    sum += ex[c];
+  }
+  for (int32_t c = 0; c < k; ++c) gates[c] = float(ex[c] / sum);
+  return LSW_OK;
+}
+
+// ---------------------------------------------------------------------------
+// step a2: the signed term list
+// ---------------------------------------------------------------------------
+static lsw_status check_list(const char* which, const int32_t* ids, const float* gates, int32_t k, int32_t E) {
+  if (k < 0 || k > LSW_MAX_K) return fail(LSW_ERR_ARG, "%s: k=%d outside 0..%d", which, k, int(LSW_MAX_K));
+  if (k > E) return fail(LSW_ERR_ARG, "%s: k=%d exceeds E=%d", which, k, E);
+  if (k > 0 && (!ids || !gates)) return fail(LSW_ERR_ARG, "%s: null list with k=%d", which, k);
+  for (int32_t a = 0; a < k; ++a) {
+    if (ids[a] < 0 || ids[a] >= E) return fail(LSW_ERR_ARG, "%s: id %d outside [0,%d)", which, ids[a], E);
+    if (!std::isfinite(gates[a])) return fail(LSW_ERR_ARG, "%s: gate %d is not finite", which, a);
+    for (int32_t b = 0; b < a; ++b)
+      if (ids[b] == ids[a]) return fail(LSW_ERR_ARG, "%s: duplicate id %d", which, ids[a]);
+  }
+  return LSW_OK;
+}
+
+extern "C" lsw_status lsw_build_terms(const int32_t* old_ids, const float* old_gates, int32_t k_old,
+                                      const int32_t* new_ids, const float* new_gates, int32_t k_new,
+                                      int32_t E, float scale, int32_t* terms_ids, float* terms_coeff,
+                                      int32_t* n_terms) {
+  if (E < 1) return fail(LSW_ERR_ARG, "E < 1");
+  if (!std::isfinite(scale)) return fail(LSW_ERR_ARG, "scale is not finite");
+  if (!n_terms) return fail(LSW_ERR_ARG, "n_terms is null");
+  lsw_status st = check_list("old", old_ids, old_gates, k_old, E);
+  if (st != LSW_OK) return st;
+  st = check_list("new", new_ids, new_gates, k_new, E);
+  if (st != LSW_OK) return st;
+  if (k_old + k_new > 0 && (!terms_ids || !terms_coeff)) return fail(LSW_ERR_ARG, "null term output");
+  int32_t n = 0;
+  for (int32_t a = 0; a < k_new; ++a) {
+    float coeff = scale * new_gates[a];
+    for (int32_t b = 0; b < k_old; ++b)
+      if (old_ids[b] == new_ids[a]) coeff = scale * new_gates[a] - scale * old_gates[b];
+    if (coeff != 0.0f) { terms_ids[n] = new_ids[a]; terms_coeff[n] = coeff; ++n; }
+  }
+  for (int32_t b = 0; b < k_old; ++b) {
+    bool also_new = false;
+    for (int32_t a = 0; a < k_new; ++a) also_new |= (new_ids[a] == old_ids[b]);
+    if (also_new) continue;
+    float coeff = -(scale * old_gates[b]);
+    if (coeff != 0.0f) { terms_ids[n] = old_ids[b]; terms_coeff[n] = coeff; ++n; }
+  }
+  *n_terms = n;
+  return LSW_OK;
+}
+
+// ---------------------------------------------------------------------------
+// work decomposition (host view; the kernels use the same decode routines)
+// ---------------------------------------------------------------------------
+static bool shapes_ok(const int32_t* out, const int32_t* in, int32_t n_lin, int32_t tr, int32_t tc) {
+  if (!out || !in || n_lin < 1 || tr < 1 || tc < 1) return false;
+  for (int32_t p = 0; p < n_lin; ++p)
+    if (out[p] < 1 || in[p] < 1) return false;
+  return true;
+}
+
+extern "C" int64_t lsw_worklist_size(const int32_t* out, const int32_t* in, int32_t n_lin,
+                                     int32_t tile_rows, int32_t tile_cols) {
+  if (!shapes_ok(out, in, n_lin, tile_rows, tile_cols)) {
+    fail(LSW_ERR_ARG, "lsw_worklist_size: bad argument");
+    return -1;
+  }
+  int64_t n = 0;
+  for (int32_t p = 0; p < n_lin; ++p)
+    n += int64_t(ceil_div(out[p], tile_rows)) * ceil_div(in[p], tile_cols);
+  return n;
+}
+
+extern "C" lsw_status lsw_worklist_item(const int32_t* out, const int32_t* in, int32_t n_lin,
+                                        int32_t tile_rows, int32_t tile_cols, int64_t item,
+                                        int32_t* lin, int32_t* row0, int32_t* n_rows, int32_t* col0,
+                                        int32_t* n_cols) {
+  if (!shapes_ok(out, in, n_lin, tile_rows, tile_cols) || !lin || !row0 || !n_rows || !col0 || !n_cols)
+    return fail(LSW_ERR_ARG, "lsw_worklist_item: bad argument");
+  std::vector<int32_t> first(size_t(n_lin) + 1, 0);
+  int64_t total = 0;
+  for (int32_t p = 0; p < n_lin; ++p) {
+    total += int64_t(ceil_div(out[p], tile_rows)) * ceil_div(in[p], tile_cols);
+    if (total > INT32_MAX) return fail(LSW_ERR_SHAPE, "more than 2^31 work items");
+    first[p + 1] = int32_t(total);
+  }
+  if (item < 0 || item >= total) return fail(LSW_ERR_ARG, "item %lld outside [0,%lld)", (long long)item, (long long)total);
+  int32_t s = find_segment(first.data(), n_lin, int32_t(item));
+  int32_t r0, c0;
+  decode_item(int32_t(item) - first[s], in[s], tile_rows, tile_cols, &r0, &c0);
+  *lin = s;
+  *row0 = r0;
+  *col0 = c0;
+  *n_rows = std::min(tile_rows, out[s] - r0);
+  *n_cols = std::min(tile_cols, in[s] - c0);
+  return LSW_OK;
+}
+
+// ---------------------------------------------------------------------------
+// create / destroy
+// ---------------------------------------------------------------------------
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+extern "C" lsw_status lsw_create_adapters(const lsw_linear* lin, int32_t n_lin, int32_t E, int32_t r,
+                                          float scale, lsw_ctx** out) {
+  if (!out) return fail(LSW_ERR_ARG, "out is null");
+  *out = nullptr;
+  if (!lin || n_lin < 1) return fail(LSW_ERR_ARG, "lin is null or n_lin < 1");
+  if (E < 1 || E > 4096) return fail(LSW_ERR_ARG, "E=%d outside 1..4096", E);
+  if (r < 1 || r > 512) return fail(LSW_ERR_ARG, "r=%d outside 1..512", r);
+  if (!std::isfinite(scale)) return fail(LSW_ERR_ARG, "scale is not finite");
+  int64_t items_valu = 0, items_mfma = 0;
+  for (int32_t p = 0; p < n_lin; ++p) {
+    const lsw_linear& L = lin[p];
+    if (!L.W || !L.A || !L.B) return fail(LSW_ERR_ARG, "linear %d: null tensor", p);
+    if (L.layer < 0) return fail(LSW_ERR_ARG, "linear %d: layer %d < 0", p, L.layer);
+    if (L.out < 1) return fail(LSW_ERR_SHAPE, "linear %d: out=%d < 1", p, L.out);
+    if (L.in < 8 || L.in % 8 != 0) return fail(LSW_ERR_SHAPE, "linear %d: in=%d is not a positive multiple of 8", p, L.in);
+    if (!aligned16(L.W) || !aligned16(L.A) || !aligned16(L.B))
+      return fail(LSW_ERR_SHAPE, "linear %d: tensor not 16-byte aligned", p);
+    items_valu += int64_t(ceil_div(L.out, kValuTileRows)) * ceil_div(L.in, kValuTileCols);
+    items_mfma += int64_t(ceil_div(L.out, kMfmaTileRows)) * ceil_div(L.in, kMfmaTileCols);
+  }
+  if (items_valu > INT32_MAX || items_mfma > INT32_MAX) return fail(LSW_ERR_SHAPE, "more than 2^31 work items");
+
+  int n_dev = 0;
+  if (hipGetDeviceCount(&n_dev) != hipSuccess || n_dev < 1) {
+    (void)hipGetLastError();
+    return fail(LSW_ERR_DEVICE, "no HIP device available");
+  }
+
+  std::unique_ptr<lsw_ctx> c(new (std::nothrow) lsw_ctx);
+  if (!c) return fail(LSW_ERR_NOMEM, "host allocation failed");
+  c->lin.assign(lin, lin + n_lin);
+  c->E = E;
+  c->r = r;
+  c->scale = scale;
+  for (int32_t p = 0; p < n_lin; ++p) c->layer_ids.push_back(lin[p].layer);
+  std::sort(c->layer_ids.begin(), c->layer_ids.end());
+  c->layer_ids.erase(std::unique(c->layer_ids.begin(), c->layer_ids.end()), c->layer_ids.end());
+  c->state.assign(c->layer_ids.size(), LayerState());
+
+  LSW_HIP(hipGetDevice(&c->device));
+  hipDeviceProp_t prop;
+  LSW_HIP(hipGetDeviceProperties(&prop, c->device));
+  c->n_cu = prop.multiProcessorCount;
+
+  // packed copy of A for the matrix-core kernel
+  std::vector<LinDesc> desc(static_cast<size_t>(n_lin));
+  const bool pack = (r % 8 == 0);
+  size_t apk_elems = 0;
+  std::vector<size_t> apk_off(size_t(n_lin), 0);
+  for (int32_t p = 0; p < n_lin; ++p) {
+    apk_off[p] = apk_elems;
+    apk_elems += size_t(E) * size_t(r) * size_t(lin[p].in) * 2;   // bf16 high + low part per element
+  }
+  lsw_ctx* raw = c.get();
+  auto cleanup = [raw]() {
+    if (raw->d_apk) (void)hipFree(raw->d_apk);
+    if (raw->d_lin) (void)hipFree(raw->d_lin);
+    raw->d_apk = nullptr;
+    raw->d_lin = nullptr;
+  };
+  if (pack) {
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&c->d_apk), apk_elems * sizeof(uint16_t));
+    if (e != hipSuccess) { (void)hipGetLastError(); return fail(LSW_ERR_NOMEM, "hipMalloc of %zu bytes for packed A failed", apk_elems * 2); }
+    c->owned_bytes += int64_t(apk_elems * sizeof(uint16_t));
+    for (int32_t p = 0; p < n_lin; ++p) {
+      e = launch_pack_A(lin[p].A, c->d_apk + apk_off[p], E, r, lin[p].in, nullptr);
+      if (e != hipSuccess) { cleanup(); return fail(LSW_ERR_DEVICE, "pack kernel launch failed: %s", hipGetErrorString(e)); }
+    }
+  }
+  for (int32_t p = 0; p < n_lin; ++p) {
+    desc[p].W = static_cast<uint16_t*>(lin[p].W);
+    desc[p].A = lin[p].A;
+    desc[p].B = lin[p].B;
+    desc[p].Apk = pack ? c->d_apk + apk_off[p] : nullptr;
+    desc[p].out = lin[p].out;
+    desc[p].in = lin[p].in;
+  }
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(&c->d_lin), desc.size() * sizeof(LinDesc));
+  if (e != hipSuccess) { (void)hipGetLastError(); cleanup(); return fail(LSW_ERR_NOMEM, "hipMalloc of the descriptor table failed"); }
+  c->owned_bytes += int64_t(desc.size() * sizeof(LinDesc));
+  e = hipMemcpy(c->d_lin, desc.data(), desc.size() * sizeof(LinDesc), hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipDeviceSynchronize();   // the pack kernels have read A
+  if (e != hipSuccess) { cleanup(); return fail(LSW_ERR_DEVICE, "descriptor upload / pack failed: %s", hipGetErrorString(e)); }
+  *out = c.release();
+  return LSW_OK;
+}
+
+extern "C" void lsw_destroy(lsw_ctx* c) {
+  if (!c) return;
+  for (auto& kv : c->plans)
+    if (kv.second.d_sel) (void)hipFree(kv.second.d_sel);
+  if (c->d_apk) (void)hipFree(c->d_apk);
+  if (c->d_lin) (void)hipFree(c->d_lin);
+  delete c;
+}
+
+// ---------------------------------------------------------------------------
+// plans: which linears a launch covers and where each one's items start
+// ---------------------------------------------------------------------------
+static lsw_status get_plan(lsw_ctx* c, int kernel, const std::vector<int32_t>& layers_sorted, DevicePlan** out) {
+  PlanKey key{kernel, layers_sorted};
+  auto it = c->plans.find(key);
+  if (it != c->plans.end()) { *out = &it->second; return LSW_OK; }
+  const int32_t tr = kernel == 2 ? kMfmaTileRows : kValuTileRows;
+  const int32_t tc = kernel == 2 ? kMfmaTileCols : kValuTileCols;
+  std::vector<int32_t> sel, first(1, 0);
+  int64_t total = 0;
+  for (size_t p = 0; p < c->lin.size(); ++p) {
+    if (!layers_sorted.empty() && !std::binary_search(layers_sorted.begin(), layers_sorted.end(), c->lin[p].layer))
+      continue;
+    sel.push_back(int32_t(p));
+    total += int64_t(ceil_div(c->lin[p].out, tr)) * ceil_div(c->lin[p].in, tc);
+    first.push_back(int32_t(total));
+  }
+  DevicePlan dp;
+  dp.n_sel = int32_t(sel.size());
+  dp.n_items = int32_t(total);
+  std::vector<int32_t> blob(sel);
+  blob.insert(blob.end(), first.begin(), first.end());
+  LSW_HIP(hipMalloc(reinterpret_cast<void**>(&dp.d_sel), blob.size() * sizeof(int32_t)));
+  hipError_t e = hipMemcpy(dp.d_sel, blob.data(), blob.size() * sizeof(int32_t), hipMemcpyHostToDevice);
+  if (e != hipSuccess) { (void)hipFree(dp.d_sel); return fail(LSW_ERR_DEVICE, "plan upload failed: %s", hipGetErrorString(e)); }
+  c->owned_bytes += int64_t(blob.size() * sizeof(int32_t));
+  auto ins = c->plans.emplace(std::move(key), dp);
+  *out = &ins.first->second;
+  return LSW_OK;
+}
+
+// ---------------------------------------------------------------------------
+// the switch
+// ---------------------------------------------------------------------------
+extern "C" lsw_status lsw_switch(lsw_ctx* c, const int32_t* layers, int32_t n_layers,
+                                 const int32_t* old_ids, const float* old_gates, int32_t k_old,
+                                 const int32_t* new_ids, const float* new_gates, int32_t k_new,
+                                 void* hip_stream) {
+  if (!c) return fail(LSW_ERR_ARG, "ctx is null");
+  if (n_layers < 0 || (n_layers > 0 && !layers)) return fail(LSW_ERR_ARG, "bad layer list");
+  std::vector<int32_t> sel_layers;
+  if (n_layers > 0) {
+    sel_layers.assign(layers, layers + n_layers);
+    std::sort(sel_layers.begin(), sel_layers.end());
+    for (int32_t a = 0; a < n_layers; ++a) {
+      if (layer_slot(c, sel_layers[a]) < 0) return fail(LSW_ERR_ARG, "unknown layer %d", sel_layers[a]);
+      if (a > 0 && sel_layers[a] == sel_layers[a - 1]) return fail(LSW_ERR_ARG, "duplicate layer %d", sel_layers[a]);
+    }
+    if (sel_layers.size() == c->layer_ids.size()) sel_layers.clear();   // every layer: the common plan
+  }
+  Terms t;
+  std::memset(&t, 0, sizeof(t));
+  lsw_status st = lsw_build_terms(old_ids, old_gates, k_old, new_ids, new_gates, k_new, c->E, c->scale,
+                                  t.e, t.coeff, &t.n);
+  if (st != LSW_OK) return st;
+
+  const std::vector<int32_t>& touched = sel_layers.empty() ? c->layer_ids : sel_layers;
+  if (c->opt_strict) {
+    for (int32_t layer : touched) {
+      const LayerState& s = c->state[size_t(layer_slot(c, layer))];
+      bool same = (s.k == k_old);
+      for (int32_t a = 0; same && a < k_old; ++a) {
+        bool found = false;
+        for (int32_t b = 0; b < s.k; ++b)
+          found |= (s.ids[b] == old_ids[a] && std::memcmp(&s.gates[b], &old_gates[a], sizeof(float)) == 0);
+        same = found;
+      }
+      if (!same) return fail(LSW_ERR_STATE, "layer %d: `old` differs from the merged state", layer);
+    }
+  }
+
+  // the matrix-core kernel keeps the fused rank (terms x r) in registers: at most 64
+  const bool mfma_fits = (c->r % 8 == 0) && (t.n * (c->r / 8) <= 8);
+  int kernel = c->opt_kernel;
+  if (kernel == 0) kernel = mfma_fits ? 2 : 1;
+  if (kernel == 2 && !mfma_fits)
+    return fail(LSW_ERR_ARG, "matrix-core kernel needs r %% 8 == 0 and a fused rank <= 64 (r=%d, terms=%d)", c->r, t.n);
+
+  c->last_kernel = 0;
+  c->last_items = 0;
+  c->last_grid = 0;
+  if (t.n > 0) {
+    DevicePlan* dp = nullptr;
+    st = get_plan(c, kernel, sel_layers, &dp);
+    if (st != LSW_OK) return st;
+    LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items};
+    int grid = c->opt_grid;
+    if (grid <= 0) grid = (kernel == 2) ? c->n_cu * 8 : c->n_cu * 2;
+    grid = std::max(8, (grid / 8) * 8);     // a multiple of the 8 XCDs (the kernels' block remap assumes it)
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = (kernel == 2) ? launch_switch_mfma(lp, t, c->r, grid, s)
+                                 : launch_switch_valu(lp, t, c->r, grid, s);
+    if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "switch launch failed: %s", hipGetErrorString(e));
+    c->last_kernel = kernel;
+    c->last_items = dp->n_items;
+    c->last_grid = grid;
+  }
+  for (int32_t layer : touched) {
+    LayerState& s = c->state[size_t(layer_slot(c, layer))];
+    s.k = k_new;
+    for (int32_t a = 0; a < k_new; ++a) { s.ids[a] = new_ids[a]; s.gates[a] = new_gates[a]; }
+  }
+  return LSW_OK;
+}
+
+// ---------------------------------------------------------------------------
+// merged decode, state, options
+// ---------------------------------------------------------------------------
+extern "C" lsw_status lsw_merged_gemv(lsw_ctx* c, int32_t lin_index, const void* x_bf16, float* y_fp32,
+                                      void* hip_stream) {
+  if (!c) return fail(LSW_ERR_ARG, "ctx is null");
+  if (lin_index < 0 || size_t(lin_index) >= c->lin.size()) return fail(LSW_ERR_ARG, "lin_index %d out of range", lin_index);
+  if (!x_bf16 || !y_fp32) return fail(LSW_ERR_ARG, "null vector");
+  if (!aligned16(x_bf16)) return fail(LSW_ERR_SHAPE, "x is not 16-byte aligned");
+  const lsw_linear& L = c->lin[size_t(lin_index)];
+  hipError_t e = launch_gemv(static_cast<const uint16_t*>(L.W), static_cast<const uint16_t*>(x_bf16), y_fp32,
+                             L.out, L.in, static_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "gemv launch failed: %s", hipGetErrorString(e));
+  return LSW_OK;
+}
+
+extern "C" lsw_status lsw_get_state(const lsw_ctx* c, int32_t layer, int32_t* ids, float* gates, int32_t* k) {
+  if (!c || !k) return fail(LSW_ERR_ARG, "null argument");
+  int slot = layer_slot(c, layer);
+  if (slot < 0) return fail(LSW_ERR_ARG, "unknown layer %d", layer);
+  const LayerState& s = c->state[size_t(slot)];
+  if (s.k > 0 && (!ids || !gates)) return fail(LSW_ERR_ARG, "null output");
+  *k = s.k;
+  for (int32_t a = 0; a < s.k; ++a) { ids[a] = s.ids[a]; gates[a] = s.gates[a]; }
+  return LSW_OK;
+}
+
+extern "C" lsw_status lsw_set_option(lsw_ctx* c, int32_t option, int64_t value) {
+  if (!c) return fail(LSW_ERR_ARG, "ctx is null");
+  switch (option) {
+    case LSW_OPT_KERNEL:
+      if (value < 0 || value > 2) return fail(LSW_ERR_ARG, "kernel option %lld outside 0..2", (long long)value);
+      if (value == 2 && c->r % 8 != 0) return fail(LSW_ERR_ARG, "matrix-core kernel needs r %% 8 == 0");
+      c->opt_kernel = int(value);
+      return LSW_OK;
+    case LSW_OPT_STRICT_STATE:
+      c->opt_strict = value != 0;
+      return LSW_OK;
+    case LSW_OPT_GRID:
+      if (value < 0 || value > (1 << 20)) return fail(LSW_ERR_ARG, "grid option out of range");
+      c->opt_grid = int(value);
+      return LSW_OK;
+    default:
+      return fail(LSW_ERR_ARG, "unknown option %d", option);
+  }
+}
+
+extern "C" int64_t lsw_query(const lsw_ctx* c, int32_t what) {
+  if (!c) return -1;
+  switch (what) {
+    case LSW_Q_N_LINEARS: return int64_t(c->lin.size());
+    case LSW_Q_N_LAYERS: return int64_t(c->layer_ids.size());
+    case LSW_Q_LAST_KERNEL: return c->last_kernel;
+    case LSW_Q_LAST_ITEMS: return c->last_items;
+    case LSW_Q_LAST_GRID: return c->last_grid;
+    case LSW_Q_PACKED_BYTES: return c->owned_bytes;
+    default: return -1;
+  }
+}

@@ -1,0 +1,85 @@
+// Internal declarations shared by the host side and the kernels of liblsw.
+#ifndef LSW_INTERNAL_H
+#define LSW_INTERNAL_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "lsw.h"
+
+#if defined(__HIPCC__) || defined(__HIP__)
+#define LSW_HD __host__ __device__
+#else
+#define LSW_HD
+#endif
+
+namespace lsw {
+
+constexpr int kMaxTerms = 2 * LSW_MAX_K;  // old + new lists
+
+// Device-side descriptor of one adapted linear.
+struct LinDesc {
+  uint16_t*       W;      // bf16 [out, in]
+  const float*    A;      // fp32 [E, r, in]
+  const float*    B;      // fp32 [E, out, r]
+  const uint16_t* Apk;    // packed A for the matrix-core kernel (see pack kernel), or null
+  int32_t         out;
+  int32_t         in;
+};
+
+// The fused low-rank update of one switch: sum over n terms of coeff * B[e] @ A[e].
+// Passed to the kernel by value (no device write, no host sync per token).
+struct Terms {
+  int32_t n;
+  int32_t e[kMaxTerms];
+  float   coeff[kMaxTerms];
+};
+
+// Work decomposition.  The selected linears are listed in `sel` (index into the
+// descriptor table); first[s] is the number of the first item of sel[s] and
+// first[n_sel] the total.  Linear p has ceil(out/TM) x ceil(in/CW) items, rows outermost.
+struct Item {
+  int32_t lin;    // index into the descriptor table
+  int32_t row0;
+  int32_t col0;
+};
+
+LSW_HD inline int32_t ceil_div(int32_t a, int32_t b) { return (a + b - 1) / b; }
+
+// Largest s with first[s] <= item  (first[] is non-decreasing, first[0] == 0, item < first[n_sel]).
+LSW_HD inline int32_t find_segment(const int32_t* first, int32_t n_sel, int32_t item) {
+  int32_t lo = 0, hi = n_sel;          // invariant: first[lo] <= item < first[hi]
+  while (hi - lo > 1) {
+    int32_t mid = (lo + hi) >> 1;
+    if (first[mid] <= item) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+LSW_HD inline void decode_item(int32_t local, int32_t in, int32_t tile_rows, int32_t tile_cols,
+                               int32_t* row0, int32_t* col0) {
+  int32_t ncc = ceil_div(in, tile_cols);
+  *row0 = (local / ncc) * tile_rows;
+  *col0 = (local % ncc) * tile_cols;
+}
+
+// Tile shapes of the two switch kernels (rows x columns of one work item).
+constexpr int kValuTileRows = 64,  kValuTileCols = 128;
+constexpr int kMfmaTileRows = 32,  kMfmaTileCols = 1024;
+
+struct LaunchPlan {             // device pointers + counts for one launch
+  const LinDesc* lin;
+  const int32_t* sel;
+  const int32_t* first;
+  int32_t n_sel;
+  int32_t n_items;
+};
+
+// Kernel launchers (lsw_kernels.hip).  All return the hipError of the launch.
+hipError_t launch_switch_valu(const LaunchPlan& p, const Terms& t, int r, int grid, hipStream_t s);
+hipError_t launch_switch_mfma(const LaunchPlan& p, const Terms& t, int r, int grid, hipStream_t s);
+hipError_t launch_pack_A(const float* A, uint16_t* Apk, int E, int r, int in, hipStream_t s);
+hipError_t launch_gemv(const uint16_t* W, const uint16_t* x, float* y, int out, int in, hipStream_t s);
+
+}  // namespace lsw
+#endif

@@ -1,0 +1,94 @@
+"""GPU parity at full workload shapes, in the launch configuration bench.py times.
+
+The 7B-shaped stack (32 layers x 7 linears, 6.48e9 weights) is switched 64 times; on steps
+1, 2, 3, 32 and 64 sampled rows of EVERY linear are compared, teacher-forced, with the oracle
+(elements are independent, so sampling rows is sound), and two whole linears are compared in
+full at step 1.  The other workloads run with their true shapes on a reduced layer count."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import lsw_oracle as O
+from paper_2405_17741_amd import binding as L
+from paper_2405_17741_amd import inputs as I
+from tests.gpu_harness import DeviceStack, check_step, merge_reports
+
+pytestmark = pytest.mark.gpu
+NONE = (np.zeros(0, np.int32), np.zeros(0, np.float32))
+
+
+def _run_sampled(wl, check_steps, full_linears=(), n_random_rows=61, kernel=L.KERNEL_AUTO):
+    shapes = wl.linear_shapes()
+    stack = I.device_stack(wl)
+    ds = DeviceStack(stack, shapes, wl.experts, wl.rank, kernel=kernel)
+    rng = np.random.default_rng(wl.seed + 1)
+    rows = [I.sample_rows(rng, o, n_random_rows) for _, _, o, _ in shapes]
+    A_host = [A.cpu().numpy() for _, A, _ in stack]
+    B_rows = [B.index_select(1, torch.as_tensor(r, device=B.device)).cpu().numpy() for (_, _, B), r in zip(stack, rows)]
+    routes = [O.route(l, wl.top_k) for l in I.router_logits(wl)]
+    old = NONE
+    reports, kernels = [], set()
+    for t, new in enumerate(routes, start=1):
+        checked = t in check_steps
+        if checked:
+            before = [ds.rows(p, rows[p]) for p in range(len(shapes))]
+            full_before = {p: ds.rows(p) for p in full_linears} if t == 1 else {}
+        ds.switch(old, new)
+        kernels.add(L.lsw_query(ds.ctx, L.LSW_Q_LAST_KERNEL))
+        if checked:
+            step_reports = []
+            for p in range(len(shapes)):
+                got = ds.rows(p, rows[p])
+                # B_rows already holds only the sampled rows, so the oracle sees a [len(rows), in] problem
+                rep, _ = check_step(before[p], got, A_host[p], B_rows[p], old, new)
+                assert rep["fail"] == 0, (wl.name, t, p, {k: v for k, v in rep.items() if k != "fail_mask"})
+                step_reports.append(rep)
+            for p, wb in full_before.items():
+                Bf = stack[p][2].cpu().numpy()
+                rep, _ = check_step(wb, ds.rows(p), A_host[p], Bf, old, new)
+                assert rep["fail"] == 0, (wl.name, "full", p)
+                step_reports.append(rep)
+            tot = merge_reports(step_reports)
+            print(f"[{wl.name} step {t}] n={tot['n']} exact={tot['exact_frac']:.6f} "
+                  f"clause2={tot['needed_clause2']} maxdist={tot['max_dist']} kernels={sorted(kernels)}", flush=True)
+            reports.append(tot)
+        old = new
+    ds.close()
+    return reports, kernels
+
+
+def test_7b_full_size_sampled_rows_every_linear():
+    wl = I.WORKLOADS["7b"]
+    rng = np.random.default_rng(7)
+    full = (int(rng.integers(0, 32)) * 7 + 0, int(rng.integers(0, 32)) * 7 + 4)   # one 4096x4096, one 11008x4096
+    reports, kernels = _run_sampled(wl, {1, 2, 3, 32, 64}, full_linears=full)
+    assert kernels <= {L.KERNEL_MFMA}
+    assert len(reports) == 5 and all(r["exact_frac"] > 0.999 for r in reports)
+
+
+def test_13b_shape_with_forced_reuse_two_layers():
+    wl = I.scaled(I.WORKLOADS["13b"], 2)
+    reports, kernels = _run_sampled(wl, {1, 2, 3, 17, 33, 64}, n_random_rows=29)
+    assert L.KERNEL_MFMA in kernels
+    assert all(r["exact_frac"] > 0.999 for r in reports)
+    # the stream really reuses experts: some steps have 3 terms (one id in both sets)
+    routes = [O.route(l, 2)[0].tolist() for l in I.router_logits(wl)]
+    reuse = sum(len(set(a) & set(b)) > 0 for a, b in zip(routes[:-1], routes[1:]))
+    assert 20 <= reuse <= 50
+
+
+def test_70b_shape_one_layer():
+    wl = I.scaled(I.WORKLOADS["70b"], 1)
+    wl = I.Workload(**{**wl.__dict__, "steps": 4})
+    reports, kernels = _run_sampled(wl, {1, 2, 4}, n_random_rows=13)
+    assert kernels == {L.KERNEL_MFMA}
+    assert all(r["exact_frac"] > 0.999 for r in reports)
+
+
+def test_7b_rank64_one_layer():
+    wl = I.scaled(I.WORKLOADS["7b_r64"], 1)
+    wl = I.Workload(**{**wl.__dict__, "steps": 3})
+    reports, kernels = _run_sampled(wl, {1, 2, 3}, n_random_rows=13)
+    assert all(r["exact_frac"] > 0.999 for r in reports)

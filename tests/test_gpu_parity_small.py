@@ -1,0 +1,249 @@
+"""GPU parity of lsw_switch against the CPU oracle on small workloads (full matrices, every step).
+
+Bar: every element within 1 bf16 ulp of the oracle applied to the GPU's own previous state (or within
+one bf16 ulp at the largest magnitude entering the sum, for results that cancel towards zero -- see
+oracle/compare.py); hand-derived rounding fixtures bit-exact; invariants bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import lsw_oracle as O
+from paper_2405_17741_amd import binding as L
+from paper_2405_17741_amd import inputs as I
+from tests.golden_cases import load_rne_cases
+from tests.gpu_harness import DeviceStack, bits_to_device, check_step, device_to_bits, merge_reports
+
+pytestmark = pytest.mark.gpu
+KERNELS = [L.KERNEL_VALU, L.KERNEL_MFMA]
+
+
+def _route_stream(wl, steps):
+    logits = I.router_logits(wl, steps)
+    return [O.route(l, wl.top_k) for l in logits]
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_tiny_workload_every_step_full_matrix(kernel):
+    wl = I.WORKLOADS["tiny"]
+    host = I.host_stack(wl)
+    ds = DeviceStack.from_host(host, wl.linear_shapes(), wl.experts, wl.rank, kernel=kernel)
+    (W0, A, B), = host
+    routes = _route_stream(wl, wl.steps)
+    old = (np.zeros(0, np.int32), np.zeros(0, np.float32))
+    prev = ds.rows(0)
+    assert (prev == W0).all()
+    free = W0.copy()
+    reports = []
+    for t, new in enumerate(routes):
+        ds.switch(old, new)
+        assert L.lsw_query(ds.ctx, L.LSW_Q_LAST_KERNEL) == kernel
+        got = ds.rows(0)
+        rep, want = check_step(prev, got, A, B, old, new)
+        assert rep["fail"] == 0, (t, {k: v for k, v in rep.items() if k != "fail_mask"})
+        reports.append(rep)
+        free = O.switch_step(free, A, B, old[0], old[1], new[0], new[1])
+        prev, old = got, new
+    tot = merge_reports(reports)
+    print(f"\n[tiny kernel={kernel}] {tot}; free-running mismatch after {wl.steps} steps: "
+          f"{(free != prev).mean():.4%}")
+    assert tot["exact_frac"] > 0.999
+    # restore the base weights: within the drift the oracle itself predicts
+    ds.switch(old, (np.zeros(0, np.int32), np.zeros(0, np.float32)))
+    rep, _ = check_step(prev, ds.rows(0), A, B, old, (np.zeros(0, np.int32), np.zeros(0, np.float32)))
+    assert rep["fail"] == 0
+    ds.close()
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_hand_derived_rounding_cases_bit_exact(kernel):
+    cases = load_rne_cases()
+    r = 8 if kernel == L.KERNEL_MFMA else 1
+    n = len(cases)
+    # one linear per case: W is 1x8 with the case in column 3; only rank 0 of expert 0 is non-zero
+    host, shapes = [], []
+    for i, c in enumerate(cases):
+        W = np.full((1, 8), 0x3F80, np.uint16)
+        W[0, 3] = c["w"]
+        A = np.zeros((1, r, 8), np.float32)
+        B = np.zeros((1, 1, r), np.float32)
+        A[0, 0, 3] = c["a"]
+        B[0, 0, 0] = c["b"]
+        host.append((W, A, B))
+        shapes.append((i, 0, 1, 8))
+    ds = DeviceStack.from_host(host, shapes, 1, r, kernel=kernel)
+    for i, c in enumerate(cases):
+        g = np.array([c["gate"]], np.float32)
+        e = np.zeros(1, np.int32)
+        none = (np.zeros(0, np.int32), np.zeros(0, np.float32))
+        if c["side"] == "new":
+            ds.switch(none, (e, g), layers=[i])
+        else:
+            ds.switch((e, g), none, layers=[i])
+    bad = []
+    for i, c in enumerate(cases):
+        got = ds.rows(i)
+        assert (np.delete(got[0], 3) == 0x3F80).all(), "neighbouring elements must not change"
+        if c["tag"] == "":
+            if int(got[0, 3]) != c["expect"]:
+                bad.append((i, c, hex(int(got[0, 3]))))
+        else:   # fp64-only ties and subnormal products: one ulp allowed
+            from oracle.compare import ulp_distance
+            assert ulp_distance(got[0, 3], np.uint16(c["expect"])) <= 1, (c, hex(int(got[0, 3])))
+            print(f"[tagged {c['tag']}] expect {c['expect']:#06x} got {int(got[0,3]):#06x}")
+    assert not bad, bad
+    ds.close()
+
+
+SHAPES = [
+    # out, in, E, r
+    (37, 8, 5, 8), (100, 264, 5, 8), (64, 1048, 4, 16), (33, 2056, 3, 8), (130, 520, 6, 24), (1, 16, 2, 8),
+    (96, 256, 8, 32), (65, 136, 3, 4), (40, 72, 4, 1), (70, 1032, 4, 3),
+]
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+@pytest.mark.parametrize("shape", SHAPES)
+def test_ragged_shapes_and_term_counts(shape, kernel):
+    out, inn, E, r = shape
+    if kernel == L.KERNEL_MFMA and r % 8:
+        pytest.skip("matrix-core kernel needs r % 8 == 0")
+    rng = np.random.default_rng(out * 1000 + inn + r)
+    W, A, B = I.host_linear(rng, out, inn, E, r, 0.02, 1 / 16, 0.01)
+    ds = DeviceStack.from_host([(W, A, B)], [(0, 0, out, inn)], E, r, scale=0.5, kernel=L.KERNEL_AUTO)
+    none = (np.zeros(0, np.int32), np.zeros(0, np.float32))
+    seq = [none]
+    kmax = min(E, 2 if r > 16 else 3)
+    for _ in range(6):
+        k = int(rng.integers(1, kmax + 1))
+        ids = rng.choice(E, k, replace=False).astype(np.int32)
+        g = rng.random(k).astype(np.float32)
+        seq.append((ids, (g / g.sum()).astype(np.float32)))
+    seq.append(none)
+    prev = ds.rows(0)
+    reports = []
+    for old, new in zip(seq[:-1], seq[1:]):
+        n_terms = len(L.lsw_build_terms(old[0], old[1], new[0], new[1], E, 0.5)[0])
+        fits = r % 8 == 0 and n_terms * (r // 8) <= 8
+        use = kernel if (kernel == L.KERNEL_VALU or fits) else L.KERNEL_VALU
+        L.lsw_set_option(ds.ctx, L.LSW_OPT_KERNEL, use)
+        ds.switch(old, new)
+        got = ds.rows(0)
+        rep, _ = check_step(prev, got, A, B, old, new, scale=0.5)
+        assert rep["fail"] == 0, (old, new, {k: v for k, v in rep.items() if k != "fail_mask"})
+        reports.append(rep)
+        prev = got
+    assert merge_reports(reports)["exact_frac"] > 0.995
+    ds.close()
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_stack_with_layer_subsets_guard_bands_and_state(kernel):
+    wl = I.Workload("mini", 3, 64, 136, 32, 6, 8, 2, 4, 0.02, 1 / 8, 0.01, 4242)
+    shapes = wl.linear_shapes()
+    host = I.host_stack(wl)
+    # every W sits inside a larger buffer with sentinel bands before and after it
+    GUARD = 256
+    dev, bufs = [], []
+    for (W, A, B), (_, _, o, n) in zip(host, shapes):
+        buf = torch.full((GUARD + o * n + GUARD,), -7.0, dtype=torch.bfloat16, device="cuda")
+        view = buf[GUARD:GUARD + o * n].view(o, n)
+        view.copy_(bits_to_device(W))
+        bufs.append(buf)
+        dev.append((view, torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()))
+    ds = DeviceStack(dev, shapes, wl.experts, wl.rank, kernel=kernel)
+    assert L.lsw_query(ds.ctx, L.LSW_Q_N_LINEARS) == 21 and L.lsw_query(ds.ctx, L.LSW_Q_N_LAYERS) == 3
+    none = (np.zeros(0, np.int32), np.zeros(0, np.float32))
+    a = (np.array([1, 4], np.int32), np.array([0.7, 0.3], np.float32))
+    b = (np.array([4, 2], np.int32), np.array([0.55, 0.45], np.float32))
+    prev = [ds.rows(p) for p in range(len(shapes))]
+
+    def run(old, new, layers):
+        ds.switch(old, new, layers=layers)
+        for p, (layer, _, _, _) in enumerate(shapes):
+            got = ds.rows(p)
+            if layers is None or layer in layers:
+                rep, _ = check_step(prev[p], got, host[p][1], host[p][2], old, new)
+                assert rep["fail"] == 0, (p, layers)
+                assert (got != prev[p]).mean() > 0.3
+            else:
+                assert (got == prev[p]).all(), f"linear {p} of an unselected layer changed"
+            prev[p] = got
+
+    run(none, a, None)
+    run(a, b, [1])                       # only layer 1 moves to b (expert 4 is in both sets: 3 terms)
+    assert L.lsw_get_state(ds.ctx, 1)[0].tolist() == [4, 2]
+    assert L.lsw_get_state(ds.ctx, 0)[0].tolist() == [1, 4]
+    run(a, b, [2, 0])                    # the other two follow
+    run(b, none, None)
+    for buf in bufs:
+        assert (buf[:GUARD] == -7.0).all() and (buf[-GUARD:] == -7.0).all(), "guard band overwritten"
+
+    # strict state: a wrong `old` is refused and nothing changes
+    L.lsw_set_option(ds.ctx, L.LSW_OPT_STRICT_STATE, 1)
+    with pytest.raises(L.LswError) as e:
+        ds.switch(a, b)
+    assert e.value.status == L.LSW_ERR_STATE
+    for p in range(len(shapes)):
+        assert (ds.rows(p) == prev[p]).all()
+    ds.switch(none, a)                   # the true state (nothing merged) is accepted
+    with pytest.raises(L.LswError) as e:
+        ds.switch(none, a, layers=[7])
+    assert e.value.status == L.LSW_ERR_ARG
+    ds.close()
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_invariants_on_device(kernel):
+    rng = np.random.default_rng(9)
+    W, A, B = I.host_linear(rng, 96, 520, 8, 8, 0.02, 1 / 16, 0.01)
+    ds = DeviceStack.from_host([(W, A, B)], [(0, 0, 96, 520)], 8, 8, kernel=kernel)
+    none = (np.zeros(0, np.int32), np.zeros(0, np.float32))
+    s = (np.array([3, 5], np.int32), np.array([0.6, 0.4], np.float32))
+    # k_old = k_new = 0: nothing is launched, W untouched
+    ds.switch(none, none)
+    assert L.lsw_query(ds.ctx, L.LSW_Q_LAST_KERNEL) == 0 and (ds.rows(0) == W).all()
+    ds.switch(none, s)
+    W1 = ds.rows(0)
+    assert (W1 == O.switch_step(W, A, B, [], [], s[0], s[1])).mean() > 0.999
+    # switching to the same set (any order): identical pairs cancel, no launch, bit-identical
+    ds.switch(s, (s[0][::-1].copy(), s[1][::-1].copy()))
+    assert L.lsw_query(ds.ctx, L.LSW_Q_LAST_KERNEL) == 0 and (ds.rows(0) == W1).all()
+    # gates one fp32 ulp apart do not cancel: a launch happens and the 1-ulp rule holds
+    s2 = (s[0], np.nextafter(s[1], np.float32(1.0)).astype(np.float32))
+    ds.switch(s, s2)
+    assert L.lsw_query(ds.ctx, L.LSW_Q_LAST_KERNEL) == kernel
+    rep, _ = check_step(W1, ds.rows(0), A, B, s, s2)
+    assert rep["fail"] == 0
+    # merge then unmerge: the GPU agrees with the oracle on which elements return exactly
+    W2p = ds.rows(0)
+    ds.switch(s2, none)
+    rep, want = check_step(W2p, ds.rows(0), A, B, s2, none)
+    assert rep["fail"] == 0
+    # bad arguments leave W untouched
+    before = ds.rows(0)
+    for old, new in [((np.array([1, 1], np.int32), np.array([.5, .5], np.float32)), none),
+                     (none, (np.array([8], np.int32), np.array([1.0], np.float32))),
+                     (none, (np.array([1], np.int32), np.array([np.nan], np.float32)))]:
+        with pytest.raises(L.LswError) as e:
+            ds.switch(old, new)
+        assert e.value.status == L.LSW_ERR_ARG
+    assert (ds.rows(0) == before).all()
+    ds.close()
+
+
+def test_merged_gemv_against_oracle():
+    rng = np.random.default_rng(10)
+    for out, inn in [(37, 264), (256, 4096), (100, 11008), (16, 8)]:
+        W, A, B = I.host_linear(rng, out, inn, 2, 8, 0.02, 1 / 16, 0.01)
+        ds = DeviceStack.from_host([(W, A, B)], [(0, 0, out, inn)], 2, 8)
+        ds.switch((np.zeros(0, np.int32), np.zeros(0, np.float32)), (np.array([1], np.int32), np.array([1.0], np.float32)))
+        x = I.f32_to_bf16_bits(rng.normal(0, 1, inn).astype(np.float32))
+        xd = bits_to_device(x)
+        y = torch.empty(out, dtype=torch.float32, device="cuda")
+        L.lsw_merged_gemv(ds.ctx, 0, xd.data_ptr(), y.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        Wm = ds.rows(0)
+        want = O.gemv(Wm, x)
+        absum = np.abs(O.bf16_bits_to_f64(Wm)) @ np.abs(O.bf16_bits_to_f64(x))
+        err = np.abs(y.cpu().numpy().astype(np.float64) - want)
+        assert (err <= 1e-5 * absum + 1e-30).all(), (out, inn, float((err / absum).max()))
+        ds.close()

@@ -1,0 +1,169 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused per-token adapter switch on one MI355X.
+
+One step = one lsw_switch over ALL layers of the Llama-2-7B-shaped adapter stack (32 layers x 7
+adapted linears, 8 experts of rank 8, top-2): route the token's logits, unmerge the previous top-2,
+merge the new top-2, in one launch.  Weights, factors and logits are seeded synthetic data already
+resident in HBM when timing starts.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps 64] [--warmup 3] [--workload 7b] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X datasheet: 8 TB/s HBM3E
+
+
+def algorithmic_bytes(wl, n_terms: int) -> float:
+    """Read + write of every bf16 weight, plus every needed factor element once (4 bytes each:
+    fp32 B, and A as bf16 high + low parts)."""
+    return 4.0 * wl.w_elements() + 4.0 * n_terms * wl.rank * wl.factor_dims()
+
+
+def cpu_baseline(wl, steps=2):
+    """The oracle as it stands, timed on the host: one 4096x4096-class linear, `steps` switches,
+    scaled by weight count to a whole-stack microseconds-per-token figure."""
+    import numpy as np
+    from oracle import lsw_oracle as O
+    from paper_2405_17741_amd import inputs as I
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    _, _, o, n = wl.linear_shapes()[0]
+    rng = np.random.default_rng(wl.seed)
+    W, A, B = I.host_linear(rng, o, n, wl.experts, wl.rank, wl.w_std, wl.a_std, wl.b_std)
+    routes = [O.route(l, wl.top_k) for l in I.router_logits(wl, steps + 1)]
+    W = O.switch_step(W, A, B, [], [], routes[0][0], routes[0][1])
+    times = []
+    for t in range(steps):
+        t0 = time.perf_counter()
+        W = O.switch_step(W, A, B, routes[t][0], routes[t][1], routes[t + 1][0], routes[t + 1][1])
+        times.append(time.perf_counter() - t0)
+    med = sorted(times)[len(times) // 2]
+    us_per_token = med * 1e6 * wl.w_elements() / (o * n)
+    return {
+        "value": round(us_per_token, 1), "unit": "us/token", "cores": int(threads), "kind": "oracle",
+        "sample": f"NumPy fp64 oracle on one {o}x{n} linear ({o * n} of {wl.w_elements()} weights), median of "
+                  f"{steps} switches, scaled by weight count; BLAS threads={threads}, element-wise part single-threaded; "
+                  f"host cores visible={len(os.sched_getaffinity(0))}",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="7b")
+    ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 vector-ALU, 2 matrix-core")
+    ap.add_argument("--grid", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (the switch needs no collective; see DESIGN.md "
+              "for how it would shard). Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2405_17741_amd import binding as L
+    from paper_2405_17741_amd import inputs as I
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    wl = I.WORKLOADS[args.workload]
+    torch.cuda.set_device(0)
+    stack = I.device_stack(wl)
+    ctx = L.create_from_tensors(stack, wl.linear_shapes(), wl.experts, wl.rank)
+    if args.kernel:
+        L.lsw_set_option(ctx, L.LSW_OPT_KERNEL, args.kernel)
+    if args.grid:
+        L.lsw_set_option(ctx, L.LSW_OPT_GRID, args.grid)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    n_tokens = args.warmup + args.steps
+    logits = I.router_logits(wl, n_tokens)
+    old = (np.zeros(0, np.int32), np.zeros(0, np.float32))
+
+    def token(t, old):
+        new = L.lsw_route(logits[t], wl.top_k)                         # step a1 (host)
+        L.lsw_switch(ctx, old[0], old[1], new[0], new[1], stream=stream)   # steps a2-a6 (one launch)
+        return new
+
+    for t in range(args.warmup):
+        old = token(t, old)
+    torch.cuda.synchronize()
+
+    # accounting pass (host only, outside the timed region): how many terms each timed launch carries
+    terms, prev = [], old
+    for i in range(args.steps):
+        nxt = L.lsw_route(logits[args.warmup + i], wl.top_k)
+        terms.append(len(L.lsw_build_terms(prev[0], prev[1], nxt[0], nxt[1], wl.experts)[0]))
+        prev = nxt
+
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    kernels = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ev[i][0].record()
+        old = token(args.warmup + i, old)
+        ev[i][1].record()
+        kernels.append(L.lsw_query(ctx, L.LSW_Q_LAST_KERNEL))
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    launch_ms = [a.elapsed_time(b) for (a, b), k in zip(ev, kernels) if k != 0]
+    launch_bytes = [algorithmic_bytes(wl, n) for n, k in zip(terms, kernels) if k != 0]
+    avg_ms = sum(launch_ms) / len(launch_ms)
+    achieved = (sum(launch_bytes) / len(launch_bytes)) / (avg_ms * 1e-3) / 1e9
+    ms_per_step = wall * 1e3 / args.steps
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(args.workload)
+        except Exception:
+            traffic = None
+
+    out = {
+        "metric": "switch latency us/token (all layers) + achieved HBM GB/s, 7B-shaped adapters",
+        "value": round(ms_per_step * 1e3, 1), "unit": "us/token",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {wl.layers} layers x 7 linears, hidden {wl.hidden}, ffn {wl.ffn}, "
+                               f"E={wl.experts}, r={wl.rank}, top-{wl.top_k}, all layers per launch",
+                   "w_elements": wl.w_elements(),
+                   "kernel": {0: "none", 1: "vector-ALU", 2: "matrix-core"}[max(kernels)],
+                   "grid": L.lsw_query(ctx, L.LSW_Q_LAST_GRID),
+                   "terms_per_step_mean": round(sum(terms) / len(terms), 3),
+                   "launch_us": {"mean": round(avg_ms * 1e3, 1), "min": round(min(launch_ms) * 1e3, 1),
+                                 "median": round(sorted(launch_ms)[len(launch_ms) // 2] * 1e3, 1)}},
+        "achieved_hbm_GBps": round(achieved, 1),
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic},
+    }
+    torch.cuda.synchronize()
+    L.lsw_destroy(ctx)
+    del stack
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -229,6 +229,8 @@ extern "C" lsw_status lsw_create_adapters(const lsw_linear* lin, int32_t n_lin, 
     if (L.layer < 0) return fail(LSW_ERR_ARG, "linear %d: layer %d < 0", p, L.layer);
     if (L.out < 1) return fail(LSW_ERR_SHAPE, "linear %d: out=%d < 1", p, L.out);
     if (L.in < 8 || L.in % 8 != 0) return fail(LSW_ERR_SHAPE, "linear %d: in=%d is not a positive multiple of 8", p, L.in);
+    if (int64_t(L.out) * L.in * 2 >= (int64_t(1) << 31))
+      return fail(LSW_ERR_SHAPE, "linear %d: out*in*2 bytes must stay below 2^31", p);
     if (!aligned16(L.W) || !aligned16(L.A) || !aligned16(L.B))
       return fail(LSW_ERR_SHAPE, "linear %d: tensor not 16-byte aligned", p);
     items_valu += int64_t(ceil_div(L.out, kValuTileRows)) * ceil_div(L.in, kValuTileCols);
@@ -265,7 +267,7 @@ extern "C" lsw_status lsw_create_adapters(const lsw_linear* lin, int32_t n_lin, 
   std::vector<size_t> apk_off(size_t(n_lin), 0);
   for (int32_t p = 0; p < n_lin; ++p) {
     apk_off[p] = apk_elems;
-    apk_elems += size_t(E) * size_t(r) * size_t(lin[p].in) * 2;   // bf16 high + low part per element
+    apk_elems += size_t(E) * size_t(r) * size_t(ceil_div(lin[p].in, kApkBlockCols) * kApkBlockCols) * 2;   // bf16 high + low part per element, columns padded to the block
   }
   lsw_ctx* raw = c.get();
   auto cleanup = [raw]() {
@@ -398,7 +400,7 @@ extern "C" lsw_status lsw_switch(lsw_ctx* c, const int32_t* layers, int32_t n_la
     if (st != LSW_OK) return st;
     LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items};
     int grid = c->opt_grid;
-    if (grid <= 0) grid = (kernel == 2) ? c->n_cu * 8 : c->n_cu * 2;
+    if (grid <= 0) grid = (kernel == 2) ? c->n_cu * 4 : c->n_cu * 2;   // matrix-core: one wave per SIMD
     grid = std::max(8, (grid / 8) * 8);     // a multiple of the 8 XCDs (the kernels' block remap assumes it)
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     hipError_t e = (kernel == 2) ? launch_switch_mfma(lp, t, c->r, grid, s)

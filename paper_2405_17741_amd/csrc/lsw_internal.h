@@ -66,6 +66,7 @@ LSW_HD inline void decode_item(int32_t local, int32_t in, int32_t tile_rows, int
 // Tile shapes of the two switch kernels (rows x columns of one work item).
 constexpr int kValuTileRows = 64,  kValuTileCols = 128;
 constexpr int kMfmaTileRows = 32,  kMfmaTileCols = 1024;
+constexpr int kApkBlockCols = 256;   // column block of the packed A layout = columns per matrix-core step
 
 struct LaunchPlan {             // device pointers + counts for one launch
   const LinDesc* lin;

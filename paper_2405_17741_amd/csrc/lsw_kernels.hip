@@ -42,28 +42,44 @@ __device__ __forceinline__ int xcd_contiguous_block(int b, int grid) {
   return (b & 7) * (grid >> 3) + (b >> 3);
 }
 
+// Values that are the same in every lane, told to the compiler so they live in scalar registers.
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+template <typename T>
+__device__ __forceinline__ T* uniform(T* ptr) {
+  const uint64_t u = reinterpret_cast<uint64_t>(ptr);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane(uint32_t(u));
+  const uint32_t hi = __builtin_amdgcn_readfirstlane(uint32_t(u >> 32));
+  return reinterpret_cast<T*>((uint64_t(hi) << 32) | lo);
+}
+
 // ---------------------------------------------------------------------------
 // A re-layout for the matrix-core kernel
-//   A   fp32 [E][r][in]                      (LoRA_DOWN as the caller stores it)
-//   Apk bf16 [E][r/8][in][2][8]              (for expert e, rank group g, column j: the 8 ranks
-//                                             8g..8g+7 as bf16 high parts, then their low parts)
-// A matrix-core lane wants 8 consecutive k for one column; this layout makes that one 16-byte
-// load for the high parts and one for the low parts, contiguous over neighbouring columns.
+//   A   fp32 [E][r][in]                       (LoRA_DOWN as the caller stores it)
+//   Apk bf16 [E][r/8][ncb][8][2][32][8]       ncb = ceil(in/256) column blocks of 256
+// For expert e, rank group g (ranks 8g..8g+7) and column j = 256*cb + 8*n + b the 8 ranks are
+// stored as 8 bf16 high parts at [e][g][cb][b][0][n][.] and 8 bf16 low parts at [..][b][1][n][.]
+// (columns past `in` hold zeros).  A matrix-core lane wants 8 consecutive k of one column; in this
+// order the 32 lanes of one access (n = 0..31, fixed b) read 512 contiguous bytes.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_pack_A(const float* __restrict__ A, uint16_t* __restrict__ Apk,
                                                 int E, int r, int in) {
   const int gpr = r >> 3;
-  const long long total = (long long)E * gpr * in;
+  const int in_pad = ceil_div(in, kApkBlockCols) * kApkBlockCols;
+  const long long total = (long long)E * gpr * in_pad;
   for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
        idx += (long long)gridDim.x * blockDim.x) {
-    const int j = int(idx % in);
-    const long long eg = idx / in;
+    const int j = int(idx % in_pad);
+    const long long eg = idx / in_pad;
     const int g = int(eg % gpr);
     const int e = int(eg / gpr);
-    const float* src = A + ((long long)e * r + 8 * g) * in + j;
     float x[8];
 #pragma unroll
-    for (int q = 0; q < 8; ++q) x[q] = src[(long long)q * in];
+    for (int q = 0; q < 8; ++q) x[q] = 0.0f;
+    if (j < in) {
+      const float* src = A + ((long long)e * r + 8 * g) * in + j;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) x[q] = src[(long long)q * in];
+    }
     u32x4 hi, lo;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -72,14 +88,16 @@ __global__ __launch_bounds__(256) void k_pack_A(const float* __restrict__ A, uin
       hi[q] = h;
       lo[q] = l;
     }
-    u32x4* dst = reinterpret_cast<u32x4*>(Apk + idx * 16);
-    dst[0] = hi;
-    dst[1] = lo;
+    const int cb = j / kApkBlockCols, jj = j % kApkBlockCols, n = jj >> 3, b = jj & 7;
+    // element offset of [e][g][cb][b][0][n][0]
+    const long long base = ((eg * (in_pad / kApkBlockCols) + cb) * 8 + b) * (2 * 32 * 8) + n * 8;
+    *reinterpret_cast<u32x4*>(Apk + base) = hi;
+    *reinterpret_cast<u32x4*>(Apk + base + 32 * 8) = lo;
   }
 }
 
 hipError_t launch_pack_A(const float* A, uint16_t* Apk, int E, int r, int in, hipStream_t s) {
-  const long long total = (long long)E * (r / 8) * in;
+  const long long total = (long long)E * (r / 8) * (ceil_div(in, kApkBlockCols) * kApkBlockCols);
   int grid = int(std::min<long long>((total + 255) / 256, 1 << 16));
   hipLaunchKernelGGL(k_pack_A, dim3(grid), dim3(256), 0, s, A, Apk, E, r, in);
   return hipGetLastError();
@@ -182,7 +200,9 @@ hipError_t launch_switch_valu(const LaunchPlan& p, const Terms& t, int r, int gr
 //
 // One wave per workgroup, no LDS staging of tiles, no barrier in the streaming loop.
 // A work item is 32 rows x up to 1024 columns of one W; the wave walks it in steps of
-// 32 rows x 256 columns (512 contiguous bytes per row, 16 KB per step).
+// 32 rows x 256 columns (512 contiguous bytes per row, 16 KB per step) and keeps going
+// through its items without draining: the W tile of the next step (of the next item, at an
+// item boundary) is requested before the matrix work of the current one starts.
 //
 // v_mfma_f32_32x32x16_bf16 computes D[m][n] += sum_k P[m][k] Q[k][n]; lane l supplies
 // P[m = l%32][8*(l/32) .. +8] and Q[8*(l/32) .. +8][n = l%32] and owns, in register v of D,
@@ -199,7 +219,97 @@ hipError_t launch_switch_valu(const LaunchPlan& p, const Terms& t, int r, int gr
 // below the one bf16 rounding of the result.  W itself is loaded into the fp32 accumulators,
 // so the sum is rounded to bf16 exactly once.
 // ---------------------------------------------------------------------------
-constexpr int MT_ROWS = kMfmaTileRows, MT_COLS = kMfmaTileCols, MT_STEP = 256;
+constexpr int MT_ROWS = kMfmaTileRows, MT_COLS = kMfmaTileCols, MT_STEP = kApkBlockCols;
+constexpr uint32_t kOutOfRange = 0x80000000u;   // byte offset beyond any W (out*in*2 < 2^31 is checked at create)
+
+// W is addressed through a buffer resource whose size is the matrix: a row past the last one or
+// a lane whose columns lie past the tile gets an offset outside the buffer, which the hardware
+// answers with zeros on loads and drops on stores.  No clamping or predication in the loop.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t w_resource(const uint16_t* W, int out, int in) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(W), 0, out * in * 2, 0x00020000);
+}
+
+template <int NKS>
+struct MfmaItem {           // what a wave keeps per work item
+  __amdgpu_buffer_rsrc_t Wres;
+  const uint16_t* Apk;      // packed A of the linear
+  int ncb;                  // its column blocks
+  int col0, col_end;
+  uint32_t row0_byte;       // byte offset of row row0 (uniform)
+  uint32_t stride_byte;     // bytes per row (uniform)
+  u32x4 p_hi[NKS], p_lo[NKS];
+};
+
+template <int NKS>
+__device__ __forceinline__ void mfma_load_item(const LaunchPlan& p, int item, int n, int gpr, int r,
+                                               const int (&term_e)[NKS], const int (&term_g)[NKS],
+                                               const float (&term_c)[NKS], MfmaItem<NKS>& it) {
+  const int seg = uniform(find_segment(p.first, p.n_sel, item));
+  const LinDesc* Lp = p.lin + uniform(p.sel[seg]);
+  LinDesc L;
+  L.W = uniform(Lp->W);
+  L.B = uniform(Lp->B);
+  L.Apk = uniform(Lp->Apk);
+  L.out = uniform(Lp->out);
+  L.in = uniform(Lp->in);
+  int row0, col0;
+  decode_item(uniform(item - p.first[seg]), L.in, MT_ROWS, MT_COLS, &row0, &col0);
+  it.Wres = w_resource(L.W, L.out, L.in);
+  it.Apk = L.Apk;
+  it.ncb = ceil_div(L.in, MT_STEP);
+  it.col0 = col0;
+  it.col_end = min(L.in, col0 + MT_COLS);
+  it.stride_byte = uint32_t(L.in) * 2u;
+  it.row0_byte = uint32_t(row0) * it.stride_byte;
+  const int prow = min(row0 + n, L.out - 1);
+  const bool prow_ok = row0 + n < L.out;
+#pragma unroll
+  for (int ks = 0; ks < NKS; ++ks) {
+    const float* src = L.B + ((long long)term_e[ks] * L.out + prow) * r + 8 * term_g[ks];
+    const f32x4 b0 = *reinterpret_cast<const f32x4*>(src);
+    const f32x4 b1 = *reinterpret_cast<const f32x4*>(src + 4);
+    const float c = prow_ok ? term_c[ks] : 0.0f;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      uint32_t hi, lo;
+      split2(c * b0[2 * q], c * b0[2 * q + 1], &hi, &lo);
+      it.p_hi[ks][q] = hi;
+      it.p_lo[ks][q] = lo;
+      split2(c * b1[2 * q], c * b1[2 * q + 1], &hi, &lo);
+      it.p_hi[ks][2 + q] = hi;
+      it.p_lo[ks][2 + q] = lo;
+    }
+  }
+}
+
+// byte offset of this lane's first row (register 0) at column step cs; register v adds
+// (8*(v/4) + v%4) rows, which is uniform over the wave
+template <int NKS>
+__device__ __forceinline__ uint32_t mfma_lane_offset(const MfmaItem<NKS>& it, int cs, int n, int h) {
+  const int col = cs + 8 * n;
+  const uint32_t off = it.row0_byte + uint32_t(4 * h) * it.stride_byte + uint32_t(col) * 2u;
+  return col < it.col_end ? off : kOutOfRange;
+}
+
+template <int NKS>
+__device__ __forceinline__ void mfma_load_w(const MfmaItem<NKS>& it, uint32_t lane_off, u32x4 (&wbuf)[16]) {
+#pragma unroll
+  for (int v = 0; v < 16; ++v)
+    wbuf[v] = __builtin_amdgcn_raw_buffer_load_b128(
+        it.Wres, lane_off + uint32_t(8 * (v >> 2) + (v & 3)) * it.stride_byte, 0, /*nt*/ 2);
+}
+
+template <int NKS>
+__device__ __forceinline__ void mfma_load_q(const MfmaItem<NKS>& it, int cs, int n, int gpr, int e, int g,
+                                            u32x4 (&q_hi)[8], u32x4 (&q_lo)[8]) {
+  const u32x4* src = reinterpret_cast<const u32x4*>(
+      it.Apk + (((long long)e * gpr + g) * it.ncb + cs / MT_STEP) * (8 * 2 * 32 * 8)) + n;
+#pragma unroll
+  for (int b = 0; b < 8; ++b) {
+    q_hi[b] = src[(2 * b) * 32];
+    q_lo[b] = src[(2 * b + 1) * 32];
+  }
+}
 
 template <int NKS>
 __global__ __launch_bounds__(64) void k_switch_mfma(LaunchPlan p, Terms t, int r) {
@@ -215,7 +325,7 @@ __global__ __launch_bounds__(64) void k_switch_mfma(LaunchPlan p, Terms t, int r
   const int n = lane & 31, h = lane >> 5;
   const int gpr = r >> 3;              // rank groups of 8 per expert
   const int n_groups = t.n * gpr;      // <= 2 * NKS
-  const int vb = xcd_contiguous_block(blockIdx.x, gridDim.x);
+  const int grid = gridDim.x;
 
   // per k-step: which (term, rank group) this lane's 8 k-values belong to
   int term_e[NKS], term_g[NKS];
@@ -230,105 +340,86 @@ __global__ __launch_bounds__(64) void k_switch_mfma(LaunchPlan p, Terms t, int r
     term_c[ks] = valid ? s_coeff[c] : 0.0f;      // a zero coefficient blanks the padded k-group
   }
 
-  for (int item = vb; item < p.n_items; item += gridDim.x) {
-    const int seg = find_segment(p.first, p.n_sel, item);
-    const LinDesc L = p.lin[p.sel[seg]];
-    int row0, col0;
-    decode_item(item - p.first[seg], L.in, MT_ROWS, MT_COLS, &row0, &col0);
-    const int col_end = min(L.in, col0 + MT_COLS);
+  int item = xcd_contiguous_block(blockIdx.x, grid);
+  if (item >= p.n_items) return;
+  MfmaItem<NKS> cur;
+  mfma_load_item<NKS>(p, item, n, gpr, r, term_e, term_g, term_c, cur);
+  int cs = cur.col0;
+  uint32_t lane_off = mfma_lane_offset<NKS>(cur, cs, n, h);
+  u32x4 wbuf[16];
+  mfma_load_w<NKS>(cur, lane_off, wbuf);
 
-    // P operand (rows): coeff * B, split; stays in registers for the whole item
-    u32x4 p_hi[NKS], p_lo[NKS];
-    {
-      const int row = min(row0 + n, L.out - 1);
-      const bool row_ok = row0 + n < L.out;
+  constexpr int QB = NKS < 2 ? NKS : 2;     // Q buffers in registers
+  while (true) {
+    u32x4 q_hi[QB][8], q_lo[QB][8];
 #pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) {
-        const float* src = L.B + ((long long)term_e[ks] * L.out + row) * r + 8 * term_g[ks];
-        const f32x4 b0 = *reinterpret_cast<const f32x4*>(src);
-        const f32x4 b1 = *reinterpret_cast<const f32x4*>(src + 4);
-        const float c = row_ok ? term_c[ks] : 0.0f;
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
-          uint32_t hi, lo;
-          split2(c * b0[2 * q], c * b0[2 * q + 1], &hi, &lo);
-          p_hi[ks][q] = hi;
-          p_lo[ks][q] = lo;
-          split2(c * b1[2 * q], c * b1[2 * q + 1], &hi, &lo);
-          p_hi[ks][2 + q] = hi;
-          p_lo[ks][2 + q] = lo;
-        }
-      }
-    }
+    for (int ks = 0; ks < QB; ++ks)
+      mfma_load_q<NKS>(cur, cs, n, gpr, term_e[ks], term_g[ks], q_hi[ks], q_lo[ks]);
 
-    // row pointers of this lane's 16 rows (register v <-> row 8*(v/4) + 4h + v%4)
-    bool row_ok[16];
-    long long row_off[16];
+    // W -> accumulators
+    f32x16 acc[8];
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      const int row = row0 + 8 * (v >> 2) + 4 * h + (v & 3);
-      row_ok[v] = row < L.out;
-      row_off[v] = (long long)min(row, L.out - 1) * L.in;
-    }
-
-    for (int cs = col0; cs < col_end; cs += MT_STEP) {
-      const int col = cs + 8 * n;                 // first of this lane's 8 columns
-      const bool col_ok = col < col_end;
-      const int colc = col_ok ? col : cs;         // clamped: operands stay finite, result unused
-
-      // Q operand (columns): packed A, 8 columns x (high, low) per k-step = 256 contiguous bytes
-      u32x4 q_hi[NKS][8], q_lo[NKS][8];
 #pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) {
-        const u32x4* src = reinterpret_cast<const u32x4*>(
-            L.Apk + (((long long)term_e[ks] * gpr + term_g[ks]) * L.in + colc) * 16);
-#pragma unroll
-        for (int b = 0; b < 8; ++b) {
-          q_hi[ks][b] = src[2 * b];
-          q_lo[ks][b] = src[2 * b + 1];
-        }
-      }
-
-      // W -> accumulators
-      f32x16 acc[8];
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        u32x4 w = {0u, 0u, 0u, 0u};
-        if (row_ok[v] && col_ok)
-          w = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(L.W + row_off[v] + col));
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          acc[2 * q][v] = bf16_lo(w[q]);
-          acc[2 * q + 1][v] = bf16_hi(w[q]);
-        }
-      }
-
-#pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) {
-        const bf16x8 ph = __builtin_bit_cast(bf16x8, p_hi[ks]);
-        const bf16x8 pl = __builtin_bit_cast(bf16x8, p_lo[ks]);
-#pragma unroll
-        for (int b = 0; b < 8; ++b)
-          acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl, __builtin_bit_cast(bf16x8, q_hi[ks][b]), acc[b], 0, 0, 0);
-#pragma unroll
-        for (int b = 0; b < 8; ++b)
-          acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, __builtin_bit_cast(bf16x8, q_lo[ks][b]), acc[b], 0, 0, 0);
-#pragma unroll
-        for (int b = 0; b < 8; ++b)
-          acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, __builtin_bit_cast(bf16x8, q_hi[ks][b]), acc[b], 0, 0, 0);
-      }
-
-      // accumulators -> W (one rounding)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        if (row_ok[v] && col_ok) {
-          u32x4 o;
-#pragma unroll
-          for (int q = 0; q < 4; ++q) o[q] = pack_bf16(acc[2 * q][v], acc[2 * q + 1][v]);
-          __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(L.W + row_off[v] + col));
-        }
+      for (int q = 0; q < 4; ++q) {
+        acc[2 * q][v] = bf16_lo(wbuf[v][q]);
+        acc[2 * q + 1][v] = bf16_hi(wbuf[v][q]);
       }
     }
+
+    // where the wave goes next
+    const bool same = cs + MT_STEP < cur.col_end;
+    const int nitem = same ? item : item + grid;
+    const bool have_next = same || nitem < p.n_items;
+    MfmaItem<NKS> nxt = cur;
+    int ncs = cs + MT_STEP;
+    uint32_t nlane_off = kOutOfRange;
+
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+      // request the next W tile once every Q load of this step has been issued: loads complete
+      // in issue order, so anything requested after it would have to wait for it
+      if (ks == (NKS > 2 ? NKS - 2 : 0)) {
+        if (have_next) {
+          if (!same) {
+            mfma_load_item<NKS>(p, nitem, n, gpr, r, term_e, term_g, term_c, nxt);
+            ncs = nxt.col0;
+          }
+          nlane_off = mfma_lane_offset<NKS>(nxt, ncs, n, h);
+          mfma_load_w<NKS>(nxt, nlane_off, wbuf);
+        }
+      }
+      const bf16x8 ph = __builtin_bit_cast(bf16x8, cur.p_hi[ks]);
+      const bf16x8 pl = __builtin_bit_cast(bf16x8, cur.p_lo[ks]);
+      u32x4(&qh)[8] = q_hi[ks % QB];
+      u32x4(&ql)[8] = q_lo[ks % QB];
+#pragma unroll
+      for (int b = 0; b < 8; ++b)
+        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl, __builtin_bit_cast(bf16x8, qh[b]), acc[b], 0, 0, 0);
+#pragma unroll
+      for (int b = 0; b < 8; ++b)
+        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, __builtin_bit_cast(bf16x8, ql[b]), acc[b], 0, 0, 0);
+#pragma unroll
+      for (int b = 0; b < 8; ++b)
+        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, __builtin_bit_cast(bf16x8, qh[b]), acc[b], 0, 0, 0);
+      if (ks + 2 < NKS)
+        mfma_load_q<NKS>(cur, cs, n, gpr, term_e[ks + 2], term_g[ks + 2], qh, ql);
+    }
+
+    // accumulators -> W (one rounding)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      u32x4 o;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) o[q] = pack_bf16(acc[2 * q][v], acc[2 * q + 1][v]);
+      __builtin_amdgcn_raw_buffer_store_b128(
+          o, cur.Wres, lane_off + uint32_t(8 * (v >> 2) + (v & 3)) * cur.stride_byte, 0, /*nt*/ 2);
+    }
+    if (!have_next) break;
+    cur = nxt;
+    cs = ncs;
+    item = nitem;
+    lane_off = nlane_off;
   }
 }
 

@@ -68,7 +68,11 @@ def main():
     ap.add_argument("--workload", default="7b")
     ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 vector-ALU, 2 matrix-core")
     ap.add_argument("--grid", type=int, default=0)
+    ap.add_argument("--tile-cols", type=int, default=0)
+    ap.add_argument("--xcd", type=int, default=-1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 4 GiB device copy (a known-size reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the switch needs no collective; see DESIGN.md "
@@ -91,6 +95,10 @@ def main():
         L.lsw_set_option(ctx, L.LSW_OPT_KERNEL, args.kernel)
     if args.grid:
         L.lsw_set_option(ctx, L.LSW_OPT_GRID, args.grid)
+    if args.tile_cols:
+        L.lsw_set_option(ctx, L.LSW_OPT_TILE_COLS, args.tile_cols)
+    if args.xcd >= 0:
+        L.lsw_set_option(ctx, L.LSW_OPT_XCD_REMAP, args.xcd)
     stream = torch.cuda.current_stream().cuda_stream
 
     n_tokens = args.warmup + args.steps
@@ -160,6 +168,13 @@ def main():
     torch.cuda.synchronize()
     L.lsw_destroy(ctx)
     del stack
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                      # reads 4 GiB, writes 4 GiB
+        torch.cuda.synchronize()
+        out["calibration_copy_bytes"] = int(src.numel() * 4)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))

@@ -147,7 +147,9 @@ lsw_status lsw_get_state(const lsw_ctx* ctx, int32_t layer, int32_t* ids, float*
 enum {
   LSW_OPT_KERNEL = 1,        /* 0 = automatic, 1 = fp32 vector-ALU kernel, 2 = matrix-core kernel (needs r % 8 == 0) */
   LSW_OPT_STRICT_STATE = 2,  /* 1: lsw_switch rejects an `old` that differs from the tracked state of a layer */
-  LSW_OPT_GRID = 3           /* workgroups per launch; 0 = automatic (fills the device once) */
+  LSW_OPT_GRID = 3,          /* workgroups per launch; 0 = automatic (fills the device once) */
+  LSW_OPT_TILE_COLS = 4,     /* matrix-core kernel: columns per work item, a multiple of 256 (tuning knob) */
+  LSW_OPT_XCD_REMAP = 5      /* 1 (default): each XCD takes a contiguous share of every round of items */
 };
 enum {
   LSW_Q_N_LINEARS = 1, LSW_Q_N_LAYERS = 2,

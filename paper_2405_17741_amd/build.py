@@ -16,6 +16,7 @@ def build_library(verbose: bool = False) -> str:
     cmd = [
         hipcc, "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 VALU forms
+        "-mllvm", "-amdgpu-mfma-vgpr-form",      # matrix-core accumulators in VGPRs: the kernels touch them with VALU ops
         "-Wno-unused-command-line-argument",
         "-I", os.path.join(ROOT, "include"), "-I", os.path.join(PKG, "csrc"),
         "-x", "hip", *SOURCES, "-o", LIB,

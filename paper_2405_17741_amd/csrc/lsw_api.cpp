@@ -43,9 +43,11 @@ extern "C" const char* lsw_last_error(void) { return g_err; }
 // ---------------------------------------------------------------------------
 struct PlanKey {
   int kernel;                 // 1 vector-ALU, 2 matrix-core
+  int tile_cols;
   std::vector<int32_t> layers;  // empty = all
   bool operator<(const PlanKey& o) const {
     if (kernel != o.kernel) return kernel < o.kernel;
+    if (tile_cols != o.tile_cols) return tile_cols < o.tile_cols;
     return layers < o.layers;
   }
 };
@@ -74,7 +76,7 @@ struct lsw_ctx {
   uint16_t* d_apk = nullptr;                 // packed A of all linears (r % 8 == 0 only)
   int64_t owned_bytes = 0;
   std::map<PlanKey, DevicePlan> plans;
-  int opt_kernel = 0, opt_strict = 0, opt_grid = 0;
+  int opt_kernel = 0, opt_strict = 0, opt_grid = 0, opt_tile_cols = kMfmaTileCols, opt_xcd = 1;
   int last_kernel = 0, last_items = 0, last_grid = 0;
 };
 
@@ -315,12 +317,11 @@ extern "C" void lsw_destroy(lsw_ctx* c) {
 // ---------------------------------------------------------------------------
 // plans: which linears a launch covers and where each one's items start
 // ---------------------------------------------------------------------------
-static lsw_status get_plan(lsw_ctx* c, int kernel, const std::vector<int32_t>& layers_sorted, DevicePlan** out) {
-  PlanKey key{kernel, layers_sorted};
+static lsw_status get_plan(lsw_ctx* c, int kernel, int tc, const std::vector<int32_t>& layers_sorted, DevicePlan** out) {
+  PlanKey key{kernel, tc, layers_sorted};
   auto it = c->plans.find(key);
   if (it != c->plans.end()) { *out = &it->second; return LSW_OK; }
-  const int32_t tr = kernel == 2 ? kMfmaTileRows : kValuTileRows;
-  const int32_t tc = kernel == 2 ? kMfmaTileCols : kValuTileCols;
+  const int32_t tr = kernel == 3 ? kMfmaWgTileRows : kernel == 2 ? kMfmaTileRows : kValuTileRows;
   std::vector<int32_t> sel, first(1, 0);
   int64_t total = 0;
   for (size_t p = 0; p < c->lin.size(); ++p) {
@@ -330,6 +331,7 @@ static lsw_status get_plan(lsw_ctx* c, int kernel, const std::vector<int32_t>& l
     total += int64_t(ceil_div(c->lin[p].out, tr)) * ceil_div(c->lin[p].in, tc);
     first.push_back(int32_t(total));
   }
+  if (total > INT32_MAX) return fail(LSW_ERR_SHAPE, "more than 2^31 work items");
   DevicePlan dp;
   dp.n_sel = int32_t(sel.size());
   dp.n_items = int32_t(total);
@@ -388,7 +390,7 @@ extern "C" lsw_status lsw_switch(lsw_ctx* c, const int32_t* layers, int32_t n_la
   const bool mfma_fits = (c->r % 8 == 0) && (t.n * (c->r / 8) <= 8);
   int kernel = c->opt_kernel;
   if (kernel == 0) kernel = mfma_fits ? 2 : 1;
-  if (kernel == 2 && !mfma_fits)
+  if (kernel >= 2 && !mfma_fits)
     return fail(LSW_ERR_ARG, "matrix-core kernel needs r %% 8 == 0 and a fused rank <= 64 (r=%d, terms=%d)", c->r, t.n);
 
   c->last_kernel = 0;
@@ -396,15 +398,17 @@ extern "C" lsw_status lsw_switch(lsw_ctx* c, const int32_t* layers, int32_t n_la
   c->last_grid = 0;
   if (t.n > 0) {
     DevicePlan* dp = nullptr;
-    st = get_plan(c, kernel, sel_layers, &dp);
+    const int tc = kernel >= 2 ? c->opt_tile_cols : kValuTileCols;
+    st = get_plan(c, kernel, tc, sel_layers, &dp);
     if (st != LSW_OK) return st;
-    LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items};
+    LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, tc, c->opt_xcd};
     int grid = c->opt_grid;
-    if (grid <= 0) grid = (kernel == 2) ? c->n_cu * 4 : c->n_cu * 2;   // matrix-core: one wave per SIMD
+    if (grid <= 0) grid = (kernel == 3) ? c->n_cu : (kernel == 2) ? c->n_cu * 4 : c->n_cu * 2;   // matrix-core: one wave per SIMD
     grid = std::max(8, (grid / 8) * 8);     // a multiple of the 8 XCDs (the kernels' block remap assumes it)
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    hipError_t e = (kernel == 2) ? launch_switch_mfma(lp, t, c->r, grid, s)
-                                 : launch_switch_valu(lp, t, c->r, grid, s);
+    hipError_t e = (kernel == 3)   ? launch_switch_mfma_wg(lp, t, c->r, grid, s)
+                   : (kernel == 2) ? launch_switch_mfma(lp, t, c->r, grid, s)
+                                   : launch_switch_valu(lp, t, c->r, grid, s);
     if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "switch launch failed: %s", hipGetErrorString(e));
     c->last_kernel = kernel;
     c->last_items = dp->n_items;
@@ -449,8 +453,8 @@ extern "C" lsw_status lsw_set_option(lsw_ctx* c, int32_t option, int64_t value) 
   if (!c) return fail(LSW_ERR_ARG, "ctx is null");
   switch (option) {
     case LSW_OPT_KERNEL:
-      if (value < 0 || value > 2) return fail(LSW_ERR_ARG, "kernel option %lld outside 0..2", (long long)value);
-      if (value == 2 && c->r % 8 != 0) return fail(LSW_ERR_ARG, "matrix-core kernel needs r %% 8 == 0");
+      if (value < 0 || value > 3) return fail(LSW_ERR_ARG, "kernel option %lld outside 0..3", (long long)value);
+      if (value >= 2 && c->r % 8 != 0) return fail(LSW_ERR_ARG, "matrix-core kernel needs r %% 8 == 0");
       c->opt_kernel = int(value);
       return LSW_OK;
     case LSW_OPT_STRICT_STATE:
@@ -459,6 +463,14 @@ extern "C" lsw_status lsw_set_option(lsw_ctx* c, int32_t option, int64_t value) 
     case LSW_OPT_GRID:
       if (value < 0 || value > (1 << 20)) return fail(LSW_ERR_ARG, "grid option out of range");
       c->opt_grid = int(value);
+      return LSW_OK;
+    case LSW_OPT_TILE_COLS:
+      if (value < kApkBlockCols || value > (1 << 20) || value % kApkBlockCols != 0)
+        return fail(LSW_ERR_ARG, "tile columns must be a multiple of %d", kApkBlockCols);
+      c->opt_tile_cols = int(value);
+      return LSW_OK;
+    case LSW_OPT_XCD_REMAP:
+      c->opt_xcd = value != 0;
       return LSW_OK;
     default:
       return fail(LSW_ERR_ARG, "unknown option %d", option);

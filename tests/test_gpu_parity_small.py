@@ -14,7 +14,7 @@ from tests.golden_cases import load_rne_cases
 from tests.gpu_harness import DeviceStack, bits_to_device, check_step, device_to_bits, merge_reports
 
 pytestmark = pytest.mark.gpu
-KERNELS = [L.KERNEL_VALU, L.KERNEL_MFMA]
+KERNELS = [L.KERNEL_VALU, L.KERNEL_MFMA, L.KERNEL_MFMA_WG]
 
 
 def _route_stream(wl, steps):
@@ -57,7 +57,7 @@ def test_tiny_workload_every_step_full_matrix(kernel):
 @pytest.mark.parametrize("kernel", KERNELS)
 def test_hand_derived_rounding_cases_bit_exact(kernel):
     cases = load_rne_cases()
-    r = 8 if kernel == L.KERNEL_MFMA else 1
+    r = 8 if kernel != L.KERNEL_VALU else 1
     n = len(cases)
     # one linear per case: W is 1x8 with the case in column 3; only rank 0 of expert 0 is non-zero
     host, shapes = [], []
@@ -105,7 +105,7 @@ SHAPES = [
 @pytest.mark.parametrize("shape", SHAPES)
 def test_ragged_shapes_and_term_counts(shape, kernel):
     out, inn, E, r = shape
-    if kernel == L.KERNEL_MFMA and r % 8:
+    if kernel != L.KERNEL_VALU and r % 8:
         pytest.skip("matrix-core kernel needs r % 8 == 0")
     rng = np.random.default_rng(out * 1000 + inn + r)
     W, A, B = I.host_linear(rng, out, inn, E, r, 0.02, 1 / 16, 0.01)

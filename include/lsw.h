@@ -76,7 +76,8 @@ typedef struct lsw_linear {
  * starts in the state "no expert merged".
  *
  * Errors: LSW_ERR_ARG (null, n_lin < 1, E/r out of range, non-finite scale, layer < 0),
- * LSW_ERR_SHAPE (out < 1, in not a positive multiple of 8, pointer not 16-byte aligned),
+ * LSW_ERR_SHAPE (out < 1, in not a positive multiple of 8, pointer not 16-byte aligned, one W of
+ * 2 GiB or more counting rows rounded up to a multiple of 128),
  * LSW_ERR_NOMEM, LSW_ERR_DEVICE (also when no GPU is present; validation comes first).
  */
 lsw_status lsw_create_adapters(const lsw_linear* lin, int32_t n_lin, int32_t E, int32_t r,
@@ -145,9 +146,10 @@ lsw_status lsw_get_state(const lsw_ctx* ctx, int32_t layer, int32_t* ids, float*
 
 /* Options (lsw_set_option) and queries (lsw_query). */
 enum {
-  LSW_OPT_KERNEL = 1,        /* 0 = automatic, 1 = fp32 vector-ALU kernel, 2 = matrix-core kernel (needs r % 8 == 0) */
+  LSW_OPT_KERNEL = 1,        /* 0 = automatic, 1 = fp32 vector-ALU kernel (any rank), 2 = matrix-core kernel
+                                (needs r % 8 == 0 and at most 64 fused ranks per switch) */
   LSW_OPT_STRICT_STATE = 2,  /* 1: lsw_switch rejects an `old` that differs from the tracked state of a layer */
-  LSW_OPT_GRID = 3,          /* workgroups per launch; 0 = automatic (fills the device once) */
+  LSW_OPT_GRID = 3,          /* workgroups per launch; 0 = automatic (one matrix-core workgroup per CU) */
   LSW_OPT_TILE_COLS = 4,     /* matrix-core kernel: columns per work item, a multiple of 256 (tuning knob) */
   LSW_OPT_XCD_REMAP = 5      /* 1 (default): each XCD takes a contiguous share of every round of items */
 };

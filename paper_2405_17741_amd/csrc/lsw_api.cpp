@@ -231,8 +231,9 @@ extern "C" lsw_status lsw_create_adapters(const lsw_linear* lin, int32_t n_lin, 
     if (L.layer < 0) return fail(LSW_ERR_ARG, "linear %d: layer %d < 0", p, L.layer);
     if (L.out < 1) return fail(LSW_ERR_SHAPE, "linear %d: out=%d < 1", p, L.out);
     if (L.in < 8 || L.in % 8 != 0) return fail(LSW_ERR_SHAPE, "linear %d: in=%d is not a positive multiple of 8", p, L.in);
-    if (int64_t(L.out) * L.in * 2 >= (int64_t(1) << 31))
-      return fail(LSW_ERR_SHAPE, "linear %d: out*in*2 bytes must stay below 2^31", p);
+    // 32-bit byte offsets inside one W, including the rows a 128-row work item may reach past the end
+    if (int64_t(ceil_div(L.out, kMfmaTileRows)) * kMfmaTileRows * L.in * 2 >= (int64_t(1) << 31))
+      return fail(LSW_ERR_SHAPE, "linear %d: W (rows rounded up to %d) must stay below 2^31 bytes", p, kMfmaTileRows);
     if (!aligned16(L.W) || !aligned16(L.A) || !aligned16(L.B))
       return fail(LSW_ERR_SHAPE, "linear %d: tensor not 16-byte aligned", p);
     items_valu += int64_t(ceil_div(L.out, kValuTileRows)) * ceil_div(L.in, kValuTileCols);
@@ -321,7 +322,7 @@ static lsw_status get_plan(lsw_ctx* c, int kernel, int tc, const std::vector<int
   PlanKey key{kernel, tc, layers_sorted};
   auto it = c->plans.find(key);
   if (it != c->plans.end()) { *out = &it->second; return LSW_OK; }
-  const int32_t tr = kernel == 3 ? kMfmaWgTileRows : kernel == 2 ? kMfmaTileRows : kValuTileRows;
+  const int32_t tr = kernel == 2 ? kMfmaTileRows : kValuTileRows;
   std::vector<int32_t> sel, first(1, 0);
   int64_t total = 0;
   for (size_t p = 0; p < c->lin.size(); ++p) {
@@ -403,12 +404,11 @@ extern "C" lsw_status lsw_switch(lsw_ctx* c, const int32_t* layers, int32_t n_la
     if (st != LSW_OK) return st;
     LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, tc, c->opt_xcd};
     int grid = c->opt_grid;
-    if (grid <= 0) grid = (kernel == 3) ? c->n_cu : (kernel == 2) ? c->n_cu * 4 : c->n_cu * 2;   // matrix-core: one wave per SIMD
+    if (grid <= 0) grid = (kernel == 2) ? c->n_cu : c->n_cu * 2;   // matrix-core: one 4-wave workgroup per CU
     grid = std::max(8, (grid / 8) * 8);     // a multiple of the 8 XCDs (the kernels' block remap assumes it)
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    hipError_t e = (kernel == 3)   ? launch_switch_mfma_wg(lp, t, c->r, grid, s)
-                   : (kernel == 2) ? launch_switch_mfma(lp, t, c->r, grid, s)
-                                   : launch_switch_valu(lp, t, c->r, grid, s);
+    hipError_t e = (kernel == 2) ? launch_switch_mfma(lp, t, c->r, grid, s)
+                                 : launch_switch_valu(lp, t, c->r, grid, s);
     if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "switch launch failed: %s", hipGetErrorString(e));
     c->last_kernel = kernel;
     c->last_items = dp->n_items;
@@ -453,7 +453,7 @@ extern "C" lsw_status lsw_set_option(lsw_ctx* c, int32_t option, int64_t value) 
   if (!c) return fail(LSW_ERR_ARG, "ctx is null");
   switch (option) {
     case LSW_OPT_KERNEL:
-      if (value < 0 || value > 3) return fail(LSW_ERR_ARG, "kernel option %lld outside 0..3", (long long)value);
+      if (value < 0 || value > 2) return fail(LSW_ERR_ARG, "kernel option %lld outside 0..2", (long long)value);
       if (value >= 2 && c->r % 8 != 0) return fail(LSW_ERR_ARG, "matrix-core kernel needs r %% 8 == 0");
       c->opt_kernel = int(value);
       return LSW_OK;

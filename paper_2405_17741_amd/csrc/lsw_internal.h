@@ -65,8 +65,7 @@ LSW_HD inline void decode_item(int32_t local, int32_t in, int32_t tile_rows, int
 
 // Tile shapes of the two switch kernels (rows x columns of one work item).
 constexpr int kValuTileRows = 64,  kValuTileCols = 128;
-constexpr int kMfmaTileRows = 32,  kMfmaTileCols = 1024;   // default item width; LSW_OPT_TILE_COLS overrides
-constexpr int kMfmaWgTileRows = 128;   // workgroup flavour of the matrix-core kernel: 4 waves x 32 rows
+constexpr int kMfmaTileRows = 128, kMfmaTileCols = 1024;   // 4 waves x 32 rows; default item width (LSW_OPT_TILE_COLS overrides)
 constexpr int kApkBlockCols = 256;   // column block of the packed A layout = columns per matrix-core step
 
 struct LaunchPlan {             // device pointers + counts for one launch
@@ -82,7 +81,6 @@ struct LaunchPlan {             // device pointers + counts for one launch
 // Kernel launchers (lsw_kernels.hip).  All return the hipError of the launch.
 hipError_t launch_switch_valu(const LaunchPlan& p, const Terms& t, int r, int grid, hipStream_t s);
 hipError_t launch_switch_mfma(const LaunchPlan& p, const Terms& t, int r, int grid, hipStream_t s);
-hipError_t launch_switch_mfma_wg(const LaunchPlan& p, const Terms& t, int r, int grid, hipStream_t s);
 hipError_t launch_pack_A(const float* A, uint16_t* Apk, int E, int r, int in, hipStream_t s);
 hipError_t launch_gemv(const uint16_t* W, const uint16_t* x, float* y, int out, int in, hipStream_t s);
 

@@ -204,48 +204,58 @@ hipError_t launch_switch_valu(const LaunchPlan& p, const Terms& t, int r, int gr
 }
 
 // ---------------------------------------------------------------------------
-// Fused switch, matrix-core flavour (rank a multiple of 8, fused rank K <= 64).
+// Fused switch, matrix-core flavour (rank a multiple of 8, fused rank K = terms * r <= 64).
 //
-// One wave per workgroup, no LDS staging of tiles, no barrier in the streaming loop.
-// A work item is 32 rows x up to 1024 columns of one W; the wave walks it in steps of
-// 32 rows x 256 columns (512 contiguous bytes per row, 16 KB per step) and keeps going
-// through its items without draining: the W tile of the next step (of the next item, at an
-// item boundary) is requested before the matrix work of the current one starts.
+// Launch shape.  A workgroup is 4 waves (one per SIMD), one workgroup per CU, persistent: it
+// walks work items  blockIdx, blockIdx + grid, ...  A work item is 128 rows x tile_cols columns
+// of one W; wave w owns rows 32w..32w+31 and walks the item in steps of 32 rows x 256 columns
+// (512 contiguous bytes per row, 16 KB per wave and step).
 //
-// v_mfma_f32_32x32x16_bf16 computes D[m][n] += sum_k P[m][k] Q[k][n]; lane l supplies
-// P[m = l%32][8*(l/32) .. +8] and Q[8*(l/32) .. +8][n = l%32] and owns, in register v of D,
-// the element (m = 8*(v/4) + 4*(l/32) + v%4, n = l%32).
-// Mapping: m <-> row of W (row0 + m), and in matrix block b (0..7) n <-> column 8n + b of the
-// step.  A lane therefore owns, for each of its 16 rows, the 8 CONTIGUOUS columns 8n..8n+7
-// (one per block): a 16-byte load of W fills one register of each of the 8 accumulators, and
-// lanes 0..31 (resp. 32..63) of one access cover 512 contiguous bytes of one row.  The
-// accumulator layout IS the coalesced layout, so W goes global -> registers -> global with
-// nothing in between.
+// Tile mapping.  v_mfma_f32_32x32x16_bf16 computes D[m][n] += sum_k P[m][k] Q[k][n]; lane l
+// supplies P[m = l%32][8*(l/32) .. +8] and Q[8*(l/32) .. +8][n = l%32] and owns, in register v of
+// D, the element (m = 8*(v/4) + 4*(l/32) + v%4, n = l%32).  Here m <-> row of W, and in matrix
+// block b (0..7) n <-> column 8n + b of the step.  A lane therefore owns, for each of its 16
+// rows, the 8 CONTIGUOUS columns 8n..8n+7 (one per block): one 16-byte load of W feeds one
+// register of each of the 8 accumulators, and lanes 0..31 (resp. 32..63) of one access cover 512
+// contiguous bytes of one row.  The accumulator layout IS the coalesced layout, so W goes
+// global -> registers -> global with no shuffle in between.
 //
-// Precision: P = coeff * B (fp32 product) and Q = A are each split into bf16 high + low parts;
-// high*high + high*low + low*high keeps the update accurate to about 2^-16 relative, far
-// below the one bf16 rounding of the result.  W itself is loaded into the fp32 accumulators,
-// so the sum is rounded to bf16 exactly once.
+// Operands.  P = coeff * B (the gate and the sign of the unmerged set, Eq. 5 / Eq. 9), computed in
+// fp32 once per item and kept in registers.  Q = A comes from the packed copy (see k_pack_A); the
+// Q of a step is the same for the 4 waves, so each wave copies a quarter of it from L2 into LDS
+// (LDS-DMA, no registers) one step ahead, and all read it from there.
+//
+// Precision.  P and Q are each split into bf16 high + low parts; high*high + high*low + low*high
+// keeps the update accurate to about 2^-16 relative, far below the one bf16 rounding of the
+// result.  W itself is widened into the fp32 accumulators, so the sum is rounded to bf16 once.
+//
+// Memory schedule of one step (per wave): start the LDS copy of the next step's Q quarter; store
+// the previous step's finished tile; request the next W tile into the registers just stored from
+// (next item's first tile at an item boundary: scalar selects, no branch); compute; wait for
+// everything requested to land; workgroup barrier (LDS-only fence).  One W tile per wave is in
+// flight at any time, which is what the memory system sustains best for this in-place pattern.
+// W is addressed through a buffer resource sized to the matrix: rows past the end and lanes whose
+// columns lie past the tile get an offset outside the buffer, which the hardware answers with
+// zeros on loads and drops on stores, so the loop has no clamping and no predication.
 // ---------------------------------------------------------------------------
-constexpr int MT_ROWS = kMfmaTileRows, MT_STEP = kApkBlockCols;
+constexpr int MT_STEP = kApkBlockCols;
+constexpr int WG_WAVES = 4;
+constexpr int WG_ROWS = kMfmaTileRows;
 constexpr uint32_t kOutOfRange = 0x80000000u;   // byte offset beyond any W (out*in*2 < 2^31 is checked at create)
+extern __shared__ u32x4 wg_lds[];               // [2 buffers][NKS][8 blocks][high, low][64 lanes]
 
-// W is addressed through a buffer resource whose size is the matrix: a row past the last one or
-// a lane whose columns lie past the tile gets an offset outside the buffer, which the hardware
-// answers with zeros on loads and drops on stores.  No clamping or predication in the loop.
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t w_resource(const uint16_t* W, int wbytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(uniform(W)), 0, uniform(wbytes), 0x00020000);
 }
 
 template <int NKS>
 struct MfmaItem {           // what a wave keeps per work item
-  const uint16_t* W;        // the resource is rebuilt from these two where it is used, so that it
-  int wbytes;               // provably lives in scalar registers
-
+  const uint16_t* W;        // the buffer resource is rebuilt from these two where it is used, so
+  int wbytes;               // that it provably lives in scalar registers
   const uint16_t* Apk;      // packed A of the linear
   int ncb;                  // its column blocks
   int col0, col_end;
-  uint32_t row0_byte;       // byte offset of row row0 (uniform)
+  uint32_t row0_byte;       // byte offset of this wave's first row (uniform)
   uint32_t stride_byte;     // bytes per row (uniform)
   u32x4 p_hi[NKS], p_lo[NKS];
 };
@@ -254,7 +264,7 @@ template <int NKS>
 __device__ __forceinline__ void mfma_load_item(const LaunchPlan& p, int item, int n, int gpr, int r,
                                                const int (&term_e)[NKS], const int (&term_g)[NKS],
                                                const float (&term_c)[NKS], MfmaItem<NKS>& it,
-                                               int tile_rows = MT_ROWS, int row_shift = 0) {
+                                               int tile_rows, int row_shift) {
   const int seg = uniform(find_segment(p.first, p.n_sel, item));
   const LinDesc* Lp = p.lin + uniform(p.sel[seg]);
   LinDesc L;
@@ -315,384 +325,24 @@ __device__ __forceinline__ void mfma_load_w(const MfmaItem<NKS>& it, uint32_t la
 }
 
 template <int NKS>
-__device__ __forceinline__ void mfma_load_q(const MfmaItem<NKS>& it, int cs, int n, int gpr, int e, int g,
-                                            u32x4 (&q_hi)[8], u32x4 (&q_lo)[8]) {
-  const LSW_GLOBAL u32x4* src = as_global(reinterpret_cast<const u32x4*>(
-      it.Apk + (((long long)e * gpr + g) * it.ncb + cs / MT_STEP) * (8 * 2 * 32 * 8)) + n);
-#pragma unroll
-  for (int b = 0; b < 8; ++b) {
-    q_hi[b] = src[(2 * b) * 32];
-    q_lo[b] = src[(2 * b + 1) * 32];
-  }
-}
-
-template <int NKS>
-__global__ __launch_bounds__(64) void k_switch_mfma(LaunchPlan p, Terms t, int r) {
-  __shared__ int32_t s_e[kMaxTerms];
-  __shared__ float s_coeff[kMaxTerms];
-  const int lane = threadIdx.x;
-  if (lane < kMaxTerms) {
-    s_e[lane] = t.e[lane];
-    s_coeff[lane] = t.coeff[lane];
-  }
-  __syncthreads();
-
-  const int n = lane & 31, h = lane >> 5;
-  const int gpr = r >> 3;              // rank groups of 8 per expert
-  const int n_groups = t.n * gpr;      // <= 2 * NKS
-  const int grid = gridDim.x;
-
-  // per k-step: which (term, rank group) this lane's 8 k-values belong to
-  int term_e[NKS], term_g[NKS];
-  float term_c[NKS];
-#pragma unroll
-  for (int ks = 0; ks < NKS; ++ks) {
-    const int G = 2 * ks + h;
-    const bool valid = G < n_groups;
-    const int c = valid ? G / gpr : 0;
-    term_e[ks] = s_e[c];
-    term_g[ks] = valid ? G - c * gpr : 0;
-    term_c[ks] = valid ? s_coeff[c] : 0.0f;      // a zero coefficient blanks the padded k-group
-  }
-
-  int item = p.xcd_remap ? xcd_contiguous_block(blockIdx.x, grid) : int(blockIdx.x);
-  if (item >= p.n_items) return;
-  MfmaItem<NKS> cur;
-  mfma_load_item<NKS>(p, item, n, gpr, r, term_e, term_g, term_c, cur);
-  int cs = cur.col0;
-  uint32_t lane_off = mfma_lane_offset<NKS>(cur, cs, n, h);
-  u32x4 wbuf[16];
-  mfma_load_w<NKS>(cur, lane_off, wbuf);
-
-  // Q operand (packed A) of the current step: two k-steps live in registers at a time.  The
-  // loads for the NEXT step are issued right after the last matrix instruction that reads the
-  // registers, so they travel while the results are rounded and stored.
-  constexpr int QB = NKS < 2 ? NKS : 2;
-  u32x4 q_hi[QB][8], q_lo[QB][8];
-#pragma unroll
-  for (int ks = 0; ks < QB; ++ks)
-    mfma_load_q<NKS>(cur, cs, n, gpr, term_e[ks], term_g[ks], q_hi[ks], q_lo[ks]);
-
-  while (true) {
-    // W -> accumulators
-    f32x16 acc[8];
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        acc[2 * q][v] = bf16_lo(wbuf[v][q]);
-        acc[2 * q + 1][v] = bf16_hi(wbuf[v][q]);
-      }
-    }
-
-    // where the wave goes next
-    const bool same = cs + MT_STEP < cur.col_end;
-    const int nitem = same ? item : item + grid;
-    const bool have_next = same || nitem < p.n_items;
-    MfmaItem<NKS> nxt = cur;
-    int ncs = cs + MT_STEP;
-    uint32_t nlane_off = kOutOfRange;
-
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) {
-      // request the next W tile once every Q load of this step has been issued: loads complete
-      // in issue order, so anything requested after it would have to wait for it
-      if (ks == (NKS > 2 ? NKS - 2 : 0)) {
-        if (have_next) {
-          if (!same) {
-            mfma_load_item<NKS>(p, nitem, n, gpr, r, term_e, term_g, term_c, nxt);
-            ncs = nxt.col0;
-          }
-          nlane_off = mfma_lane_offset<NKS>(nxt, ncs, n, h);
-          mfma_load_w<NKS>(nxt, nlane_off, wbuf);
-        }
-      }
-      const bf16x8 ph = __builtin_bit_cast(bf16x8, cur.p_hi[ks]);
-      const bf16x8 pl = __builtin_bit_cast(bf16x8, cur.p_lo[ks]);
-      u32x4(&qh)[8] = q_hi[ks % QB];
-      u32x4(&ql)[8] = q_lo[ks % QB];
-#pragma unroll
-      for (int b = 0; b < 8; ++b)
-        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl, __builtin_bit_cast(bf16x8, qh[b]), acc[b], 0, 0, 0);
-#pragma unroll
-      for (int b = 0; b < 8; ++b)
-        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, __builtin_bit_cast(bf16x8, ql[b]), acc[b], 0, 0, 0);
-#pragma unroll
-      for (int b = 0; b < 8; ++b)
-        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, __builtin_bit_cast(bf16x8, qh[b]), acc[b], 0, 0, 0);
-      // refill this Q buffer: with the k-step two ahead of this one, or, past the end of the
-      // step, with the matching k-step of the next step
-      if (ks + 2 < NKS) {
-        mfma_load_q<NKS>(cur, cs, n, gpr, term_e[ks + 2], term_g[ks + 2], qh, ql);
-      } else if (have_next) {
-        constexpr int kNextFirst = NKS - QB;      // first k-step whose buffer is free for the next step
-        const int nks = ks - kNextFirst;           // 0 .. QB-1
-        if ((NKS % QB) == 0 || NKS == 1) {         // buffer parity carries over: buffer ks%QB serves k-step nks
-          mfma_load_q<NKS>(nxt, ncs, n, gpr, term_e[nks], term_g[nks], q_hi[nks % QB], q_lo[nks % QB]);
-        }
-      }
-    }
-    if ((NKS % QB) != 0 && NKS != 1 && have_next) {   // odd number of k-steps: reload both buffers in order
-#pragma unroll
-      for (int ks = 0; ks < QB; ++ks)
-        mfma_load_q<NKS>(nxt, ncs, n, gpr, term_e[ks], term_g[ks], q_hi[ks], q_lo[ks]);
-    }
-
-    // accumulators -> W (one rounding)
-    const __amdgpu_buffer_rsrc_t cres = w_resource(cur.W, cur.wbytes);
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      u32x4 o;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) o[q] = pack_bf16(acc[2 * q][v], acc[2 * q + 1][v]);
-      __builtin_amdgcn_raw_buffer_store_b128(
-          o, cres, lane_off + uint32_t(8 * (v >> 2) + (v & 3)) * cur.stride_byte, 0, /*nt*/ 2);
-    }
-    if (!have_next) break;
-    cur = nxt;
-    cs = ncs;
-    item = nitem;
-    lane_off = nlane_off;
-  }
-}
-
-// ---------------------------------------------------------------------------
-// The same kernel for a fused rank of at most 32 (one or two k-steps), which is what top-2 of
-// rank-8 experts needs (old + new set).  All Q operands of a step fit in registers, so the
-// step is reorganised to shorten the serial chain of one wave:
-//   * two W buffers alternate: the next tile is requested at the top of a step, a full step
-//     before it is needed;
-//   * the 8 matrix blocks are processed as 4 pairs (the two bf16 halves of one 32-bit word of
-//     each row): widen that word of all 16 rows, run the pair's matrix instructions, round the
-//     pair back into the same word.  Widening and rounding of neighbouring pairs overlap with
-//     the matrix pipe, and only two accumulators are live at a time.
-// ---------------------------------------------------------------------------
-// The compute part of one step: wcur holds the bf16 tile on entry and the updated tile on exit.
-// Pair q = blocks 2q and 2q+1 = low and high bf16 half of word q of each row.  The pairs are
-// software-pipelined by hand: while the matrix pipe works on pair q, the vector ALU widens pair
-// q+1 and rounds pair q-1.  The scheduling directives pin that interleaving (one matrix
-// instruction, then a few vector instructions), which the compiler would otherwise undo.
-template <int NKS>
-__device__ __forceinline__ void mfma2_compute(const u32x4 (&p_hi)[NKS], const u32x4 (&p_lo)[NKS],
-                                              const u32x4 (&q_hi)[NKS][8], const u32x4 (&q_lo)[NKS][8],
-                                              u32x4 (&wcur)[16]) {
-  f32x16 a0[4], a1[4];
-#pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    a0[0][v] = bf16_lo(wcur[v][0]);
-    a1[0][v] = bf16_hi(wcur[v][0]);
-  }
-  __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    if (q + 1 < 4) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        a0[q + 1][v] = bf16_lo(wcur[v][q + 1]);
-        a1[q + 1][v] = bf16_hi(wcur[v][q + 1]);
-      }
-    }
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) {
-      const bf16x8 ph = __builtin_bit_cast(bf16x8, p_hi[ks]);
-      const bf16x8 pl = __builtin_bit_cast(bf16x8, p_lo[ks]);
-      a0[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl, __builtin_bit_cast(bf16x8, q_hi[ks][2 * q]), a0[q], 0, 0, 0);
-      a1[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl, __builtin_bit_cast(bf16x8, q_hi[ks][2 * q + 1]), a1[q], 0, 0, 0);
-      a0[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, __builtin_bit_cast(bf16x8, q_lo[ks][2 * q]), a0[q], 0, 0, 0);
-      a1[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, __builtin_bit_cast(bf16x8, q_lo[ks][2 * q + 1]), a1[q], 0, 0, 0);
-      a0[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, __builtin_bit_cast(bf16x8, q_hi[ks][2 * q]), a0[q], 0, 0, 0);
-      a1[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, __builtin_bit_cast(bf16x8, q_hi[ks][2 * q + 1]), a1[q], 0, 0, 0);
-    }
-    if (q > 0) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        uint32_t w = pack_bf16(a0[q - 1][v], a1[q - 1][v]);   // the one rounding
-        asm volatile("" : "+v"(w));   // keeps the rounding here, under the matrix pipe, instead of next to the store
-        wcur[v][q - 1] = w;
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < 6 * NKS; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);               // one matrix instruction
-      __builtin_amdgcn_sched_group_barrier(0x002, 48 / (6 * NKS), 0);  // a few vector instructions
-    }
-    __builtin_amdgcn_sched_barrier(0);
-  }
-#pragma unroll
-  for (int v = 0; v < 16; ++v) wcur[v][3] = pack_bf16(a0[3][v], a1[3][v]);
-}
-
-// One step, without branches around the memory traffic.  On entry `wcur` holds the (landed or
-// landing) bf16 tile of this step and `wprev` the finished tile of the previous step, not yet
-// stored.  The step waits for its tile, stores the previous one, requests the next tile into the
-// freed buffer (of this item, or the first tile of the next item: scalar selects), updates its
-// tile in place and requests the next step's Q operands.  Storing one step late keeps every wait
-// of the loop on data that is needed at that point anyway.  Returns false after the last tile.
-template <int NKS>
-__device__ __forceinline__ bool mfma2_step(const LaunchPlan& p, int grid, int n, int h, int gpr, int r,
-                                           const int (&term_e)[NKS], const int (&term_g)[NKS],
-                                           const float (&term_c)[NKS], MfmaItem<NKS>& cur, MfmaItem<NKS>& nxt,
-                                           bool& have_nxt, int& item, int& cs, uint32_t& lane_off,
-                                           __amdgpu_buffer_rsrc_t& prev_res, uint32_t& prev_off, uint32_t& prev_stride,
-                                           u32x4 (&wcur)[16], u32x4 (&wprev)[16],
-                                           u32x4 (&q_hi)[NKS][8], u32x4 (&q_lo)[NKS][8]) {
-  const bool last = uniform(int(!(cs + MT_STEP < cur.col_end))) != 0;     // last step of this item
-  const bool more = !last || have_nxt;
-  // where the next tile lives: this item or the next one (scalar selects)
-  const __amdgpu_buffer_rsrc_t nres = w_resource(last ? nxt.W : cur.W, last ? nxt.wbytes : cur.wbytes);
-  const int ncs = uniform(last ? nxt.col0 : cs + MT_STEP);
-  const int ncol_end = uniform(last ? nxt.col_end : cur.col_end);
-  const uint32_t nrow0_byte = uint32_t(uniform(int(last ? nxt.row0_byte : cur.row0_byte)));
-  const uint32_t nstride = uint32_t(uniform(int(last ? nxt.stride_byte : cur.stride_byte)));
-  uint32_t nlane_off = kOutOfRange;
-  {
-    const int col = ncs + 8 * n;
-    if (more && col < ncol_end) nlane_off = nrow0_byte + uint32_t(4 * h) * nstride + uint32_t(col) * 2u;
-  }
-  // this step's tile has landed (loads return in order, the last register stands for all) ...
-  asm volatile("" : "+v"(prev_off) : "v"(wcur[15][3]));
-  // ... store the previous step's results (offset kOutOfRange on the very first step: dropped) ...
-#pragma unroll
-  for (int v = 0; v < 16; ++v)
-    __builtin_amdgcn_raw_buffer_store_b128(
-        wprev[v], prev_res, prev_off + uint32_t(8 * (v >> 2) + (v & 3)) * prev_stride, 0, /*nt*/ 2);
-  // ... and request the next tile into the buffer just stored from
-  asm volatile("" : "+v"(nlane_off) : "v"(prev_off));
-#pragma unroll
-  for (int v = 0; v < 16; ++v)
-    wprev[v] = __builtin_amdgcn_raw_buffer_load_b128(
-        nres, nlane_off + uint32_t(8 * (v >> 2) + (v & 3)) * nstride, 0, /*nt*/ 2);
-
-  mfma2_compute<NKS>(cur.p_hi, cur.p_lo, q_hi, q_lo, wcur);
-
-  // Q operands of the next step (a finished wave re-reads its last block, which is harmless)
-  {
-    const int qcs = uniform(more ? ncs : cs);
-    const uint16_t* qApk = uniform((more && last) ? nxt.Apk : cur.Apk);
-    const int qncb = uniform((more && last) ? nxt.ncb : cur.ncb);
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) {
-      const LSW_GLOBAL u32x4* src = as_global(reinterpret_cast<const u32x4*>(
-          qApk + (((long long)term_e[ks] * gpr + term_g[ks]) * qncb + qcs / MT_STEP) * (8 * 2 * 32 * 8)) + n);
-#pragma unroll
-      for (int b = 0; b < 8; ++b) {
-        q_hi[ks][b] = src[(2 * b) * 32];
-        q_lo[ks][b] = src[(2 * b + 1) * 32];
-      }
-    }
-  }
-  prev_res = w_resource(cur.W, cur.wbytes);
-  prev_off = lane_off;
-  prev_stride = cur.stride_byte;
-  lane_off = nlane_off;
-  cs = ncs;
-  if (last) {                      // item boundary: rare, and the only branch of the step
-    if (!have_nxt) return false;
-    cur = nxt;
-    item += grid;
-    have_nxt = item + grid < p.n_items;
-    if (have_nxt) mfma_load_item<NKS>(p, item + grid, n, gpr, r, term_e, term_g, term_c, nxt);
-  }
-  return true;
-}
-
-template <int NKS>
-__global__ __launch_bounds__(64) void k_switch_mfma2(LaunchPlan p, Terms t, int r) {
-  static_assert(NKS <= 2, "all Q operands of a step must fit in registers");
-  __shared__ int32_t s_e[kMaxTerms];
-  __shared__ float s_coeff[kMaxTerms];
-  const int lane = threadIdx.x;
-  if (lane < kMaxTerms) {
-    s_e[lane] = t.e[lane];
-    s_coeff[lane] = t.coeff[lane];
-  }
-  __syncthreads();
-
-  const int n = lane & 31, h = lane >> 5;
-  const int gpr = r >> 3;
-  const int n_groups = t.n * gpr;
-  const int grid = gridDim.x;
-  int term_e[NKS], term_g[NKS];
-  float term_c[NKS];
-#pragma unroll
-  for (int ks = 0; ks < NKS; ++ks) {
-    const int G = 2 * ks + h;
-    const bool valid = G < n_groups;
-    const int c = valid ? G / gpr : 0;
-    term_e[ks] = s_e[c];
-    term_g[ks] = valid ? G - c * gpr : 0;
-    term_c[ks] = valid ? s_coeff[c] : 0.0f;
-  }
-
-  int item = p.xcd_remap ? xcd_contiguous_block(blockIdx.x, grid) : int(blockIdx.x);
-  if (item >= p.n_items) return;
-  MfmaItem<NKS> cur, nxt;
-  mfma_load_item<NKS>(p, item, n, gpr, r, term_e, term_g, term_c, cur);
-  bool have_nxt = item + grid < p.n_items;
-  if (have_nxt) mfma_load_item<NKS>(p, item + grid, n, gpr, r, term_e, term_g, term_c, nxt);
-  else nxt = cur;
-  int cs = cur.col0;
-  uint32_t lane_off = mfma_lane_offset<NKS>(cur, cs, n, h);
-  u32x4 wa[16], wb[16];
-  mfma_load_w<NKS>(cur, lane_off, wa);
-#pragma unroll
-  for (int v = 0; v < 16; ++v) wb[v] = u32x4{0u, 0u, 0u, 0u};
-  u32x4 q_hi[NKS][8], q_lo[NKS][8];
-#pragma unroll
-  for (int ks = 0; ks < NKS; ++ks)
-    mfma_load_q<NKS>(cur, cs, n, gpr, term_e[ks], term_g[ks], q_hi[ks], q_lo[ks]);
-  __amdgpu_buffer_rsrc_t prev_res = w_resource(cur.W, cur.wbytes);
-  uint32_t prev_off = kOutOfRange, prev_stride = 0;
-
-  bool a_is_cur = true;
-  while (true) {
-    if (!mfma2_step<NKS>(p, grid, n, h, gpr, r, term_e, term_g, term_c, cur, nxt, have_nxt, item, cs, lane_off,
-                         prev_res, prev_off, prev_stride, wa, wb, q_hi, q_lo)) { a_is_cur = true; break; }
-    if (!mfma2_step<NKS>(p, grid, n, h, gpr, r, term_e, term_g, term_c, cur, nxt, have_nxt, item, cs, lane_off,
-                         prev_res, prev_off, prev_stride, wb, wa, q_hi, q_lo)) { a_is_cur = false; break; }
-  }
-  // the last tile is still in registers
-  if (a_is_cur) {
-#pragma unroll
-    for (int v = 0; v < 16; ++v)
-      __builtin_amdgcn_raw_buffer_store_b128(
-          wa[v], prev_res, prev_off + uint32_t(8 * (v >> 2) + (v & 3)) * prev_stride, 0, /*nt*/ 2);
-  } else {
-#pragma unroll
-    for (int v = 0; v < 16; ++v)
-      __builtin_amdgcn_raw_buffer_store_b128(
-          wb[v], prev_res, prev_off + uint32_t(8 * (v >> 2) + (v & 3)) * prev_stride, 0, /*nt*/ 2);
-  }
-}
-
-// ---------------------------------------------------------------------------
-// Matrix-core switch with the column-side operand shared through LDS (fused rank <= 64).
-//
-// A workgroup is 4 waves; a work item is 128 rows x tile_cols columns, wave w owning rows
-// 32w..32w+31.  The four waves walk the same column steps, so the packed-A operand of a step
-// (Q: 256 columns x K, 16*NKS KB) is the same for all of them: each wave fetches a quarter of
-// it from L2 one step ahead, parks it in registers, and drops it into the LDS buffer of the next
-// step at the end of the current one; one workgroup barrier per step (LDS-only fence, so global
-// loads stay in flight across it).  Per step a wave then issues 16 W loads, 16 W stores and
-// 4*NKS operand loads instead of 16*NKS, and the matrix instructions read Q from LDS pair by
-// pair.  Everything else (tile mapping, buffer addressing, late stores, pair pipeline) is as above.
-// ---------------------------------------------------------------------------
-constexpr int WG_WAVES = 4;
-constexpr int WG_ROWS = kMfmaWgTileRows;
-extern __shared__ u32x4 wg_lds[];     // [2 buffers][NKS][8 blocks][hi,lo][64 lanes]
-
-template <int NKS>
 __device__ __forceinline__ void wg_compute(const u32x4 (&p_hi)[NKS], const u32x4 (&p_lo)[NKS],
                                            const u32x4* qbuf /* LDS: slot 0 of this step's buffer + lane */,
                                            u32x4 (&wcur)[16]) {
+  // Pair q = blocks 2q and 2q+1 = low and high bf16 half of word q of each row.  The work is a
+  // chain of 4*NKS chunks (pair q, k-step ks), each 6 matrix instructions on the pair's two
+  // accumulators.  While the matrix pipe runs a chunk, LDS delivers the operands of the next chunk
+  // and the vector ALU widens pair q+1 and rounds pair q-1; the scheduling directives pin that
+  // interleaving, which the compiler would otherwise undo.
   f32x16 a0[4], a1[4];
-  u32x4 qr[2][NKS][2][2];      // [register set][k-step][block of the pair][high, low]
-#pragma unroll
-  for (int ks = 0; ks < NKS; ++ks)
+  u32x4 qr[2][2][2];           // [chunk parity][block of the pair][high, low]
+  auto fetch = [&](int chunk) {
+    const int q = chunk / NKS, ks = chunk % NKS;
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int hl = 0; hl < 2; ++hl) qr[0][ks][j][hl] = qbuf[((ks * 8 + j) * 2 + hl) * 64];
+      for (int hl = 0; hl < 2; ++hl) qr[chunk & 1][j][hl] = qbuf[((ks * 8 + 2 * q + j) * 2 + hl) * 64];
+  };
+  fetch(0);
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
     a0[0][v] = bf16_lo(wcur[v][0]);
@@ -701,50 +351,44 @@ __device__ __forceinline__ void wg_compute(const u32x4 (&p_hi)[NKS], const u32x4
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
-    if (q + 1 < 4) {
-#pragma unroll
-      for (int ks = 0; ks < NKS; ++ks)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-          for (int hl = 0; hl < 2; ++hl)
-            qr[(q + 1) & 1][ks][j][hl] = qbuf[((ks * 8 + 2 * (q + 1) + j) * 2 + hl) * 64];
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        a0[q + 1][v] = bf16_lo(wcur[v][q + 1]);
-        a1[q + 1][v] = bf16_hi(wcur[v][q + 1]);
-      }
-    }
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
+      const int chunk = q * NKS + ks;
+      if (chunk + 1 < 4 * NKS) fetch(chunk + 1);
+      // vector work spread over the pair's k-steps: widen pair q+1, round pair q-1
+      constexpr int kRowsPer = (16 + NKS - 1) / NKS;
+#pragma unroll
+      for (int v = ks * kRowsPer; v < (ks + 1) * kRowsPer && v < 16; ++v) {
+        if (q + 1 < 4) {
+          a0[q + 1][v] = bf16_lo(wcur[v][q + 1]);
+          a1[q + 1][v] = bf16_hi(wcur[v][q + 1]);
+        }
+        if (q > 0) {
+          uint32_t w = pack_bf16(a0[q - 1][v], a1[q - 1][v]);   // the one rounding
+          asm volatile("" : "+v"(w));
+          wcur[v][q - 1] = w;
+        }
+      }
       const bf16x8 ph = __builtin_bit_cast(bf16x8, p_hi[ks]);
       const bf16x8 pl = __builtin_bit_cast(bf16x8, p_lo[ks]);
-      const bf16x8 h0 = __builtin_bit_cast(bf16x8, qr[q & 1][ks][0][0]);
-      const bf16x8 l0 = __builtin_bit_cast(bf16x8, qr[q & 1][ks][0][1]);
-      const bf16x8 h1 = __builtin_bit_cast(bf16x8, qr[q & 1][ks][1][0]);
-      const bf16x8 l1 = __builtin_bit_cast(bf16x8, qr[q & 1][ks][1][1]);
+      const bf16x8 h0 = __builtin_bit_cast(bf16x8, qr[chunk & 1][0][0]);
+      const bf16x8 l0 = __builtin_bit_cast(bf16x8, qr[chunk & 1][0][1]);
+      const bf16x8 h1 = __builtin_bit_cast(bf16x8, qr[chunk & 1][1][0]);
+      const bf16x8 l1 = __builtin_bit_cast(bf16x8, qr[chunk & 1][1][1]);
       a0[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl, h0, a0[q], 0, 0, 0);
       a1[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl, h1, a1[q], 0, 0, 0);
       a0[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, l0, a0[q], 0, 0, 0);
       a1[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, l1, a1[q], 0, 0, 0);
       a0[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, h0, a0[q], 0, 0, 0);
       a1[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, h1, a1[q], 0, 0, 0);
-    }
-    if (q > 0) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);          // the next chunk's 4 LDS reads first
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        uint32_t w = pack_bf16(a0[q - 1][v], a1[q - 1][v]);   // the one rounding
-        asm volatile("" : "+v"(w));
-        wcur[v][q - 1] = w;
+      for (int i = 0; i < 6; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        // one matrix instruction
+        __builtin_amdgcn_sched_group_barrier(0x002, (3 * kRowsPer + 5) / 6, 0);   // a few vector instructions
       }
+      __builtin_amdgcn_sched_barrier(0);
     }
-    __builtin_amdgcn_sched_group_barrier(0x100, 4 * NKS, 0);                 // LDS reads of the next pair first
-#pragma unroll
-    for (int i = 0; i < 6 * NKS; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                     // one matrix instruction
-      __builtin_amdgcn_sched_group_barrier(0x002, (48 + 6 * NKS - 1) / (6 * NKS), 0);  // a few vector instructions
-    }
-    __builtin_amdgcn_sched_barrier(0);
   }
 #pragma unroll
   for (int v = 0; v < 16; ++v) wcur[v][3] = pack_bf16(a0[3][v], a1[3][v]);
@@ -843,7 +487,7 @@ __device__ __forceinline__ bool wg_step(const LaunchPlan& p, int grid, int n, in
 }
 
 template <int NKS>
-__global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma_wg(LaunchPlan p, Terms t, int r) {
+__global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma(LaunchPlan p, Terms t, int r) {
   __shared__ int32_t s_e[kMaxTerms];
   __shared__ float s_coeff[kMaxTerms];
   const int lane = threadIdx.x & 63;
@@ -910,19 +554,19 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma_wg(LaunchPlan p, 
 
 template <int NKS>
 static hipError_t launch_wg(const LaunchPlan& p, const Terms& t, int r, int grid, hipStream_t s) {
-  const size_t lds = size_t(2) * NKS * 8 * 2 * 64 * sizeof(u32x4);
+  const size_t lds = size_t(2) * NKS * 8 * 2 * 64 * sizeof(u32x4);     // 32 KB per k-step
   static bool configured = false;
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_switch_mfma_wg<NKS>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_switch_mfma<NKS>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
     if (e != hipSuccess) return e;
     configured = true;
   }
-  hipLaunchKernelGGL(k_switch_mfma_wg<NKS>, dim3(grid), dim3(64 * WG_WAVES), lds, s, p, t, r);
+  hipLaunchKernelGGL(k_switch_mfma<NKS>, dim3(grid), dim3(64 * WG_WAVES), lds, s, p, t, r);
   return hipGetLastError();
 }
 
-hipError_t launch_switch_mfma_wg(const LaunchPlan& p, const Terms& t, int r, int grid, hipStream_t s) {
+hipError_t launch_switch_mfma(const LaunchPlan& p, const Terms& t, int r, int grid, hipStream_t s) {
   const int n_groups = t.n * (r / 8);
   switch ((n_groups + 1) / 2) {
     case 1: return launch_wg<1>(p, t, r, grid, s);
@@ -931,19 +575,6 @@ hipError_t launch_switch_mfma_wg(const LaunchPlan& p, const Terms& t, int r, int
     case 4: return launch_wg<4>(p, t, r, grid, s);
     default: return hipErrorInvalidValue;
   }
-}
-
-hipError_t launch_switch_mfma(const LaunchPlan& p, const Terms& t, int r, int grid, hipStream_t s) {
-  const int n_groups = t.n * (r / 8);
-  const int nks = (n_groups + 1) / 2;
-  switch (nks) {
-    case 1: hipLaunchKernelGGL(k_switch_mfma2<1>, dim3(grid), dim3(64), 0, s, p, t, r); break;
-    case 2: hipLaunchKernelGGL(k_switch_mfma2<2>, dim3(grid), dim3(64), 0, s, p, t, r); break;
-    case 3: hipLaunchKernelGGL(k_switch_mfma<3>, dim3(grid), dim3(64), 0, s, p, t, r); break;
-    case 4: hipLaunchKernelGGL(k_switch_mfma<4>, dim3(grid), dim3(64), 0, s, p, t, r); break;
-    default: return hipErrorInvalidValue;
-  }
-  return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------

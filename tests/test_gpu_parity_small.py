@@ -14,7 +14,7 @@ from tests.golden_cases import load_rne_cases
 from tests.gpu_harness import DeviceStack, bits_to_device, check_step, device_to_bits, merge_reports
 
 pytestmark = pytest.mark.gpu
-KERNELS = [L.KERNEL_VALU, L.KERNEL_MFMA, L.KERNEL_MFMA_WG]
+KERNELS = [L.KERNEL_VALU, L.KERNEL_MFMA]
 
 
 def _route_stream(wl, steps):

@@ -139,6 +139,19 @@ def main():
     achieved = (sum(launch_bytes) / len(launch_bytes)) / (avg_ms * 1e-3) / 1e9
     ms_per_step = wall * 1e3 / args.steps
 
+    # yardstick: the same tensors, the same access pattern, no factor traffic and no matrix work
+    probe = {}
+    for wpc in (2, 4):
+        L.lsw_probe_inplace(ctx, wpc, stream)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(5):
+            L.lsw_probe_inplace(ctx, wpc, stream)
+        b.record()
+        b.synchronize()
+        probe[f"{wpc}_waves_per_cu_GBps"] = round(4.0 * wl.w_elements() / (a.elapsed_time(b) / 5 * 1e-3) / 1e9, 1)
+
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
@@ -164,6 +177,9 @@ def main():
         "achieved_hbm_GBps": round(achieved, 1),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic},
+        "inplace_probe": {**probe, "note": "lsw_probe_inplace on the same weights: in-place bf16 read+write only; "
+                                           "the practical ceiling of the switch's access pattern",
+                          "switch_over_best_probe": round(achieved / max(probe.values()), 4)},
     }
     torch.cuda.synchronize()
     L.lsw_destroy(ctx)

@@ -139,6 +139,17 @@ lsw_status lsw_build_terms(const int32_t* old_ids, const float* old_gates, int32
                            int32_t* terms_ids, float* terms_coeff, int32_t* n_terms);
 
 /*
+ * Bandwidth probe for callers that cannot judge a switch latency without a yardstick (benchmarks):
+ * one in-place pass over every registered W with the switch kernel's access pattern and no factor
+ * traffic or matrix work: each bf16 is widened, has +0.0f added, is rounded back and stored, so
+ * every finite value is unchanged (only a negative zero becomes +0).  `waves_per_cu` (1..16)
+ * single-wave workgroups per CU are launched.  Asynchronous on hip_stream.  What it sustains
+ * (4 bytes per weight / elapsed time) bounds what lsw_switch can reach on the same tensors.
+ * Errors: LSW_ERR_ARG, LSW_ERR_DEVICE.
+ */
+lsw_status lsw_probe_inplace(lsw_ctx* ctx, int32_t waves_per_cu, void* hip_stream);
+
+/*
  * What the context believes is merged in `layer` now (the pair Eq. 7 needs for the next
  * switch).  ids/gates HOST arrays with room for LSW_MAX_K entries; k receives the count.
  */

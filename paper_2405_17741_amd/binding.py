@@ -20,7 +20,7 @@ KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
 EXPORTS = (
     "lsw_create_adapters", "lsw_switch", "lsw_merged_gemv", "lsw_route", "lsw_build_terms",
     "lsw_get_state", "lsw_set_option", "lsw_query", "lsw_worklist_size", "lsw_worklist_item",
-    "lsw_destroy", "lsw_last_error",
+    "lsw_destroy", "lsw_last_error", "lsw_probe_inplace",
 )
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblsw.so")
@@ -65,6 +65,7 @@ def lib() -> C.CDLL:
         L.lsw_worklist_size.restype = C.c_int64
         L.lsw_worklist_item.argtypes = [_i32p, _i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int64,
                                         _i32p, _i32p, _i32p, _i32p, _i32p]
+        L.lsw_probe_inplace.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         L.lsw_destroy.argtypes = [C.c_void_p]
         L.lsw_destroy.restype = None
         L.lsw_last_error.restype = C.c_char_p
@@ -176,6 +177,10 @@ def lsw_worklist_item(out, inn, tile_rows: int, tile_cols: int, item: int):
     v = [C.c_int32(0) for _ in range(5)]
     _check(lib().lsw_worklist_item(op, ip, n, tile_rows, tile_cols, item, *[C.byref(x) for x in v]))
     return tuple(x.value for x in v)   # lin, row0, n_rows, col0, n_cols
+
+
+def lsw_probe_inplace(ctx: int, waves_per_cu: int, stream: int = 0) -> None:
+    _check(lib().lsw_probe_inplace(ctx, waves_per_cu, C.c_void_p(stream)))
 
 
 def lsw_destroy(ctx: int) -> None:

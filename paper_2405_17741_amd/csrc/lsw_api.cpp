@@ -322,7 +322,7 @@ static lsw_status get_plan(lsw_ctx* c, int kernel, int tc, const std::vector<int
   PlanKey key{kernel, tc, layers_sorted};
   auto it = c->plans.find(key);
   if (it != c->plans.end()) { *out = &it->second; return LSW_OK; }
-  const int32_t tr = kernel == 2 ? kMfmaTileRows : kValuTileRows;
+  const int32_t tr = kernel == 3 ? 32 : kernel == 2 ? kMfmaTileRows : kValuTileRows;   // 3 = bandwidth probe
   std::vector<int32_t> sel, first(1, 0);
   int64_t total = 0;
   for (size_t p = 0; p < c->lin.size(); ++p) {
@@ -419,6 +419,21 @@ extern "C" lsw_status lsw_switch(lsw_ctx* c, const int32_t* layers, int32_t n_la
     s.k = k_new;
     for (int32_t a = 0; a < k_new; ++a) { s.ids[a] = new_ids[a]; s.gates[a] = new_gates[a]; }
   }
+  return LSW_OK;
+}
+
+// ---------------------------------------------------------------------------
+// bandwidth probe over the registered weights
+// ---------------------------------------------------------------------------
+extern "C" lsw_status lsw_probe_inplace(lsw_ctx* c, int32_t waves_per_cu, void* hip_stream) {
+  if (!c) return fail(LSW_ERR_ARG, "ctx is null");
+  if (waves_per_cu < 1 || waves_per_cu > 16) return fail(LSW_ERR_ARG, "waves_per_cu=%d outside 1..16", waves_per_cu);
+  DevicePlan* dp = nullptr;
+  lsw_status st = get_plan(c, 3, c->opt_tile_cols, std::vector<int32_t>(), &dp);
+  if (st != LSW_OK) return st;
+  LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, c->opt_tile_cols, c->opt_xcd};
+  hipError_t e = launch_probe_inplace(lp, c->n_cu * waves_per_cu, static_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "probe launch failed: %s", hipGetErrorString(e));
   return LSW_OK;
 }
 

@@ -81,6 +81,7 @@ struct LaunchPlan {             // device pointers + counts for one launch
 // Kernel launchers (lsw_kernels.hip).  All return the hipError of the launch.
 hipError_t launch_switch_valu(const LaunchPlan& p, const Terms& t, int r, int grid, hipStream_t s);
 hipError_t launch_switch_mfma(const LaunchPlan& p, const Terms& t, int r, int grid, hipStream_t s);
+hipError_t launch_probe_inplace(const LaunchPlan& p, int grid, hipStream_t s);
 hipError_t launch_pack_A(const float* A, uint16_t* Apk, int E, int r, int in, hipStream_t s);
 hipError_t launch_gemv(const uint16_t* W, const uint16_t* x, float* y, int out, int in, hipStream_t s);
 

@@ -247,3 +247,19 @@ def test_merged_gemv_against_oracle():
         err = np.abs(y.cpu().numpy().astype(np.float64) - want)
         assert (err <= 1e-5 * absum + 1e-30).all(), (out, inn, float((err / absum).max()))
         ds.close()
+
+
+def test_probe_inplace_leaves_weights_unchanged():
+    wl = I.Workload("mini", 2, 64, 136, 32, 4, 8, 2, 4, 0.02, 1 / 8, 0.01, 515)
+    host = I.host_stack(wl)
+    ds = DeviceStack.from_host(host, wl.linear_shapes(), wl.experts, wl.rank)
+    for wpc in (1, 4):
+        L.lsw_probe_inplace(ds.ctx, wpc, torch.cuda.current_stream().cuda_stream)
+    for p_, (W, _, _) in enumerate(host):
+        got = ds.rows(p_)
+        neg_zero = W == 0x8000
+        assert (got[~neg_zero] == W[~neg_zero]).all()
+        assert (got[neg_zero] == 0).all()
+    with pytest.raises(L.LswError):
+        L.lsw_probe_inplace(ds.ctx, 0)
+    ds.close()

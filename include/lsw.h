@@ -162,7 +162,9 @@ enum {
   LSW_OPT_STRICT_STATE = 2,  /* 1: lsw_switch rejects an `old` that differs from the tracked state of a layer */
   LSW_OPT_GRID = 3,          /* workgroups per launch; 0 = automatic (one matrix-core workgroup per CU) */
   LSW_OPT_TILE_COLS = 4,     /* matrix-core kernel: columns per work item, a multiple of 256 (tuning knob) */
-  LSW_OPT_XCD_REMAP = 5      /* 1 (default): each XCD takes a contiguous share of every round of items */
+  LSW_OPT_XCD_REMAP = 5,     /* 1 (default): each XCD takes a contiguous share of every round of items */
+  LSW_OPT_STAGGER = 6        /* fused ranks above 64: workgroup i of an XCD starts (i mod 8) * value * 64 cycles late,
+                                so that the workgroups do not all request their W tiles at the same instant (tuning knob) */
 };
 enum {
   LSW_Q_N_LINEARS = 1, LSW_Q_N_LAYERS = 2,

@@ -18,6 +18,7 @@ def build_library(verbose: bool = False) -> str:
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 VALU forms
         "-mllvm", "-amdgpu-mfma-vgpr-form",      # matrix-core accumulators in VGPRs: the kernels touch them with VALU ops
         "-Wno-unused-command-line-argument",
+        "-Wno-inline-asm",                       # the LDS-DMA helper names M0, a register the compiler reserves, as clobbered
         "-I", os.path.join(ROOT, "include"), "-I", os.path.join(PKG, "csrc"),
         "-x", "hip", *SOURCES, "-o", LIB,
     ]

@@ -76,7 +76,7 @@ struct lsw_ctx {
   uint16_t* d_apk = nullptr;                 // packed A of all linears (r % 8 == 0 only)
   int64_t owned_bytes = 0;
   std::map<PlanKey, DevicePlan> plans;
-  int opt_kernel = 0, opt_strict = 0, opt_grid = 0, opt_tile_cols = kMfmaTileCols, opt_xcd = 1;
+  int opt_kernel = 0, opt_strict = 0, opt_grid = 0, opt_tile_cols = kMfmaTileCols, opt_tile_cols_bigk = kMfmaBigkTileCols, opt_xcd = 1, opt_stagger = 0;
   int last_kernel = 0, last_items = 0, last_grid = 0;
 };
 
@@ -387,27 +387,30 @@ extern "C" lsw_status lsw_switch(lsw_ctx* c, const int32_t* layers, int32_t n_la
     }
   }
 
-  // the matrix-core kernel keeps the fused rank (terms x r) in registers: at most 64
-  const bool mfma_fits = (c->r % 8 == 0) && (t.n * (c->r / 8) <= 8);
+  // the matrix-core kernels keep the fused rank (terms x r) in registers: up to 64 in the streaming
+  // kernel, up to 256 in the chunked one
+  const int n_groups = (c->r % 8 == 0) ? t.n * (c->r / 8) : 0;
+  const bool mfma_fits = (c->r % 8 == 0) && n_groups <= 32;
+  const bool bigk = n_groups > 8;
   int kernel = c->opt_kernel;
   if (kernel == 0) kernel = mfma_fits ? 2 : 1;
   if (kernel >= 2 && !mfma_fits)
-    return fail(LSW_ERR_ARG, "matrix-core kernel needs r %% 8 == 0 and a fused rank <= 64 (r=%d, terms=%d)", c->r, t.n);
+    return fail(LSW_ERR_ARG, "matrix-core kernel needs r %% 8 == 0 and a fused rank <= 256 (r=%d, terms=%d)", c->r, t.n);
 
   c->last_kernel = 0;
   c->last_items = 0;
   c->last_grid = 0;
   if (t.n > 0) {
     DevicePlan* dp = nullptr;
-    const int tc = kernel >= 2 ? c->opt_tile_cols : kValuTileCols;
+    const int tc = kernel >= 2 ? (bigk ? c->opt_tile_cols_bigk : c->opt_tile_cols) : kValuTileCols;
     st = get_plan(c, kernel, tc, sel_layers, &dp);
     if (st != LSW_OK) return st;
-    LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, tc, c->opt_xcd};
+    LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, tc, c->opt_xcd, c->opt_stagger};
     int grid = c->opt_grid;
     if (grid <= 0) grid = (kernel == 2) ? c->n_cu : c->n_cu * 2;   // matrix-core: one 4-wave workgroup per CU
     grid = std::max(8, (grid / 8) * 8);     // a multiple of the 8 XCDs (the kernels' block remap assumes it)
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    hipError_t e = (kernel == 2) ? launch_switch_mfma(lp, t, c->r, grid, s)
+    hipError_t e = (kernel == 2) ? (bigk ? launch_switch_mfma_bigk(lp, t, c->r, grid, s) : launch_switch_mfma(lp, t, c->r, grid, s))
                                  : launch_switch_valu(lp, t, c->r, grid, s);
     if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "switch launch failed: %s", hipGetErrorString(e));
     c->last_kernel = kernel;
@@ -431,7 +434,7 @@ extern "C" lsw_status lsw_probe_inplace(lsw_ctx* c, int32_t waves_per_cu, void* 
   DevicePlan* dp = nullptr;
   lsw_status st = get_plan(c, 3, c->opt_tile_cols, std::vector<int32_t>(), &dp);
   if (st != LSW_OK) return st;
-  LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, c->opt_tile_cols, c->opt_xcd};
+  LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, c->opt_tile_cols, c->opt_xcd, 0};
   hipError_t e = launch_probe_inplace(lp, c->n_cu * waves_per_cu, static_cast<hipStream_t>(hip_stream));
   if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "probe launch failed: %s", hipGetErrorString(e));
   return LSW_OK;
@@ -483,9 +486,14 @@ extern "C" lsw_status lsw_set_option(lsw_ctx* c, int32_t option, int64_t value) 
       if (value < kApkBlockCols || value > (1 << 20) || value % kApkBlockCols != 0)
         return fail(LSW_ERR_ARG, "tile columns must be a multiple of %d", kApkBlockCols);
       c->opt_tile_cols = int(value);
+      c->opt_tile_cols_bigk = int(value);
       return LSW_OK;
     case LSW_OPT_XCD_REMAP:
       c->opt_xcd = value != 0;
+      return LSW_OK;
+    case LSW_OPT_STAGGER:
+      if (value < 0 || value > 4096) return fail(LSW_ERR_ARG, "stagger option out of range");
+      c->opt_stagger = int(value);
       return LSW_OK;
     default:
       return fail(LSW_ERR_ARG, "unknown option %d", option);

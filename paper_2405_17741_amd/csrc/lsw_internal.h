@@ -66,6 +66,7 @@ LSW_HD inline void decode_item(int32_t local, int32_t in, int32_t tile_rows, int
 // Tile shapes of the two switch kernels (rows x columns of one work item).
 constexpr int kValuTileRows = 64,  kValuTileCols = 128;
 constexpr int kMfmaTileRows = 128, kMfmaTileCols = 1024;   // 4 waves x 32 rows; default item width (LSW_OPT_TILE_COLS overrides)
+constexpr int kMfmaBigkTileCols = 4096;                     // default item width of the chunked (fused rank > 64) matrix-core kernel
 constexpr int kApkBlockCols = 256;   // column block of the packed A layout = columns per matrix-core step
 
 struct LaunchPlan {             // device pointers + counts for one launch
@@ -76,11 +77,13 @@ struct LaunchPlan {             // device pointers + counts for one launch
   int32_t n_items;
   int32_t tile_cols;            // columns of one work item (matrix-core kernel: a multiple of kApkBlockCols)
   int32_t xcd_remap;            // 1: each XCD takes a contiguous eighth of every grid-wide round of items
+  int32_t stagger;              // chunked matrix-core kernel: start-up delay unit (in 64-cycle sleeps) between workgroup phases
 };
 
 // Kernel launchers (lsw_kernels.hip).  All return the hipError of the launch.
 hipError_t launch_switch_valu(const LaunchPlan& p, const Terms& t, int r, int grid, hipStream_t s);
 hipError_t launch_switch_mfma(const LaunchPlan& p, const Terms& t, int r, int grid, hipStream_t s);
+hipError_t launch_switch_mfma_bigk(const LaunchPlan& p, const Terms& t, int r, int grid, hipStream_t s);
 hipError_t launch_probe_inplace(const LaunchPlan& p, int grid, hipStream_t s);
 hipError_t launch_pack_A(const float* A, uint16_t* Apk, int E, int r, int in, hipStream_t s);
 hipError_t launch_gemv(const uint16_t* W, const uint16_t* x, float* y, int out, int in, hipStream_t s);

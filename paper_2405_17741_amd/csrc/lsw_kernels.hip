@@ -50,6 +50,20 @@ __device__ __forceinline__ const LSW_GLOBAL T* as_global(const T* ptr) {
   return (const LSW_GLOBAL T*)ptr;
 }
 
+// One 16-byte-per-lane copy from global memory straight into LDS (no registers): lane l's 16 bytes
+// land at lds_base + 16*l.  Written as inline assembly on purpose: the compiler's wait-count pass
+// treats its own LDS-DMA builtin as "may touch both memory kinds" and, while one is in flight, turns
+// every later wait on an LDS read or a global load into a full drain, which serialises the LDS
+// prefetch of the matrix-core loops.  Hidden from that pass, the copy only makes the compiler's own
+// vector-memory waits more conservative (the counter is in order); its completion is waited for by
+// hand (s_waitcnt vmcnt) before the workgroup barrier that publishes the buffer.  M0 is written here
+// and has no other user in these kernels.
+__device__ __forceinline__ void lds_dma16(const void* src, const void* lds_base) {
+  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(
+      uint32_t(uintptr_t((const __attribute__((address_space(3))) void*)lds_base)));
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_addr) : "memory", "m0");
+}
+
 // Values that are the same in every lane, told to the compiler so they live in scalar registers.
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 template <typename T>
@@ -573,6 +587,253 @@ hipError_t launch_switch_mfma(const LaunchPlan& p, const Terms& t, int r, int gr
     case 2: return launch_wg<2>(p, t, r, grid, s);
     case 3: return launch_wg<3>(p, t, r, grid, s);
     case 4: return launch_wg<4>(p, t, r, grid, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Fused switch on the matrix cores for large fused ranks (64 < K = terms * r <= 256).
+//
+// Same launch shape, tile mapping, operand split and W addressing as k_switch_mfma.  What differs:
+// the Q operand of one 256-column step no longer fits LDS (K * 256 columns * 4 bytes = 256 KB at
+// K = 256), so the fused rank is cut into chunks of 4 k-steps (64 ranks, 64 KB of Q) that are
+// double-buffered in LDS, and the fp32 accumulators of the whole 32 x 256 tile stay in registers
+// across the chunks of a step.  P (coeff * B, split) for the whole fused rank stays in registers for
+// the item.  Per chunk: start the LDS copy of the next chunk's Q quarter, run the chunk's
+// 4 x 8 x 3 matrix instructions, wait for the copy, workgroup barrier.  The next W tile is requested
+// right after the current one has been widened into the accumulators (its registers are free then)
+// and has every chunk but the first to arrive; the finished tile is stored after the last chunk and
+// has the whole next step to drain.  At K = 256 the three-pass product needs about as long on the
+// matrix cores as the W traffic needs on HBM, so this kernel is bound by the matrix cores.
+// ---------------------------------------------------------------------------
+constexpr int BK_KC = 4;                       // k-steps per LDS chunk
+constexpr int BK_MAX_GROUPS = 32;              // 8-rank groups of the fused rank: K <= 256
+
+// this wave's quarter of chunk `ch` of the Q operand of column step `cs`
+__device__ __forceinline__ void bk_fetch_q(const uint16_t* Apk, int ncb, int cs, int ch, int n, int h, int gpr, int wave,
+                                           const int32_t* s_eg, u32x4* buf) {
+#pragma unroll
+  for (int kk = 0; kk < BK_KC; ++kk) {
+    const int eg = s_eg[2 * (ch * BK_KC + kk) + h];          // expert * gpr + group of this lane's half
+    const u32x4* src = reinterpret_cast<const u32x4*>(
+        Apk + ((long long)eg * ncb + cs / MT_STEP) * (8 * 2 * 32 * 8)) + n;
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int hl = 0; hl < 2; ++hl)
+        lds_dma16(src + (2 * (2 * wave + j) + hl) * 32, buf + ((kk * 8 + 2 * wave + j) * 2 + hl) * 64);
+  }
+}
+
+// one chunk: acc += P[chunk] * Q[chunk] for the 8 blocks of the step, three passes
+__device__ __forceinline__ void bk_compute(const u32x4* p_hi, const u32x4* p_lo /* the chunk's BK_KC entries */,
+                                           const u32x4* qbuf /* LDS: slot 0 of the chunk's buffer + lane */,
+                                           f32x16 (&a0)[4], f32x16 (&a1)[4]) {
+  u32x4 qr[2][2][2];           // [parity][block of the pair][high, low]
+  auto fetch = [&](int idx) {
+    const int q = idx / BK_KC, kk = idx % BK_KC;
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int hl = 0; hl < 2; ++hl) qr[idx & 1][j][hl] = qbuf[((kk * 8 + 2 * q + j) * 2 + hl) * 64];
+  };
+  fetch(0);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+#pragma unroll
+    for (int kk = 0; kk < BK_KC; ++kk) {
+      const int idx = q * BK_KC + kk;
+      if (idx + 1 < 4 * BK_KC) fetch(idx + 1);
+      const bf16x8 ph = __builtin_bit_cast(bf16x8, p_hi[kk]);
+      const bf16x8 pl = __builtin_bit_cast(bf16x8, p_lo[kk]);
+      const bf16x8 h0 = __builtin_bit_cast(bf16x8, qr[idx & 1][0][0]);
+      const bf16x8 l0 = __builtin_bit_cast(bf16x8, qr[idx & 1][0][1]);
+      const bf16x8 h1 = __builtin_bit_cast(bf16x8, qr[idx & 1][1][0]);
+      const bf16x8 l1 = __builtin_bit_cast(bf16x8, qr[idx & 1][1][1]);
+      a0[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl, h0, a0[q], 0, 0, 0);
+      a1[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl, h1, a1[q], 0, 0, 0);
+      a0[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, l0, a0[q], 0, 0, 0);
+      a1[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, l1, a1[q], 0, 0, 0);
+      a0[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, h0, a0[q], 0, 0, 0);
+      a1[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, h1, a1[q], 0, 0, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);          // the next 4 LDS reads first
+      __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);          // then the six matrix instructions
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+}
+
+// the wave's LDS copies (and everything older) have landed; up to `newer` younger requests may still fly
+template <int NEWER>
+__device__ __forceinline__ void bk_drain_and_barrier() {
+  static_assert(NEWER == 0 || NEWER == 16, "encoded below");
+  // No fence builtins here: a workgroup-scope release would make the compiler wait for EVERY outstanding
+  // vector-memory request, the younger W loads and stores included.  The LDS copies count in the wave's
+  // vector-memory counter in issue order, so waiting until only NEWER requests remain proves they have
+  // landed; LDS itself needs no cache maintenance.  The empty asm statements keep the compiler from moving
+  // LDS reads across the barrier.
+  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_s_waitcnt(NEWER == 0 ? 0x0F70 : 0x4F70);      // vmcnt(0) or vmcnt(16); expcnt, lgkmcnt untouched
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+template <int NCH>
+__global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t, int r) {
+  constexpr int NKS = BK_KC * NCH;
+  constexpr int kBufSlots = BK_KC * 8 * 2 * 64;
+  static_assert(NCH >= 2 && 2 * NKS <= BK_MAX_GROUPS, "chunks per step");
+  __shared__ int32_t s_te[kMaxTerms];
+  __shared__ float s_tc[kMaxTerms];
+  __shared__ int32_t s_e[BK_MAX_GROUPS], s_g[BK_MAX_GROUPS], s_eg[BK_MAX_GROUPS];
+  __shared__ float s_c[BK_MAX_GROUPS];
+  const int lane = threadIdx.x & 63;
+  const int wave = uniform(int(threadIdx.x >> 6));
+  const int n = lane & 31, h = lane >> 5;
+  const int gpr = r >> 3;
+  const int n_groups = t.n * gpr;
+  if (threadIdx.x < kMaxTerms) {
+    s_te[threadIdx.x] = t.e[threadIdx.x];
+    s_tc[threadIdx.x] = t.coeff[threadIdx.x];
+  }
+  __syncthreads();
+  if (threadIdx.x < BK_MAX_GROUPS) {           // group G of the fused rank: (expert, 8-rank group, coefficient); padding gets 0
+    const int G = threadIdx.x;
+    const bool valid = G < n_groups;
+    const int c = valid ? G / gpr : 0;
+    const int g = valid ? G - c * gpr : 0;
+    s_e[G] = s_te[c];
+    s_g[G] = g;
+    s_eg[G] = s_te[c] * gpr + g;
+    s_c[G] = valid ? s_tc[c] : 0.0f;
+  }
+  __syncthreads();
+
+  const int grid = gridDim.x;
+  const int first_item = p.xcd_remap ? xcd_contiguous_block(blockIdx.x, grid) : int(blockIdx.x);
+  // Start-up phases.  Every workgroup runs the same loop at the same pace, so without this all of them
+  // request their W tiles in the same instant and the burst, not the bandwidth, sets the waiting time.
+  for (int d = uniform(int((blockIdx.x >> 3) & 7) * p.stagger); d > 0; --d) __builtin_amdgcn_s_sleep(1);
+  int buf = 0;
+  for (int item = first_item; item < p.n_items; item += grid) {       // uniform over the workgroup
+    const int seg = uniform(find_segment(p.first, p.n_sel, item));
+    const LinDesc* Lp = p.lin + uniform(p.sel[seg]);
+    const uint16_t* W = uniform(Lp->W);
+    const float* B = uniform(Lp->B);
+    const uint16_t* Apk = uniform(Lp->Apk);
+    const int out = uniform(Lp->out), in = uniform(Lp->in);
+    int row0, col0;
+    decode_item(uniform(item - p.first[seg]), in, kMfmaTileRows, p.tile_cols, &row0, &col0);
+    row0 += 32 * wave;
+    const int col_end = min(in, col0 + p.tile_cols);
+    const int ncb = ceil_div(in, MT_STEP);
+    const int wbytes = out * in * 2;
+    const uint32_t stride = uint32_t(in) * 2u;
+    const uint32_t row0_byte = uint32_t(row0) * stride;
+
+    // P = coeff * B for this lane's row and its half of every k-step, split into bf16 high + low
+    u32x4 p_hi[NKS], p_lo[NKS];
+    {
+      const int prow = min(row0 + n, out - 1);
+      const bool prow_ok = row0 + n < out;       // rows past the end: zero coefficient (their W offsets lie outside the buffer)
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) {
+        const int G = 2 * ks + h;
+        const LSW_GLOBAL f32x4* src = as_global(reinterpret_cast<const f32x4*>(
+            B + ((long long)s_e[G] * out + prow) * r + 8 * s_g[G]));
+        const f32x4 b0 = src[0];
+        const f32x4 b1 = src[1];
+        const float c = prow_ok ? s_c[G] : 0.0f;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          uint32_t hi, lo;
+          split2(c * b0[2 * q], c * b0[2 * q + 1], &hi, &lo);
+          p_hi[ks][q] = hi;
+          p_lo[ks][q] = lo;
+          split2(c * b1[2 * q], c * b1[2 * q + 1], &hi, &lo);
+          p_hi[ks][2 + q] = hi;
+          p_lo[ks][2 + q] = lo;
+        }
+      }
+    }
+
+    auto lane_offset = [&](int cs) {
+      const int col = cs + 8 * n;
+      return col < col_end ? row0_byte + uint32_t(4 * h) * stride + uint32_t(col) * 2u : kOutOfRange;
+    };
+    const __amdgpu_buffer_rsrc_t res = w_resource(W, wbytes);
+    u32x4 wt[16];
+    uint32_t lane_off = lane_offset(col0);
+    bk_fetch_q(Apk, ncb, col0, 0, n, h, gpr, wave, s_eg, wg_lds + buf * kBufSlots);
+#pragma unroll
+    for (int v = 0; v < 16; ++v)
+      wt[v] = __builtin_amdgcn_raw_buffer_load_b128(res, lane_off + uint32_t(8 * (v >> 2) + (v & 3)) * stride, 0, /*nt*/ 2);
+    bk_drain_and_barrier<0>();
+
+    for (int cs = col0; cs < col_end; cs += MT_STEP) {
+      const bool more = uniform(int(cs + MT_STEP < col_end)) != 0;
+      f32x16 a0[4], a1[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          a0[q][v] = bf16_lo(wt[v][q]);
+          a1[q][v] = bf16_hi(wt[v][q]);
+        }
+      const uint32_t cur_off = lane_off;
+      lane_off = more ? lane_offset(cs + MT_STEP) : kOutOfRange;
+#pragma unroll
+      for (int ch = 0; ch < NCH; ++ch) {
+        // the next chunk's Q quarter into the idle buffer (after the last step: a harmless re-read)
+        const int fcs = uniform(ch + 1 < NCH ? cs : (more ? cs + MT_STEP : cs));
+        bk_fetch_q(Apk, ncb, fcs, (ch + 1) % NCH, n, h, gpr, wave, s_eg, wg_lds + (buf ^ 1) * kBufSlots);
+        if (ch == 0) {
+          __builtin_amdgcn_sched_barrier(0);                    // keep the W requests younger than the Q copy
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            wt[v] = __builtin_amdgcn_raw_buffer_load_b128(res, lane_off + uint32_t(8 * (v >> 2) + (v & 3)) * stride, 0, /*nt*/ 2);
+        }
+        bk_compute(p_hi + ch * BK_KC, p_lo + ch * BK_KC, wg_lds + buf * kBufSlots + lane, a0, a1);
+        if (ch == NCH - 1) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            u32x4 o;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) o[q] = pack_bf16(a0[q][v], a1[q][v]);      // the one rounding
+            __builtin_amdgcn_raw_buffer_store_b128(o, res, cur_off + uint32_t(8 * (v >> 2) + (v & 3)) * stride, 0, /*nt*/ 2);
+          }
+        }
+        if (ch == 0 || ch == NCH - 1) bk_drain_and_barrier<16>();   // 16 younger W loads / stores may still be in flight
+        else bk_drain_and_barrier<0>();
+        buf ^= 1;
+      }
+    }
+  }
+}
+
+template <int NCH>
+static hipError_t launch_bigk(const LaunchPlan& p, const Terms& t, int r, int grid, hipStream_t s) {
+  const size_t lds = size_t(2) * BK_KC * 8 * 2 * 64 * sizeof(u32x4);     // 2 x 64 KB
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_switch_mfma_bigk<NCH>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  hipLaunchKernelGGL(k_switch_mfma_bigk<NCH>, dim3(grid), dim3(256), lds, s, p, t, r);
+  return hipGetLastError();
+}
+
+hipError_t launch_switch_mfma_bigk(const LaunchPlan& p, const Terms& t, int r, int grid, hipStream_t s) {
+  const int n_groups = t.n * (r / 8);
+  switch ((n_groups + 2 * BK_KC - 1) / (2 * BK_KC)) {
+    case 2: return launch_bigk<2>(p, t, r, grid, s);
+    case 3: return launch_bigk<3>(p, t, r, grid, s);
+    case 4: return launch_bigk<4>(p, t, r, grid, s);
     default: return hipErrorInvalidValue;
   }
 }

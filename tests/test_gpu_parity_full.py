@@ -91,4 +91,5 @@ def test_7b_rank64_one_layer():
     wl = I.scaled(I.WORKLOADS["7b_r64"], 1)
     wl = I.Workload(**{**wl.__dict__, "steps": 3})
     reports, kernels = _run_sampled(wl, {1, 2, 3}, n_random_rows=13)
+    assert kernels == {L.KERNEL_MFMA}          # fused ranks 64..256: the chunked matrix-core kernel
     assert all(r["exact_frac"] > 0.999 for r in reports)

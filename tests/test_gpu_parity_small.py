@@ -98,6 +98,8 @@ SHAPES = [
     # out, in, E, r
     (37, 8, 5, 8), (100, 264, 5, 8), (64, 1048, 4, 16), (33, 2056, 3, 8), (130, 520, 6, 24), (1, 16, 2, 8),
     (96, 256, 8, 32), (65, 136, 3, 4), (40, 72, 4, 1), (70, 1032, 4, 3),
+    # fused ranks above 64: the chunked matrix-core kernel (2, 3 and 4 chunks per step), ragged rows and columns
+    (150, 776, 5, 64), (129, 264, 4, 32), (33, 4360, 4, 48), (260, 520, 6, 40),
 ]
 
 
@@ -113,6 +115,7 @@ def test_ragged_shapes_and_term_counts(shape, kernel):
     none = (np.zeros(0, np.int32), np.zeros(0, np.float32))
     seq = [none]
     kmax = min(E, 2 if r > 16 else 3)
+    kernels_used = set()
     for _ in range(6):
         k = int(rng.integers(1, kmax + 1))
         ids = rng.choice(E, k, replace=False).astype(np.int32)
@@ -123,16 +126,19 @@ def test_ragged_shapes_and_term_counts(shape, kernel):
     reports = []
     for old, new in zip(seq[:-1], seq[1:]):
         n_terms = len(L.lsw_build_terms(old[0], old[1], new[0], new[1], E, 0.5)[0])
-        fits = r % 8 == 0 and n_terms * (r // 8) <= 8
+        fits = r % 8 == 0 and n_terms * (r // 8) <= 32
         use = kernel if (kernel == L.KERNEL_VALU or fits) else L.KERNEL_VALU
         L.lsw_set_option(ds.ctx, L.LSW_OPT_KERNEL, use)
         ds.switch(old, new)
+        kernels_used.add(L.lsw_query(ds.ctx, L.LSW_Q_LAST_KERNEL))
         got = ds.rows(0)
         rep, _ = check_step(prev, got, A, B, old, new, scale=0.5)
         assert rep["fail"] == 0, (old, new, {k: v for k, v in rep.items() if k != "fail_mask"})
         reports.append(rep)
         prev = got
     assert merge_reports(reports)["exact_frac"] > 0.995
+    if kernel == L.KERNEL_MFMA and r >= 32:
+        assert L.KERNEL_MFMA in kernels_used
     ds.close()
 
 

@@ -114,6 +114,20 @@ lsw_status lsw_merged_gemv(lsw_ctx* ctx, int32_t lin_index, const void* x_bf16, 
                            void* hip_stream);
 
 /*
+ * The same decode through EVERY registered linear in one launch (the backbone pass that follows
+ * the switch in Alg. 1, step 5, as far as the weights are concerned: no activations are chained
+ * here, each linear gets the input the caller supplies).
+ *
+ *   x_all_bf16  DEVICE bf16, 16-byte aligned: the inputs of the linears back to back in registration
+ *               order, linear p at element offset sum_{q<p} in_q (lsw_query LSW_Q_GEMV_X_ELEMS = total;
+ *               every in is a multiple of 8, so each part stays 16-byte aligned).
+ *   y_all_fp32  DEVICE fp32: the outputs back to back, linear p at offset sum_{q<p} out_q
+ *               (LSW_Q_GEMV_Y_ELEMS = total).
+ * Asynchronous on hip_stream.  Errors: LSW_ERR_ARG, LSW_ERR_SHAPE (misaligned x), LSW_ERR_DEVICE.
+ */
+lsw_status lsw_merged_gemv_all(lsw_ctx* ctx, const void* x_all_bf16, float* y_all_fp32, void* hip_stream);
+
+/*
  * Router on given logits: G = Softmax(TopK(logits)) (definition of G under Eq. 1, used by the
  * single token-wise router of Eq. 2).  Host helper, touches no device.
  *
@@ -163,6 +177,7 @@ enum {
   LSW_OPT_GRID = 3,          /* workgroups per launch; 0 = automatic (one matrix-core workgroup per CU) */
   LSW_OPT_TILE_COLS = 4,     /* matrix-core kernel: columns per work item, a multiple of 256 (tuning knob) */
   LSW_OPT_XCD_REMAP = 5,     /* 1 (default): each XCD takes a contiguous share of every round of items */
+  LSW_OPT_GEMV_GRID = 7,     /* workgroups of the merged-decode launches; 0 = automatic (2 per CU) */
   LSW_OPT_STAGGER = 6        /* fused ranks above 64: workgroup i of an XCD starts (i mod 8) * value * 64 cycles late,
                                 so that the workgroups do not all request their W tiles at the same instant (tuning knob) */
 };
@@ -171,7 +186,9 @@ enum {
   LSW_Q_LAST_KERNEL = 3,     /* kernel the last lsw_switch launched: 0 none, 1 vector-ALU, 2 matrix-core */
   LSW_Q_LAST_ITEMS = 4,      /* work items of the last launch */
   LSW_Q_LAST_GRID = 5,       /* workgroups of the last launch */
-  LSW_Q_PACKED_BYTES = 6     /* bytes of device memory the context owns */
+  LSW_Q_PACKED_BYTES = 6,    /* bytes of device memory the context owns */
+  LSW_Q_GEMV_X_ELEMS = 7,    /* elements of lsw_merged_gemv_all's x_all (sum of in over the linears) */
+  LSW_Q_GEMV_Y_ELEMS = 8     /* elements of its y_all (sum of out) */
 };
 lsw_status lsw_set_option(lsw_ctx* ctx, int32_t option, int64_t value);
 int64_t    lsw_query(const lsw_ctx* ctx, int32_t what);   /* -1 on a bad argument */

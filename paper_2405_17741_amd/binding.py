@@ -13,14 +13,15 @@ import numpy as np
 
 LSW_OK, LSW_ERR_ARG, LSW_ERR_SHAPE, LSW_ERR_STATE, LSW_ERR_NOMEM, LSW_ERR_DEVICE = range(6)
 LSW_MAX_K = 8
-LSW_OPT_KERNEL, LSW_OPT_STRICT_STATE, LSW_OPT_GRID, LSW_OPT_TILE_COLS, LSW_OPT_XCD_REMAP, LSW_OPT_STAGGER = 1, 2, 3, 4, 5, 6
-LSW_Q_N_LINEARS, LSW_Q_N_LAYERS, LSW_Q_LAST_KERNEL, LSW_Q_LAST_ITEMS, LSW_Q_LAST_GRID, LSW_Q_PACKED_BYTES = range(1, 7)
+LSW_OPT_KERNEL, LSW_OPT_STRICT_STATE, LSW_OPT_GRID, LSW_OPT_TILE_COLS, LSW_OPT_XCD_REMAP, LSW_OPT_STAGGER, LSW_OPT_GEMV_GRID = 1, 2, 3, 4, 5, 6, 7
+(LSW_Q_N_LINEARS, LSW_Q_N_LAYERS, LSW_Q_LAST_KERNEL, LSW_Q_LAST_ITEMS, LSW_Q_LAST_GRID, LSW_Q_PACKED_BYTES,
+ LSW_Q_GEMV_X_ELEMS, LSW_Q_GEMV_Y_ELEMS) = range(1, 9)
 KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
 
 EXPORTS = (
     "lsw_create_adapters", "lsw_switch", "lsw_merged_gemv", "lsw_route", "lsw_build_terms",
     "lsw_get_state", "lsw_set_option", "lsw_query", "lsw_worklist_size", "lsw_worklist_item",
-    "lsw_destroy", "lsw_last_error", "lsw_probe_inplace",
+    "lsw_destroy", "lsw_last_error", "lsw_probe_inplace", "lsw_merged_gemv_all",
 )
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblsw.so")
@@ -54,6 +55,7 @@ def lib() -> C.CDLL:
         L.lsw_switch.argtypes = [C.c_void_p, _i32p, C.c_int32, _i32p, _f32p, C.c_int32, _i32p, _f32p, C.c_int32,
                                  C.c_void_p]
         L.lsw_merged_gemv.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.lsw_merged_gemv_all.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.lsw_route.argtypes = [_f32p, C.c_int32, C.c_int32, _i32p, _f32p]
         L.lsw_build_terms.argtypes = [_i32p, _f32p, C.c_int32, _i32p, _f32p, C.c_int32, C.c_int32, C.c_float,
                                       _i32p, _f32p, _i32p]
@@ -126,6 +128,10 @@ def lsw_switch(ctx: int, old_ids, old_gates, new_ids, new_gates, layers=None, st
 
 def lsw_merged_gemv(ctx: int, lin_index: int, x_ptr: int, y_ptr: int, stream: int = 0) -> None:
     _check(lib().lsw_merged_gemv(ctx, lin_index, C.c_void_p(x_ptr), C.c_void_p(y_ptr), C.c_void_p(stream)))
+
+
+def lsw_merged_gemv_all(ctx: int, x_all_ptr: int, y_all_ptr: int, stream: int = 0) -> None:
+    _check(lib().lsw_merged_gemv_all(ctx, C.c_void_p(x_all_ptr), C.c_void_p(y_all_ptr), C.c_void_p(stream)))
 
 
 def lsw_route(logits, k: int):

@@ -75,8 +75,9 @@ struct lsw_ctx {
   LinDesc* d_lin = nullptr;
   uint16_t* d_apk = nullptr;                 // packed A of all linears (r % 8 == 0 only)
   int64_t owned_bytes = 0;
+  int64_t x_elems = 0, y_elems = 0;          // sizes of the back-to-back x and y of lsw_merged_gemv_all
   std::map<PlanKey, DevicePlan> plans;
-  int opt_kernel = 0, opt_strict = 0, opt_grid = 0, opt_tile_cols = kMfmaTileCols, opt_tile_cols_bigk = kMfmaBigkTileCols, opt_xcd = 1, opt_stagger = 0;
+  int opt_kernel = 0, opt_strict = 0, opt_grid = 0, opt_tile_cols = kMfmaTileCols, opt_tile_cols_bigk = kMfmaBigkTileCols, opt_xcd = 1, opt_stagger = 0, opt_gemv_grid = 0;
   int last_kernel = 0, last_items = 0, last_grid = 0;
 };
 
@@ -295,6 +296,10 @@ extern "C" lsw_status lsw_create_adapters(const lsw_linear* lin, int32_t n_lin, 
     desc[p].Apk = pack ? c->d_apk + apk_off[p] : nullptr;
     desc[p].out = lin[p].out;
     desc[p].in = lin[p].in;
+    desc[p].x_off = c->x_elems;
+    desc[p].y_off = c->y_elems;
+    c->x_elems += lin[p].in;
+    c->y_elems += lin[p].out;
   }
   hipError_t e = hipMalloc(reinterpret_cast<void**>(&c->d_lin), desc.size() * sizeof(LinDesc));
   if (e != hipSuccess) { (void)hipGetLastError(); cleanup(); return fail(LSW_ERR_NOMEM, "hipMalloc of the descriptor table failed"); }
@@ -322,7 +327,7 @@ static lsw_status get_plan(lsw_ctx* c, int kernel, int tc, const std::vector<int
   PlanKey key{kernel, tc, layers_sorted};
   auto it = c->plans.find(key);
   if (it != c->plans.end()) { *out = &it->second; return LSW_OK; }
-  const int32_t tr = kernel == 3 ? 32 : kernel == 2 ? kMfmaTileRows : kValuTileRows;   // 3 = bandwidth probe
+  const int32_t tr = kernel == 4 ? kGemvRows : kernel == 3 ? 32 : kernel == 2 ? kMfmaTileRows : kValuTileRows;   // 3 = bandwidth probe, 4 = merged decode
   std::vector<int32_t> sel, first(1, 0);
   int64_t total = 0;
   for (size_t p = 0; p < c->lin.size(); ++p) {
@@ -451,7 +456,24 @@ extern "C" lsw_status lsw_merged_gemv(lsw_ctx* c, int32_t lin_index, const void*
   if (!aligned16(x_bf16)) return fail(LSW_ERR_SHAPE, "x is not 16-byte aligned");
   const lsw_linear& L = c->lin[size_t(lin_index)];
   hipError_t e = launch_gemv(static_cast<const uint16_t*>(L.W), static_cast<const uint16_t*>(x_bf16), y_fp32,
-                             L.out, L.in, static_cast<hipStream_t>(hip_stream));
+                             L.out, L.in, c->opt_gemv_grid > 0 ? c->opt_gemv_grid : c->n_cu * 2,
+                             static_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "gemv launch failed: %s", hipGetErrorString(e));
+  return LSW_OK;
+}
+
+extern "C" lsw_status lsw_merged_gemv_all(lsw_ctx* c, const void* x_all_bf16, float* y_all_fp32, void* hip_stream) {
+  if (!c) return fail(LSW_ERR_ARG, "ctx is null");
+  if (!x_all_bf16 || !y_all_fp32) return fail(LSW_ERR_ARG, "null vector");
+  if (!aligned16(x_all_bf16)) return fail(LSW_ERR_SHAPE, "x is not 16-byte aligned");
+  DevicePlan* dp = nullptr;
+  lsw_status st = get_plan(c, 4, 1 << 30, std::vector<int32_t>(), &dp);   // items: blocks of rows, whole rows wide
+  if (st != LSW_OK) return st;
+  LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, 1 << 30, c->opt_xcd, 0};
+  int grid = c->opt_gemv_grid > 0 ? c->opt_gemv_grid : c->n_cu * 2;
+  grid = std::max(8, (grid / 8) * 8);
+  hipError_t e = launch_gemv_all(lp, static_cast<const uint16_t*>(x_all_bf16), y_all_fp32, grid,
+                                 static_cast<hipStream_t>(hip_stream));
   if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "gemv launch failed: %s", hipGetErrorString(e));
   return LSW_OK;
 }
@@ -491,6 +513,10 @@ extern "C" lsw_status lsw_set_option(lsw_ctx* c, int32_t option, int64_t value) 
     case LSW_OPT_XCD_REMAP:
       c->opt_xcd = value != 0;
       return LSW_OK;
+    case LSW_OPT_GEMV_GRID:
+      if (value < 0 || value > (1 << 20)) return fail(LSW_ERR_ARG, "grid option out of range");
+      c->opt_gemv_grid = int(value);
+      return LSW_OK;
     case LSW_OPT_STAGGER:
       if (value < 0 || value > 4096) return fail(LSW_ERR_ARG, "stagger option out of range");
       c->opt_stagger = int(value);
@@ -509,6 +535,8 @@ extern "C" int64_t lsw_query(const lsw_ctx* c, int32_t what) {
     case LSW_Q_LAST_ITEMS: return c->last_items;
     case LSW_Q_LAST_GRID: return c->last_grid;
     case LSW_Q_PACKED_BYTES: return c->owned_bytes;
+    case LSW_Q_GEMV_X_ELEMS: return c->x_elems;
+    case LSW_Q_GEMV_Y_ELEMS: return c->y_elems;
     default: return -1;
   }
 }

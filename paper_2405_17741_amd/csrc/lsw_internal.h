@@ -25,6 +25,8 @@ struct LinDesc {
   const uint16_t* Apk;    // packed A for the matrix-core kernel (see pack kernel), or null
   int32_t         out;
   int32_t         in;
+  int64_t         x_off;  // element offset of this linear's input in the back-to-back x of lsw_merged_gemv_all
+  int64_t         y_off;  // element offset of its output in the back-to-back y
 };
 
 // The fused low-rank update of one switch: sum over n terms of coeff * B[e] @ A[e].
@@ -67,6 +69,7 @@ LSW_HD inline void decode_item(int32_t local, int32_t in, int32_t tile_rows, int
 constexpr int kValuTileRows = 64,  kValuTileCols = 128;
 constexpr int kMfmaTileRows = 128, kMfmaTileCols = 1024;   // 4 waves x 32 rows; default item width (LSW_OPT_TILE_COLS overrides)
 constexpr int kMfmaBigkTileCols = 4096;                     // default item width of the chunked (fused rank > 64) matrix-core kernel
+constexpr int kGemvRows = 4;                                // rows of one wave's block in the merged-decode kernels
 constexpr int kApkBlockCols = 256;   // column block of the packed A layout = columns per matrix-core step
 
 struct LaunchPlan {             // device pointers + counts for one launch
@@ -86,7 +89,8 @@ hipError_t launch_switch_mfma(const LaunchPlan& p, const Terms& t, int r, int gr
 hipError_t launch_switch_mfma_bigk(const LaunchPlan& p, const Terms& t, int r, int grid, hipStream_t s);
 hipError_t launch_probe_inplace(const LaunchPlan& p, int grid, hipStream_t s);
 hipError_t launch_pack_A(const float* A, uint16_t* Apk, int E, int r, int in, hipStream_t s);
-hipError_t launch_gemv(const uint16_t* W, const uint16_t* x, float* y, int out, int in, hipStream_t s);
+hipError_t launch_gemv(const uint16_t* W, const uint16_t* x, float* y, int out, int in, int grid_cap, hipStream_t s);
+hipError_t launch_gemv_all(const LaunchPlan& p, const uint16_t* x_all, float* y_all, int grid, hipStream_t s);
 
 }  // namespace lsw
 #endif

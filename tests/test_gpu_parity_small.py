@@ -255,6 +255,37 @@ def test_merged_gemv_against_oracle():
         ds.close()
 
 
+def test_merged_gemv_all_linears_in_one_launch():
+    """Every linear of a small ragged stack decoded by ONE launch; each output row against the fp64 oracle."""
+    rng = np.random.default_rng(11)
+    dims = [(37, 264), (5, 8), (130, 1032), (64, 4096), (3, 11008), (258, 520)]
+    host = [I.host_linear(rng, o, n, 2, 8, 0.02, 1 / 16, 0.01) for o, n in dims]
+    shapes = [(p // 3, p % 3, o, n) for p, (o, n) in enumerate(dims)]
+    ds = DeviceStack.from_host(host, shapes, 2, 8)
+    ds.switch((np.zeros(0, np.int32), np.zeros(0, np.float32)), (np.array([0], np.int32), np.array([1.0], np.float32)))
+    assert L.lsw_query(ds.ctx, L.LSW_Q_GEMV_X_ELEMS) == sum(n for _, n in dims)
+    assert L.lsw_query(ds.ctx, L.LSW_Q_GEMV_Y_ELEMS) == sum(o for o, _ in dims)
+    xs = [I.f32_to_bf16_bits(rng.normal(0, 1, n).astype(np.float32)) for _, n in dims]
+    xd = bits_to_device(np.concatenate(xs))
+    guard = 16
+    y = torch.full((sum(o for o, _ in dims) + guard,), 7.5, dtype=torch.float32, device="cuda")
+    for grid in (0, 8, 64):
+        L.lsw_set_option(ds.ctx, L.LSW_OPT_GEMV_GRID, grid)
+        y.fill_(7.5)
+        L.lsw_merged_gemv_all(ds.ctx, xd.data_ptr(), y.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        got = y.cpu().numpy().astype(np.float64)
+        assert (got[-guard:] == 7.5).all()
+        at = 0
+        for p, (o, n) in enumerate(dims):
+            Wm = ds.rows(p)
+            want = O.gemv(Wm, xs[p])
+            absum = np.abs(O.bf16_bits_to_f64(Wm)) @ np.abs(O.bf16_bits_to_f64(xs[p]))
+            err = np.abs(got[at:at + o] - want)
+            assert (err <= 1e-5 * absum + 1e-30).all(), (grid, p, o, n, float((err / absum).max()))
+            at += o
+    ds.close()
+
+
 def test_probe_inplace_leaves_weights_unchanged():
     wl = I.Workload("mini", 2, 64, 136, 32, 4, 8, 2, 4, 0.02, 1 / 8, 0.01, 515)
     host = I.host_stack(wl)

@@ -29,9 +29,10 @@ def algorithmic_bytes(wl, n_terms: int) -> float:
     return 4.0 * wl.w_elements() + 4.0 * n_terms * wl.rank * wl.factor_dims()
 
 
-def cpu_baseline(wl, steps=2):
-    """The oracle as it stands, timed on the host: one 4096x4096-class linear, `steps` switches,
-    scaled by weight count to a whole-stack microseconds-per-token figure."""
+def cpu_baseline(wl, steps=3):
+    """The oracle as it stands, timed on the host: ONE full layer of the workload (its 7 linears),
+    `steps` switches after an untimed first merge, median per switch, scaled by the layer count to a
+    whole-stack microseconds-per-token figure.  About 10-30 s of CPU work at the 7B shapes."""
     import numpy as np
     from oracle import lsw_oracle as O
     from paper_2405_17741_amd import inputs as I
@@ -40,24 +41,29 @@ def cpu_baseline(wl, steps=2):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = 1
-    _, _, o, n = wl.linear_shapes()[0]
+    layer0 = [(o, n) for layer, _, o, n in wl.linear_shapes() if layer == 0]
     rng = np.random.default_rng(wl.seed)
-    W, A, B = I.host_linear(rng, o, n, wl.experts, wl.rank, wl.w_std, wl.a_std, wl.b_std)
+    lin = [I.host_linear(rng, o, n, wl.experts, wl.rank, wl.w_std, wl.a_std, wl.b_std) for o, n in layer0]
     routes = [O.route(l, wl.top_k) for l in I.router_logits(wl, steps + 1)]
-    W = O.switch_step(W, A, B, [], [], routes[0][0], routes[0][1])
+    Ws = [O.switch_step(W, A, B, [], [], routes[0][0], routes[0][1]) for W, A, B in lin]
     times = []
     for t in range(steps):
         t0 = time.perf_counter()
-        W = O.switch_step(W, A, B, routes[t][0], routes[t][1], routes[t + 1][0], routes[t + 1][1])
+        Ws = [O.switch_step(W, A, B, routes[t][0], routes[t][1], routes[t + 1][0], routes[t + 1][1])
+              for W, (_, A, B) in zip(Ws, lin)]
         times.append(time.perf_counter() - t0)
     med = sorted(times)[len(times) // 2]
-    us_per_token = med * 1e6 * wl.w_elements() / (o * n)
+    layer_elems = sum(o * n for o, n in layer0)
+    us_per_token = med * 1e6 * wl.w_elements() / layer_elems
     return {
         "value": round(us_per_token, 1), "unit": "us/token", "cores": int(threads), "kind": "oracle",
-        "sample": f"NumPy fp64 oracle on one {o}x{n} linear ({o * n} of {wl.w_elements()} weights), median of "
-                  f"{steps} switches, scaled by weight count; BLAS threads={threads}, element-wise part single-threaded; "
-                  f"host cores visible={len(os.sched_getaffinity(0))}",
+        "sample": f"NumPy fp64 oracle on one full layer ({len(layer0)} linears, {layer_elems} of {wl.w_elements()} weights), "
+                  f"median of {steps} switches ({sum(times):.1f} s of CPU work), scaled by weight count; BLAS threads={threads}, "
+                  f"element-wise part single-threaded; host cores visible={len(os.sched_getaffinity(0))}",
     }
+
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
 
 
 def main():
@@ -67,6 +73,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="7b")
     ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 vector-ALU, 2 matrix-core")
+    ap.add_argument("--cpu-steps", type=int, default=3, help="switches the CPU oracle baseline times")
     ap.add_argument("--grid", type=int, default=0)
     ap.add_argument("--tile-cols", type=int, default=0)
     ap.add_argument("--xcd", type=int, default=-1)
@@ -152,6 +159,22 @@ def main():
         b.synchronize()
         probe[f"{wpc}_waves_per_cu_GBps"] = round(4.0 * wl.w_elements() / (a.elapsed_time(b) / 5 * 1e-3) / 1e9, 1)
 
+    # the decode that follows the switch (timed separately): every merged linear once, batch 1
+    nx, ny = L.lsw_query(ctx, L.LSW_Q_GEMV_X_ELEMS), L.lsw_query(ctx, L.LSW_Q_GEMV_Y_ELEMS)
+    xg = torch.randn(nx, device="cuda").to(torch.bfloat16)
+    yg = torch.empty(ny, device="cuda", dtype=torch.float32)
+    L.lsw_merged_gemv_all(ctx, xg.data_ptr(), yg.data_ptr(), stream)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(5):
+        L.lsw_merged_gemv_all(ctx, xg.data_ptr(), yg.data_ptr(), stream)
+    b.record()
+    b.synchronize()
+    gemv_ms = a.elapsed_time(b) / 5
+    gemv_gbps = 2.0 * wl.w_elements() / (gemv_ms * 1e-3) / 1e9
+    del xg, yg
+
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
@@ -159,6 +182,17 @@ def main():
             traffic = json.load(open(tpath)).get(args.workload)
         except Exception:
             traffic = None
+
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic}
+    mean_terms = sum(terms) / len(terms)
+    if max(kernels) == 2 and mean_terms * wl.rank > 64:
+        # fused ranks above 64: three bf16 passes of 2*K flop per weight take longer on the matrix cores than the
+        # W traffic takes on HBM, so that is the roofline of this launch
+        flops = [3.0 * 2.0 * n * wl.rank * wl.w_elements() for n, k in zip(terms, kernels) if k != 0]
+        tf = (sum(flops) / len(flops)) / (avg_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic}
 
     out = {
         "metric": "switch latency us/token (all layers) + achieved HBM GB/s, 7B-shaped adapters",
@@ -170,13 +204,16 @@ def main():
                                f"E={wl.experts}, r={wl.rank}, top-{wl.top_k}, all layers per launch",
                    "w_elements": wl.w_elements(),
                    "kernel": {0: "none", 1: "vector-ALU", 2: "matrix-core"}[max(kernels)],
+                   "fused_rank_mean": round(mean_terms * wl.rank, 1),
                    "grid": L.lsw_query(ctx, L.LSW_Q_LAST_GRID),
                    "terms_per_step_mean": round(sum(terms) / len(terms), 3),
                    "launch_us": {"mean": round(avg_ms * 1e3, 1), "min": round(min(launch_ms) * 1e3, 1),
                                  "median": round(sorted(launch_ms)[len(launch_ms) // 2] * 1e3, 1)}},
         "achieved_hbm_GBps": round(achieved, 1),
-        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic},
+        "roofline": roofline,
+        "merged_gemv": {"us": round(gemv_ms * 1e3, 1), "GBps": round(gemv_gbps, 1), "frac_of_hbm_peak": round(gemv_gbps / HBM_PEAK_GBPS, 4),
+                        "note": "lsw_merged_gemv_all: batch-1 bf16 decode through every merged linear in one launch, "
+                                "2 bytes per weight, timed separately from the switch"},
         "inplace_probe": {**probe, "note": "lsw_probe_inplace on the same weights: in-place bf16 read+write only; "
                                            "the practical ceiling of the switch's access pattern",
                           "switch_over_best_probe": round(achieved / max(probe.values()), 4)},
@@ -192,7 +229,7 @@ def main():
         torch.cuda.synchronize()
         out["calibration_copy_bytes"] = int(src.numel() * 4)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl)
+        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_steps)
     print(json.dumps(out))
 
 

@@ -77,7 +77,8 @@ typedef struct lsw_linear {
  *
  * Errors: LSW_ERR_ARG (null, n_lin < 1, E/r out of range, non-finite scale, layer < 0),
  * LSW_ERR_SHAPE (out < 1, in not a positive multiple of 8, pointer not 16-byte aligned, one W of
- * 2 GiB or more counting rows rounded up to a multiple of 128),
+ * 2 GiB or more counting rows rounded up to a multiple of 128, E * r * in * 4 bytes of 2 GiB or more
+ * for one linear when r is a multiple of 8),
  * LSW_ERR_NOMEM, LSW_ERR_DEVICE (also when no GPU is present; validation comes first).
  */
 lsw_status lsw_create_adapters(const lsw_linear* lin, int32_t n_lin, int32_t E, int32_t r,
@@ -171,15 +172,13 @@ lsw_status lsw_get_state(const lsw_ctx* ctx, int32_t layer, int32_t* ids, float*
 
 /* Options (lsw_set_option) and queries (lsw_query). */
 enum {
-  LSW_OPT_KERNEL = 1,        /* 0 = automatic, 1 = fp32 vector-ALU kernel (any rank), 2 = matrix-core kernel
-                                (needs r % 8 == 0 and at most 64 fused ranks per switch) */
+  LSW_OPT_KERNEL = 1,        /* 0 = automatic, 1 = fp32 vector-ALU kernel (any rank), 2 = matrix-core kernels
+                                (need r % 8 == 0 and at most 256 fused ranks = terms * r per switch) */
   LSW_OPT_STRICT_STATE = 2,  /* 1: lsw_switch rejects an `old` that differs from the tracked state of a layer */
   LSW_OPT_GRID = 3,          /* workgroups per launch; 0 = automatic (one matrix-core workgroup per CU) */
   LSW_OPT_TILE_COLS = 4,     /* matrix-core kernel: columns per work item, a multiple of 256 (tuning knob) */
   LSW_OPT_XCD_REMAP = 5,     /* 1 (default): each XCD takes a contiguous share of every round of items */
-  LSW_OPT_GEMV_GRID = 7,     /* workgroups of the merged-decode launches; 0 = automatic (2 per CU) */
-  LSW_OPT_STAGGER = 6        /* fused ranks above 64: workgroup i of an XCD starts (i mod 8) * value * 64 cycles late,
-                                so that the workgroups do not all request their W tiles at the same instant (tuning knob) */
+  LSW_OPT_GEMV_GRID = 6      /* workgroups of the merged-decode launches; 0 = automatic (2 per CU) */
 };
 enum {
   LSW_Q_N_LINEARS = 1, LSW_Q_N_LAYERS = 2,

@@ -77,7 +77,7 @@ struct lsw_ctx {
   int64_t owned_bytes = 0;
   int64_t x_elems = 0, y_elems = 0;          // sizes of the back-to-back x and y of lsw_merged_gemv_all
   std::map<PlanKey, DevicePlan> plans;
-  int opt_kernel = 0, opt_strict = 0, opt_grid = 0, opt_tile_cols = kMfmaTileCols, opt_tile_cols_bigk = kMfmaBigkTileCols, opt_xcd = 1, opt_stagger = 0, opt_gemv_grid = 0;
+  int opt_kernel = 0, opt_strict = 0, opt_grid = 0, opt_tile_cols = kMfmaTileCols, opt_tile_cols_bigk = kMfmaBigkTileCols, opt_xcd = 1, opt_gemv_grid = 0;
   int last_kernel = 0, last_items = 0, last_grid = 0;
 };
 
@@ -235,6 +235,9 @@ extern "C" lsw_status lsw_create_adapters(const lsw_linear* lin, int32_t n_lin, 
     // 32-bit byte offsets inside one W, including the rows a 128-row work item may reach past the end
     if (int64_t(ceil_div(L.out, kMfmaTileRows)) * kMfmaTileRows * L.in * 2 >= (int64_t(1) << 31))
       return fail(LSW_ERR_SHAPE, "linear %d: W (rows rounded up to %d) must stay below 2^31 bytes", p, kMfmaTileRows);
+    // 32-bit byte offsets inside one linear's packed A (E * r * padded in * 4 bytes)
+    if (r % 8 == 0 && int64_t(E) * r * ceil_div(L.in, kApkBlockCols) * kApkBlockCols * 4 >= (int64_t(1) << 31))
+      return fail(LSW_ERR_SHAPE, "linear %d: E * r * in * 4 must stay below 2^31 bytes", p);
     if (!aligned16(L.W) || !aligned16(L.A) || !aligned16(L.B))
       return fail(LSW_ERR_SHAPE, "linear %d: tensor not 16-byte aligned", p);
     items_valu += int64_t(ceil_div(L.out, kValuTileRows)) * ceil_div(L.in, kValuTileCols);
@@ -410,7 +413,7 @@ extern "C" lsw_status lsw_switch(lsw_ctx* c, const int32_t* layers, int32_t n_la
     const int tc = kernel >= 2 ? (bigk ? c->opt_tile_cols_bigk : c->opt_tile_cols) : kValuTileCols;
     st = get_plan(c, kernel, tc, sel_layers, &dp);
     if (st != LSW_OK) return st;
-    LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, tc, c->opt_xcd, c->opt_stagger};
+    LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, tc, c->opt_xcd};
     int grid = c->opt_grid;
     if (grid <= 0) grid = (kernel == 2) ? c->n_cu : c->n_cu * 2;   // matrix-core: one 4-wave workgroup per CU
     grid = std::max(8, (grid / 8) * 8);     // a multiple of the 8 XCDs (the kernels' block remap assumes it)
@@ -439,7 +442,7 @@ extern "C" lsw_status lsw_probe_inplace(lsw_ctx* c, int32_t waves_per_cu, void* 
   DevicePlan* dp = nullptr;
   lsw_status st = get_plan(c, 3, c->opt_tile_cols, std::vector<int32_t>(), &dp);
   if (st != LSW_OK) return st;
-  LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, c->opt_tile_cols, c->opt_xcd, 0};
+  LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, c->opt_tile_cols, c->opt_xcd};
   hipError_t e = launch_probe_inplace(lp, c->n_cu * waves_per_cu, static_cast<hipStream_t>(hip_stream));
   if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "probe launch failed: %s", hipGetErrorString(e));
   return LSW_OK;
@@ -469,7 +472,7 @@ extern "C" lsw_status lsw_merged_gemv_all(lsw_ctx* c, const void* x_all_bf16, fl
   DevicePlan* dp = nullptr;
   lsw_status st = get_plan(c, 4, 1 << 30, std::vector<int32_t>(), &dp);   // items: blocks of rows, whole rows wide
   if (st != LSW_OK) return st;
-  LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, 1 << 30, c->opt_xcd, 0};
+  LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, 1 << 30, c->opt_xcd};
   int grid = c->opt_gemv_grid > 0 ? c->opt_gemv_grid : c->n_cu * 2;
   grid = std::max(8, (grid / 8) * 8);
   hipError_t e = launch_gemv_all(lp, static_cast<const uint16_t*>(x_all_bf16), y_all_fp32, grid,
@@ -516,10 +519,6 @@ extern "C" lsw_status lsw_set_option(lsw_ctx* c, int32_t option, int64_t value) 
     case LSW_OPT_GEMV_GRID:
       if (value < 0 || value > (1 << 20)) return fail(LSW_ERR_ARG, "grid option out of range");
       c->opt_gemv_grid = int(value);
-      return LSW_OK;
-    case LSW_OPT_STAGGER:
-      if (value < 0 || value > 4096) return fail(LSW_ERR_ARG, "stagger option out of range");
-      c->opt_stagger = int(value);
       return LSW_OK;
     default:
       return fail(LSW_ERR_ARG, "unknown option %d", option);

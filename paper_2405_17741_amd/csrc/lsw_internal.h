@@ -80,7 +80,6 @@ struct LaunchPlan {             // device pointers + counts for one launch
   int32_t n_items;
   int32_t tile_cols;            // columns of one work item (matrix-core kernel: a multiple of kApkBlockCols)
   int32_t xcd_remap;            // 1: each XCD takes a contiguous eighth of every grid-wide round of items
-  int32_t stagger;              // chunked matrix-core kernel: start-up delay unit (in 64-cycle sleeps) between workgroup phases
 };
 
 // Kernel launchers (lsw_kernels.hip).  All return the hipError of the launch.

@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <type_traits>
+#include <utility>
 
 #include "lsw_internal.h"
 
@@ -597,36 +599,69 @@ hipError_t launch_switch_mfma(const LaunchPlan& p, const Terms& t, int r, int gr
 // K = 256), so the fused rank is cut into chunks of 4 k-steps (64 ranks, 64 KB of Q) that are
 // double-buffered in LDS, and the fp32 accumulators of the whole 32 x 256 tile stay in registers
 // across the chunks of a step.  P (coeff * B, split) for the whole fused rank stays in registers for
-// the item.  Per chunk: start the LDS copy of the next chunk's Q quarter, run the chunk's
-// 4 x 8 x 3 matrix instructions, wait for the copy, workgroup barrier.  The next W tile is requested
-// right after the current one has been widened into the accumulators (its registers are free then)
-// and has every chunk but the first to arrive; the finished tile is stored after the last chunk and
-// has the whole next step to drain.  At K = 256 the three-pass product needs about as long on the
-// matrix cores as the W traffic needs on HBM, so this kernel is bound by the matrix cores.
+// the item.
+//
+// Schedule of one step (per wave).  Chunk 0: request the copy of chunk 1's Q quarter, store the
+// previous step's tile, request the next tile into the registers just stored from; then compute,
+// widening the W words of block pair q+1 into their accumulators while the matrix pipe works on
+// pair q.  Chunks 1..: two LDS-copy instructions of the following chunk's Q ride along with each of
+// the first 8 of the 16 groups of matrix instructions; in the last chunk the finished accumulators of pair q-1 are
+// rounded to bf16 while pair q computes.  Every chunk ends with "my LDS copies have landed" + a
+// workgroup barrier.  The vector-memory counter is in order, so the wait after chunk 0 lets the 32
+// younger W requests fly on (they get two chunks to complete); the waits after the other chunks
+// drain everything.  At K = 256 the three-pass product needs longer on the matrix cores than the W
+// traffic needs on HBM: this kernel is bound by the matrix cores.
 // ---------------------------------------------------------------------------
 constexpr int BK_KC = 4;                       // k-steps per LDS chunk
 constexpr int BK_MAX_GROUPS = 32;              // 8-rank groups of the fused rank: K <= 256
+constexpr int kBkBufBytes = BK_KC * 8 * 2 * 64 * 16;     // one LDS buffer: 64 KB
 
-// this wave's quarter of chunk `ch` of the Q operand of column step `cs`
-__device__ __forceinline__ void bk_fetch_q(const uint16_t* Apk, int ncb, int cs, int ch, int n, int h, int gpr, int wave,
-                                           const int32_t* s_eg, u32x4* buf) {
-#pragma unroll
-  for (int kk = 0; kk < BK_KC; ++kk) {
-    const int eg = s_eg[2 * (ch * BK_KC + kk) + h];          // expert * gpr + group of this lane's half
-    const u32x4* src = reinterpret_cast<const u32x4*>(
-        Apk + ((long long)eg * ncb + cs / MT_STEP) * (8 * 2 * 32 * 8)) + n;
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int hl = 0; hl < 2; ++hl)
-        lds_dma16(src + (2 * (2 * wave + j) + hl) * 32, buf + ((kk * 8 + 2 * wave + j) * 2 + hl) * 64);
+// 16-byte-per-lane LDS copy, source = scalar base + 32-bit lane offset + immediate (see lds_dma16);
+// lane l lands at lds_addr + 16*l.  The hardware adds the instruction's immediate to the LDS address as
+// well as to the memory address (measured), so it is taken off the LDS base here.
+template <int IMM>
+__device__ __forceinline__ void lds_dma16_s(uint32_t voff, const void* sbase, uint32_t lds_addr) {
+  static_assert(IMM >= 0 && IMM < 4096, "13-bit signed immediate");
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 offset:%3" ::"v"(voff), "s"(sbase),
+               "s"(lds_addr - uint32_t(IMM)), "n"(IMM)
+               : "memory", "m0");
+}
+
+// What one wave needs to copy its quarter of a Q chunk: instruction d = 4*kk + 2*j + hl moves block
+// 2*wave + j, part hl, of k-step kk.
+struct BkCopy {
+  const void* sbase;          // packed A of the linear + column block + this wave's two blocks (uniform)
+  uint32_t lds_base;          // LDS byte address of the target buffer + this wave's two blocks (uniform)
+  uint32_t voff[BK_KC];       // per lane: start of the (expert, rank group) of this lane's half of k-step kk, + 16 * n
+};
+
+template <int D>
+__device__ __forceinline__ void bk_copy_one(const BkCopy& c) {
+  constexpr int kk = D >> 2, j = (D >> 1) & 1, hl = D & 1;
+  lds_dma16_s<(2 * j + hl) * 512>(c.voff[kk], c.sbase, c.lds_base + uint32_t(kk * 16384 + j * 2048 + hl * 1024));
+}
+
+template <int D0, int D1>
+__device__ __forceinline__ void bk_copy_range(const BkCopy& c) {
+  if constexpr (D0 < D1) {
+    bk_copy_one<D0>(c);
+    bk_copy_range<D0 + 1, D1>(c);
   }
 }
 
-// one chunk: acc += P[chunk] * Q[chunk] for the 8 blocks of the step, three passes
-__device__ __forceinline__ void bk_compute(const u32x4* p_hi, const u32x4* p_lo /* the chunk's BK_KC entries */,
-                                           const u32x4* qbuf /* LDS: slot 0 of the chunk's buffer + lane */,
-                                           f32x16 (&a0)[4], f32x16 (&a1)[4]) {
+template <typename F, int... I>
+__device__ __forceinline__ void bk_for_each_group(F& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+
+// One chunk: acc += P[chunk] * Q[chunk] for the 8 blocks of the step, three passes, in 16 groups of six
+// matrix instructions (pair q outermost, k-step kk inside).  FIRST: widen the W words of pair q+1
+// during pair q (pair 0 is widened by the caller).  LAST: round pair q-1 during pair q (pair 3 by the
+// caller).  COPY: issue the 16 LDS-copy instructions of `cp` along with the first 8 groups.
+template <bool FIRST, bool LAST, bool COPY>
+__device__ __forceinline__ void bk_chunk(const u32x4* p_hi, const u32x4* p_lo /* the chunk's BK_KC entries */,
+                                         const u32x4* qbuf /* LDS: slot 0 of the chunk's buffer + lane */,
+                                         f32x16 (&a0)[4], f32x16 (&a1)[4], u32x4 (&wcur)[16], const BkCopy& cp) {
   u32x4 qr[2][2][2];           // [parity][block of the pair][high, low]
   auto fetch = [&](int idx) {
     const int q = idx / BK_KC, kk = idx % BK_KC;
@@ -637,42 +672,61 @@ __device__ __forceinline__ void bk_compute(const u32x4* p_hi, const u32x4* p_lo 
   };
   fetch(0);
   __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-#pragma unroll
-    for (int kk = 0; kk < BK_KC; ++kk) {
-      const int idx = q * BK_KC + kk;
-      if (idx + 1 < 4 * BK_KC) fetch(idx + 1);
-      const bf16x8 ph = __builtin_bit_cast(bf16x8, p_hi[kk]);
-      const bf16x8 pl = __builtin_bit_cast(bf16x8, p_lo[kk]);
-      const bf16x8 h0 = __builtin_bit_cast(bf16x8, qr[idx & 1][0][0]);
-      const bf16x8 l0 = __builtin_bit_cast(bf16x8, qr[idx & 1][0][1]);
-      const bf16x8 h1 = __builtin_bit_cast(bf16x8, qr[idx & 1][1][0]);
-      const bf16x8 l1 = __builtin_bit_cast(bf16x8, qr[idx & 1][1][1]);
-      a0[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl, h0, a0[q], 0, 0, 0);
-      a1[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl, h1, a1[q], 0, 0, 0);
-      a0[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, l0, a0[q], 0, 0, 0);
-      a1[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, l1, a1[q], 0, 0, 0);
-      a0[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, h0, a0[q], 0, 0, 0);
-      a1[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, h1, a1[q], 0, 0, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);          // the next 4 LDS reads first
-      __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);          // then the six matrix instructions
-      __builtin_amdgcn_sched_barrier(0);
+  auto group = [&](auto IDX) {
+    constexpr int idx = decltype(IDX)::value;
+    constexpr int q = idx / BK_KC, kk = idx % BK_KC;
+    if (idx + 1 < 4 * BK_KC) fetch(idx + 1);
+    if constexpr (COPY && idx < 8) {          // two per group in the first half: the last copy has half a chunk to land
+      bk_copy_one<2 * idx>(cp);
+      bk_copy_one<2 * idx + 1>(cp);
     }
-  }
+    constexpr int kRowsPer = 16 / BK_KC;
+#pragma unroll
+    for (int v = kk * kRowsPer; v < (kk + 1) * kRowsPer; ++v) {
+      if constexpr (FIRST && q + 1 < 4) {
+        a0[q + 1][v] = bf16_lo(wcur[v][q + 1]);
+        a1[q + 1][v] = bf16_hi(wcur[v][q + 1]);
+      }
+      if constexpr (LAST && q > 0) {
+        uint32_t w = pack_bf16(a0[q - 1][v], a1[q - 1][v]);   // the one rounding
+        asm volatile("" : "+v"(w));
+        wcur[v][q - 1] = w;
+      }
+    }
+    const bf16x8 ph = __builtin_bit_cast(bf16x8, p_hi[kk]);
+    const bf16x8 pl = __builtin_bit_cast(bf16x8, p_lo[kk]);
+    const bf16x8 h0 = __builtin_bit_cast(bf16x8, qr[idx & 1][0][0]);
+    const bf16x8 l0 = __builtin_bit_cast(bf16x8, qr[idx & 1][0][1]);
+    const bf16x8 h1 = __builtin_bit_cast(bf16x8, qr[idx & 1][1][0]);
+    const bf16x8 l1 = __builtin_bit_cast(bf16x8, qr[idx & 1][1][1]);
+    a0[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl, h0, a0[q], 0, 0, 0);
+    a1[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl, h1, a1[q], 0, 0, 0);
+    a0[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, l0, a0[q], 0, 0, 0);
+    a1[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, l1, a1[q], 0, 0, 0);
+    a0[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, h0, a0[q], 0, 0, 0);
+    a1[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, h1, a1[q], 0, 0, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);          // the next group's 4 LDS reads first
+#pragma unroll
+    for (int i = 0; i < 6; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        // one matrix instruction
+      __builtin_amdgcn_sched_group_barrier(0x002, (FIRST || LAST) ? 2 : 0, 0);   // a few vector instructions
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  bk_for_each_group(group, std::make_integer_sequence<int, 4 * BK_KC>{});
 }
 
-// the wave's LDS copies (and everything older) have landed; up to `newer` younger requests may still fly
+// the wave's LDS copies (and everything older) have landed; up to NEWER younger requests may still fly
 template <int NEWER>
 __device__ __forceinline__ void bk_drain_and_barrier() {
-  static_assert(NEWER == 0 || NEWER == 16, "encoded below");
+  static_assert(NEWER == 0 || NEWER == 32, "encoded below");
   // No fence builtins here: a workgroup-scope release would make the compiler wait for EVERY outstanding
   // vector-memory request, the younger W loads and stores included.  The LDS copies count in the wave's
   // vector-memory counter in issue order, so waiting until only NEWER requests remain proves they have
   // landed; LDS itself needs no cache maintenance.  The empty asm statements keep the compiler from moving
   // LDS reads across the barrier.
   __builtin_amdgcn_sched_barrier(0);
-  __builtin_amdgcn_s_waitcnt(NEWER == 0 ? 0x0F70 : 0x4F70);      // vmcnt(0) or vmcnt(16); expcnt, lgkmcnt untouched
+  __builtin_amdgcn_s_waitcnt(NEWER == 0 ? 0x0F70 : 0x8F70);      // vmcnt(0) or vmcnt(32); expcnt, lgkmcnt untouched
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
@@ -680,9 +734,75 @@ __device__ __forceinline__ void bk_drain_and_barrier() {
 }
 
 template <int NCH>
+struct BkWave {             // per-wave state of the chunked kernel that outlives a step
+  u32x4 p_hi[BK_KC * NCH], p_lo[BK_KC * NCH];
+  int32_t eg[2][BK_KC * NCH];       // expert * (r/8) + rank group of lane half h, k-step ks (uniform: scalar registers)
+  int32_t eg_bytes;                 // bytes of one (expert, rank group) slab of the linear's packed A: column blocks * 8 KB (uniform)
+  const uint16_t* Apk;
+  const uint16_t* W;
+  int wbytes;
+  uint32_t stride;
+  uint32_t lds0;                    // LDS byte address of buffer 0 + this wave's two blocks
+  int n, h;
+};
+
+template <int NCH>
+__device__ __forceinline__ BkCopy bk_copy_desc(const BkWave<NCH>& w, int cs, int ch, int buf) {
+  BkCopy c;
+  c.sbase = uniform(reinterpret_cast<const char*>(w.Apk) + (long long)(cs / MT_STEP) * 8192);
+  c.lds_base = w.lds0 + uint32_t(buf) * kBkBufBytes;
+#pragma unroll
+  for (int kk = 0; kk < BK_KC; ++kk)
+    c.voff[kk] = uint32_t(w.h ? w.eg[1][ch * BK_KC + kk] * w.eg_bytes : w.eg[0][ch * BK_KC + kk] * w.eg_bytes) + uint32_t(16 * w.n);
+  return c;
+}
+
+// One 32 x 256 step of a wave.  wcur holds the tile to update (loaded one step ago); wprev holds the finished
+// tile of the previous step: it is stored, then reloaded with the tile of the next step.
+template <int NCH>
+__device__ __forceinline__ void bk_step(const BkWave<NCH>& w, int cs, bool more, int lane, int& buf, uint32_t prev_off,
+                                        uint32_t next_off, u32x4 (&wcur)[16], u32x4 (&wprev)[16]) {
+  const __amdgpu_buffer_rsrc_t res = w_resource(w.W, w.wbytes);
+  f32x16 a0[4], a1[4];
+  {
+    const BkCopy cp = bk_copy_desc<NCH>(w, cs, 1 % NCH, buf ^ 1);
+    bk_copy_range<0, 16>(cp);
+    __builtin_amdgcn_sched_barrier(0);                    // keep the W requests younger than the Q copy
+#pragma unroll
+    for (int v = 0; v < 16; ++v)
+      __builtin_amdgcn_raw_buffer_store_b128(wprev[v], res, prev_off + uint32_t(8 * (v >> 2) + (v & 3)) * w.stride, 0, /*nt*/ 2);
+    asm volatile("" : "+v"(next_off) : "v"(prev_off));      // keep the loads after the stores that free their registers
+#pragma unroll
+    for (int v = 0; v < 16; ++v)
+      wprev[v] = __builtin_amdgcn_raw_buffer_load_b128(res, next_off + uint32_t(8 * (v >> 2) + (v & 3)) * w.stride, 0, /*nt*/ 2);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      a0[0][v] = bf16_lo(wcur[v][0]);
+      a1[0][v] = bf16_hi(wcur[v][0]);
+    }
+    bk_chunk<true, false, false>(w.p_hi, w.p_lo, wg_lds + buf * (kBkBufBytes / 16) + lane, a0, a1, wcur, cp);
+    bk_drain_and_barrier<32>();
+    buf ^= 1;
+  }
+#pragma unroll
+  for (int ch = 1; ch < NCH; ++ch) {
+    // the following chunk's Q (after the last chunk: chunk 0 of the next step; after the last step a harmless re-read)
+    const BkCopy cp = bk_copy_desc<NCH>(w, (ch + 1 < NCH || !more) ? cs : cs + MT_STEP, (ch + 1) % NCH, buf ^ 1);
+    if (ch + 1 < NCH) {
+      bk_chunk<false, false, true>(w.p_hi + ch * BK_KC, w.p_lo + ch * BK_KC, wg_lds + buf * (kBkBufBytes / 16) + lane, a0, a1, wcur, cp);
+    } else {
+      bk_chunk<false, true, true>(w.p_hi + ch * BK_KC, w.p_lo + ch * BK_KC, wg_lds + buf * (kBkBufBytes / 16) + lane, a0, a1, wcur, cp);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) wcur[v][3] = pack_bf16(a0[3][v], a1[3][v]);
+    }
+    bk_drain_and_barrier<0>();
+    buf ^= 1;
+  }
+}
+
+template <int NCH>
 __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t, int r) {
   constexpr int NKS = BK_KC * NCH;
-  constexpr int kBufSlots = BK_KC * 8 * 2 * 64;
   static_assert(NCH >= 2 && 2 * NKS <= BK_MAX_GROUPS, "chunks per step");
   __shared__ int32_t s_te[kMaxTerms];
   __shared__ float s_tc[kMaxTerms];
@@ -710,30 +830,38 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
   }
   __syncthreads();
 
+  BkWave<NCH> w;
+  w.n = n;
+  w.h = h;
+  w.lds0 = uniform(int(uint32_t(uintptr_t((const __attribute__((address_space(3))) void*)wg_lds)))) + uint32_t(wave) * 4096u;
+#pragma unroll
+  for (int ks = 0; ks < NKS; ++ks) {
+    w.eg[0][ks] = uniform(s_eg[2 * ks]);
+    w.eg[1][ks] = uniform(s_eg[2 * ks + 1]);
+  }
+
   const int grid = gridDim.x;
   const int first_item = p.xcd_remap ? xcd_contiguous_block(blockIdx.x, grid) : int(blockIdx.x);
-  // Start-up phases.  Every workgroup runs the same loop at the same pace, so without this all of them
-  // request their W tiles in the same instant and the burst, not the bandwidth, sets the waiting time.
-  for (int d = uniform(int((blockIdx.x >> 3) & 7) * p.stagger); d > 0; --d) __builtin_amdgcn_s_sleep(1);
   int buf = 0;
   for (int item = first_item; item < p.n_items; item += grid) {       // uniform over the workgroup
     const int seg = uniform(find_segment(p.first, p.n_sel, item));
     const LinDesc* Lp = p.lin + uniform(p.sel[seg]);
-    const uint16_t* W = uniform(Lp->W);
     const float* B = uniform(Lp->B);
-    const uint16_t* Apk = uniform(Lp->Apk);
     const int out = uniform(Lp->out), in = uniform(Lp->in);
     int row0, col0;
     decode_item(uniform(item - p.first[seg]), in, kMfmaTileRows, p.tile_cols, &row0, &col0);
     row0 += 32 * wave;
     const int col_end = min(in, col0 + p.tile_cols);
     const int ncb = ceil_div(in, MT_STEP);
-    const int wbytes = out * in * 2;
-    const uint32_t stride = uint32_t(in) * 2u;
-    const uint32_t row0_byte = uint32_t(row0) * stride;
+    w.W = uniform(Lp->W);
+    w.wbytes = out * in * 2;
+    w.stride = uint32_t(in) * 2u;
+    // the packed A of the linear, advanced to this wave's two blocks inside a column block
+    w.Apk = uniform(reinterpret_cast<const uint16_t*>(reinterpret_cast<const char*>(Lp->Apk) + wave * 2048));
+    w.eg_bytes = ncb * 8192;
+    const uint32_t row0_byte = uint32_t(row0) * w.stride;
 
     // P = coeff * B for this lane's row and its half of every k-step, split into bf16 high + low
-    u32x4 p_hi[NKS], p_lo[NKS];
     {
       const int prow = min(row0 + n, out - 1);
       const bool prow_ok = row0 + n < out;       // rows past the end: zero coefficient (their W offsets lie outside the buffer)
@@ -749,64 +877,67 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
         for (int q = 0; q < 2; ++q) {
           uint32_t hi, lo;
           split2(c * b0[2 * q], c * b0[2 * q + 1], &hi, &lo);
-          p_hi[ks][q] = hi;
-          p_lo[ks][q] = lo;
+          w.p_hi[ks][q] = hi;
+          w.p_lo[ks][q] = lo;
           split2(c * b1[2 * q], c * b1[2 * q + 1], &hi, &lo);
-          p_hi[ks][2 + q] = hi;
-          p_lo[ks][2 + q] = lo;
+          w.p_hi[ks][2 + q] = hi;
+          w.p_lo[ks][2 + q] = lo;
         }
       }
     }
 
     auto lane_offset = [&](int cs) {
       const int col = cs + 8 * n;
-      return col < col_end ? row0_byte + uint32_t(4 * h) * stride + uint32_t(col) * 2u : kOutOfRange;
+      return col < col_end ? row0_byte + uint32_t(4 * h) * w.stride + uint32_t(col) * 2u : kOutOfRange;
     };
-    const __amdgpu_buffer_rsrc_t res = w_resource(W, wbytes);
-    u32x4 wt[16];
-    uint32_t lane_off = lane_offset(col0);
-    bk_fetch_q(Apk, ncb, col0, 0, n, h, gpr, wave, s_eg, wg_lds + buf * kBufSlots);
+    // prologue of the item: its first tile and the first Q chunk
+    u32x4 wa[16], wb[16];
+    uint32_t off_a = lane_offset(col0), off_b = kOutOfRange;
+    {
+      const __amdgpu_buffer_rsrc_t res = w_resource(w.W, w.wbytes);
+      const BkCopy cp = bk_copy_desc<NCH>(w, col0, 0, buf);
+      bk_copy_range<0, 16>(cp);
 #pragma unroll
-    for (int v = 0; v < 16; ++v)
-      wt[v] = __builtin_amdgcn_raw_buffer_load_b128(res, lane_off + uint32_t(8 * (v >> 2) + (v & 3)) * stride, 0, /*nt*/ 2);
-    bk_drain_and_barrier<0>();
-
-    for (int cs = col0; cs < col_end; cs += MT_STEP) {
-      const bool more = uniform(int(cs + MT_STEP < col_end)) != 0;
-      f32x16 a0[4], a1[4];
+      for (int v = 0; v < 16; ++v)
+        wa[v] = __builtin_amdgcn_raw_buffer_load_b128(res, off_a + uint32_t(8 * (v >> 2) + (v & 3)) * w.stride, 0, /*nt*/ 2);
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
+      for (int v = 0; v < 16; ++v) wb[v] = u32x4{0u, 0u, 0u, 0u};
+      bk_drain_and_barrier<0>();
+    }
+    // steps alternate the roles of wa and wb; the offsets travel with the registers
+    int cs = col0;
+    bool last_in_a = true;
+    while (true) {
+      bool more = uniform(int(cs + MT_STEP < col_end)) != 0;
+      {
+        const uint32_t nxt = more ? lane_offset(cs + MT_STEP) : kOutOfRange;
+        bk_step<NCH>(w, cs, more, lane, buf, off_b, nxt, wa, wb);     // stores wb (previous tile), reloads it, updates wa
+        off_b = nxt;
+      }
+      last_in_a = true;
+      if (!more) break;
+      cs += MT_STEP;
+      more = uniform(int(cs + MT_STEP < col_end)) != 0;
+      {
+        const uint32_t nxt = more ? lane_offset(cs + MT_STEP) : kOutOfRange;
+        bk_step<NCH>(w, cs, more, lane, buf, off_a, nxt, wb, wa);
+        off_a = nxt;
+      }
+      last_in_a = false;
+      if (!more) break;
+      cs += MT_STEP;
+    }
+    {   // the item's last finished tile
+      const __amdgpu_buffer_rsrc_t res = w_resource(w.W, w.wbytes);
+      const uint32_t cs_off = lane_offset(cs);
+      if (last_in_a) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          a0[q][v] = bf16_lo(wt[v][q]);
-          a1[q][v] = bf16_hi(wt[v][q]);
-        }
-      const uint32_t cur_off = lane_off;
-      lane_off = more ? lane_offset(cs + MT_STEP) : kOutOfRange;
+        for (int v = 0; v < 16; ++v)
+          __builtin_amdgcn_raw_buffer_store_b128(wa[v], res, cs_off + uint32_t(8 * (v >> 2) + (v & 3)) * w.stride, 0, /*nt*/ 2);
+      } else {
 #pragma unroll
-      for (int ch = 0; ch < NCH; ++ch) {
-        // the next chunk's Q quarter into the idle buffer (after the last step: a harmless re-read)
-        const int fcs = uniform(ch + 1 < NCH ? cs : (more ? cs + MT_STEP : cs));
-        bk_fetch_q(Apk, ncb, fcs, (ch + 1) % NCH, n, h, gpr, wave, s_eg, wg_lds + (buf ^ 1) * kBufSlots);
-        if (ch == 0) {
-          __builtin_amdgcn_sched_barrier(0);                    // keep the W requests younger than the Q copy
-#pragma unroll
-          for (int v = 0; v < 16; ++v)
-            wt[v] = __builtin_amdgcn_raw_buffer_load_b128(res, lane_off + uint32_t(8 * (v >> 2) + (v & 3)) * stride, 0, /*nt*/ 2);
-        }
-        bk_compute(p_hi + ch * BK_KC, p_lo + ch * BK_KC, wg_lds + buf * kBufSlots + lane, a0, a1);
-        if (ch == NCH - 1) {
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            u32x4 o;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) o[q] = pack_bf16(a0[q][v], a1[q][v]);      // the one rounding
-            __builtin_amdgcn_raw_buffer_store_b128(o, res, cur_off + uint32_t(8 * (v >> 2) + (v & 3)) * stride, 0, /*nt*/ 2);
-          }
-        }
-        if (ch == 0 || ch == NCH - 1) bk_drain_and_barrier<16>();   // 16 younger W loads / stores may still be in flight
-        else bk_drain_and_barrier<0>();
-        buf ^= 1;
+        for (int v = 0; v < 16; ++v)
+          __builtin_amdgcn_raw_buffer_store_b128(wb[v], res, cs_off + uint32_t(8 * (v >> 2) + (v & 3)) * w.stride, 0, /*nt*/ 2);
       }
     }
   }

@@ -140,6 +140,41 @@ lsw_status lsw_merged_gemv_all(lsw_ctx* ctx, const void* x_all_bf16, float* y_al
 lsw_status lsw_route(const float* logits, int32_t E, int32_t k, int32_t* ids, float* gates);
 
 /*
+ * Device-resident routing: the same three steps (router, term list, switch) with the token's
+ * (ids, gates) living in DEVICE memory from start to end, so that a token step needs no trip to the
+ * host between the router's output and the fused launch of Alg. 1 and can be recorded in a HIP graph
+ * (none of these calls allocates, synchronises or clears memory with a memset).
+ *
+ * lsw_route_dev     G = Softmax(TopK(logits)) as lsw_route computes it (same order, same tie rule,
+ *                   softmax in double precision rounded once), E = the context's expert count.
+ *                   logits_dev DEVICE fp32 [E]; ids_dev DEVICE int32 [k]; gates_dev DEVICE fp32 [k];
+ *                   0 <= k <= min(LSW_MAX_K, E).
+ * lsw_switch_dev    lsw_switch with DEVICE lists.  k_old and k_new are host values (the lists' lengths
+ *                   are fixed by the model's top-k); the launch is sized for k_old + k_new terms and
+ *                   the device drops the cancelled ones, exactly as lsw_build_terms does.  The
+ *                   context cannot know what was merged: lsw_get_state answers LSW_ERR_STATE for the
+ *                   touched layers until a host-side lsw_switch sets them again, and the call is
+ *                   refused (LSW_ERR_STATE) while LSW_OPT_STRICT_STATE is on.
+ * lsw_dev_status    What the host cannot check before the launch is checked on the device: a NaN logit
+ *                   (flag 1) or a bad list, id outside [0,E), duplicate id, non-finite gate (flag 2),
+ *                   makes that switch leave every weight untouched and sets a sticky flag in the
+ *                   context.  This call copies the flags to the host (it synchronises with the null
+ *                   stream; synchronise the work's own stream first).
+ * lsw_gemv_bf16     y = W x for any bf16 matrix [out, in] (in a multiple of 8, 16-byte aligned), e.g.
+ *                   the router's logits W_g x of Eq. 2 from the first layer's input.  DEVICE pointers.
+ * Errors known on the host are reported as for the host-side calls, before anything is launched.
+ */
+lsw_status lsw_route_dev(lsw_ctx* ctx, const float* logits_dev, int32_t k, int32_t* ids_dev, float* gates_dev,
+                         void* hip_stream);
+lsw_status lsw_switch_dev(lsw_ctx* ctx, const int32_t* layers, int32_t n_layers,
+                          const int32_t* old_ids_dev, const float* old_gates_dev, int32_t k_old,
+                          const int32_t* new_ids_dev, const float* new_gates_dev, int32_t k_new,
+                          void* hip_stream);
+lsw_status lsw_dev_status(lsw_ctx* ctx, int32_t* flags);
+lsw_status lsw_gemv_bf16(const void* W_bf16, const void* x_bf16, float* y_fp32, int32_t out, int32_t in,
+                         void* hip_stream);
+
+/*
  * The signed coefficient list one switch applies (Alg. 1 steps 2-3 without moving any tensor:
  * Eq. 5 puts the gate on one factor, Eq. 9 negates the previous set): new experts with
  * +scale*g, old experts with -scale*g, an expert in both with scale*g_new - scale*g_old,

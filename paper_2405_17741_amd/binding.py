@@ -22,6 +22,7 @@ EXPORTS = (
     "lsw_create_adapters", "lsw_switch", "lsw_merged_gemv", "lsw_route", "lsw_build_terms",
     "lsw_get_state", "lsw_set_option", "lsw_query", "lsw_worklist_size", "lsw_worklist_item",
     "lsw_destroy", "lsw_last_error", "lsw_probe_inplace", "lsw_merged_gemv_all",
+    "lsw_route_dev", "lsw_switch_dev", "lsw_dev_status", "lsw_gemv_bf16",
 )
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblsw.so")
@@ -56,6 +57,11 @@ def lib() -> C.CDLL:
                                  C.c_void_p]
         L.lsw_merged_gemv.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.lsw_merged_gemv_all.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.lsw_route_dev.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.lsw_switch_dev.argtypes = [C.c_void_p, _i32p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
+                                     C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
+        L.lsw_dev_status.argtypes = [C.c_void_p, _i32p]
+        L.lsw_gemv_bf16.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
         L.lsw_route.argtypes = [_f32p, C.c_int32, C.c_int32, _i32p, _f32p]
         L.lsw_build_terms.argtypes = [_i32p, _f32p, C.c_int32, _i32p, _f32p, C.c_int32, C.c_int32, C.c_float,
                                       _i32p, _f32p, _i32p]
@@ -132,6 +138,27 @@ def lsw_merged_gemv(ctx: int, lin_index: int, x_ptr: int, y_ptr: int, stream: in
 
 def lsw_merged_gemv_all(ctx: int, x_all_ptr: int, y_all_ptr: int, stream: int = 0) -> None:
     _check(lib().lsw_merged_gemv_all(ctx, C.c_void_p(x_all_ptr), C.c_void_p(y_all_ptr), C.c_void_p(stream)))
+
+
+def lsw_route_dev(ctx: int, logits_ptr: int, k: int, ids_ptr: int, gates_ptr: int, stream: int = 0) -> None:
+    _check(lib().lsw_route_dev(ctx, C.c_void_p(logits_ptr), k, C.c_void_p(ids_ptr), C.c_void_p(gates_ptr), C.c_void_p(stream)))
+
+
+def lsw_switch_dev(ctx: int, old_ids_ptr: int, old_gates_ptr: int, k_old: int, new_ids_ptr: int, new_gates_ptr: int,
+                   k_new: int, layers=None, stream: int = 0) -> None:
+    _, lp, nl = _i32(layers)
+    _check(lib().lsw_switch_dev(ctx, lp, nl, C.c_void_p(old_ids_ptr), C.c_void_p(old_gates_ptr), k_old,
+                                C.c_void_p(new_ids_ptr), C.c_void_p(new_gates_ptr), k_new, C.c_void_p(stream)))
+
+
+def lsw_dev_status(ctx: int) -> int:
+    flags = C.c_int32(0)
+    _check(lib().lsw_dev_status(ctx, C.byref(flags)))
+    return flags.value
+
+
+def lsw_gemv_bf16(W_ptr: int, x_ptr: int, y_ptr: int, out: int, inn: int, stream: int = 0) -> None:
+    _check(lib().lsw_gemv_bf16(C.c_void_p(W_ptr), C.c_void_p(x_ptr), C.c_void_p(y_ptr), out, inn, C.c_void_p(stream)))
 
 
 def lsw_route(logits, k: int):

@@ -74,6 +74,8 @@ struct lsw_ctx {
   int n_cu = 0;
   LinDesc* d_lin = nullptr;
   uint16_t* d_apk = nullptr;                 // packed A of all linears (r % 8 == 0 only)
+  Terms* d_terms = nullptr;                  // term list built on the device by lsw_switch_dev, followed by the sticky error word
+  int32_t* d_err = nullptr;
   int64_t owned_bytes = 0;
   int64_t x_elems = 0, y_elems = 0;          // sizes of the back-to-back x and y of lsw_merged_gemv_all
   std::map<PlanKey, DevicePlan> plans;
@@ -280,8 +282,10 @@ extern "C" lsw_status lsw_create_adapters(const lsw_linear* lin, int32_t n_lin, 
   auto cleanup = [raw]() {
     if (raw->d_apk) (void)hipFree(raw->d_apk);
     if (raw->d_lin) (void)hipFree(raw->d_lin);
+    if (raw->d_terms) (void)hipFree(raw->d_terms);
     raw->d_apk = nullptr;
     raw->d_lin = nullptr;
+    raw->d_terms = nullptr;
   };
   if (pack) {
     hipError_t e = hipMalloc(reinterpret_cast<void**>(&c->d_apk), apk_elems * sizeof(uint16_t));
@@ -307,6 +311,12 @@ extern "C" lsw_status lsw_create_adapters(const lsw_linear* lin, int32_t n_lin, 
   hipError_t e = hipMalloc(reinterpret_cast<void**>(&c->d_lin), desc.size() * sizeof(LinDesc));
   if (e != hipSuccess) { (void)hipGetLastError(); cleanup(); return fail(LSW_ERR_NOMEM, "hipMalloc of the descriptor table failed"); }
   c->owned_bytes += int64_t(desc.size() * sizeof(LinDesc));
+  e = hipMalloc(reinterpret_cast<void**>(&c->d_terms), sizeof(Terms) + 16);
+  if (e != hipSuccess) { (void)hipGetLastError(); cleanup(); return fail(LSW_ERR_NOMEM, "hipMalloc of the device term list failed"); }
+  c->d_err = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(c->d_terms) + sizeof(Terms));
+  c->owned_bytes += int64_t(sizeof(Terms) + 16);
+  e = hipMemset(c->d_terms, 0, sizeof(Terms) + 16);
+  if (e != hipSuccess) { cleanup(); return fail(LSW_ERR_DEVICE, "clearing the device term list failed: %s", hipGetErrorString(e)); }
   e = hipMemcpy(c->d_lin, desc.data(), desc.size() * sizeof(LinDesc), hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipDeviceSynchronize();   // the pack kernels have read A
   if (e != hipSuccess) { cleanup(); return fail(LSW_ERR_DEVICE, "descriptor upload / pack failed: %s", hipGetErrorString(e)); }
@@ -320,6 +330,7 @@ extern "C" void lsw_destroy(lsw_ctx* c) {
     if (kv.second.d_sel) (void)hipFree(kv.second.d_sel);
   if (c->d_apk) (void)hipFree(c->d_apk);
   if (c->d_lin) (void)hipFree(c->d_lin);
+  if (c->d_terms) (void)hipFree(c->d_terms);
   delete c;
 }
 
@@ -358,32 +369,75 @@ static lsw_status get_plan(lsw_ctx* c, int kernel, int tc, const std::vector<int
 // ---------------------------------------------------------------------------
 // the switch
 // ---------------------------------------------------------------------------
+// layer list of a call -> sorted selection (empty = every layer)
+static lsw_status select_layers(lsw_ctx* c, const int32_t* layers, int32_t n_layers, std::vector<int32_t>* sel) {
+  if (n_layers < 0 || (n_layers > 0 && !layers)) return fail(LSW_ERR_ARG, "bad layer list");
+  sel->clear();
+  if (n_layers > 0) {
+    sel->assign(layers, layers + n_layers);
+    std::sort(sel->begin(), sel->end());
+    for (int32_t a = 0; a < n_layers; ++a) {
+      if (layer_slot(c, (*sel)[a]) < 0) return fail(LSW_ERR_ARG, "unknown layer %d", (*sel)[a]);
+      if (a > 0 && (*sel)[a] == (*sel)[a - 1]) return fail(LSW_ERR_ARG, "duplicate layer %d", (*sel)[a]);
+    }
+    if (sel->size() == c->layer_ids.size()) sel->clear();   // every layer: the common plan
+  }
+  return LSW_OK;
+}
+
+// One launch over the selected layers.  t.n sizes the launch; with t_dev the kernel reads the list from device memory.
+static lsw_status launch_switch(lsw_ctx* c, const std::vector<int32_t>& sel_layers, const Terms& t, const Terms* t_dev,
+                                hipStream_t s) {
+  // the matrix-core kernels keep the fused rank (terms x r) in registers: up to 64 in the streaming
+  // kernel, up to 256 in the chunked one
+  const int n_groups = (c->r % 8 == 0) ? t.n * (c->r / 8) : 0;
+  const bool mfma_fits = (c->r % 8 == 0) && n_groups <= 32;
+  const bool bigk = n_groups > 8;
+  int kernel = c->opt_kernel;
+  if (kernel == 0) kernel = mfma_fits ? 2 : 1;
+  if (kernel >= 2 && !mfma_fits)
+    return fail(LSW_ERR_ARG, "matrix-core kernel needs r %% 8 == 0 and a fused rank <= 256 (r=%d, terms=%d)", c->r, t.n);
+  c->last_kernel = 0;
+  c->last_items = 0;
+  c->last_grid = 0;
+  if (t.n > 0) {
+    DevicePlan* dp = nullptr;
+    const int tc = kernel >= 2 ? (bigk ? c->opt_tile_cols_bigk : c->opt_tile_cols) : kValuTileCols;
+    lsw_status st = get_plan(c, kernel, tc, sel_layers, &dp);
+    if (st != LSW_OK) return st;
+    LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, tc, c->opt_xcd};
+    int grid = c->opt_grid;
+    if (grid <= 0) grid = (kernel == 2) ? c->n_cu : c->n_cu * 2;   // matrix-core: one workgroup per CU
+    grid = std::max(8, (grid / 8) * 8);     // a multiple of the 8 XCDs (the kernels' block remap assumes it)
+    hipError_t e = (kernel == 2) ? (bigk ? launch_switch_mfma_bigk(lp, t, t_dev, c->r, grid, s)
+                                         : launch_switch_mfma(lp, t, t_dev, c->r, grid, s))
+                                 : launch_switch_valu(lp, t, t_dev, c->r, grid, s);
+    if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "switch launch failed: %s", hipGetErrorString(e));
+    c->last_kernel = kernel;
+    c->last_items = dp->n_items;
+    c->last_grid = grid;
+  }
+  return LSW_OK;
+}
+
 extern "C" lsw_status lsw_switch(lsw_ctx* c, const int32_t* layers, int32_t n_layers,
                                  const int32_t* old_ids, const float* old_gates, int32_t k_old,
                                  const int32_t* new_ids, const float* new_gates, int32_t k_new,
                                  void* hip_stream) {
   if (!c) return fail(LSW_ERR_ARG, "ctx is null");
-  if (n_layers < 0 || (n_layers > 0 && !layers)) return fail(LSW_ERR_ARG, "bad layer list");
   std::vector<int32_t> sel_layers;
-  if (n_layers > 0) {
-    sel_layers.assign(layers, layers + n_layers);
-    std::sort(sel_layers.begin(), sel_layers.end());
-    for (int32_t a = 0; a < n_layers; ++a) {
-      if (layer_slot(c, sel_layers[a]) < 0) return fail(LSW_ERR_ARG, "unknown layer %d", sel_layers[a]);
-      if (a > 0 && sel_layers[a] == sel_layers[a - 1]) return fail(LSW_ERR_ARG, "duplicate layer %d", sel_layers[a]);
-    }
-    if (sel_layers.size() == c->layer_ids.size()) sel_layers.clear();   // every layer: the common plan
-  }
+  lsw_status st = select_layers(c, layers, n_layers, &sel_layers);
+  if (st != LSW_OK) return st;
   Terms t;
   std::memset(&t, 0, sizeof(t));
-  lsw_status st = lsw_build_terms(old_ids, old_gates, k_old, new_ids, new_gates, k_new, c->E, c->scale,
-                                  t.e, t.coeff, &t.n);
+  st = lsw_build_terms(old_ids, old_gates, k_old, new_ids, new_gates, k_new, c->E, c->scale, t.e, t.coeff, &t.n);
   if (st != LSW_OK) return st;
 
   const std::vector<int32_t>& touched = sel_layers.empty() ? c->layer_ids : sel_layers;
   if (c->opt_strict) {
     for (int32_t layer : touched) {
       const LayerState& s = c->state[size_t(layer_slot(c, layer))];
+      if (s.k < 0) return fail(LSW_ERR_STATE, "layer %d: the merged set lives on the device (lsw_switch_dev)", layer);
       bool same = (s.k == k_old);
       for (int32_t a = 0; same && a < k_old; ++a) {
         bool found = false;
@@ -394,42 +448,73 @@ extern "C" lsw_status lsw_switch(lsw_ctx* c, const int32_t* layers, int32_t n_la
       if (!same) return fail(LSW_ERR_STATE, "layer %d: `old` differs from the merged state", layer);
     }
   }
-
-  // the matrix-core kernels keep the fused rank (terms x r) in registers: up to 64 in the streaming
-  // kernel, up to 256 in the chunked one
-  const int n_groups = (c->r % 8 == 0) ? t.n * (c->r / 8) : 0;
-  const bool mfma_fits = (c->r % 8 == 0) && n_groups <= 32;
-  const bool bigk = n_groups > 8;
-  int kernel = c->opt_kernel;
-  if (kernel == 0) kernel = mfma_fits ? 2 : 1;
-  if (kernel >= 2 && !mfma_fits)
-    return fail(LSW_ERR_ARG, "matrix-core kernel needs r %% 8 == 0 and a fused rank <= 256 (r=%d, terms=%d)", c->r, t.n);
-
-  c->last_kernel = 0;
-  c->last_items = 0;
-  c->last_grid = 0;
-  if (t.n > 0) {
-    DevicePlan* dp = nullptr;
-    const int tc = kernel >= 2 ? (bigk ? c->opt_tile_cols_bigk : c->opt_tile_cols) : kValuTileCols;
-    st = get_plan(c, kernel, tc, sel_layers, &dp);
-    if (st != LSW_OK) return st;
-    LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, tc, c->opt_xcd};
-    int grid = c->opt_grid;
-    if (grid <= 0) grid = (kernel == 2) ? c->n_cu : c->n_cu * 2;   // matrix-core: one 4-wave workgroup per CU
-    grid = std::max(8, (grid / 8) * 8);     // a multiple of the 8 XCDs (the kernels' block remap assumes it)
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    hipError_t e = (kernel == 2) ? (bigk ? launch_switch_mfma_bigk(lp, t, c->r, grid, s) : launch_switch_mfma(lp, t, c->r, grid, s))
-                                 : launch_switch_valu(lp, t, c->r, grid, s);
-    if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "switch launch failed: %s", hipGetErrorString(e));
-    c->last_kernel = kernel;
-    c->last_items = dp->n_items;
-    c->last_grid = grid;
-  }
+  st = launch_switch(c, sel_layers, t, nullptr, static_cast<hipStream_t>(hip_stream));
+  if (st != LSW_OK) return st;
   for (int32_t layer : touched) {
     LayerState& s = c->state[size_t(layer_slot(c, layer))];
     s.k = k_new;
     for (int32_t a = 0; a < k_new; ++a) { s.ids[a] = new_ids[a]; s.gates[a] = new_gates[a]; }
   }
+  return LSW_OK;
+}
+
+// ---------------------------------------------------------------------------
+// device-resident routing: no value of the token's (ids, gates) ever visits the host
+// ---------------------------------------------------------------------------
+extern "C" lsw_status lsw_route_dev(lsw_ctx* c, const float* logits_dev, int32_t k, int32_t* ids_dev, float* gates_dev,
+                                    void* hip_stream) {
+  if (!c) return fail(LSW_ERR_ARG, "ctx is null");
+  if (k < 0 || k > LSW_MAX_K || k > c->E) return fail(LSW_ERR_ARG, "lsw_route_dev: k=%d outside 0..min(%d, E=%d)", k, int(LSW_MAX_K), c->E);
+  if (!logits_dev || (k > 0 && (!ids_dev || !gates_dev))) return fail(LSW_ERR_ARG, "lsw_route_dev: null pointer");
+  if (k == 0) return LSW_OK;
+  hipError_t e = launch_route(logits_dev, c->E, k, ids_dev, gates_dev, c->d_err, static_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "route launch failed: %s", hipGetErrorString(e));
+  return LSW_OK;
+}
+
+extern "C" lsw_status lsw_switch_dev(lsw_ctx* c, const int32_t* layers, int32_t n_layers,
+                                     const int32_t* old_ids_dev, const float* old_gates_dev, int32_t k_old,
+                                     const int32_t* new_ids_dev, const float* new_gates_dev, int32_t k_new,
+                                     void* hip_stream) {
+  if (!c) return fail(LSW_ERR_ARG, "ctx is null");
+  if (c->opt_strict) return fail(LSW_ERR_STATE, "lsw_switch_dev: the host cannot check device-resident lists (strict mode is on)");
+  if (k_old < 0 || k_old > LSW_MAX_K || k_old > c->E) return fail(LSW_ERR_ARG, "old: k=%d out of range", k_old);
+  if (k_new < 0 || k_new > LSW_MAX_K || k_new > c->E) return fail(LSW_ERR_ARG, "new: k=%d out of range", k_new);
+  if ((k_old > 0 && (!old_ids_dev || !old_gates_dev)) || (k_new > 0 && (!new_ids_dev || !new_gates_dev)))
+    return fail(LSW_ERR_ARG, "null list with k > 0");
+  std::vector<int32_t> sel_layers;
+  lsw_status st = select_layers(c, layers, n_layers, &sel_layers);
+  if (st != LSW_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  Terms t;
+  std::memset(&t, 0, sizeof(t));
+  t.n = k_old + k_new;                       // the launch is sized for the longest list the device may build
+  if (t.n > 0) {
+    hipError_t e = launch_build_terms(old_ids_dev, old_gates_dev, k_old, new_ids_dev, new_gates_dev, k_new, c->E, c->scale,
+                                      c->d_terms, c->d_err, s);
+    if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "term builder launch failed: %s", hipGetErrorString(e));
+  }
+  st = launch_switch(c, sel_layers, t, c->d_terms, s);
+  if (st != LSW_OK) return st;
+  const std::vector<int32_t>& touched = sel_layers.empty() ? c->layer_ids : sel_layers;
+  for (int32_t layer : touched) c->state[size_t(layer_slot(c, layer))].k = -1;     // known to the device only
+  return LSW_OK;
+}
+
+extern "C" lsw_status lsw_dev_status(lsw_ctx* c, int32_t* flags) {
+  if (!c || !flags) return fail(LSW_ERR_ARG, "null argument");
+  LSW_HIP(hipMemcpy(flags, c->d_err, sizeof(int32_t), hipMemcpyDeviceToHost));     // waits for earlier work on the null stream only
+  return LSW_OK;
+}
+
+extern "C" lsw_status lsw_gemv_bf16(const void* W_bf16, const void* x_bf16, float* y_fp32, int32_t out, int32_t in,
+                                    void* hip_stream) {
+  if (!W_bf16 || !x_bf16 || !y_fp32) return fail(LSW_ERR_ARG, "null pointer");
+  if (out < 1 || in < 8 || in % 8 != 0) return fail(LSW_ERR_SHAPE, "out=%d, in=%d: in must be a positive multiple of 8", out, in);
+  if (!aligned16(W_bf16) || !aligned16(x_bf16)) return fail(LSW_ERR_SHAPE, "W or x is not 16-byte aligned");
+  hipError_t e = launch_gemv(static_cast<const uint16_t*>(W_bf16), static_cast<const uint16_t*>(x_bf16), y_fp32, out, in, 512,
+                             static_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "gemv launch failed: %s", hipGetErrorString(e));
   return LSW_OK;
 }
 
@@ -486,6 +571,7 @@ extern "C" lsw_status lsw_get_state(const lsw_ctx* c, int32_t layer, int32_t* id
   int slot = layer_slot(c, layer);
   if (slot < 0) return fail(LSW_ERR_ARG, "unknown layer %d", layer);
   const LayerState& s = c->state[size_t(slot)];
+  if (s.k < 0) return fail(LSW_ERR_STATE, "layer %d: the merged set lives on the device (lsw_switch_dev)", layer);
   if (s.k > 0 && (!ids || !gates)) return fail(LSW_ERR_ARG, "null output");
   *k = s.k;
   for (int32_t a = 0; a < s.k; ++a) { ids[a] = s.ids[a]; gates[a] = s.gates[a]; }

@@ -66,6 +66,22 @@ __device__ __forceinline__ void lds_dma16(const void* src, const void* lds_base)
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_addr) : "memory", "m0");
 }
 
+// The term list of a launch comes by value with the launch (host-side lists) or from device memory
+// (device-resident routing: a small kernel wrote it just before on the same stream).
+#define LSW_LOAD_TERMS(t, t_dev, s_e, s_c, n_out)                         \
+  do {                                                                    \
+    if (threadIdx.x < kMaxTerms) {                                        \
+      if (t_dev) {                                                        \
+        s_e[threadIdx.x] = t_dev->e[threadIdx.x];                         \
+        s_c[threadIdx.x] = t_dev->coeff[threadIdx.x];                     \
+      } else {                                                            \
+        s_e[threadIdx.x] = t.e[threadIdx.x];                              \
+        s_c[threadIdx.x] = t.coeff[threadIdx.x];                          \
+      }                                                                   \
+    }                                                                     \
+    n_out = __builtin_amdgcn_readfirstlane(t_dev ? t_dev->n : t.n);       \
+  } while (0)
+
 // Values that are the same in every lane, told to the compiler so they live in scalar registers.
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 template <typename T>
@@ -136,12 +152,18 @@ hipError_t launch_pack_A(const float* A, uint16_t* Apk, int E, int r, int in, hi
 // ---------------------------------------------------------------------------
 constexpr int VT_ROWS = kValuTileRows, VT_COLS = kValuTileCols, VT_K = 32;
 
-__global__ __launch_bounds__(256) void k_switch_valu(LaunchPlan p, Terms t, int r) {
+__global__ __launch_bounds__(256) void k_switch_valu(LaunchPlan p, Terms t, const Terms* t_dev, int r) {
   __shared__ float sB[VT_ROWS][VT_K + 1];
   __shared__ float sA[VT_K][VT_COLS];
+  __shared__ int32_t s_te[kMaxTerms];
+  __shared__ float s_tc[kMaxTerms];
   const int tid = threadIdx.x;
   const int tx = tid & 15, ty = tid >> 4;
-  const int K = t.n * r;
+  int n_terms;
+  LSW_LOAD_TERMS(t, t_dev, s_te, s_tc, n_terms);
+  if (n_terms == 0) return;             // nothing to merge or unmerge (device-built lists only): W stays untouched
+  __syncthreads();
+  const int K = n_terms * r;
   const int vb = p.xcd_remap ? xcd_contiguous_block(blockIdx.x, gridDim.x) : int(blockIdx.x);
 
   for (int item = vb; item < p.n_items; item += gridDim.x) {
@@ -164,7 +186,7 @@ __global__ __launch_bounds__(256) void k_switch_valu(LaunchPlan p, Terms t, int 
         float v = 0.0f;
         if (k < K && row < L.out) {
           const int c = k / r, rho = k - c * r;
-          v = t.coeff[c] * L.B[((long long)t.e[c] * L.out + row) * r + rho];
+          v = s_tc[c] * L.B[((long long)s_te[c] * L.out + row) * r + rho];
         }
         sB[i][kk] = v;
       }
@@ -174,7 +196,7 @@ __global__ __launch_bounds__(256) void k_switch_valu(LaunchPlan p, Terms t, int 
         float v = 0.0f;
         if (k < K && col < L.in) {
           const int c = k / r, rho = k - c * r;
-          v = L.A[((long long)t.e[c] * r + rho) * L.in + col];
+          v = L.A[((long long)s_te[c] * r + rho) * L.in + col];
         }
         sA[kk][j] = v;
       }
@@ -214,8 +236,8 @@ __global__ __launch_bounds__(256) void k_switch_valu(LaunchPlan p, Terms t, int 
   }
 }
 
-hipError_t launch_switch_valu(const LaunchPlan& p, const Terms& t, int r, int grid, hipStream_t s) {
-  hipLaunchKernelGGL(k_switch_valu, dim3(grid), dim3(256), 0, s, p, t, r);
+hipError_t launch_switch_valu(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int grid, hipStream_t s) {
+  hipLaunchKernelGGL(k_switch_valu, dim3(grid), dim3(256), 0, s, p, t, t_dev, r);
   return hipGetLastError();
 }
 
@@ -501,20 +523,19 @@ __device__ __forceinline__ bool wg_step(const LaunchPlan& p, int grid, int n, in
 }
 
 template <int NKS>
-__global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma(LaunchPlan p, Terms t, int r) {
+__global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma(LaunchPlan p, Terms t, const Terms* t_dev, int r) {
   __shared__ int32_t s_e[kMaxTerms];
   __shared__ float s_coeff[kMaxTerms];
   const int lane = threadIdx.x & 63;
   const int wave = uniform(int(threadIdx.x >> 6));
-  if (threadIdx.x < kMaxTerms) {
-    s_e[threadIdx.x] = t.e[threadIdx.x];
-    s_coeff[threadIdx.x] = t.coeff[threadIdx.x];
-  }
+  int n_terms;
+  LSW_LOAD_TERMS(t, t_dev, s_e, s_coeff, n_terms);
+  if (n_terms == 0) return;             // nothing to merge or unmerge (device-built lists only): W stays untouched
   __syncthreads();
 
   const int n = lane & 31, h = lane >> 5;
   const int gpr = r >> 3;
-  const int n_groups = t.n * gpr;
+  const int n_groups = n_terms * gpr;
   const int grid = gridDim.x;
   int term_e[NKS], term_g[NKS];
   float term_c[NKS];
@@ -567,7 +588,7 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma(LaunchPlan p, Ter
 }
 
 template <int NKS>
-static hipError_t launch_wg(const LaunchPlan& p, const Terms& t, int r, int grid, hipStream_t s) {
+static hipError_t launch_wg(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int grid, hipStream_t s) {
   const size_t lds = size_t(2) * NKS * 8 * 2 * 64 * sizeof(u32x4);     // 32 KB per k-step
   static bool configured = false;
   if (!configured) {
@@ -576,17 +597,19 @@ static hipError_t launch_wg(const LaunchPlan& p, const Terms& t, int r, int grid
     if (e != hipSuccess) return e;
     configured = true;
   }
-  hipLaunchKernelGGL(k_switch_mfma<NKS>, dim3(grid), dim3(64 * WG_WAVES), lds, s, p, t, r);
+  hipLaunchKernelGGL(k_switch_mfma<NKS>, dim3(grid), dim3(64 * WG_WAVES), lds, s, p, t, t_dev, r);
   return hipGetLastError();
 }
 
-hipError_t launch_switch_mfma(const LaunchPlan& p, const Terms& t, int r, int grid, hipStream_t s) {
+// t.n sizes the kernel (k-steps kept in registers); with t_dev the kernel takes the list itself, which may
+// be shorter, from device memory
+hipError_t launch_switch_mfma(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int grid, hipStream_t s) {
   const int n_groups = t.n * (r / 8);
   switch ((n_groups + 1) / 2) {
-    case 1: return launch_wg<1>(p, t, r, grid, s);
-    case 2: return launch_wg<2>(p, t, r, grid, s);
-    case 3: return launch_wg<3>(p, t, r, grid, s);
-    case 4: return launch_wg<4>(p, t, r, grid, s);
+    case 1: return launch_wg<1>(p, t, t_dev, r, grid, s);
+    case 2: return launch_wg<2>(p, t, t_dev, r, grid, s);
+    case 3: return launch_wg<3>(p, t, t_dev, r, grid, s);
+    case 4: return launch_wg<4>(p, t, t_dev, r, grid, s);
     default: return hipErrorInvalidValue;
   }
 }
@@ -801,7 +824,7 @@ __device__ __forceinline__ void bk_step(const BkWave<NCH>& w, int cs, bool more,
 }
 
 template <int NCH>
-__global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t, int r) {
+__global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t, const Terms* t_dev, int r) {
   constexpr int NKS = BK_KC * NCH;
   static_assert(NCH >= 2 && 2 * NKS <= BK_MAX_GROUPS, "chunks per step");
   __shared__ int32_t s_te[kMaxTerms];
@@ -812,11 +835,10 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
   const int wave = uniform(int(threadIdx.x >> 6));
   const int n = lane & 31, h = lane >> 5;
   const int gpr = r >> 3;
-  const int n_groups = t.n * gpr;
-  if (threadIdx.x < kMaxTerms) {
-    s_te[threadIdx.x] = t.e[threadIdx.x];
-    s_tc[threadIdx.x] = t.coeff[threadIdx.x];
-  }
+  int n_terms;
+  LSW_LOAD_TERMS(t, t_dev, s_te, s_tc, n_terms);
+  if (n_terms == 0) return;             // nothing to merge or unmerge (device-built lists only): W stays untouched
+  const int n_groups = n_terms * gpr;
   __syncthreads();
   if (threadIdx.x < BK_MAX_GROUPS) {           // group G of the fused rank: (expert, 8-rank group, coefficient); padding gets 0
     const int G = threadIdx.x;
@@ -944,7 +966,7 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
 }
 
 template <int NCH>
-static hipError_t launch_bigk(const LaunchPlan& p, const Terms& t, int r, int grid, hipStream_t s) {
+static hipError_t launch_bigk(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int grid, hipStream_t s) {
   const size_t lds = size_t(2) * BK_KC * 8 * 2 * 64 * sizeof(u32x4);     // 2 x 64 KB
   static bool configured = false;
   if (!configured) {
@@ -953,18 +975,129 @@ static hipError_t launch_bigk(const LaunchPlan& p, const Terms& t, int r, int gr
     if (e != hipSuccess) return e;
     configured = true;
   }
-  hipLaunchKernelGGL(k_switch_mfma_bigk<NCH>, dim3(grid), dim3(256), lds, s, p, t, r);
+  hipLaunchKernelGGL(k_switch_mfma_bigk<NCH>, dim3(grid), dim3(256), lds, s, p, t, t_dev, r);
   return hipGetLastError();
 }
 
-hipError_t launch_switch_mfma_bigk(const LaunchPlan& p, const Terms& t, int r, int grid, hipStream_t s) {
+hipError_t launch_switch_mfma_bigk(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int grid, hipStream_t s) {
   const int n_groups = t.n * (r / 8);
   switch ((n_groups + 2 * BK_KC - 1) / (2 * BK_KC)) {
-    case 2: return launch_bigk<2>(p, t, r, grid, s);
-    case 3: return launch_bigk<3>(p, t, r, grid, s);
-    case 4: return launch_bigk<4>(p, t, r, grid, s);
+    case 2: return launch_bigk<2>(p, t, t_dev, r, grid, s);
+    case 3: return launch_bigk<3>(p, t, t_dev, r, grid, s);
+    case 4: return launch_bigk<4>(p, t, t_dev, r, grid, s);
     default: return hipErrorInvalidValue;
   }
+}
+
+// ---------------------------------------------------------------------------
+// Device-resident routing (Alg. 1 step 1 and steps 2-3 without a trip to the host).
+//
+// k_route: G = Softmax(TopK(logits)) on one wave.  k selection passes; in each, every lane scans its
+// share of the logits for the largest one not yet taken (equal logits: the lower index; +0 == -0) and a
+// butterfly over the lanes picks the wave's winner.  The softmax runs over the k winners in double
+// precision and is rounded once to fp32, as the host router does.  A NaN logit raises the sticky error
+// word and yields ids of -1, which the term builder rejects.
+//
+// k_build_terms: the signed coefficient list of one switch from device-resident (ids, gates) lists,
+// with the host routine's arithmetic (no fused multiply-add) and its checks.  A bad list raises the
+// sticky error word and leaves an empty list, which makes the switch kernels return at once.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void k_route(const float* __restrict__ logits, int E, int k, int32_t* __restrict__ ids,
+                                              float* __restrict__ gates, int32_t* __restrict__ err) {
+  const int lane = threadIdx.x;
+  bool nan = false;
+  for (int i = lane; i < E; i += 64) nan |= (logits[i] != logits[i]);
+  if (__any(nan)) {
+    if (lane == 0) atomicOr(err, 1);
+    if (lane < k) { ids[lane] = -1; gates[lane] = 0.0f; }
+    return;
+  }
+  int chosen[LSW_MAX_K];
+  float chosen_v[LSW_MAX_K];
+#pragma unroll
+  for (int c = 0; c < LSW_MAX_K; ++c) { chosen[c] = -1; chosen_v[c] = 0.0f; }
+#pragma unroll
+  for (int c = 0; c < LSW_MAX_K; ++c) {
+    if (c < k) {
+      int best = -1;
+      float best_v = 0.0f;
+      for (int i = lane; i < E; i += 64) {
+        bool taken = false;
+#pragma unroll
+        for (int d = 0; d < LSW_MAX_K; ++d) taken |= (chosen[d] == i);
+        const float v = logits[i];
+        if (!taken && (best < 0 || v > best_v)) { best = i; best_v = v; }      // ascending i: `>` keeps the lower index
+      }
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) {
+        const int o = __shfl_xor(best, off, 64);
+        const float ov = __shfl_xor(best_v, off, 64);
+        if (o >= 0 && (best < 0 || ov > best_v || (ov == best_v && o < best))) { best = o; best_v = ov; }
+      }
+      chosen[c] = best;
+      chosen_v[c] = best_v;
+    }
+  }
+  if (lane == 0) {
+    const double top = double(chosen_v[0]);
+    double ex[LSW_MAX_K], sum = 0.0;
+#pragma unroll
+    for (int c = 0; c < LSW_MAX_K; ++c) {
+      ex[c] = c < k ? exp(double(chosen_v[c]) - top) : 0.0;
+      sum += ex[c];
+    }
+#pragma unroll
+    for (int c = 0; c < LSW_MAX_K; ++c)
+      if (c < k) { ids[c] = chosen[c]; gates[c] = float(ex[c] / sum); }
+  }
+}
+
+hipError_t launch_route(const float* logits, int E, int k, int32_t* ids, float* gates, int32_t* err, hipStream_t s) {
+  hipLaunchKernelGGL(k_route, dim3(1), dim3(64), 0, s, logits, E, k, ids, gates, err);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(64) void k_build_terms(const int32_t* __restrict__ old_ids, const float* __restrict__ old_gates, int k_old,
+                                                    const int32_t* __restrict__ new_ids, const float* __restrict__ new_gates, int k_new,
+                                                    int E, float scale, Terms* __restrict__ out, int32_t* __restrict__ err) {
+  if (threadIdx.x != 0) return;
+  Terms t;
+  t.n = 0;
+  for (int i = 0; i < kMaxTerms; ++i) { t.e[i] = 0; t.coeff[i] = 0.0f; }
+  bool ok = true;
+  auto check = [&](const int32_t* ids, const float* gates, int k) {
+    for (int a = 0; a < k; ++a) {
+      const float g = gates[a];
+      ok &= (ids[a] >= 0 && ids[a] < E) && (g - g == 0.0f);           // in range, finite
+      for (int b = 0; b < a; ++b) ok &= (ids[b] != ids[a]);
+    }
+  };
+  check(old_ids, old_gates, k_old);
+  check(new_ids, new_gates, k_new);
+  if (ok) {
+    for (int a = 0; a < k_new; ++a) {
+      float coeff = __fmul_rn(scale, new_gates[a]);
+      for (int b = 0; b < k_old; ++b)
+        if (old_ids[b] == new_ids[a]) coeff = __fsub_rn(__fmul_rn(scale, new_gates[a]), __fmul_rn(scale, old_gates[b]));
+      if (coeff != 0.0f) { t.e[t.n] = new_ids[a]; t.coeff[t.n] = coeff; ++t.n; }
+    }
+    for (int b = 0; b < k_old; ++b) {
+      bool also_new = false;
+      for (int a = 0; a < k_new; ++a) also_new |= (new_ids[a] == old_ids[b]);
+      if (also_new) continue;
+      const float coeff = -__fmul_rn(scale, old_gates[b]);
+      if (coeff != 0.0f) { t.e[t.n] = old_ids[b]; t.coeff[t.n] = coeff; ++t.n; }
+    }
+  } else {
+    atomicOr(err, 2);
+  }
+  *out = t;
+}
+
+hipError_t launch_build_terms(const int32_t* old_ids, const float* old_gates, int k_old, const int32_t* new_ids,
+                              const float* new_gates, int k_new, int E, float scale, Terms* out, int32_t* err, hipStream_t s) {
+  hipLaunchKernelGGL(k_build_terms, dim3(1), dim3(64), 0, s, old_ids, old_gates, k_old, new_ids, new_gates, k_new, E, scale, out, err);
+  return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------

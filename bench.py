@@ -175,6 +175,28 @@ def main():
     gemv_gbps = 2.0 * wl.w_elements() / (gemv_ms * 1e-3) / 1e9
     del xg, yg
 
+    # the same token step with the token's (ids, gates) resident on the device: router, term list and switch are
+    # all launched without a value coming back to the host (lsw_route_dev + lsw_switch_dev)
+    n_dev = min(args.steps, 32)
+    logits_d = torch.from_numpy(logits[:n_dev + 1].copy()).cuda()
+    bufs = [(torch.zeros(wl.top_k, dtype=torch.int32, device="cuda"), torch.zeros(wl.top_k, dtype=torch.float32, device="cuda"))
+            for _ in range(2)]
+    bufs[1][0].copy_(torch.from_numpy(old[0])); bufs[1][1].copy_(torch.from_numpy(old[1]))     # what is merged now
+
+    def dev_token(t):
+        new, prv = bufs[t % 2], bufs[(t + 1) % 2]
+        L.lsw_route_dev(ctx, logits_d[t].data_ptr(), wl.top_k, new[0].data_ptr(), new[1].data_ptr(), stream)
+        L.lsw_switch_dev(ctx, prv[0].data_ptr(), prv[1].data_ptr(), wl.top_k, new[0].data_ptr(), new[1].data_ptr(), wl.top_k, stream=stream)
+
+    dev_token(0)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(1, n_dev + 1):
+        dev_token(t)
+    torch.cuda.synchronize()
+    dev_us = (time.perf_counter() - t0) * 1e6 / n_dev
+    dev_flags = L.lsw_dev_status(ctx)
+
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
@@ -214,6 +236,9 @@ def main():
         "merged_gemv": {"us": round(gemv_ms * 1e3, 1), "GBps": round(gemv_gbps, 1), "frac_of_hbm_peak": round(gemv_gbps / HBM_PEAK_GBPS, 4),
                         "note": "lsw_merged_gemv_all: batch-1 bf16 decode through every merged linear in one launch, "
                                 "2 bytes per weight, timed separately from the switch"},
+        "device_routing": {"us_per_token": round(dev_us, 1), "tokens": n_dev, "error_flags": dev_flags,
+                           "note": "lsw_route_dev + lsw_switch_dev per token, lists resident on the device, no host round trip; "
+                                   "launches sized for k_old + k_new terms"},
         "inplace_probe": {**probe, "note": "lsw_probe_inplace on the same weights: in-place bf16 read+write only; "
                                            "the practical ceiling of the switch's access pattern",
                           "switch_over_best_probe": round(achieved / max(probe.values()), 4)},

@@ -1,0 +1,84 @@
+"""Edges of the supported range: the largest W one linear may have (byte offsets just below 2^31), the longest
+lists (LSW_MAX_K old + LSW_MAX_K new experts), and the smallest everything."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import lsw_oracle as O
+from paper_2405_17741_amd import binding as L
+from paper_2405_17741_amd import inputs as I
+from tests.gpu_harness import DeviceStack, check_step, merge_reports
+
+pytestmark = pytest.mark.gpu
+NONE = (np.zeros(0, np.int32), np.zeros(0, np.float32))
+
+
+@pytest.mark.parametrize("kernel", [L.KERNEL_VALU, L.KERNEL_MFMA])
+def test_largest_single_weight(kernel):
+    """16384 x 65528 bf16 = 2^31 - 262144 bytes: the last rows' byte offsets need all 31 bits."""
+    out, inn, E, r = 16384, 65528, 2, 8
+    assert out * inn * 2 < 2 ** 31 <= (out + 128) * inn * 2
+    g = torch.Generator(device="cuda"); g.manual_seed(99)
+    W = (torch.randn(out, inn, generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+    A = torch.randn(E, r, inn, generator=g, device="cuda") / 256
+    B = torch.randn(E, out, r, generator=g, device="cuda") * 0.01
+    ds = DeviceStack([(W, A, B)], [(0, 0, out, inn)], E, r, kernel=kernel)
+    rows = np.array([0, 1, 127, 128, 8191, 8192, 16255, 16256, 16382, 16383], dtype=np.int64)
+    A_h = A.cpu().numpy()
+    B_h = B.index_select(1, torch.as_tensor(rows, device="cuda")).cpu().numpy()
+    steps = [NONE, (np.array([1], np.int32), np.array([1.0], np.float32)),
+             (np.array([0, 1], np.int32), np.array([0.3, 0.7], np.float32)), NONE]
+    reports = []
+    for old, new in zip(steps[:-1], steps[1:]):
+        before = ds.rows(0, rows)
+        guard = W[-1, -8:].clone()
+        ds.switch(old, new)
+        got = ds.rows(0, rows)
+        rep, _ = check_step(before, got, A_h, B_h, old, new)
+        assert rep["fail"] == 0, {k: v for k, v in rep.items() if k != "fail_mask"}
+        assert not torch.equal(W[-1, -8:], guard)          # the very last 16 bytes were updated
+        reports.append(rep)
+    assert merge_reports(reports)["exact_frac"] > 0.999
+    ds.close()
+    # one more row of 128 would cross 2^31 bytes: refused at create time, before any launch
+    with pytest.raises(L.LswError) as e:
+        L.lsw_create_adapters([(W.data_ptr(), A.data_ptr(), B.data_ptr(), out + 1, inn, 0, 0)], E, r)
+    assert e.value.status == L.LSW_ERR_SHAPE
+
+
+def test_longest_lists_and_smallest_shapes():
+    rng = np.random.default_rng(77)
+    # 8 old + 8 new distinct experts of rank 8: 16 terms, fused rank 128 (chunked matrix-core kernel)
+    out, inn, E, r = 200, 520, 16, 8
+    W, A, B = I.host_linear(rng, out, inn, E, r, 0.02, 1 / 16, 0.01)
+    for kernel in (L.KERNEL_VALU, L.KERNEL_MFMA):
+        ds = DeviceStack.from_host([(W, A, B)], [(0, 0, out, inn)], E, r, kernel=kernel)
+        perm = rng.permutation(E).astype(np.int32)
+        g = rng.random(E).astype(np.float32)
+        old = (perm[:8].copy(), (g[:8] / g[:8].sum()).astype(np.float32))
+        new = (perm[8:].copy(), (g[8:] / g[8:].sum()).astype(np.float32))
+        mixed = (np.concatenate([perm[4:8], perm[8:12]]).astype(np.int32), np.full(8, 0.125, np.float32))   # 4 shared with each
+        prev = ds.rows(0)
+        for a, b in [(NONE, old), (old, new), (new, mixed), (mixed, NONE)]:
+            ds.switch(a, b)
+            assert L.lsw_query(ds.ctx, L.LSW_Q_LAST_KERNEL) == kernel
+            got = ds.rows(0)
+            rep, _ = check_step(prev, got, A, B, a, b)
+            assert rep["fail"] == 0, (kernel, {k: v for k, v in rep.items() if k != "fail_mask"})
+            prev = got
+        with pytest.raises(L.LswError):
+            ds.switch(NONE, (np.arange(9, dtype=np.int32), np.full(9, 1 / 9, np.float32)))      # k > LSW_MAX_K
+        ds.close()
+    # one expert, one row, eight columns
+    W, A, B = I.host_linear(rng, 1, 8, 1, 8, 0.02, 0.5, 0.1)
+    for kernel in (L.KERNEL_VALU, L.KERNEL_MFMA):
+        ds = DeviceStack.from_host([(W, A, B)], [(0, 0, 1, 8)], 1, 8, kernel=kernel)
+        one = (np.array([0], np.int32), np.array([1.0], np.float32))
+        prev = ds.rows(0)
+        for a, b in [(NONE, one), (one, NONE)]:
+            ds.switch(a, b)
+            got = ds.rows(0)
+            rep, _ = check_step(prev, got, A, B, a, b)
+            assert rep["fail"] == 0
+            prev = got
+        ds.close()

@@ -23,10 +23,10 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X datasheet: 8 TB/s HBM3E
 
 
-def algorithmic_bytes(wl, n_terms: int) -> float:
-    """Read + write of every bf16 weight, plus every needed factor element once (4 bytes each:
-    fp32 B, and A as bf16 high + low parts)."""
-    return 4.0 * wl.w_elements() + 4.0 * n_terms * wl.rank * wl.factor_dims()
+def algorithmic_bytes(wl, n_terms: int, factor_bytes: int = 4) -> float:
+    """Read + write of every bf16 weight, plus every needed factor element once (fp32 storage: 4 bytes each,
+    fp32 B, and A as bf16 high + low parts; bf16 storage: 2 bytes each)."""
+    return 4.0 * wl.w_elements() + float(factor_bytes) * n_terms * wl.rank * wl.factor_dims()
 
 
 def cpu_baseline(wl, steps=3):
@@ -77,6 +77,8 @@ def main():
     ap.add_argument("--grid", type=int, default=0)
     ap.add_argument("--tile-cols", type=int, default=0)
     ap.add_argument("--xcd", type=int, default=-1)
+    ap.add_argument("--factor-dtype", choices=("fp32", "bf16"), default="fp32",
+                    help="storage type of the LoRA factors (fp32 is what the workloads prescribe)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 4 GiB device copy (a known-size reference for HBM byte counters)")
@@ -96,7 +98,8 @@ def main():
         sys.exit(2)
     wl = I.WORKLOADS[args.workload]
     torch.cuda.set_device(0)
-    stack = I.device_stack(wl)
+    bf16_factors = args.factor_dtype == "bf16"
+    stack = I.device_stack(wl, factor_dtype=torch.bfloat16 if bf16_factors else torch.float32)
     ctx = L.create_from_tensors(stack, wl.linear_shapes(), wl.experts, wl.rank)
     if args.kernel:
         L.lsw_set_option(ctx, L.LSW_OPT_KERNEL, args.kernel)
@@ -141,7 +144,7 @@ def main():
     wall = time.perf_counter() - t0
 
     launch_ms = [a.elapsed_time(b) for (a, b), k in zip(ev, kernels) if k != 0]
-    launch_bytes = [algorithmic_bytes(wl, n) for n, k in zip(terms, kernels) if k != 0]
+    launch_bytes = [algorithmic_bytes(wl, n, 2 if bf16_factors else 4) for n, k in zip(terms, kernels) if k != 0]
     avg_ms = sum(launch_ms) / len(launch_ms)
     achieved = (sum(launch_bytes) / len(launch_bytes)) / (avg_ms * 1e-3) / 1e9
     ms_per_step = wall * 1e3 / args.steps
@@ -201,7 +204,7 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(args.workload)
+            traffic = json.load(open(tpath)).get(args.workload + ("_bf16_factors" if bf16_factors else ""))
         except Exception:
             traffic = None
 
@@ -209,9 +212,10 @@ def main():
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic}
     mean_terms = sum(terms) / len(terms)
     if max(kernels) == 2 and mean_terms * wl.rank > 64:
-        # fused ranks above 64: three bf16 passes of 2*K flop per weight take longer on the matrix cores than the
-        # W traffic takes on HBM, so that is the roofline of this launch
-        flops = [3.0 * 2.0 * n * wl.rank * wl.w_elements() for n, k in zip(terms, kernels) if k != 0]
+        # fused ranks above 64: three bf16 passes (two with bf16-stored factors) of 2*K flop per weight take longer on
+        # the matrix cores than the W traffic takes on HBM, so that is the roofline of this launch
+        passes = 2.0 if bf16_factors else 3.0
+        flops = [passes * 2.0 * n * wl.rank * wl.w_elements() for n, k in zip(terms, kernels) if k != 0]
         tf = (sum(flops) / len(flops)) / (avg_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic}
@@ -223,7 +227,7 @@ def main():
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{wl.name}: {wl.layers} layers x 7 linears, hidden {wl.hidden}, ffn {wl.ffn}, "
-                               f"E={wl.experts}, r={wl.rank}, top-{wl.top_k}, all layers per launch",
+                               f"E={wl.experts}, r={wl.rank}, top-{wl.top_k}, all layers per launch, factors stored as {args.factor_dtype}",
                    "w_elements": wl.w_elements(),
                    "kernel": {0: "none", 1: "vector-ALU", 2: "matrix-core"}[max(kernels)],
                    "fused_rank_mean": round(mean_terms * wl.rank, 1),

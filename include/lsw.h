@@ -51,8 +51,9 @@ enum { LSW_MAX_K = 8 };  /* largest top-k per list (old or new) */
 /* One adapted linear.  All three tensors are BORROWED and must outlive the context. */
 typedef struct lsw_linear {
   void*        W;      /* DEVICE bf16 [out, in] row-major, 16-byte aligned; updated in place by lsw_switch */
-  const float* A;      /* DEVICE fp32 [E, r, in]  (LoRA_DOWN), 16-byte aligned; read at create time (see below) */
-  const float* B;      /* DEVICE fp32 [E, out, r] (LoRA_UP),   16-byte aligned; read by every switch */
+  const void*  A;      /* DEVICE fp32 (or bf16, see lsw_create_adapters_ex) [E, r, in]  (LoRA_DOWN), 16-byte aligned;
+                          read at create time when r is a multiple of 8 (see below) */
+  const void*  B;      /* DEVICE fp32 (or bf16) [E, out, r] (LoRA_UP), 16-byte aligned; read by every switch */
   int32_t      out;    /* rows of W, >= 1 */
   int32_t      in;     /* columns of W, a positive multiple of 8 (rows stay 16-byte aligned) */
   int32_t      layer;  /* layer number >= 0; several linears share one layer */
@@ -83,6 +84,19 @@ typedef struct lsw_linear {
  */
 lsw_status lsw_create_adapters(const lsw_linear* lin, int32_t n_lin, int32_t E, int32_t r,
                                float scale, lsw_ctx** out);
+
+/*
+ * The same with the storage type of the LoRA factors chosen (the paper states none; adapter
+ * checkpoints are commonly kept in bf16).  LSW_FACTOR_F32 is lsw_create_adapters.  With
+ * LSW_FACTOR_BF16 every A and B is a bf16 tensor of the same shape, r must be a multiple of 8,
+ * and the update is computed from the stored bf16 values exactly as from fp32 ones: same formula,
+ * fp32-grade accumulation, one rounding.  What changes is cost: the stored values need no low part on
+ * the matrix cores (two passes instead of three), and the factor traffic halves.
+ * Additional error: LSW_ERR_ARG (unknown dtype), LSW_ERR_SHAPE (bf16 with r not a multiple of 8).
+ */
+enum { LSW_FACTOR_F32 = 0, LSW_FACTOR_BF16 = 1 };
+lsw_status lsw_create_adapters_ex(const lsw_linear* lin, int32_t n_lin, int32_t E, int32_t r,
+                                  float scale, int32_t factor_dtype, lsw_ctx** out);
 
 /*
  * The fused switch (Alg. 1 steps 2-4; Eq. 8 == Eq. 10; one launch as in Eq. 11).

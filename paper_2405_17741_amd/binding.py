@@ -17,12 +17,13 @@ LSW_OPT_KERNEL, LSW_OPT_STRICT_STATE, LSW_OPT_GRID, LSW_OPT_TILE_COLS, LSW_OPT_X
 (LSW_Q_N_LINEARS, LSW_Q_N_LAYERS, LSW_Q_LAST_KERNEL, LSW_Q_LAST_ITEMS, LSW_Q_LAST_GRID, LSW_Q_PACKED_BYTES,
  LSW_Q_GEMV_X_ELEMS, LSW_Q_GEMV_Y_ELEMS) = range(1, 9)
 KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
+LSW_FACTOR_F32, LSW_FACTOR_BF16 = 0, 1
 
 EXPORTS = (
     "lsw_create_adapters", "lsw_switch", "lsw_merged_gemv", "lsw_route", "lsw_build_terms",
     "lsw_get_state", "lsw_set_option", "lsw_query", "lsw_worklist_size", "lsw_worklist_item",
     "lsw_destroy", "lsw_last_error", "lsw_probe_inplace", "lsw_merged_gemv_all",
-    "lsw_route_dev", "lsw_switch_dev", "lsw_dev_status", "lsw_gemv_bf16",
+    "lsw_route_dev", "lsw_switch_dev", "lsw_dev_status", "lsw_gemv_bf16", "lsw_create_adapters_ex",
 )
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblsw.so")
@@ -53,6 +54,8 @@ def lib() -> C.CDLL:
         L = C.CDLL(_LIB_PATH)
         L.lsw_create_adapters.argtypes = [C.POINTER(lsw_linear), C.c_int32, C.c_int32, C.c_int32, C.c_float,
                                           C.POINTER(C.c_void_p)]
+        L.lsw_create_adapters_ex.argtypes = [C.POINTER(lsw_linear), C.c_int32, C.c_int32, C.c_int32, C.c_float,
+                                             C.c_int32, C.POINTER(C.c_void_p)]
         L.lsw_switch.argtypes = [C.c_void_p, _i32p, C.c_int32, _i32p, _f32p, C.c_int32, _i32p, _f32p, C.c_int32,
                                  C.c_void_p]
         L.lsw_merged_gemv.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -107,17 +110,21 @@ def _f32(a):
     return arr, arr.ctypes.data_as(_f32p), arr.size
 
 
-def lsw_create_adapters(linears, E: int, r: int, scale: float = 1.0) -> int:
+def lsw_create_adapters(linears, E: int, r: int, scale: float = 1.0, factor_dtype=None) -> int:
     """linears: iterable of (W_ptr, A_ptr, B_ptr, out, in, layer, kind) with device addresses as ints.
 
-    Returns the opaque context handle (an int); release it with lsw_destroy.
+    factor_dtype None calls lsw_create_adapters (fp32 factors); LSW_FACTOR_F32 / LSW_FACTOR_BF16 call
+    lsw_create_adapters_ex.  Returns the opaque context handle (an int); release it with lsw_destroy.
     """
     linears = list(linears)
     arr = (lsw_linear * max(len(linears), 1))()
     for i, (w, a, b, o, n, layer, kind) in enumerate(linears):
         arr[i] = lsw_linear(w, a, b, o, n, layer, kind)
     ctx = C.c_void_p()
-    _check(lib().lsw_create_adapters(arr if linears else None, len(linears), E, r, scale, C.byref(ctx)))
+    if factor_dtype is None:
+        _check(lib().lsw_create_adapters(arr if linears else None, len(linears), E, r, scale, C.byref(ctx)))
+    else:
+        _check(lib().lsw_create_adapters_ex(arr if linears else None, len(linears), E, r, scale, factor_dtype, C.byref(ctx)))
     return ctx.value
 
 
@@ -224,11 +231,15 @@ def lsw_destroy(ctx: int) -> None:
 # convenience for torch users: tensors -> device addresses (still marshalling only)
 # ---------------------------------------------------------------------------
 def create_from_tensors(stack, shapes, E: int, r: int, scale: float = 1.0) -> int:
-    """stack: [(W bf16 [out,in], A fp32 [E,r,in], B fp32 [E,out,r])] torch CUDA tensors;
+    """stack: [(W bf16 [out,in], A [E,r,in], B [E,out,r])] torch CUDA tensors, A and B all fp32 or all bf16;
     shapes: [(layer, kind, out, in)] as produced by inputs.Workload.linear_shapes()."""
+    import torch
+    dtypes = {t.dtype for _, A, B in stack for t in (A, B)}
+    assert dtypes in ({torch.float32}, {torch.bfloat16}), dtypes
+    factor_dtype = None if dtypes == {torch.float32} else LSW_FACTOR_BF16
     lin = []
     for (W, A, B), (layer, kind, o, n) in zip(stack, shapes):
         assert W.is_contiguous() and A.is_contiguous() and B.is_contiguous()
         assert tuple(W.shape) == (o, n) and tuple(A.shape) == (E, r, n) and tuple(B.shape) == (E, o, r)
         lin.append((W.data_ptr(), A.data_ptr(), B.data_ptr(), o, n, layer, kind))
-    return lsw_create_adapters(lin, E, r, scale)
+    return lsw_create_adapters(lin, E, r, scale, factor_dtype)

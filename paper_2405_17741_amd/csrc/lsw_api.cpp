@@ -69,6 +69,7 @@ struct lsw_ctx {
   std::vector<int32_t> layer_ids;            // sorted distinct layer numbers
   std::vector<LayerState> state;             // parallel to layer_ids
   int32_t E = 0, r = 0;
+  int qp = 2;                                // Q parts: 2 = fp32-stored factors, 1 = bf16-stored factors
   float scale = 1.0f;
   int device = 0;
   int n_cu = 0;
@@ -221,8 +222,16 @@ static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 extern "C" lsw_status lsw_create_adapters(const lsw_linear* lin, int32_t n_lin, int32_t E, int32_t r,
                                           float scale, lsw_ctx** out) {
+  return lsw_create_adapters_ex(lin, n_lin, E, r, scale, LSW_FACTOR_F32, out);
+}
+
+extern "C" lsw_status lsw_create_adapters_ex(const lsw_linear* lin, int32_t n_lin, int32_t E, int32_t r,
+                                             float scale, int32_t factor_dtype, lsw_ctx** out) {
   if (!out) return fail(LSW_ERR_ARG, "out is null");
   *out = nullptr;
+  if (factor_dtype != LSW_FACTOR_F32 && factor_dtype != LSW_FACTOR_BF16) return fail(LSW_ERR_ARG, "unknown factor dtype %d", factor_dtype);
+  const int qp = factor_dtype == LSW_FACTOR_BF16 ? 1 : 2;
+  if (qp == 1 && r % 8 != 0) return fail(LSW_ERR_SHAPE, "bf16 factors need r %% 8 == 0 (rows of B stay 16-byte aligned)");
   if (!lin || n_lin < 1) return fail(LSW_ERR_ARG, "lin is null or n_lin < 1");
   if (E < 1 || E > 4096) return fail(LSW_ERR_ARG, "E=%d outside 1..4096", E);
   if (r < 1 || r > 512) return fail(LSW_ERR_ARG, "r=%d outside 1..512", r);
@@ -238,7 +247,7 @@ extern "C" lsw_status lsw_create_adapters(const lsw_linear* lin, int32_t n_lin, 
     if (int64_t(ceil_div(L.out, kMfmaTileRows)) * kMfmaTileRows * L.in * 2 >= (int64_t(1) << 31))
       return fail(LSW_ERR_SHAPE, "linear %d: W (rows rounded up to %d) must stay below 2^31 bytes", p, kMfmaTileRows);
     // 32-bit byte offsets inside one linear's packed A (E * r * padded in * 4 bytes)
-    if (r % 8 == 0 && int64_t(E) * r * ceil_div(L.in, kApkBlockCols) * kApkBlockCols * 4 >= (int64_t(1) << 31))
+    if (r % 8 == 0 && int64_t(E) * r * ceil_div(L.in, kApkBlockCols) * kApkBlockCols * 2 * qp >= (int64_t(1) << 31))
       return fail(LSW_ERR_SHAPE, "linear %d: E * r * in * 4 must stay below 2^31 bytes", p);
     if (!aligned16(L.W) || !aligned16(L.A) || !aligned16(L.B))
       return fail(LSW_ERR_SHAPE, "linear %d: tensor not 16-byte aligned", p);
@@ -259,6 +268,7 @@ extern "C" lsw_status lsw_create_adapters(const lsw_linear* lin, int32_t n_lin, 
   c->E = E;
   c->r = r;
   c->scale = scale;
+  c->qp = qp;
   for (int32_t p = 0; p < n_lin; ++p) c->layer_ids.push_back(lin[p].layer);
   std::sort(c->layer_ids.begin(), c->layer_ids.end());
   c->layer_ids.erase(std::unique(c->layer_ids.begin(), c->layer_ids.end()), c->layer_ids.end());
@@ -276,7 +286,7 @@ extern "C" lsw_status lsw_create_adapters(const lsw_linear* lin, int32_t n_lin, 
   std::vector<size_t> apk_off(size_t(n_lin), 0);
   for (int32_t p = 0; p < n_lin; ++p) {
     apk_off[p] = apk_elems;
-    apk_elems += size_t(E) * size_t(r) * size_t(ceil_div(lin[p].in, kApkBlockCols) * kApkBlockCols) * 2;   // bf16 high + low part per element, columns padded to the block
+    apk_elems += size_t(E) * size_t(r) * size_t(ceil_div(lin[p].in, kApkBlockCols) * kApkBlockCols) * size_t(qp);   // bf16 high (+ low) part per element, columns padded to the block
   }
   lsw_ctx* raw = c.get();
   auto cleanup = [raw]() {
@@ -292,7 +302,7 @@ extern "C" lsw_status lsw_create_adapters(const lsw_linear* lin, int32_t n_lin, 
     if (e != hipSuccess) { (void)hipGetLastError(); return fail(LSW_ERR_NOMEM, "hipMalloc of %zu bytes for packed A failed", apk_elems * 2); }
     c->owned_bytes += int64_t(apk_elems * sizeof(uint16_t));
     for (int32_t p = 0; p < n_lin; ++p) {
-      e = launch_pack_A(lin[p].A, c->d_apk + apk_off[p], E, r, lin[p].in, nullptr);
+      e = launch_pack_A(lin[p].A, c->d_apk + apk_off[p], E, r, lin[p].in, qp, nullptr);
       if (e != hipSuccess) { cleanup(); return fail(LSW_ERR_DEVICE, "pack kernel launch failed: %s", hipGetErrorString(e)); }
     }
   }
@@ -409,9 +419,9 @@ static lsw_status launch_switch(lsw_ctx* c, const std::vector<int32_t>& sel_laye
     int grid = c->opt_grid;
     if (grid <= 0) grid = (kernel == 2) ? c->n_cu : c->n_cu * 2;   // matrix-core: one workgroup per CU
     grid = std::max(8, (grid / 8) * 8);     // a multiple of the 8 XCDs (the kernels' block remap assumes it)
-    hipError_t e = (kernel == 2) ? (bigk ? launch_switch_mfma_bigk(lp, t, t_dev, c->r, grid, s)
-                                         : launch_switch_mfma(lp, t, t_dev, c->r, grid, s))
-                                 : launch_switch_valu(lp, t, t_dev, c->r, grid, s);
+    hipError_t e = (kernel == 2) ? (bigk ? launch_switch_mfma_bigk(lp, t, t_dev, c->r, c->qp, grid, s)
+                                         : launch_switch_mfma(lp, t, t_dev, c->r, c->qp, grid, s))
+                                 : launch_switch_valu(lp, t, t_dev, c->r, c->qp, grid, s);
     if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "switch launch failed: %s", hipGetErrorString(e));
     c->last_kernel = kernel;
     c->last_items = dp->n_items;

@@ -20,8 +20,8 @@ constexpr int kMaxTerms = 2 * LSW_MAX_K;  // old + new lists
 // Device-side descriptor of one adapted linear.
 struct LinDesc {
   uint16_t*       W;      // bf16 [out, in]
-  const float*    A;      // fp32 [E, r, in]
-  const float*    B;      // fp32 [E, out, r]
+  const void*     A;      // fp32 or bf16 [E, r, in]
+  const void*     B;      // fp32 or bf16 [E, out, r]
   const uint16_t* Apk;    // packed A for the matrix-core kernel (see pack kernel), or null
   int32_t         out;
   int32_t         in;
@@ -84,14 +84,15 @@ struct LaunchPlan {             // device pointers + counts for one launch
 
 // Kernel launchers (lsw_kernels.hip).  All return the hipError of the launch.
 // t.n sizes the launch; with t_dev != null the kernels read the list (possibly shorter, or empty) from device memory
-hipError_t launch_switch_valu(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int grid, hipStream_t s);
-hipError_t launch_switch_mfma(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int grid, hipStream_t s);
-hipError_t launch_switch_mfma_bigk(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int grid, hipStream_t s);
+// qp: 2 = fp32-stored factors (split into two bf16 parts on the matrix cores), 1 = bf16-stored factors
+hipError_t launch_switch_valu(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int qp, int grid, hipStream_t s);
+hipError_t launch_switch_mfma(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int qp, int grid, hipStream_t s);
+hipError_t launch_switch_mfma_bigk(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int qp, int grid, hipStream_t s);
 hipError_t launch_route(const float* logits, int E, int k, int32_t* ids, float* gates, int32_t* err, hipStream_t s);
 hipError_t launch_build_terms(const int32_t* old_ids, const float* old_gates, int k_old, const int32_t* new_ids,
                               const float* new_gates, int k_new, int E, float scale, Terms* out, int32_t* err, hipStream_t s);
 hipError_t launch_probe_inplace(const LaunchPlan& p, int grid, hipStream_t s);
-hipError_t launch_pack_A(const float* A, uint16_t* Apk, int E, int r, int in, hipStream_t s);
+hipError_t launch_pack_A(const void* A, uint16_t* Apk, int E, int r, int in, int qp, hipStream_t s);
 hipError_t launch_gemv(const uint16_t* W, const uint16_t* x, float* y, int out, int in, int grid_cap, hipStream_t s);
 hipError_t launch_gemv_all(const LaunchPlan& p, const uint16_t* x_all, float* y_all, int grid, hipStream_t s);
 

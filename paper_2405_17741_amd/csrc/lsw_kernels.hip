@@ -22,6 +22,9 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 // ---------------------------------------------------------------------------
 // small helpers
 // ---------------------------------------------------------------------------
+// Pointers read from the descriptor table are generic to the compiler; casts to this address space tell it
+// they point to global memory, so it emits global_load (vmcnt only) instead of flat_load.
+#define LSW_GLOBAL __attribute__((address_space(1)))
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
@@ -38,15 +41,33 @@ __device__ __forceinline__ void split2(float x0, float x1, uint32_t* hi, uint32_
   *lo = pack_bf16(x0 - bf16_lo(h), x1 - bf16_hi(h));
 }
 
+// Eight consecutive factor elements as fp32.  QP = 2: the factors are stored as fp32 (the matrix-core kernels
+// split them into bf16 high + low parts, "two Q parts"); QP = 1: they are stored as bf16 and are exact as they are.
+template <int QP>
+__device__ __forceinline__ void load8(const void* base, long long elem, float (&x)[8]) {
+  if constexpr (QP == 2) {
+    const LSW_GLOBAL f32x4* src = (const LSW_GLOBAL f32x4*)(reinterpret_cast<const float*>(base) + elem);
+    const f32x4 b0 = src[0], b1 = src[1];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) { x[q] = b0[q]; x[4 + q] = b1[q]; }
+  } else {
+    const u32x4 w = *(const LSW_GLOBAL u32x4*)(reinterpret_cast<const uint16_t*>(base) + elem);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) { x[2 * q] = bf16_lo(w[q]); x[2 * q + 1] = bf16_hi(w[q]); }
+  }
+}
+template <int QP>
+__device__ __forceinline__ float load1(const void* base, long long elem) {
+  if constexpr (QP == 2) return reinterpret_cast<const float*>(base)[elem];
+  else return __uint_as_float(uint32_t(reinterpret_cast<const uint16_t*>(base)[elem]) << 16);
+}
+
 // Blocks are dealt round-robin to the 8 XCDs; this gives XCD x a contiguous eighth of every
 // grid-wide round of items, so one XCD's L2 sees neighbouring tiles of the same linear.
 __device__ __forceinline__ int xcd_contiguous_block(int b, int grid) {
   return (b & 7) * (grid >> 3) + (b >> 3);
 }
 
-// Pointers read from the descriptor table are generic to the compiler; these casts tell it they
-// point to global memory, so it emits global_load (vmcnt only) instead of flat_load.
-#define LSW_GLOBAL __attribute__((address_space(1)))
 template <typename T>
 __device__ __forceinline__ const LSW_GLOBAL T* as_global(const T* ptr) {
   return (const LSW_GLOBAL T*)ptr;
@@ -94,14 +115,15 @@ __device__ __forceinline__ T* uniform(T* ptr) {
 
 // ---------------------------------------------------------------------------
 // A re-layout for the matrix-core kernel
-//   A   fp32 [E][r][in]                       (LoRA_DOWN as the caller stores it)
-//   Apk bf16 [E][r/8][ncb][8][2][32][8]       ncb = ceil(in/256) column blocks of 256
+//   A   fp32 or bf16 [E][r][in]               (LoRA_DOWN as the caller stores it)
+//   Apk bf16 [E][r/8][ncb][8][QP][32][8]      ncb = ceil(in/256) column blocks of 256
 // For expert e, rank group g (ranks 8g..8g+7) and column j = 256*cb + 8*n + b the 8 ranks are
-// stored as 8 bf16 high parts at [e][g][cb][b][0][n][.] and 8 bf16 low parts at [..][b][1][n][.]
-// (columns past `in` hold zeros).  A matrix-core lane wants 8 consecutive k of one column; in this
+// stored as 8 bf16 high parts at [e][g][cb][b][0][n][.] and, for fp32 factors (QP = 2), 8 bf16 low
+// parts at [..][b][1][n][.]; bf16 factors (QP = 1) are exact in the one part (columns past `in` hold zeros).  A matrix-core lane wants 8 consecutive k of one column; in this
 // order the 32 lanes of one access (n = 0..31, fixed b) read 512 contiguous bytes.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_pack_A(const float* __restrict__ A, uint16_t* __restrict__ Apk,
+template <int QP>
+__global__ __launch_bounds__(256) void k_pack_A(const void* __restrict__ A, uint16_t* __restrict__ Apk,
                                                 int E, int r, int in) {
   const int gpr = r >> 3;
   const int in_pad = ceil_div(in, kApkBlockCols) * kApkBlockCols;
@@ -116,9 +138,8 @@ __global__ __launch_bounds__(256) void k_pack_A(const float* __restrict__ A, uin
 #pragma unroll
     for (int q = 0; q < 8; ++q) x[q] = 0.0f;
     if (j < in) {
-      const float* src = A + ((long long)e * r + 8 * g) * in + j;
 #pragma unroll
-      for (int q = 0; q < 8; ++q) x[q] = src[(long long)q * in];
+      for (int q = 0; q < 8; ++q) x[q] = load1<QP>(A, ((long long)e * r + 8 * g + q) * in + j);
     }
     u32x4 hi, lo;
 #pragma unroll
@@ -130,16 +151,17 @@ __global__ __launch_bounds__(256) void k_pack_A(const float* __restrict__ A, uin
     }
     const int cb = j / kApkBlockCols, jj = j % kApkBlockCols, n = jj >> 3, b = jj & 7;
     // element offset of [e][g][cb][b][0][n][0]
-    const long long base = ((eg * (in_pad / kApkBlockCols) + cb) * 8 + b) * (2 * 32 * 8) + n * 8;
+    const long long base = ((eg * (in_pad / kApkBlockCols) + cb) * 8 + b) * (QP * 32 * 8) + n * 8;
     *reinterpret_cast<u32x4*>(Apk + base) = hi;
-    *reinterpret_cast<u32x4*>(Apk + base + 32 * 8) = lo;
+    if constexpr (QP == 2) *reinterpret_cast<u32x4*>(Apk + base + 32 * 8) = lo;
   }
 }
 
-hipError_t launch_pack_A(const float* A, uint16_t* Apk, int E, int r, int in, hipStream_t s) {
+hipError_t launch_pack_A(const void* A, uint16_t* Apk, int E, int r, int in, int qp, hipStream_t s) {
   const long long total = (long long)E * (r / 8) * (ceil_div(in, kApkBlockCols) * kApkBlockCols);
   int grid = int(std::min<long long>((total + 255) / 256, 1 << 16));
-  hipLaunchKernelGGL(k_pack_A, dim3(grid), dim3(256), 0, s, A, Apk, E, r, in);
+  if (qp == 2) hipLaunchKernelGGL(k_pack_A<2>, dim3(grid), dim3(256), 0, s, A, Apk, E, r, in);
+  else hipLaunchKernelGGL(k_pack_A<1>, dim3(grid), dim3(256), 0, s, A, Apk, E, r, in);
   return hipGetLastError();
 }
 
@@ -152,6 +174,7 @@ hipError_t launch_pack_A(const float* A, uint16_t* Apk, int E, int r, int in, hi
 // ---------------------------------------------------------------------------
 constexpr int VT_ROWS = kValuTileRows, VT_COLS = kValuTileCols, VT_K = 32;
 
+template <int QP>
 __global__ __launch_bounds__(256) void k_switch_valu(LaunchPlan p, Terms t, const Terms* t_dev, int r) {
   __shared__ float sB[VT_ROWS][VT_K + 1];
   __shared__ float sA[VT_K][VT_COLS];
@@ -186,7 +209,7 @@ __global__ __launch_bounds__(256) void k_switch_valu(LaunchPlan p, Terms t, cons
         float v = 0.0f;
         if (k < K && row < L.out) {
           const int c = k / r, rho = k - c * r;
-          v = s_tc[c] * L.B[((long long)s_te[c] * L.out + row) * r + rho];
+          v = s_tc[c] * load1<QP>(L.B, ((long long)s_te[c] * L.out + row) * r + rho);
         }
         sB[i][kk] = v;
       }
@@ -196,7 +219,7 @@ __global__ __launch_bounds__(256) void k_switch_valu(LaunchPlan p, Terms t, cons
         float v = 0.0f;
         if (k < K && col < L.in) {
           const int c = k / r, rho = k - c * r;
-          v = L.A[((long long)s_te[c] * r + rho) * L.in + col];
+          v = load1<QP>(L.A, ((long long)s_te[c] * r + rho) * L.in + col);
         }
         sA[kk][j] = v;
       }
@@ -236,8 +259,9 @@ __global__ __launch_bounds__(256) void k_switch_valu(LaunchPlan p, Terms t, cons
   }
 }
 
-hipError_t launch_switch_valu(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int grid, hipStream_t s) {
-  hipLaunchKernelGGL(k_switch_valu, dim3(grid), dim3(256), 0, s, p, t, t_dev, r);
+hipError_t launch_switch_valu(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int qp, int grid, hipStream_t s) {
+  if (qp == 2) hipLaunchKernelGGL(k_switch_valu<2>, dim3(grid), dim3(256), 0, s, p, t, t_dev, r);
+  else hipLaunchKernelGGL(k_switch_valu<1>, dim3(grid), dim3(256), 0, s, p, t, t_dev, r);
   return hipGetLastError();
 }
 
@@ -298,7 +322,7 @@ struct MfmaItem {           // what a wave keeps per work item
   u32x4 p_hi[NKS], p_lo[NKS];
 };
 
-template <int NKS>
+template <int NKS, int QP>
 __device__ __forceinline__ void mfma_load_item(const LaunchPlan& p, int item, int n, int gpr, int r,
                                                const int (&term_e)[NKS], const int (&term_g)[NKS],
                                                const float (&term_c)[NKS], MfmaItem<NKS>& it,
@@ -326,20 +350,15 @@ __device__ __forceinline__ void mfma_load_item(const LaunchPlan& p, int item, in
   const bool prow_ok = row0 + n < L.out;       // rows past the end get a zero coefficient and an offset outside W
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks) {
-    const LSW_GLOBAL f32x4* src = as_global(reinterpret_cast<const f32x4*>(
-        L.B + ((long long)term_e[ks] * L.out + prow) * r + 8 * term_g[ks]));
-    const f32x4 b0 = src[0];
-    const f32x4 b1 = src[1];
+    float b[8];
+    load8<QP>(L.B, ((long long)term_e[ks] * L.out + prow) * r + 8 * term_g[ks], b);
     const float c = prow_ok ? term_c[ks] : 0.0f;
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
+    for (int q = 0; q < 4; ++q) {
       uint32_t hi, lo;
-      split2(c * b0[2 * q], c * b0[2 * q + 1], &hi, &lo);
+      split2(c * b[2 * q], c * b[2 * q + 1], &hi, &lo);
       it.p_hi[ks][q] = hi;
       it.p_lo[ks][q] = lo;
-      split2(c * b1[2 * q], c * b1[2 * q + 1], &hi, &lo);
-      it.p_hi[ks][2 + q] = hi;
-      it.p_lo[ks][2 + q] = lo;
     }
   }
 }
@@ -362,23 +381,23 @@ __device__ __forceinline__ void mfma_load_w(const MfmaItem<NKS>& it, uint32_t la
         res, lane_off + uint32_t(8 * (v >> 2) + (v & 3)) * it.stride_byte, 0, /*nt*/ 2);
 }
 
-template <int NKS>
+template <int NKS, int QP>
 __device__ __forceinline__ void wg_compute(const u32x4 (&p_hi)[NKS], const u32x4 (&p_lo)[NKS],
                                            const u32x4* qbuf /* LDS: slot 0 of this step's buffer + lane */,
                                            u32x4 (&wcur)[16]) {
   // Pair q = blocks 2q and 2q+1 = low and high bf16 half of word q of each row.  The work is a
-  // chain of 4*NKS chunks (pair q, k-step ks), each 6 matrix instructions on the pair's two
-  // accumulators.  While the matrix pipe runs a chunk, LDS delivers the operands of the next chunk
+  // chain of 4*NKS chunks (pair q, k-step ks), each 6 matrix instructions (4 when the factors are
+  // stored as bf16 and Q has no low part) on the pair's two accumulators.  While the matrix pipe runs a chunk, LDS delivers the operands of the next chunk
   // and the vector ALU widens pair q+1 and rounds pair q-1; the scheduling directives pin that
   // interleaving, which the compiler would otherwise undo.
   f32x16 a0[4], a1[4];
-  u32x4 qr[2][2][2];           // [chunk parity][block of the pair][high, low]
+  u32x4 qr[2][2][QP];          // [chunk parity][block of the pair][high, low]
   auto fetch = [&](int chunk) {
     const int q = chunk / NKS, ks = chunk % NKS;
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int hl = 0; hl < 2; ++hl) qr[chunk & 1][j][hl] = qbuf[((ks * 8 + 2 * q + j) * 2 + hl) * 64];
+      for (int hl = 0; hl < QP; ++hl) qr[chunk & 1][j][hl] = qbuf[((ks * 8 + 2 * q + j) * QP + hl) * 64];
   };
   fetch(0);
 #pragma unroll
@@ -410,20 +429,23 @@ __device__ __forceinline__ void wg_compute(const u32x4 (&p_hi)[NKS], const u32x4
       const bf16x8 ph = __builtin_bit_cast(bf16x8, p_hi[ks]);
       const bf16x8 pl = __builtin_bit_cast(bf16x8, p_lo[ks]);
       const bf16x8 h0 = __builtin_bit_cast(bf16x8, qr[chunk & 1][0][0]);
-      const bf16x8 l0 = __builtin_bit_cast(bf16x8, qr[chunk & 1][0][1]);
       const bf16x8 h1 = __builtin_bit_cast(bf16x8, qr[chunk & 1][1][0]);
-      const bf16x8 l1 = __builtin_bit_cast(bf16x8, qr[chunk & 1][1][1]);
       a0[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl, h0, a0[q], 0, 0, 0);
       a1[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl, h1, a1[q], 0, 0, 0);
-      a0[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, l0, a0[q], 0, 0, 0);
-      a1[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, l1, a1[q], 0, 0, 0);
+      if constexpr (QP == 2) {
+        const bf16x8 l0 = __builtin_bit_cast(bf16x8, qr[chunk & 1][0][QP - 1]);
+        const bf16x8 l1 = __builtin_bit_cast(bf16x8, qr[chunk & 1][1][QP - 1]);
+        a0[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, l0, a0[q], 0, 0, 0);
+        a1[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, l1, a1[q], 0, 0, 0);
+      }
       a0[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, h0, a0[q], 0, 0, 0);
       a1[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, h1, a1[q], 0, 0, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);          // the next chunk's 4 LDS reads first
+      constexpr int kMfma = 2 + 2 * QP;
+      __builtin_amdgcn_sched_group_barrier(0x100, 2 * QP, 0);     // the next chunk's LDS reads first
 #pragma unroll
-      for (int i = 0; i < 6; ++i) {
+      for (int i = 0; i < kMfma; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        // one matrix instruction
-        __builtin_amdgcn_sched_group_barrier(0x002, (3 * kRowsPer + 5) / 6, 0);   // a few vector instructions
+        __builtin_amdgcn_sched_group_barrier(0x002, (3 * kRowsPer + kMfma - 1) / kMfma, 0);   // a few vector instructions
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -436,19 +458,19 @@ __device__ __forceinline__ void wg_compute(const u32x4 (&p_hi)[NKS], const u32x4
 // copied from L2 straight into LDS: lane l of a 16-byte LDS-DMA load lands at base + 16*l, which is
 // exactly the [slot][lane] layout wg_compute reads.  No registers are involved; the data is
 // complete when the wave's vector-memory counter has drained.
-template <int NKS>
+template <int NKS, int QP>
 __device__ __forceinline__ void wg_fetch_q(const uint16_t* Apk, int ncb, int cs, int n, int gpr, int wave,
                                            const int (&term_e)[NKS], const int (&term_g)[NKS],
                                            u32x4* buf /* LDS: slot 0 of the target buffer */) {
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks) {
     const u32x4* src = reinterpret_cast<const u32x4*>(
-        Apk + (((long long)term_e[ks] * gpr + term_g[ks]) * ncb + cs / MT_STEP) * (8 * 2 * 32 * 8)) + n;
+        Apk + (((long long)term_e[ks] * gpr + term_g[ks]) * ncb + cs / MT_STEP) * (8 * QP * 32 * 8)) + n;
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int hl = 0; hl < 2; ++hl)
-        lds_dma16(src + (2 * (2 * wave + j) + hl) * 32, buf + ((ks * 8 + 2 * wave + j) * 2 + hl) * 64);
+      for (int hl = 0; hl < QP; ++hl)
+        lds_dma16(src + (QP * (2 * wave + j) + hl) * 32, buf + ((ks * 8 + 2 * wave + j) * QP + hl) * 64);
   }
 }
 
@@ -467,14 +489,14 @@ __device__ __forceinline__ void wg_drain_and_barrier() {
 // the previous step's tile, request the next tile into the freed registers, update the current
 // tile, then drain and meet the workgroup.  Everything requested at the top has the whole compute
 // phase to arrive.  Returns false after the last tile of the workgroup.
-template <int NKS>
+template <int NKS, int QP>
 __device__ __forceinline__ bool wg_step(const LaunchPlan& p, int grid, int n, int h, int lane, int wave, int gpr, int r,
                                         const int (&term_e)[NKS], const int (&term_g)[NKS],
                                         const float (&term_c)[NKS], MfmaItem<NKS>& cur, MfmaItem<NKS>& nxt,
                                         bool& have_nxt, int& item, int& cs, uint32_t& lane_off,
                                         __amdgpu_buffer_rsrc_t& prev_res, uint32_t& prev_off, uint32_t& prev_stride,
                                         u32x4 (&wcur)[16], u32x4 (&wprev)[16], int buf) {
-  constexpr int kBufSlots = NKS * 8 * 2 * 64;
+  constexpr int kBufSlots = NKS * 8 * QP * 64;
   const bool last = uniform(int(!(cs + MT_STEP < cur.col_end))) != 0;
   const bool more = !last || have_nxt;
   const __amdgpu_buffer_rsrc_t nres = w_resource(last ? nxt.W : cur.W, last ? nxt.wbytes : cur.wbytes);
@@ -491,7 +513,7 @@ __device__ __forceinline__ bool wg_step(const LaunchPlan& p, int grid, int n, in
     const int qcs = uniform(more ? ncs : cs);
     const uint16_t* qApk = uniform((more && last) ? nxt.Apk : cur.Apk);
     const int qncb = uniform((more && last) ? nxt.ncb : cur.ncb);
-    wg_fetch_q<NKS>(qApk, qncb, qcs, n, gpr, wave, term_e, term_g, wg_lds + (buf ^ 1) * kBufSlots);
+    wg_fetch_q<NKS, QP>(qApk, qncb, qcs, n, gpr, wave, term_e, term_g, wg_lds + (buf ^ 1) * kBufSlots);
   }
 #pragma unroll
   for (int v = 0; v < 16; ++v)
@@ -503,7 +525,7 @@ __device__ __forceinline__ bool wg_step(const LaunchPlan& p, int grid, int n, in
     wprev[v] = __builtin_amdgcn_raw_buffer_load_b128(
         nres, nlane_off + uint32_t(8 * (v >> 2) + (v & 3)) * nstride, 0, /*nt*/ 2);
 
-  wg_compute<NKS>(cur.p_hi, cur.p_lo, wg_lds + buf * kBufSlots + lane, wcur);
+  wg_compute<NKS, QP>(cur.p_hi, cur.p_lo, wg_lds + buf * kBufSlots + lane, wcur);
 
   wg_drain_and_barrier();
 
@@ -517,12 +539,12 @@ __device__ __forceinline__ bool wg_step(const LaunchPlan& p, int grid, int n, in
     cur = nxt;
     item += grid;
     have_nxt = item + grid < p.n_items;
-    if (have_nxt) mfma_load_item<NKS>(p, item + grid, n, gpr, r, term_e, term_g, term_c, nxt, WG_ROWS, 32 * wave);
+    if (have_nxt) mfma_load_item<NKS, QP>(p, item + grid, n, gpr, r, term_e, term_g, term_c, nxt, WG_ROWS, 32 * wave);
   }
   return true;
 }
 
-template <int NKS>
+template <int NKS, int QP>
 __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma(LaunchPlan p, Terms t, const Terms* t_dev, int r) {
   __shared__ int32_t s_e[kMaxTerms];
   __shared__ float s_coeff[kMaxTerms];
@@ -552,9 +574,9 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma(LaunchPlan p, Ter
   int item = p.xcd_remap ? xcd_contiguous_block(blockIdx.x, grid) : int(blockIdx.x);
   if (item >= p.n_items) return;        // uniform over the workgroup
   MfmaItem<NKS> cur, nxt;
-  mfma_load_item<NKS>(p, item, n, gpr, r, term_e, term_g, term_c, cur, WG_ROWS, 32 * wave);
+  mfma_load_item<NKS, QP>(p, item, n, gpr, r, term_e, term_g, term_c, cur, WG_ROWS, 32 * wave);
   bool have_nxt = item + grid < p.n_items;
-  if (have_nxt) mfma_load_item<NKS>(p, item + grid, n, gpr, r, term_e, term_g, term_c, nxt, WG_ROWS, 32 * wave);
+  if (have_nxt) mfma_load_item<NKS, QP>(p, item + grid, n, gpr, r, term_e, term_g, term_c, nxt, WG_ROWS, 32 * wave);
   else nxt = cur;
   int cs = cur.col0;
   uint32_t lane_off = mfma_lane_offset<NKS>(cur, cs, n, h);
@@ -562,16 +584,16 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma(LaunchPlan p, Ter
   mfma_load_w<NKS>(cur, lane_off, wa);
 #pragma unroll
   for (int v = 0; v < 16; ++v) wb[v] = u32x4{0u, 0u, 0u, 0u};
-  wg_fetch_q<NKS>(cur.Apk, cur.ncb, cs, n, gpr, wave, term_e, term_g, wg_lds);
+  wg_fetch_q<NKS, QP>(cur.Apk, cur.ncb, cs, n, gpr, wave, term_e, term_g, wg_lds);
   wg_drain_and_barrier();
   __amdgpu_buffer_rsrc_t prev_res = w_resource(cur.W, cur.wbytes);
   uint32_t prev_off = kOutOfRange, prev_stride = 0;
 
   bool a_is_cur = true;
   while (true) {
-    if (!wg_step<NKS>(p, grid, n, h, lane, wave, gpr, r, term_e, term_g, term_c, cur, nxt, have_nxt, item, cs, lane_off,
+    if (!wg_step<NKS, QP>(p, grid, n, h, lane, wave, gpr, r, term_e, term_g, term_c, cur, nxt, have_nxt, item, cs, lane_off,
                       prev_res, prev_off, prev_stride, wa, wb, 0)) { a_is_cur = true; break; }
-    if (!wg_step<NKS>(p, grid, n, h, lane, wave, gpr, r, term_e, term_g, term_c, cur, nxt, have_nxt, item, cs, lane_off,
+    if (!wg_step<NKS, QP>(p, grid, n, h, lane, wave, gpr, r, term_e, term_g, term_c, cur, nxt, have_nxt, item, cs, lane_off,
                       prev_res, prev_off, prev_stride, wb, wa, 1)) { a_is_cur = false; break; }
   }
   if (a_is_cur) {
@@ -587,31 +609,36 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma(LaunchPlan p, Ter
   }
 }
 
-template <int NKS>
+template <int NKS, int QP>
 static hipError_t launch_wg(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int grid, hipStream_t s) {
-  const size_t lds = size_t(2) * NKS * 8 * 2 * 64 * sizeof(u32x4);     // 32 KB per k-step
+  const size_t lds = size_t(2) * NKS * 8 * QP * 64 * sizeof(u32x4);     // 16 KB per k-step and Q part, two buffers
   static bool configured = false;
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_switch_mfma<NKS>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_switch_mfma<NKS, QP>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
     if (e != hipSuccess) return e;
     configured = true;
   }
-  hipLaunchKernelGGL(k_switch_mfma<NKS>, dim3(grid), dim3(64 * WG_WAVES), lds, s, p, t, t_dev, r);
+  hipLaunchKernelGGL((k_switch_mfma<NKS, QP>), dim3(grid), dim3(64 * WG_WAVES), lds, s, p, t, t_dev, r);
   return hipGetLastError();
+}
+
+template <int QP>
+static hipError_t launch_wg_qp(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int grid, hipStream_t s) {
+  const int n_groups = t.n * (r / 8);
+  switch ((n_groups + 1) / 2) {
+    case 1: return launch_wg<1, QP>(p, t, t_dev, r, grid, s);
+    case 2: return launch_wg<2, QP>(p, t, t_dev, r, grid, s);
+    case 3: return launch_wg<3, QP>(p, t, t_dev, r, grid, s);
+    case 4: return launch_wg<4, QP>(p, t, t_dev, r, grid, s);
+    default: return hipErrorInvalidValue;
+  }
 }
 
 // t.n sizes the kernel (k-steps kept in registers); with t_dev the kernel takes the list itself, which may
 // be shorter, from device memory
-hipError_t launch_switch_mfma(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int grid, hipStream_t s) {
-  const int n_groups = t.n * (r / 8);
-  switch ((n_groups + 1) / 2) {
-    case 1: return launch_wg<1>(p, t, t_dev, r, grid, s);
-    case 2: return launch_wg<2>(p, t, t_dev, r, grid, s);
-    case 3: return launch_wg<3>(p, t, t_dev, r, grid, s);
-    case 4: return launch_wg<4>(p, t, t_dev, r, grid, s);
-    default: return hipErrorInvalidValue;
-  }
+hipError_t launch_switch_mfma(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int qp, int grid, hipStream_t s) {
+  return qp == 2 ? launch_wg_qp<2>(p, t, t_dev, r, grid, s) : launch_wg_qp<1>(p, t, t_dev, r, grid, s);
 }
 
 // ---------------------------------------------------------------------------
@@ -637,7 +664,8 @@ hipError_t launch_switch_mfma(const LaunchPlan& p, const Terms& t, const Terms* 
 // ---------------------------------------------------------------------------
 constexpr int BK_KC = 4;                       // k-steps per LDS chunk
 constexpr int BK_MAX_GROUPS = 32;              // 8-rank groups of the fused rank: K <= 256
-constexpr int kBkBufBytes = BK_KC * 8 * 2 * 64 * 16;     // one LDS buffer: 64 KB
+template <int QP>
+constexpr int kBkBufBytes = BK_KC * 8 * QP * 64 * 16;    // one LDS buffer: 64 KB (32 KB when Q has no low part)
 
 // 16-byte-per-lane LDS copy, source = scalar base + 32-bit lane offset + immediate (see lds_dma16);
 // lane l lands at lds_addr + 16*l.  The hardware adds the instruction's immediate to the LDS address as
@@ -650,7 +678,7 @@ __device__ __forceinline__ void lds_dma16_s(uint32_t voff, const void* sbase, ui
                : "memory", "m0");
 }
 
-// What one wave needs to copy its quarter of a Q chunk: instruction d = 4*kk + 2*j + hl moves block
+// What one wave needs to copy its quarter of a Q chunk: instruction d = (2*kk + j)*QP + hl moves block
 // 2*wave + j, part hl, of k-step kk.
 struct BkCopy {
   const void* sbase;          // packed A of the linear + column block + this wave's two blocks (uniform)
@@ -658,17 +686,17 @@ struct BkCopy {
   uint32_t voff[BK_KC];       // per lane: start of the (expert, rank group) of this lane's half of k-step kk, + 16 * n
 };
 
-template <int D>
+template <int D, int QP>
 __device__ __forceinline__ void bk_copy_one(const BkCopy& c) {
-  constexpr int kk = D >> 2, j = (D >> 1) & 1, hl = D & 1;
-  lds_dma16_s<(2 * j + hl) * 512>(c.voff[kk], c.sbase, c.lds_base + uint32_t(kk * 16384 + j * 2048 + hl * 1024));
+  constexpr int kk = D / (2 * QP), j = (D / QP) & 1, hl = D % QP;
+  lds_dma16_s<(QP * j + hl) * 512>(c.voff[kk], c.sbase, c.lds_base + uint32_t((kk * 16 + j * 2) * QP * 512 + hl * 1024));
 }
 
-template <int D0, int D1>
+template <int D0, int D1, int QP>
 __device__ __forceinline__ void bk_copy_range(const BkCopy& c) {
   if constexpr (D0 < D1) {
-    bk_copy_one<D0>(c);
-    bk_copy_range<D0 + 1, D1>(c);
+    bk_copy_one<D0, QP>(c);
+    bk_copy_range<D0 + 1, D1, QP>(c);
   }
 }
 
@@ -681,17 +709,17 @@ __device__ __forceinline__ void bk_for_each_group(F& f, std::integer_sequence<in
 // matrix instructions (pair q outermost, k-step kk inside).  FIRST: widen the W words of pair q+1
 // during pair q (pair 0 is widened by the caller).  LAST: round pair q-1 during pair q (pair 3 by the
 // caller).  COPY: issue the 16 LDS-copy instructions of `cp` along with the first 8 groups.
-template <bool FIRST, bool LAST, bool COPY>
+template <bool FIRST, bool LAST, bool COPY, int QP>
 __device__ __forceinline__ void bk_chunk(const u32x4* p_hi, const u32x4* p_lo /* the chunk's BK_KC entries */,
                                          const u32x4* qbuf /* LDS: slot 0 of the chunk's buffer + lane */,
                                          f32x16 (&a0)[4], f32x16 (&a1)[4], u32x4 (&wcur)[16], const BkCopy& cp) {
-  u32x4 qr[2][2][2];           // [parity][block of the pair][high, low]
+  u32x4 qr[2][2][QP];          // [parity][block of the pair][high, low]
   auto fetch = [&](int idx) {
     const int q = idx / BK_KC, kk = idx % BK_KC;
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int hl = 0; hl < 2; ++hl) qr[idx & 1][j][hl] = qbuf[((kk * 8 + 2 * q + j) * 2 + hl) * 64];
+      for (int hl = 0; hl < QP; ++hl) qr[idx & 1][j][hl] = qbuf[((kk * 8 + 2 * q + j) * QP + hl) * 64];
   };
   fetch(0);
   __builtin_amdgcn_sched_barrier(0);
@@ -699,9 +727,8 @@ __device__ __forceinline__ void bk_chunk(const u32x4* p_hi, const u32x4* p_lo /*
     constexpr int idx = decltype(IDX)::value;
     constexpr int q = idx / BK_KC, kk = idx % BK_KC;
     if (idx + 1 < 4 * BK_KC) fetch(idx + 1);
-    if constexpr (COPY && idx < 8) {          // two per group in the first half: the last copy has half a chunk to land
-      bk_copy_one<2 * idx>(cp);
-      bk_copy_one<2 * idx + 1>(cp);
+    if constexpr (COPY && idx < 8) {          // the 8 * QP copies in the first half: the last one has half a chunk to land
+      bk_copy_range<QP * idx, QP * idx + QP, QP>(cp);
     }
     constexpr int kRowsPer = 16 / BK_KC;
 #pragma unroll
@@ -719,18 +746,20 @@ __device__ __forceinline__ void bk_chunk(const u32x4* p_hi, const u32x4* p_lo /*
     const bf16x8 ph = __builtin_bit_cast(bf16x8, p_hi[kk]);
     const bf16x8 pl = __builtin_bit_cast(bf16x8, p_lo[kk]);
     const bf16x8 h0 = __builtin_bit_cast(bf16x8, qr[idx & 1][0][0]);
-    const bf16x8 l0 = __builtin_bit_cast(bf16x8, qr[idx & 1][0][1]);
     const bf16x8 h1 = __builtin_bit_cast(bf16x8, qr[idx & 1][1][0]);
-    const bf16x8 l1 = __builtin_bit_cast(bf16x8, qr[idx & 1][1][1]);
     a0[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl, h0, a0[q], 0, 0, 0);
     a1[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl, h1, a1[q], 0, 0, 0);
-    a0[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, l0, a0[q], 0, 0, 0);
-    a1[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, l1, a1[q], 0, 0, 0);
+    if constexpr (QP == 2) {
+      const bf16x8 l0 = __builtin_bit_cast(bf16x8, qr[idx & 1][0][QP - 1]);
+      const bf16x8 l1 = __builtin_bit_cast(bf16x8, qr[idx & 1][1][QP - 1]);
+      a0[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, l0, a0[q], 0, 0, 0);
+      a1[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, l1, a1[q], 0, 0, 0);
+    }
     a0[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, h0, a0[q], 0, 0, 0);
     a1[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, h1, a1[q], 0, 0, 0);
-    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);          // the next group's 4 LDS reads first
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 * QP, 0);     // the next group's LDS reads first
 #pragma unroll
-    for (int i = 0; i < 6; ++i) {
+    for (int i = 0; i < 2 + 2 * QP; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        // one matrix instruction
       __builtin_amdgcn_sched_group_barrier(0x002, (FIRST || LAST) ? 2 : 0, 0);   // a few vector instructions
     }
@@ -760,7 +789,7 @@ template <int NCH>
 struct BkWave {             // per-wave state of the chunked kernel that outlives a step
   u32x4 p_hi[BK_KC * NCH], p_lo[BK_KC * NCH];
   int32_t eg[2][BK_KC * NCH];       // expert * (r/8) + rank group of lane half h, k-step ks (uniform: scalar registers)
-  int32_t eg_bytes;                 // bytes of one (expert, rank group) slab of the linear's packed A: column blocks * 8 KB (uniform)
+  int32_t eg_bytes;                 // bytes of one (expert, rank group) slab of the linear's packed A: column blocks * 4 KB * Q parts (uniform)
   const uint16_t* Apk;
   const uint16_t* W;
   int wbytes;
@@ -769,11 +798,11 @@ struct BkWave {             // per-wave state of the chunked kernel that outlive
   int n, h;
 };
 
-template <int NCH>
+template <int NCH, int QP>
 __device__ __forceinline__ BkCopy bk_copy_desc(const BkWave<NCH>& w, int cs, int ch, int buf) {
   BkCopy c;
-  c.sbase = uniform(reinterpret_cast<const char*>(w.Apk) + (long long)(cs / MT_STEP) * 8192);
-  c.lds_base = w.lds0 + uint32_t(buf) * kBkBufBytes;
+  c.sbase = uniform(reinterpret_cast<const char*>(w.Apk) + (long long)(cs / MT_STEP) * (4096 * QP));
+  c.lds_base = w.lds0 + uint32_t(buf) * kBkBufBytes<QP>;
 #pragma unroll
   for (int kk = 0; kk < BK_KC; ++kk)
     c.voff[kk] = uint32_t(w.h ? w.eg[1][ch * BK_KC + kk] * w.eg_bytes : w.eg[0][ch * BK_KC + kk] * w.eg_bytes) + uint32_t(16 * w.n);
@@ -782,14 +811,14 @@ __device__ __forceinline__ BkCopy bk_copy_desc(const BkWave<NCH>& w, int cs, int
 
 // One 32 x 256 step of a wave.  wcur holds the tile to update (loaded one step ago); wprev holds the finished
 // tile of the previous step: it is stored, then reloaded with the tile of the next step.
-template <int NCH>
+template <int NCH, int QP>
 __device__ __forceinline__ void bk_step(const BkWave<NCH>& w, int cs, bool more, int lane, int& buf, uint32_t prev_off,
                                         uint32_t next_off, u32x4 (&wcur)[16], u32x4 (&wprev)[16]) {
   const __amdgpu_buffer_rsrc_t res = w_resource(w.W, w.wbytes);
   f32x16 a0[4], a1[4];
   {
-    const BkCopy cp = bk_copy_desc<NCH>(w, cs, 1 % NCH, buf ^ 1);
-    bk_copy_range<0, 16>(cp);
+    const BkCopy cp = bk_copy_desc<NCH, QP>(w, cs, 1 % NCH, buf ^ 1);
+    bk_copy_range<0, 8 * QP, QP>(cp);
     __builtin_amdgcn_sched_barrier(0);                    // keep the W requests younger than the Q copy
 #pragma unroll
     for (int v = 0; v < 16; ++v)
@@ -803,18 +832,18 @@ __device__ __forceinline__ void bk_step(const BkWave<NCH>& w, int cs, bool more,
       a0[0][v] = bf16_lo(wcur[v][0]);
       a1[0][v] = bf16_hi(wcur[v][0]);
     }
-    bk_chunk<true, false, false>(w.p_hi, w.p_lo, wg_lds + buf * (kBkBufBytes / 16) + lane, a0, a1, wcur, cp);
+    bk_chunk<true, false, false, QP>(w.p_hi, w.p_lo, wg_lds + buf * (kBkBufBytes<QP> / 16) + lane, a0, a1, wcur, cp);
     bk_drain_and_barrier<32>();
     buf ^= 1;
   }
 #pragma unroll
   for (int ch = 1; ch < NCH; ++ch) {
     // the following chunk's Q (after the last chunk: chunk 0 of the next step; after the last step a harmless re-read)
-    const BkCopy cp = bk_copy_desc<NCH>(w, (ch + 1 < NCH || !more) ? cs : cs + MT_STEP, (ch + 1) % NCH, buf ^ 1);
+    const BkCopy cp = bk_copy_desc<NCH, QP>(w, (ch + 1 < NCH || !more) ? cs : cs + MT_STEP, (ch + 1) % NCH, buf ^ 1);
     if (ch + 1 < NCH) {
-      bk_chunk<false, false, true>(w.p_hi + ch * BK_KC, w.p_lo + ch * BK_KC, wg_lds + buf * (kBkBufBytes / 16) + lane, a0, a1, wcur, cp);
+      bk_chunk<false, false, true, QP>(w.p_hi + ch * BK_KC, w.p_lo + ch * BK_KC, wg_lds + buf * (kBkBufBytes<QP> / 16) + lane, a0, a1, wcur, cp);
     } else {
-      bk_chunk<false, true, true>(w.p_hi + ch * BK_KC, w.p_lo + ch * BK_KC, wg_lds + buf * (kBkBufBytes / 16) + lane, a0, a1, wcur, cp);
+      bk_chunk<false, true, true, QP>(w.p_hi + ch * BK_KC, w.p_lo + ch * BK_KC, wg_lds + buf * (kBkBufBytes<QP> / 16) + lane, a0, a1, wcur, cp);
 #pragma unroll
       for (int v = 0; v < 16; ++v) wcur[v][3] = pack_bf16(a0[3][v], a1[3][v]);
     }
@@ -823,7 +852,7 @@ __device__ __forceinline__ void bk_step(const BkWave<NCH>& w, int cs, bool more,
   }
 }
 
-template <int NCH>
+template <int NCH, int QP>
 __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t, const Terms* t_dev, int r) {
   constexpr int NKS = BK_KC * NCH;
   static_assert(NCH >= 2 && 2 * NKS <= BK_MAX_GROUPS, "chunks per step");
@@ -855,7 +884,7 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
   BkWave<NCH> w;
   w.n = n;
   w.h = h;
-  w.lds0 = uniform(int(uint32_t(uintptr_t((const __attribute__((address_space(3))) void*)wg_lds)))) + uint32_t(wave) * 4096u;
+  w.lds0 = uniform(int(uint32_t(uintptr_t((const __attribute__((address_space(3))) void*)wg_lds)))) + uint32_t(wave) * (2048u * QP);
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks) {
     w.eg[0][ks] = uniform(s_eg[2 * ks]);
@@ -868,7 +897,7 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
   for (int item = first_item; item < p.n_items; item += grid) {       // uniform over the workgroup
     const int seg = uniform(find_segment(p.first, p.n_sel, item));
     const LinDesc* Lp = p.lin + uniform(p.sel[seg]);
-    const float* B = uniform(Lp->B);
+    const void* B = uniform(Lp->B);
     const int out = uniform(Lp->out), in = uniform(Lp->in);
     int row0, col0;
     decode_item(uniform(item - p.first[seg]), in, kMfmaTileRows, p.tile_cols, &row0, &col0);
@@ -879,8 +908,8 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
     w.wbytes = out * in * 2;
     w.stride = uint32_t(in) * 2u;
     // the packed A of the linear, advanced to this wave's two blocks inside a column block
-    w.Apk = uniform(reinterpret_cast<const uint16_t*>(reinterpret_cast<const char*>(Lp->Apk) + wave * 2048));
-    w.eg_bytes = ncb * 8192;
+    w.Apk = uniform(reinterpret_cast<const uint16_t*>(reinterpret_cast<const char*>(Lp->Apk) + wave * (1024 * QP)));
+    w.eg_bytes = ncb * (4096 * QP);
     const uint32_t row0_byte = uint32_t(row0) * w.stride;
 
     // P = coeff * B for this lane's row and its half of every k-step, split into bf16 high + low
@@ -890,20 +919,15 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
 #pragma unroll
       for (int ks = 0; ks < NKS; ++ks) {
         const int G = 2 * ks + h;
-        const LSW_GLOBAL f32x4* src = as_global(reinterpret_cast<const f32x4*>(
-            B + ((long long)s_e[G] * out + prow) * r + 8 * s_g[G]));
-        const f32x4 b0 = src[0];
-        const f32x4 b1 = src[1];
+        float b[8];
+        load8<QP>(B, ((long long)s_e[G] * out + prow) * r + 8 * s_g[G], b);
         const float c = prow_ok ? s_c[G] : 0.0f;
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
+        for (int q = 0; q < 4; ++q) {
           uint32_t hi, lo;
-          split2(c * b0[2 * q], c * b0[2 * q + 1], &hi, &lo);
+          split2(c * b[2 * q], c * b[2 * q + 1], &hi, &lo);
           w.p_hi[ks][q] = hi;
           w.p_lo[ks][q] = lo;
-          split2(c * b1[2 * q], c * b1[2 * q + 1], &hi, &lo);
-          w.p_hi[ks][2 + q] = hi;
-          w.p_lo[ks][2 + q] = lo;
         }
       }
     }
@@ -917,8 +941,8 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
     uint32_t off_a = lane_offset(col0), off_b = kOutOfRange;
     {
       const __amdgpu_buffer_rsrc_t res = w_resource(w.W, w.wbytes);
-      const BkCopy cp = bk_copy_desc<NCH>(w, col0, 0, buf);
-      bk_copy_range<0, 16>(cp);
+      const BkCopy cp = bk_copy_desc<NCH, QP>(w, col0, 0, buf);
+      bk_copy_range<0, 8 * QP, QP>(cp);
 #pragma unroll
       for (int v = 0; v < 16; ++v)
         wa[v] = __builtin_amdgcn_raw_buffer_load_b128(res, off_a + uint32_t(8 * (v >> 2) + (v & 3)) * w.stride, 0, /*nt*/ 2);
@@ -933,7 +957,7 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
       bool more = uniform(int(cs + MT_STEP < col_end)) != 0;
       {
         const uint32_t nxt = more ? lane_offset(cs + MT_STEP) : kOutOfRange;
-        bk_step<NCH>(w, cs, more, lane, buf, off_b, nxt, wa, wb);     // stores wb (previous tile), reloads it, updates wa
+        bk_step<NCH, QP>(w, cs, more, lane, buf, off_b, nxt, wa, wb);     // stores wb (previous tile), reloads it, updates wa
         off_b = nxt;
       }
       last_in_a = true;
@@ -942,7 +966,7 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
       more = uniform(int(cs + MT_STEP < col_end)) != 0;
       {
         const uint32_t nxt = more ? lane_offset(cs + MT_STEP) : kOutOfRange;
-        bk_step<NCH>(w, cs, more, lane, buf, off_a, nxt, wb, wa);
+        bk_step<NCH, QP>(w, cs, more, lane, buf, off_a, nxt, wb, wa);
         off_a = nxt;
       }
       last_in_a = false;
@@ -965,28 +989,33 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
   }
 }
 
-template <int NCH>
+template <int NCH, int QP>
 static hipError_t launch_bigk(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int grid, hipStream_t s) {
-  const size_t lds = size_t(2) * BK_KC * 8 * 2 * 64 * sizeof(u32x4);     // 2 x 64 KB
+  const size_t lds = size_t(2) * kBkBufBytes<QP>;     // 2 x 64 KB (2 x 32 KB for bf16 factors)
   static bool configured = false;
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_switch_mfma_bigk<NCH>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_switch_mfma_bigk<NCH, QP>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
     if (e != hipSuccess) return e;
     configured = true;
   }
-  hipLaunchKernelGGL(k_switch_mfma_bigk<NCH>, dim3(grid), dim3(256), lds, s, p, t, t_dev, r);
+  hipLaunchKernelGGL((k_switch_mfma_bigk<NCH, QP>), dim3(grid), dim3(256), lds, s, p, t, t_dev, r);
   return hipGetLastError();
 }
 
-hipError_t launch_switch_mfma_bigk(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int grid, hipStream_t s) {
+template <int QP>
+static hipError_t launch_bigk_qp(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int grid, hipStream_t s) {
   const int n_groups = t.n * (r / 8);
   switch ((n_groups + 2 * BK_KC - 1) / (2 * BK_KC)) {
-    case 2: return launch_bigk<2>(p, t, t_dev, r, grid, s);
-    case 3: return launch_bigk<3>(p, t, t_dev, r, grid, s);
-    case 4: return launch_bigk<4>(p, t, t_dev, r, grid, s);
+    case 2: return launch_bigk<2, QP>(p, t, t_dev, r, grid, s);
+    case 3: return launch_bigk<3, QP>(p, t, t_dev, r, grid, s);
+    case 4: return launch_bigk<4, QP>(p, t, t_dev, r, grid, s);
     default: return hipErrorInvalidValue;
   }
+}
+
+hipError_t launch_switch_mfma_bigk(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int qp, int grid, hipStream_t s) {
+  return qp == 2 ? launch_bigk_qp<2>(p, t, t_dev, r, grid, s) : launch_bigk_qp<1>(p, t, t_dev, r, grid, s);
 }
 
 // ---------------------------------------------------------------------------

@@ -110,10 +110,11 @@ def host_stack(wl: Workload):
             for _, _, o, i in wl.linear_shapes()]
 
 
-def device_stack(wl: Workload, device="cuda"):
+def device_stack(wl: Workload, device="cuda", factor_dtype=torch.float32):
     """Every linear of a workload drawn on the device with wl.seed.
 
-    Returns a list of (W bf16 [out,in], A fp32 [E,r,in], B fp32 [E,out,r]) torch tensors.
+    Returns a list of (W bf16 [out,in], A [E,r,in], B [E,out,r]) torch tensors; the factors are drawn in
+    fp32 and stored as `factor_dtype` (fp32, or bf16: each value rounded once to the nearest bf16).
     """
     g = torch.Generator(device=device)
     g.manual_seed(wl.seed)
@@ -122,7 +123,7 @@ def device_stack(wl: Workload, device="cuda"):
         W = (torch.randn(o, i, generator=g, device=device, dtype=torch.float32) * wl.w_std).to(torch.bfloat16)
         A = torch.randn(wl.experts, wl.rank, i, generator=g, device=device, dtype=torch.float32) * wl.a_std
         B = torch.randn(wl.experts, o, wl.rank, generator=g, device=device, dtype=torch.float32) * wl.b_std
-        stack.append((W, A, B))
+        stack.append((W, A.to(factor_dtype), B.to(factor_dtype)))
     return stack
 
 

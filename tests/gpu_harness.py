@@ -28,8 +28,14 @@ class DeviceStack:
             L.lsw_set_option(self.ctx, L.LSW_OPT_KERNEL, kernel)
 
     @classmethod
-    def from_host(cls, host_stack, shapes, E, r, scale=1.0, kernel=L.KERNEL_AUTO):
-        dev = [(bits_to_device(W), torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()) for W, A, B in host_stack]
+    def from_host(cls, host_stack, shapes, E, r, scale=1.0, kernel=L.KERNEL_AUTO, bf16_factors=False):
+        """bf16_factors: upload A and B as bf16 tensors (the host arrays must already hold bf16-representable values,
+        see bf16_factor_stack), so that the library is created with LSW_FACTOR_BF16."""
+        conv = (lambda x: torch.from_numpy(x).cuda().to(torch.bfloat16)) if bf16_factors else (lambda x: torch.from_numpy(x).cuda())
+        dev = [(bits_to_device(W), conv(A), conv(B)) for W, A, B in host_stack]
+        if bf16_factors:
+            for (_, A, B), (_, Ad, Bd) in zip(host_stack, dev):
+                assert torch.equal(Ad.float().cpu(), torch.from_numpy(A)) and torch.equal(Bd.float().cpu(), torch.from_numpy(B))
         return cls(dev, shapes, E, r, scale, kernel)
 
     def switch(self, old, new, layers=None):
@@ -53,6 +59,13 @@ class DeviceStack:
             self.close()
         except Exception:
             pass
+
+
+def bf16_factor_stack(host_stack):
+    """The same stack with every factor rounded to the nearest bf16 value (kept in fp32 arrays for the oracle)."""
+    def rnd(x):
+        return torch.from_numpy(x).to(torch.bfloat16).float().numpy()
+    return [(W, rnd(A), rnd(B)) for W, A, B in host_stack]
 
 
 def check_step(prev_bits, got_bits, A, B, old, new, scale=1.0, rows=None):

@@ -11,7 +11,7 @@ from oracle import lsw_oracle as O
 from paper_2405_17741_amd import binding as L
 from paper_2405_17741_amd import inputs as I
 from tests.golden_cases import load_rne_cases
-from tests.gpu_harness import DeviceStack, bits_to_device, check_step, device_to_bits, merge_reports
+from tests.gpu_harness import bf16_factor_stack, DeviceStack, bits_to_device, check_step, device_to_bits, merge_reports
 
 pytestmark = pytest.mark.gpu
 KERNELS = [L.KERNEL_VALU, L.KERNEL_MFMA]

@@ -169,6 +169,17 @@ def test_create_validates_before_touching_any_device(lin, E, r, scale, status):
     assert L.lsw_last_error()
 
 
+@pytest.mark.parametrize("r,dtype,status", [
+    (4, L.LSW_FACTOR_BF16, L.LSW_ERR_SHAPE),      # bf16 rows of B must stay 16-byte aligned
+    (8, 2, L.LSW_ERR_ARG),                        # unknown storage type
+    (8, -1, L.LSW_ERR_ARG),
+])
+def test_create_ex_validates_the_factor_dtype(r, dtype, status):
+    with pytest.raises(L.LswError) as e:
+        L.lsw_create_adapters([_fake_linear()], 8, r, 1.0, dtype)
+    assert e.value.status == status
+
+
 def test_null_context_calls_fail_cleanly():
     lib = L.lib()
     assert lib.lsw_switch(None, None, 0, None, None, 0, None, None, 0, None) == L.LSW_ERR_ARG

@@ -200,6 +200,43 @@ def main():
     dev_us = (time.perf_counter() - t0) * 1e6 / n_dev
     dev_flags = L.lsw_dev_status(ctx)
 
+    # a partial layer set (the `layers` argument): the first half of the layers, there and back
+    half = list(range(wl.layers // 2)) or [0]
+    other = L.lsw_route(logits[0], wl.top_k)
+    sub_bytes = algorithmic_bytes(wl, len(L.lsw_build_terms(old[0], old[1], other[0], other[1], wl.experts)[0]),
+                                  2 if bf16_factors else 4) * len(half) / wl.layers
+    L.lsw_switch(ctx, old[0], old[1], other[0], other[1], layers=half, stream=stream)
+    L.lsw_switch(ctx, other[0], other[1], old[0], old[1], layers=half, stream=stream)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(3):
+        L.lsw_switch(ctx, old[0], old[1], other[0], other[1], layers=half, stream=stream)
+        L.lsw_switch(ctx, other[0], other[1], old[0], old[1], layers=half, stream=stream)
+    b.record()
+    b.synchronize()
+    sub_us = a.elapsed_time(b) * 1e3 / 6
+    subset = {"layers": len(half), "us": round(sub_us, 1), "GBps": round(sub_bytes / (sub_us * 1e-6) / 1e9, 1)}
+
+    # drift control: rebuild every weight from a base copy with the current set merged (reads the copy, writes W)
+    rebase = None
+    if 2 * 2 * wl.w_elements() < 200e9:
+        base = [W.clone() for W, _, _ in stack]
+        L.lsw_set_base(ctx, [t.data_ptr() for t in base])
+        L.lsw_rebase(ctx, old[0], old[1], stream=stream)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(5):
+            L.lsw_rebase(ctx, old[0], old[1], stream=stream)
+        b.record()
+        b.synchronize()
+        rb_us = a.elapsed_time(b) * 1e3 / 5
+        rebase = {"us": round(rb_us, 1), "GBps": round(algorithmic_bytes(wl, len(old[0]), 2 if bf16_factors else 4) / (rb_us * 1e-6) / 1e9, 1),
+                  "note": "lsw_rebase: W <- rne(W_base + current set), base copy read, W written, one launch"}
+        torch.cuda.synchronize()
+        del base
+
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
@@ -243,6 +280,8 @@ def main():
         "device_routing": {"us_per_token": round(dev_us, 1), "tokens": n_dev, "error_flags": dev_flags,
                            "note": "lsw_route_dev + lsw_switch_dev per token, lists resident on the device, no host round trip; "
                                    "launches sized for k_old + k_new terms"},
+        "layer_subset": subset,
+        "rebase": rebase,
         "inplace_probe": {**probe, "note": "lsw_probe_inplace on the same weights: in-place bf16 read+write only; "
                                            "the practical ceiling of the switch's access pattern",
                           "switch_over_best_probe": round(achieved / max(probe.values()), 4)},

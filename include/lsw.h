@@ -118,6 +118,28 @@ lsw_status lsw_switch(lsw_ctx* ctx, const int32_t* layers, int32_t n_layers,
                       void* hip_stream);
 
 /*
+ * Drift control.  Eq. 7 treats the unmerge as exact; in bf16 it is not: every switch rounds once, so after T
+ * switches W differs from rne(W_base + delta_current) by a random walk of about 0.3 * sqrt(T) ulp.  A caller
+ * that keeps a copy of the base weights (the second copy Sec. 3.3 avoids for memory's sake; at 288 GB per GPU
+ * it is affordable) can remove the accumulated error at any token:
+ *
+ * lsw_set_base   registers the copies.  W_base is a HOST array of n_lin DEVICE pointers, entry p a bf16
+ *                [out_p, in_p] row-major tensor, 16-byte aligned, BORROWED and never written, that holds
+ *                linear p with NOTHING merged.  n_lin must equal the number of registered linears.  The call
+ *                synchronises the device (it rewrites the descriptor table the kernels read).
+ * lsw_rebase     W_p <- rne_bf16(W_base_p + sum_c s*g_c*(B_c A_c)) for every linear of the selected layers
+ *                (Eq. 4 applied to the base copy): the same kernels as lsw_switch, one launch, reading the base
+ *                copy and writing W.  ids/gates/k: HOST, the set that is to be merged afterwards (what
+ *                lsw_switch would have been given as `new`); k = 0 copies the base weights back.
+ *                Asynchronous on hip_stream.  The tracked state of the touched layers becomes (ids, gates).
+ * Errors: LSW_ERR_ARG (null, n_lin mismatch, base copy == W, bad list or layer), LSW_ERR_SHAPE (misaligned),
+ * LSW_ERR_STATE (lsw_rebase before lsw_set_base), LSW_ERR_DEVICE.
+ */
+lsw_status lsw_set_base(lsw_ctx* ctx, const void* const* W_base, int32_t n_lin);
+lsw_status lsw_rebase(lsw_ctx* ctx, const int32_t* layers, int32_t n_layers,
+                      const int32_t* ids, const float* gates, int32_t k, void* hip_stream);
+
+/*
  * Decode through one merged linear (Eq. 3: the backbone runs as if it had no adapters):
  * y[i] = sum_j W[i,j] * x[j], fp32 accumulation.
  *

@@ -24,6 +24,7 @@ EXPORTS = (
     "lsw_get_state", "lsw_set_option", "lsw_query", "lsw_worklist_size", "lsw_worklist_item",
     "lsw_destroy", "lsw_last_error", "lsw_probe_inplace", "lsw_merged_gemv_all",
     "lsw_route_dev", "lsw_switch_dev", "lsw_dev_status", "lsw_gemv_bf16", "lsw_create_adapters_ex",
+    "lsw_set_base", "lsw_rebase",
 )
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblsw.so")
@@ -58,6 +59,8 @@ def lib() -> C.CDLL:
                                              C.c_int32, C.POINTER(C.c_void_p)]
         L.lsw_switch.argtypes = [C.c_void_p, _i32p, C.c_int32, _i32p, _f32p, C.c_int32, _i32p, _f32p, C.c_int32,
                                  C.c_void_p]
+        L.lsw_set_base.argtypes = [C.c_void_p, C.POINTER(C.c_void_p), C.c_int32]
+        L.lsw_rebase.argtypes = [C.c_void_p, _i32p, C.c_int32, _i32p, _f32p, C.c_int32, C.c_void_p]
         L.lsw_merged_gemv.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.lsw_merged_gemv_all.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.lsw_route_dev.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -137,6 +140,22 @@ def lsw_switch(ctx: int, old_ids, old_gates, new_ids, new_gates, layers=None, st
     if n_og != k_old or n_ng != k_new:
         raise LswError(LSW_ERR_ARG, "ids and gates differ in length")
     _check(lib().lsw_switch(ctx, lp, nl, oi, og, k_old, ni, ng, k_new, C.c_void_p(stream)))
+
+
+def lsw_set_base(ctx: int, base_ptrs) -> None:
+    """base_ptrs: device addresses (ints) of the base copy of every registered linear, in registration order."""
+    base_ptrs = list(base_ptrs)
+    arr = (C.c_void_p * max(len(base_ptrs), 1))(*base_ptrs)
+    _check(lib().lsw_set_base(ctx, arr if base_ptrs else None, len(base_ptrs)))
+
+
+def lsw_rebase(ctx: int, ids, gates, layers=None, stream: int = 0) -> None:
+    _, lp, nl = _i32(layers)
+    ki, ip, k = _i32(ids)
+    kg, gp, n_g = _f32(gates)
+    if n_g != k:
+        raise LswError(LSW_ERR_ARG, "ids and gates differ in length")
+    _check(lib().lsw_rebase(ctx, lp, nl, ip, gp, k, C.c_void_p(stream)))
 
 
 def lsw_merged_gemv(ctx: int, lin_index: int, x_ptr: int, y_ptr: int, stream: int = 0) -> None:

@@ -74,6 +74,8 @@ struct lsw_ctx {
   int device = 0;
   int n_cu = 0;
   LinDesc* d_lin = nullptr;
+  std::vector<LinDesc> desc;                 // host copy of the descriptor table
+  bool have_base = false;                    // lsw_set_base has registered the base copies
   uint16_t* d_apk = nullptr;                 // packed A of all linears (r % 8 == 0 only)
   Terms* d_terms = nullptr;                  // term list built on the device by lsw_switch_dev, followed by the sticky error word
   int32_t* d_err = nullptr;
@@ -311,6 +313,7 @@ extern "C" lsw_status lsw_create_adapters_ex(const lsw_linear* lin, int32_t n_li
     desc[p].A = lin[p].A;
     desc[p].B = lin[p].B;
     desc[p].Apk = pack ? c->d_apk + apk_off[p] : nullptr;
+    desc[p].Wbase = nullptr;
     desc[p].out = lin[p].out;
     desc[p].in = lin[p].in;
     desc[p].x_off = c->x_elems;
@@ -330,6 +333,7 @@ extern "C" lsw_status lsw_create_adapters_ex(const lsw_linear* lin, int32_t n_li
   e = hipMemcpy(c->d_lin, desc.data(), desc.size() * sizeof(LinDesc), hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipDeviceSynchronize();   // the pack kernels have read A
   if (e != hipSuccess) { cleanup(); return fail(LSW_ERR_DEVICE, "descriptor upload / pack failed: %s", hipGetErrorString(e)); }
+  c->desc = std::move(desc);
   *out = c.release();
   return LSW_OK;
 }
@@ -397,7 +401,7 @@ static lsw_status select_layers(lsw_ctx* c, const int32_t* layers, int32_t n_lay
 
 // One launch over the selected layers.  t.n sizes the launch; with t_dev the kernel reads the list from device memory.
 static lsw_status launch_switch(lsw_ctx* c, const std::vector<int32_t>& sel_layers, const Terms& t, const Terms* t_dev,
-                                hipStream_t s) {
+                                hipStream_t s, bool from_base = false) {
   // the matrix-core kernels keep the fused rank (terms x r) in registers: up to 64 in the streaming
   // kernel, up to 256 in the chunked one
   const int n_groups = (c->r % 8 == 0) ? t.n * (c->r / 8) : 0;
@@ -415,7 +419,7 @@ static lsw_status launch_switch(lsw_ctx* c, const std::vector<int32_t>& sel_laye
     const int tc = kernel >= 2 ? (bigk ? c->opt_tile_cols_bigk : c->opt_tile_cols) : kValuTileCols;
     lsw_status st = get_plan(c, kernel, tc, sel_layers, &dp);
     if (st != LSW_OK) return st;
-    LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, tc, c->opt_xcd};
+    LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, tc, c->opt_xcd, from_base ? 1 : 0};
     int grid = c->opt_grid;
     if (grid <= 0) grid = (kernel == 2) ? c->n_cu : c->n_cu * 2;   // matrix-core: one workgroup per CU
     grid = std::max(8, (grid / 8) * 8);     // a multiple of the 8 XCDs (the kernels' block remap assumes it)
@@ -464,6 +468,57 @@ extern "C" lsw_status lsw_switch(lsw_ctx* c, const int32_t* layers, int32_t n_la
     LayerState& s = c->state[size_t(layer_slot(c, layer))];
     s.k = k_new;
     for (int32_t a = 0; a < k_new; ++a) { s.ids[a] = new_ids[a]; s.gates[a] = new_gates[a]; }
+  }
+  return LSW_OK;
+}
+
+// ---------------------------------------------------------------------------
+// drift control: re-base the merged weights on a caller-kept copy of the base weights
+// ---------------------------------------------------------------------------
+extern "C" lsw_status lsw_set_base(lsw_ctx* c, const void* const* W_base, int32_t n_lin) {
+  if (!c) return fail(LSW_ERR_ARG, "ctx is null");
+  if (!W_base || n_lin != int32_t(c->lin.size())) return fail(LSW_ERR_ARG, "W_base is null or n_lin differs from the %zu registered linears", c->lin.size());
+  for (int32_t p = 0; p < n_lin; ++p) {
+    if (!W_base[p]) return fail(LSW_ERR_ARG, "linear %d: null base copy", p);
+    if (!aligned16(W_base[p])) return fail(LSW_ERR_SHAPE, "linear %d: base copy not 16-byte aligned", p);
+    if (W_base[p] == c->lin[size_t(p)].W) return fail(LSW_ERR_ARG, "linear %d: the base copy is the merged weight itself", p);
+  }
+  for (int32_t p = 0; p < n_lin; ++p) c->desc[size_t(p)].Wbase = static_cast<const uint16_t*>(W_base[p]);
+  LSW_HIP(hipDeviceSynchronize());     // no launch may be reading the table while it changes
+  LSW_HIP(hipMemcpy(c->d_lin, c->desc.data(), c->desc.size() * sizeof(LinDesc), hipMemcpyHostToDevice));
+  c->have_base = true;
+  return LSW_OK;
+}
+
+extern "C" lsw_status lsw_rebase(lsw_ctx* c, const int32_t* layers, int32_t n_layers,
+                                 const int32_t* ids, const float* gates, int32_t k, void* hip_stream) {
+  if (!c) return fail(LSW_ERR_ARG, "ctx is null");
+  if (!c->have_base) return fail(LSW_ERR_STATE, "lsw_rebase: no base copies registered (lsw_set_base)");
+  std::vector<int32_t> sel_layers;
+  lsw_status st = select_layers(c, layers, n_layers, &sel_layers);
+  if (st != LSW_OK) return st;
+  Terms t;
+  std::memset(&t, 0, sizeof(t));
+  st = lsw_build_terms(nullptr, nullptr, 0, ids, gates, k, c->E, c->scale, t.e, t.coeff, &t.n);
+  if (st != LSW_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const std::vector<int32_t>& touched = sel_layers.empty() ? c->layer_ids : sel_layers;
+  if (t.n == 0) {          // nothing to merge: the base weights themselves
+    c->last_kernel = 0;
+    c->last_items = 0;
+    c->last_grid = 0;
+    for (size_t p = 0; p < c->lin.size(); ++p) {
+      if (!sel_layers.empty() && !std::binary_search(sel_layers.begin(), sel_layers.end(), c->lin[p].layer)) continue;
+      LSW_HIP(hipMemcpyAsync(c->lin[p].W, c->desc[p].Wbase, size_t(c->lin[p].out) * size_t(c->lin[p].in) * 2, hipMemcpyDeviceToDevice, s));
+    }
+  } else {
+    st = launch_switch(c, sel_layers, t, nullptr, s, /*from_base*/ true);
+    if (st != LSW_OK) return st;
+  }
+  for (int32_t layer : touched) {
+    LayerState& ls = c->state[size_t(layer_slot(c, layer))];
+    ls.k = k;
+    for (int32_t a = 0; a < k; ++a) { ls.ids[a] = ids[a]; ls.gates[a] = gates[a]; }
   }
   return LSW_OK;
 }
@@ -537,7 +592,7 @@ extern "C" lsw_status lsw_probe_inplace(lsw_ctx* c, int32_t waves_per_cu, void* 
   DevicePlan* dp = nullptr;
   lsw_status st = get_plan(c, 3, c->opt_tile_cols, std::vector<int32_t>(), &dp);
   if (st != LSW_OK) return st;
-  LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, c->opt_tile_cols, c->opt_xcd};
+  LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, c->opt_tile_cols, c->opt_xcd, 0};
   hipError_t e = launch_probe_inplace(lp, c->n_cu * waves_per_cu, static_cast<hipStream_t>(hip_stream));
   if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "probe launch failed: %s", hipGetErrorString(e));
   return LSW_OK;
@@ -567,7 +622,7 @@ extern "C" lsw_status lsw_merged_gemv_all(lsw_ctx* c, const void* x_all_bf16, fl
   DevicePlan* dp = nullptr;
   lsw_status st = get_plan(c, 4, 1 << 30, std::vector<int32_t>(), &dp);   // items: blocks of rows, whole rows wide
   if (st != LSW_OK) return st;
-  LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, 1 << 30, c->opt_xcd};
+  LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, 1 << 30, c->opt_xcd, 0};
   int grid = c->opt_gemv_grid > 0 ? c->opt_gemv_grid : c->n_cu * 2;
   grid = std::max(8, (grid / 8) * 8);
   hipError_t e = launch_gemv_all(lp, static_cast<const uint16_t*>(x_all_bf16), y_all_fp32, grid,

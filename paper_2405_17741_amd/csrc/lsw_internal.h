@@ -23,6 +23,7 @@ struct LinDesc {
   const void*     A;      // fp32 or bf16 [E, r, in]
   const void*     B;      // fp32 or bf16 [E, out, r]
   const uint16_t* Apk;    // packed A for the matrix-core kernel (see pack kernel), or null
+  const uint16_t* Wbase;  // caller-kept copy of the weights with nothing merged (lsw_set_base), or null
   int32_t         out;
   int32_t         in;
   int64_t         x_off;  // element offset of this linear's input in the back-to-back x of lsw_merged_gemv_all
@@ -80,6 +81,7 @@ struct LaunchPlan {             // device pointers + counts for one launch
   int32_t n_items;
   int32_t tile_cols;            // columns of one work item (matrix-core kernel: a multiple of kApkBlockCols)
   int32_t xcd_remap;            // 1: each XCD takes a contiguous eighth of every grid-wide round of items
+  int32_t from_base;            // 1: the switch kernels read Wbase instead of W (and still write W): lsw_rebase
 };
 
 // Kernel launchers (lsw_kernels.hip).  All return the hipError of the launch.

@@ -247,7 +247,8 @@ __global__ __launch_bounds__(256) void k_switch_valu(LaunchPlan p, Terms t, cons
         const int row = row0 + ty * 4 + m;
         if (row < L.out) {
           u32x4* ptr = reinterpret_cast<u32x4*>(L.W + (long long)row * L.in + col);
-          const u32x4 w = __builtin_nontemporal_load(ptr);
+          const u32x4 w = __builtin_nontemporal_load(
+              p.from_base ? reinterpret_cast<const u32x4*>(L.Wbase + (long long)row * L.in + col) : ptr);
           u32x4 o;
 #pragma unroll
           for (int q = 0; q < 4; ++q)
@@ -314,6 +315,7 @@ template <int NKS>
 struct MfmaItem {           // what a wave keeps per work item
   const uint16_t* W;        // the buffer resource is rebuilt from these two where it is used, so
   int wbytes;               // that it provably lives in scalar registers
+  const uint16_t* Wsrc;     // where the tile is read from: W, or the base copy when re-basing
   const uint16_t* Apk;      // packed A of the linear
   int ncb;                  // its column blocks
   int col0, col_end;
@@ -339,6 +341,7 @@ __device__ __forceinline__ void mfma_load_item(const LaunchPlan& p, int item, in
   decode_item(uniform(item - p.first[seg]), L.in, tile_rows, p.tile_cols, &row0, &col0);
   row0 += row_shift;          // the calling wave's 32 rows inside a taller item (may lie past the last row)
   it.W = L.W;
+  it.Wsrc = p.from_base ? uniform(Lp->Wbase) : L.W;
   it.wbytes = L.out * L.in * 2;
   it.Apk = L.Apk;
   it.ncb = ceil_div(L.in, MT_STEP);
@@ -374,7 +377,7 @@ __device__ __forceinline__ uint32_t mfma_lane_offset(const MfmaItem<NKS>& it, in
 
 template <int NKS>
 __device__ __forceinline__ void mfma_load_w(const MfmaItem<NKS>& it, uint32_t lane_off, u32x4 (&wbuf)[16]) {
-  const __amdgpu_buffer_rsrc_t res = w_resource(it.W, it.wbytes);
+  const __amdgpu_buffer_rsrc_t res = w_resource(it.Wsrc, it.wbytes);
 #pragma unroll
   for (int v = 0; v < 16; ++v)
     wbuf[v] = __builtin_amdgcn_raw_buffer_load_b128(
@@ -499,7 +502,7 @@ __device__ __forceinline__ bool wg_step(const LaunchPlan& p, int grid, int n, in
   constexpr int kBufSlots = NKS * 8 * QP * 64;
   const bool last = uniform(int(!(cs + MT_STEP < cur.col_end))) != 0;
   const bool more = !last || have_nxt;
-  const __amdgpu_buffer_rsrc_t nres = w_resource(last ? nxt.W : cur.W, last ? nxt.wbytes : cur.wbytes);
+  const __amdgpu_buffer_rsrc_t nres = w_resource(last ? nxt.Wsrc : cur.Wsrc, last ? nxt.wbytes : cur.wbytes);
   const int ncs = uniform(last ? nxt.col0 : cs + MT_STEP);
   const int ncol_end = uniform(last ? nxt.col_end : cur.col_end);
   const uint32_t nrow0_byte = uint32_t(uniform(int(last ? nxt.row0_byte : cur.row0_byte)));
@@ -792,6 +795,7 @@ struct BkWave {             // per-wave state of the chunked kernel that outlive
   int32_t eg_bytes;                 // bytes of one (expert, rank group) slab of the linear's packed A: column blocks * 4 KB * Q parts (uniform)
   const uint16_t* Apk;
   const uint16_t* W;
+  const uint16_t* Wsrc;             // where tiles are read from: W, or the base copy when re-basing
   int wbytes;
   uint32_t stride;
   uint32_t lds0;                    // LDS byte address of buffer 0 + this wave's two blocks
@@ -815,6 +819,7 @@ template <int NCH, int QP>
 __device__ __forceinline__ void bk_step(const BkWave<NCH>& w, int cs, bool more, int lane, int& buf, uint32_t prev_off,
                                         uint32_t next_off, u32x4 (&wcur)[16], u32x4 (&wprev)[16]) {
   const __amdgpu_buffer_rsrc_t res = w_resource(w.W, w.wbytes);
+  const __amdgpu_buffer_rsrc_t res_src = w_resource(w.Wsrc, w.wbytes);
   f32x16 a0[4], a1[4];
   {
     const BkCopy cp = bk_copy_desc<NCH, QP>(w, cs, 1 % NCH, buf ^ 1);
@@ -826,7 +831,7 @@ __device__ __forceinline__ void bk_step(const BkWave<NCH>& w, int cs, bool more,
     asm volatile("" : "+v"(next_off) : "v"(prev_off));      // keep the loads after the stores that free their registers
 #pragma unroll
     for (int v = 0; v < 16; ++v)
-      wprev[v] = __builtin_amdgcn_raw_buffer_load_b128(res, next_off + uint32_t(8 * (v >> 2) + (v & 3)) * w.stride, 0, /*nt*/ 2);
+      wprev[v] = __builtin_amdgcn_raw_buffer_load_b128(res_src, next_off + uint32_t(8 * (v >> 2) + (v & 3)) * w.stride, 0, /*nt*/ 2);
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       a0[0][v] = bf16_lo(wcur[v][0]);
@@ -905,6 +910,7 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
     const int col_end = min(in, col0 + p.tile_cols);
     const int ncb = ceil_div(in, MT_STEP);
     w.W = uniform(Lp->W);
+    w.Wsrc = p.from_base ? uniform(Lp->Wbase) : w.W;
     w.wbytes = out * in * 2;
     w.stride = uint32_t(in) * 2u;
     // the packed A of the linear, advanced to this wave's two blocks inside a column block
@@ -940,7 +946,7 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
     u32x4 wa[16], wb[16];
     uint32_t off_a = lane_offset(col0), off_b = kOutOfRange;
     {
-      const __amdgpu_buffer_rsrc_t res = w_resource(w.W, w.wbytes);
+      const __amdgpu_buffer_rsrc_t res = w_resource(w.Wsrc, w.wbytes);
       const BkCopy cp = bk_copy_desc<NCH, QP>(w, col0, 0, buf);
       bk_copy_range<0, 8 * QP, QP>(cp);
 #pragma unroll

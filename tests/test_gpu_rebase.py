@@ -1,0 +1,105 @@
+"""GPU parity of lsw_rebase (drift control): W <- rne(W_base + merge of the given set), read from a caller-kept base
+copy, against the oracle's merge of the same set into the same base weights (Eq. 4 on the base copy)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import lsw_oracle as O
+from paper_2405_17741_amd import binding as L
+from paper_2405_17741_amd import inputs as I
+from tests.gpu_harness import DeviceStack, bits_to_device, check_step
+
+pytestmark = pytest.mark.gpu
+NONE = (np.zeros(0, np.int32), np.zeros(0, np.float32))
+
+
+def _stack(wl, kernel):
+    host = I.host_stack(wl)
+    ds = DeviceStack.from_host(host, wl.linear_shapes(), wl.experts, wl.rank, kernel=kernel)
+    base = [bits_to_device(W) for W, _, _ in host]
+    return host, ds, base
+
+
+@pytest.mark.parametrize("kernel", [L.KERNEL_VALU, L.KERNEL_MFMA])
+@pytest.mark.parametrize("rank", [8, 64])
+def test_rebase_removes_the_drift_of_free_running_switches(kernel, rank):
+    wl = I.Workload("mini", 2, 64, 264, 32, 6, rank, 2, 12, 0.02, 1 / 8, 0.01, 99 + rank)
+    shapes = wl.linear_shapes()
+    host, ds, base = _stack(wl, kernel)
+    with pytest.raises(L.LswError) as e:        # no base copies yet
+        L.lsw_rebase(ds.ctx, [1], [1.0])
+    assert e.value.status == L.LSW_ERR_STATE
+    L.lsw_set_base(ds.ctx, [b.data_ptr() for b in base])
+    routes = [O.route(l, wl.top_k) for l in I.router_logits(wl, wl.steps)]
+    old = NONE
+    for new in routes:
+        ds.switch(old, new)
+        old = new
+    # what the weights should be with no accumulated rounding: the current set merged into the base weights
+    drifted = 0
+    for p, (W0, A, B) in enumerate(host):
+        closed = O.switch_step(W0, A, B, [], [], old[0], old[1])
+        drifted += int((ds.rows(p) != closed).sum())
+    assert drifted > 0, "twelve bf16 switches must have left some rounding drift"
+    L.lsw_rebase(ds.ctx, old[0], old[1], stream=torch.cuda.current_stream().cuda_stream)
+    assert L.lsw_query(ds.ctx, L.LSW_Q_LAST_KERNEL) == kernel
+    exact = total = 0
+    for p, (W0, A, B) in enumerate(host):
+        got = ds.rows(p)
+        rep, want = check_step(W0, got, A, B, NONE, old)
+        assert rep["fail"] == 0, (p, {k: v for k, v in rep.items() if k != "fail_mask"})
+        exact += int((got == want).sum())
+        total += got.size
+        assert (base[p].view(torch.int16).cpu().numpy().view(np.uint16) == W0).all(), "the base copy is read-only"
+    assert exact > 0.995 * total      # diagnostic (the gate is fail == 0): how often the split-bf16 product flips a rounding
+    # the tracked state is the re-based set: the next switch starts from it
+    assert L.lsw_get_state(ds.ctx, 0)[0].tolist() == old[0].tolist()
+    prev = [ds.rows(p) for p in range(len(shapes))]
+    nxt = (np.array([0, 5], np.int32), np.array([0.25, 0.75], np.float32))
+    ds.switch(old, nxt)
+    for p, (_, A, B) in enumerate(host):
+        rep, _ = check_step(prev[p], ds.rows(p), A, B, old, nxt)
+        assert rep["fail"] == 0
+    ds.close()
+
+
+def test_rebase_layer_subset_and_empty_set():
+    wl = I.Workload("mini", 3, 64, 136, 32, 4, 8, 2, 4, 0.02, 1 / 8, 0.01, 4243)
+    shapes = wl.linear_shapes()
+    host, ds, base = _stack(wl, L.KERNEL_AUTO)
+    L.lsw_set_base(ds.ctx, [b.data_ptr() for b in base])
+    a = (np.array([1, 3], np.int32), np.array([0.7, 0.3], np.float32))
+    b = (np.array([0, 2], np.int32), np.array([0.4, 0.6], np.float32))
+    ds.switch(NONE, a)
+    before = [ds.rows(p) for p in range(len(shapes))]
+    L.lsw_rebase(ds.ctx, b[0], b[1], layers=[1])           # only layer 1 is rebuilt, straight to set b
+    for p, (layer, _, _, _) in enumerate(shapes):
+        got = ds.rows(p)
+        if layer == 1:
+            rep, _ = check_step(host[p][0], got, host[p][1], host[p][2], NONE, b)
+            assert rep["fail"] == 0
+        else:
+            assert (got == before[p]).all()
+    assert L.lsw_get_state(ds.ctx, 1)[0].tolist() == [0, 2] and L.lsw_get_state(ds.ctx, 0)[0].tolist() == [1, 3]
+    L.lsw_rebase(ds.ctx, NONE[0], NONE[1])                  # k = 0: the base weights, bit for bit, in every layer
+    assert L.lsw_query(ds.ctx, L.LSW_Q_LAST_KERNEL) == 0
+    for p, (W0, _, _) in enumerate(host):
+        assert (ds.rows(p) == W0).all()
+    assert len(L.lsw_get_state(ds.ctx, 2)[0]) == 0
+    ds.close()
+
+
+def test_set_base_rejects_what_it_documents():
+    wl = I.Workload("mini", 1, 64, 136, 32, 4, 8, 2, 4, 0.02, 1 / 8, 0.01, 4244)
+    host, ds, base = _stack(wl, L.KERNEL_AUTO)
+    ptrs = [b.data_ptr() for b in base]
+    for bad, status in [(ptrs[:-1], L.LSW_ERR_ARG), ([0] + ptrs[1:], L.LSW_ERR_ARG),
+                        ([ds.stack[0][0].data_ptr()] + ptrs[1:], L.LSW_ERR_ARG), ([ptrs[0] + 2] + ptrs[1:], L.LSW_ERR_SHAPE)]:
+        with pytest.raises(L.LswError) as e:
+            L.lsw_set_base(ds.ctx, bad)
+        assert e.value.status == status
+    L.lsw_set_base(ds.ctx, ptrs)
+    with pytest.raises(L.LswError) as e:
+        L.lsw_rebase(ds.ctx, [9], [1.0])
+    assert e.value.status == L.LSW_ERR_ARG
+    ds.close()

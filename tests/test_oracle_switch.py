@@ -215,3 +215,25 @@ def test_planted_mistakes_are_caught():
     assert (variant(drop_last=True) != want).any()
     assert (variant(swap_expert=True) != want).any()
     assert (O.switch_step(W, A, B, [0], [0.375], [1, 3], [0.5, 0.25]) == want).all()
+
+
+def test_iterated_switches_drift_like_a_random_walk_and_a_rebase_removes_it():
+    # Eq. 7 treats the unmerge as exact.  In bf16 every switch adds a fresh rounding error of at most half an ulp
+    # (uniform: standard deviation 1/sqrt(12) = 0.29 ulp), so after T switches the weights sit a random walk of about
+    # 0.29*sqrt(T) ulp away from the closed form rne(W0 + delta_T); merging the current set into W0 again (what
+    # lsw_rebase does) is that closed form by definition.
+    wl = I.WORKLOADS["tiny"]
+    (W0, A, B), = I.host_stack(wl)
+    routes = [O.route(l, wl.top_k) for l in I.router_logits(wl, wl.steps)]
+    W, old = W0, ([], [])
+    for new in routes:
+        W = O.switch_step(W, A, B, old[0], old[1], new[0], new[1])
+        old = new
+    closed = O.switch_step(W0, A, B, [], [], old[0], old[1])
+    sel = (W0 & 0x7F80) == (closed & 0x7F80)          # same binade before and after: the ulp did not change
+    d = (C.ulp_key(W).astype(np.int64) - C.ulp_key(closed))[sel]
+    rms = float(np.sqrt((d.astype(np.float64) ** 2).mean()))
+    expect = 0.29 * np.sqrt(wl.steps)
+    assert 0.6 * expect < rms < 1.6 * expect, (rms, expect)
+    assert abs(d.mean()) < 0.05                        # unbiased: round-to-nearest-even
+    assert (W != closed).mean() > 0.3

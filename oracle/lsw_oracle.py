@@ -44,6 +44,9 @@ __all__ = [
     "switch_step",
     "switch_magnitude",
     "gemv",
+    "adapter_term",
+    "adapter_forward",
+    "adapter_magnitude",
 ]
 
 
@@ -173,3 +176,42 @@ def switch_magnitude(A, B, old_ids, old_gates, new_ids, new_gates,
 def gemv(W_bits, x_bits) -> np.ndarray:
     """y[i] = sum_j W[i,j] * x[j] in float64, W and x given as bf16 bit patterns."""
     return bf16_bits_to_f64(W_bits) @ bf16_bits_to_f64(x_bits)
+
+
+# --------------------------------------------------------------------------
+# Un-merged adapter path for many tokens      (Eq. 2: y = f(x) + sum_i G(x1)_i E_i(x))
+# --------------------------------------------------------------------------
+
+def adapter_term(X_bits, A, B, ids, gates, scale=1.0) -> np.ndarray:
+    """The dynamic-adapter sum of Eq. 2 for T tokens, float64 [T, out].
+
+    term[t, i] = sum_c (scale*g[t,c]) * sum_rho B[e][i,rho] * (sum_j A[e][rho,j] * x[t,j]),  e = ids[t,c].
+    X_bits: bf16 bit patterns [T, in]; ids int [T, k]; gates fp32 [T, k] (each token carries the gates its
+    own router output gave it; with the token-wise pre-gated structure they are the same in every layer).
+    E_i(x) = W_up (W_down x) as under Eq. 1: the down projection first, then the up projection.
+    """
+    X = bf16_bits_to_f64(X_bits)
+    A = np.asarray(A)
+    B = np.asarray(B)
+    ids = np.asarray(ids).reshape(X.shape[0], -1)
+    gates = np.asarray(gates, dtype=np.float32).reshape(X.shape[0], -1)
+    out = np.zeros((X.shape[0], B.shape[1]), dtype=np.float64)
+    for t in range(X.shape[0]):
+        for c in range(ids.shape[1]):
+            e = int(ids[t, c])
+            coeff = np.float64(scale) * np.float64(gates[t, c])
+            down = A[e].astype(np.float64) @ X[t]                 # [r]
+            out[t] += coeff * (B[e].astype(np.float64) @ down)    # [out]
+    return out
+
+
+def adapter_forward(Y_bits, X_bits, A, B, ids, gates, scale=1.0) -> np.ndarray:
+    """Y <- RNE_bf16(Y + adapter_term): the term added to the backbone's bf16 output f(x), one rounding."""
+    return f64_to_bf16_bits(bf16_bits_to_f64(Y_bits) + adapter_term(X_bits, A, B, ids, gates, scale))
+
+
+def adapter_magnitude(X_bits, A, B, ids, gates, scale=1.0) -> np.ndarray:
+    """S[t,i] = sum_c |scale*g| sum_rho |B| sum_j |A||x|: the size of the partial sums entering an output."""
+    Xa = f64_to_bf16_bits(np.abs(bf16_bits_to_f64(X_bits)))       # |x| is again a bf16 value
+    return adapter_term(Xa, np.abs(np.asarray(A)), np.abs(np.asarray(B)), ids,
+                        np.abs(np.asarray(gates, dtype=np.float32)), abs(float(scale)))

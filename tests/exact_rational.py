@@ -74,3 +74,28 @@ def exact_switch(W_bits, A, B, old, new, scale=1.0):
                     acc += sgn * sc * f32_to_fraction(g) * dot
             res[i][j] = fraction_to_bf16_bits(acc)
     return res
+
+
+def exact_adapter_forward(Y_bits, X_bits, A, B, ids, gates, scale=1.0):
+    """Eq. 2's adapter sum added to Y, element by element, in exact arithmetic; one rounding to bf16.
+
+    Y_bits [T][out], X_bits [T][in] ints; A[e][rho][j], B[e][i][rho] floats; ids[t][c], gates[t][c].
+    """
+    T, n_out, n_in = len(Y_bits), len(Y_bits[0]), len(X_bits[0])
+    sc = f32_to_fraction(scale)
+    res = [[0] * n_out for _ in range(T)]
+    for t in range(T):
+        x = [bf16_bits_to_fraction(int(X_bits[t][j])) for j in range(n_in)]
+        for i in range(n_out):
+            acc = bf16_bits_to_fraction(int(Y_bits[t][i]))
+            for c in range(len(ids[t])):
+                e = int(ids[t][c])
+                up = Fraction(0)
+                for rho in range(len(A[e])):
+                    down = Fraction(0)
+                    for j in range(n_in):
+                        down += f32_to_fraction(A[e][rho][j]) * x[j]
+                    up += f32_to_fraction(B[e][i][rho]) * down
+                acc += sc * f32_to_fraction(gates[t][c]) * up
+            res[t][i] = fraction_to_bf16_bits(acc)
+    return res

@@ -211,6 +211,38 @@ lsw_status lsw_gemv_bf16(const void* W_bf16, const void* x_bf16, float* y_fp32, 
                          void* hip_stream);
 
 /*
+ * The un-merged adapter path for many tokens (Eq. 2: y = f(x) + sum_i G(x1)_i E_i(x) with E_i(x) = W_up (W_down x)),
+ * what a prompt runs through before decoding starts: every token has its own (ids, gates), so nothing can be merged.
+ * The backbone's own product f(x) = W x is the caller's (a plain GEMM on the base weights: switch with k_new = 0
+ * first); the library adds the dynamic-adapter sum of one linear to it:
+ *
+ *   Y[t, i] <- rne_bf16( Y[t, i] + sum_{c<k} s*g[t,c] * sum_rho B[e][i,rho] * (sum_j A[e][rho,j] * X[t,j]) ),  e = ids[t,c]
+ *
+ * lsw_enable_adapter_path  builds, once, the two re-laid-out operand copies the path needs for every linear (A for
+ *                          the down-projection, B^T for the up-projection, E*r*(in+out)*4 bytes per linear for fp32
+ *                          factors, half for bf16).  Needs r % 8 == 0, E*r <= 256 and every out % 8 == 0
+ *                          (LSW_ERR_SHAPE otherwise); synchronises the device.
+ * lsw_route_batch_dev      G = Softmax(TopK(.)) for n_tokens rows of logits at once (the router of Eq. 2 over a prompt):
+ *                          logits_dev DEVICE fp32 [n_tokens, E]; ids_dev DEVICE int32 [n_tokens, k]; gates_dev DEVICE
+ *                          fp32 [n_tokens, k]; per row exactly what lsw_route_dev computes.
+ * lsw_adapter_forward      the update above for linear lin_index and T tokens.  X_bf16 DEVICE bf16 [T, in]; ids_dev
+ *                          DEVICE int32 [T, k]; gates_dev DEVICE fp32 [T, k]; Y_bf16 DEVICE bf16 [T, out], read and
+ *                          written; workspace DEVICE, lsw_adapter_workspace_bytes(ctx, lin_index, T) bytes, contents
+ *                          irrelevant before and after; all 16-byte aligned.  Three launches, asynchronous on
+ *                          hip_stream, nothing allocated.  A token whose list is bad (id outside [0,E), duplicate id,
+ *                          non-finite gate) keeps its row of Y unchanged and raises flag 2 of lsw_dev_status.
+ * Errors: LSW_ERR_ARG, LSW_ERR_SHAPE (misaligned, X or Y of 2 GiB or more), LSW_ERR_STATE (path not enabled),
+ * LSW_ERR_NOMEM, LSW_ERR_DEVICE.
+ */
+lsw_status lsw_enable_adapter_path(lsw_ctx* ctx);
+int64_t    lsw_adapter_workspace_bytes(const lsw_ctx* ctx, int32_t lin_index, int32_t T);   /* -1 on a bad argument */
+lsw_status lsw_route_batch_dev(lsw_ctx* ctx, const float* logits_dev, int32_t n_tokens, int32_t k, int32_t* ids_dev,
+                               float* gates_dev, void* hip_stream);
+lsw_status lsw_adapter_forward(lsw_ctx* ctx, int32_t lin_index, const void* X_bf16, int32_t T,
+                               const int32_t* ids_dev, const float* gates_dev, int32_t k,
+                               void* Y_bf16, void* workspace, void* hip_stream);
+
+/*
  * The signed coefficient list one switch applies (Alg. 1 steps 2-3 without moving any tensor:
  * Eq. 5 puts the gate on one factor, Eq. 9 negates the previous set): new experts with
  * +scale*g, old experts with -scale*g, an expert in both with scale*g_new - scale*g_old,

@@ -24,7 +24,8 @@ EXPORTS = (
     "lsw_get_state", "lsw_set_option", "lsw_query", "lsw_worklist_size", "lsw_worklist_item",
     "lsw_destroy", "lsw_last_error", "lsw_probe_inplace", "lsw_merged_gemv_all",
     "lsw_route_dev", "lsw_switch_dev", "lsw_dev_status", "lsw_gemv_bf16", "lsw_create_adapters_ex",
-    "lsw_set_base", "lsw_rebase",
+    "lsw_set_base", "lsw_rebase", "lsw_enable_adapter_path", "lsw_adapter_workspace_bytes", "lsw_route_batch_dev",
+    "lsw_adapter_forward",
 )
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblsw.so")
@@ -59,6 +60,12 @@ def lib() -> C.CDLL:
                                              C.c_int32, C.POINTER(C.c_void_p)]
         L.lsw_switch.argtypes = [C.c_void_p, _i32p, C.c_int32, _i32p, _f32p, C.c_int32, _i32p, _f32p, C.c_int32,
                                  C.c_void_p]
+        L.lsw_enable_adapter_path.argtypes = [C.c_void_p]
+        L.lsw_adapter_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+        L.lsw_adapter_workspace_bytes.restype = C.c_int64
+        L.lsw_route_batch_dev.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.lsw_adapter_forward.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
+                                          C.c_void_p, C.c_void_p, C.c_void_p]
         L.lsw_set_base.argtypes = [C.c_void_p, C.POINTER(C.c_void_p), C.c_int32]
         L.lsw_rebase.argtypes = [C.c_void_p, _i32p, C.c_int32, _i32p, _f32p, C.c_int32, C.c_void_p]
         L.lsw_merged_gemv.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -84,7 +91,7 @@ def lib() -> C.CDLL:
         L.lsw_destroy.restype = None
         L.lsw_last_error.restype = C.c_char_p
         for name in EXPORTS:
-            if name not in ("lsw_query", "lsw_worklist_size", "lsw_destroy", "lsw_last_error"):
+            if name not in ("lsw_query", "lsw_worklist_size", "lsw_destroy", "lsw_last_error", "lsw_adapter_workspace_bytes"):
                 getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -140,6 +147,28 @@ def lsw_switch(ctx: int, old_ids, old_gates, new_ids, new_gates, layers=None, st
     if n_og != k_old or n_ng != k_new:
         raise LswError(LSW_ERR_ARG, "ids and gates differ in length")
     _check(lib().lsw_switch(ctx, lp, nl, oi, og, k_old, ni, ng, k_new, C.c_void_p(stream)))
+
+
+def lsw_enable_adapter_path(ctx: int) -> None:
+    _check(lib().lsw_enable_adapter_path(ctx))
+
+
+def lsw_adapter_workspace_bytes(ctx: int, lin_index: int, T: int) -> int:
+    n = int(lib().lsw_adapter_workspace_bytes(ctx, lin_index, T))
+    if n < 0:
+        raise LswError(LSW_ERR_ARG, lsw_last_error())
+    return n
+
+
+def lsw_route_batch_dev(ctx: int, logits_ptr: int, n_tokens: int, k: int, ids_ptr: int, gates_ptr: int, stream: int = 0) -> None:
+    _check(lib().lsw_route_batch_dev(ctx, C.c_void_p(logits_ptr), n_tokens, k, C.c_void_p(ids_ptr), C.c_void_p(gates_ptr),
+                                     C.c_void_p(stream)))
+
+
+def lsw_adapter_forward(ctx: int, lin_index: int, X_ptr: int, T: int, ids_ptr: int, gates_ptr: int, k: int, Y_ptr: int,
+                        workspace_ptr: int, stream: int = 0) -> None:
+    _check(lib().lsw_adapter_forward(ctx, lin_index, C.c_void_p(X_ptr), T, C.c_void_p(ids_ptr), C.c_void_p(gates_ptr), k,
+                                     C.c_void_p(Y_ptr), C.c_void_p(workspace_ptr), C.c_void_p(stream)))
 
 
 def lsw_set_base(ctx: int, base_ptrs) -> None:

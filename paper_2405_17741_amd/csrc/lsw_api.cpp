@@ -77,6 +77,8 @@ struct lsw_ctx {
   std::vector<LinDesc> desc;                 // host copy of the descriptor table
   bool have_base = false;                    // lsw_set_base has registered the base copies
   uint16_t* d_apk = nullptr;                 // packed A of all linears (r % 8 == 0 only)
+  uint16_t* d_adapter = nullptr;             // adapter path: per linear the down-projection layout of A, then the packed B^T
+  std::vector<size_t> atk_off, bpk_off;      // element offsets of the two parts of linear p inside d_adapter
   Terms* d_terms = nullptr;                  // term list built on the device by lsw_switch_dev, followed by the sticky error word
   int32_t* d_err = nullptr;
   int64_t owned_bytes = 0;
@@ -304,7 +306,7 @@ extern "C" lsw_status lsw_create_adapters_ex(const lsw_linear* lin, int32_t n_li
     if (e != hipSuccess) { (void)hipGetLastError(); return fail(LSW_ERR_NOMEM, "hipMalloc of %zu bytes for packed A failed", apk_elems * 2); }
     c->owned_bytes += int64_t(apk_elems * sizeof(uint16_t));
     for (int32_t p = 0; p < n_lin; ++p) {
-      e = launch_pack_A(lin[p].A, c->d_apk + apk_off[p], E, r, lin[p].in, qp, nullptr);
+      e = launch_pack_A(lin[p].A, c->d_apk + apk_off[p], E, r, lin[p].in, qp, 0, nullptr);
       if (e != hipSuccess) { cleanup(); return fail(LSW_ERR_DEVICE, "pack kernel launch failed: %s", hipGetErrorString(e)); }
     }
   }
@@ -343,6 +345,7 @@ extern "C" void lsw_destroy(lsw_ctx* c) {
   for (auto& kv : c->plans)
     if (kv.second.d_sel) (void)hipFree(kv.second.d_sel);
   if (c->d_apk) (void)hipFree(c->d_apk);
+  if (c->d_adapter) (void)hipFree(c->d_adapter);
   if (c->d_lin) (void)hipFree(c->d_lin);
   if (c->d_terms) (void)hipFree(c->d_terms);
   delete c;
@@ -419,7 +422,7 @@ static lsw_status launch_switch(lsw_ctx* c, const std::vector<int32_t>& sel_laye
     const int tc = kernel >= 2 ? (bigk ? c->opt_tile_cols_bigk : c->opt_tile_cols) : kValuTileCols;
     lsw_status st = get_plan(c, kernel, tc, sel_layers, &dp);
     if (st != LSW_OK) return st;
-    LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, tc, c->opt_xcd, from_base ? 1 : 0};
+    LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, tc, c->opt_xcd, from_base ? 1 : 0, nullptr, 0, LinDesc{}};
     int grid = c->opt_grid;
     if (grid <= 0) grid = (kernel == 2) ? c->n_cu : c->n_cu * 2;   // matrix-core: one workgroup per CU
     grid = std::max(8, (grid / 8) * 8);     // a multiple of the 8 XCDs (the kernels' block remap assumes it)
@@ -532,7 +535,7 @@ extern "C" lsw_status lsw_route_dev(lsw_ctx* c, const float* logits_dev, int32_t
   if (k < 0 || k > LSW_MAX_K || k > c->E) return fail(LSW_ERR_ARG, "lsw_route_dev: k=%d outside 0..min(%d, E=%d)", k, int(LSW_MAX_K), c->E);
   if (!logits_dev || (k > 0 && (!ids_dev || !gates_dev))) return fail(LSW_ERR_ARG, "lsw_route_dev: null pointer");
   if (k == 0) return LSW_OK;
-  hipError_t e = launch_route(logits_dev, c->E, k, ids_dev, gates_dev, c->d_err, static_cast<hipStream_t>(hip_stream));
+  hipError_t e = launch_route(logits_dev, 1, c->E, k, ids_dev, gates_dev, c->d_err, static_cast<hipStream_t>(hip_stream));
   if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "route launch failed: %s", hipGetErrorString(e));
   return LSW_OK;
 }
@@ -566,6 +569,111 @@ extern "C" lsw_status lsw_switch_dev(lsw_ctx* c, const int32_t* layers, int32_t 
   return LSW_OK;
 }
 
+extern "C" lsw_status lsw_route_batch_dev(lsw_ctx* c, const float* logits_dev, int32_t n_tokens, int32_t k, int32_t* ids_dev,
+                                          float* gates_dev, void* hip_stream) {
+  if (!c) return fail(LSW_ERR_ARG, "ctx is null");
+  if (n_tokens < 1 || n_tokens > (1 << 24)) return fail(LSW_ERR_ARG, "lsw_route_batch_dev: n_tokens=%d outside 1..2^24", n_tokens);
+  if (k < 0 || k > LSW_MAX_K || k > c->E) return fail(LSW_ERR_ARG, "lsw_route_batch_dev: k=%d outside 0..min(%d, E=%d)", k, int(LSW_MAX_K), c->E);
+  if (!logits_dev || (k > 0 && (!ids_dev || !gates_dev))) return fail(LSW_ERR_ARG, "lsw_route_batch_dev: null pointer");
+  if (k == 0) return LSW_OK;
+  hipError_t e = launch_route(logits_dev, n_tokens, c->E, k, ids_dev, gates_dev, c->d_err, static_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "route launch failed: %s", hipGetErrorString(e));
+  return LSW_OK;
+}
+
+// ---------------------------------------------------------------------------
+// un-merged adapter path over many tokens (Eq. 2)
+// ---------------------------------------------------------------------------
+static int z_stride_of(const lsw_ctx* c) { return ceil_div(c->E * c->r, 16) * 16; }   // whole k-steps of 16: the pad columns hold zeros
+
+extern "C" lsw_status lsw_enable_adapter_path(lsw_ctx* c) {
+  if (!c) return fail(LSW_ERR_ARG, "ctx is null");
+  if (c->d_adapter) return LSW_OK;
+  if (c->r % 8 != 0 || c->E * c->r > 256)
+    return fail(LSW_ERR_SHAPE, "the adapter path needs r %% 8 == 0 and E * r <= 256 (E=%d, r=%d)", c->E, c->r);
+  const size_t n_lin = c->lin.size();
+  size_t elems = 0;
+  c->atk_off.assign(n_lin, 0);
+  c->bpk_off.assign(n_lin, 0);
+  for (size_t p = 0; p < n_lin; ++p) {
+    const lsw_linear& L = c->lin[p];
+    if (L.out % 8 != 0) return fail(LSW_ERR_SHAPE, "linear %zu: the adapter path needs out %% 8 == 0 (out=%d)", p, L.out);
+    if (int64_t(c->E) * c->r * ceil_div(L.out, kApkBlockCols) * kApkBlockCols * 2 * c->qp >= (int64_t(1) << 31))
+      return fail(LSW_ERR_SHAPE, "linear %zu: E * r * out * 4 must stay below 2^31 bytes", p);
+    c->atk_off[p] = elems;
+    elems += size_t(adapter_atk_elems(c->E, c->r, L.in, c->qp));
+    c->bpk_off[p] = elems;
+    elems += size_t(c->E) * size_t(c->r) * size_t(ceil_div(L.out, kApkBlockCols) * kApkBlockCols) * size_t(c->qp);
+  }
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(&c->d_adapter), elems * sizeof(uint16_t));
+  if (e != hipSuccess) { (void)hipGetLastError(); c->d_adapter = nullptr; return fail(LSW_ERR_NOMEM, "hipMalloc of %zu bytes for the adapter path failed", elems * 2); }
+  for (size_t p = 0; p < n_lin && e == hipSuccess; ++p) {
+    const lsw_linear& L = c->lin[p];
+    e = launch_pack_Atk(L.A, c->d_adapter + c->atk_off[p], c->E, c->r, L.in, c->qp, nullptr);
+    if (e == hipSuccess) e = launch_pack_A(L.B, c->d_adapter + c->bpk_off[p], c->E, c->r, L.out, c->qp, 1, nullptr);
+  }
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  if (e != hipSuccess) {
+    (void)hipFree(c->d_adapter);
+    c->d_adapter = nullptr;
+    return fail(LSW_ERR_DEVICE, "packing the adapter-path operands failed: %s", hipGetErrorString(e));
+  }
+  c->owned_bytes += int64_t(elems * sizeof(uint16_t));
+  return LSW_OK;
+}
+
+extern "C" int64_t lsw_adapter_workspace_bytes(const lsw_ctx* c, int32_t lin_index, int32_t T) {
+  if (!c || lin_index < 0 || size_t(lin_index) >= c->lin.size() || T < 1) {
+    fail(LSW_ERR_ARG, "lsw_adapter_workspace_bytes: bad argument");
+    return -1;
+  }
+  const int64_t N = int64_t(c->E) * c->r;
+  return 4 * (int64_t(adapter_slices(T, c->lin[size_t(lin_index)].in)) * T * N + int64_t(T) * z_stride_of(c));
+}
+
+extern "C" lsw_status lsw_adapter_forward(lsw_ctx* c, int32_t lin_index, const void* X_bf16, int32_t T,
+                                          const int32_t* ids_dev, const float* gates_dev, int32_t k,
+                                          void* Y_bf16, void* workspace, void* hip_stream) {
+  if (!c) return fail(LSW_ERR_ARG, "ctx is null");
+  if (!c->d_adapter) return fail(LSW_ERR_STATE, "lsw_adapter_forward: call lsw_enable_adapter_path first");
+  if (lin_index < 0 || size_t(lin_index) >= c->lin.size()) return fail(LSW_ERR_ARG, "lin_index %d out of range", lin_index);
+  if (T < 1) return fail(LSW_ERR_ARG, "T=%d < 1", T);
+  if (k < 0 || k > LSW_MAX_K || k > c->E) return fail(LSW_ERR_ARG, "k=%d outside 0..min(%d, E=%d)", k, int(LSW_MAX_K), c->E);
+  if (!X_bf16 || !Y_bf16 || !workspace || (k > 0 && (!ids_dev || !gates_dev))) return fail(LSW_ERR_ARG, "null pointer");
+  if (!aligned16(X_bf16) || !aligned16(Y_bf16) || !aligned16(workspace)) return fail(LSW_ERR_SHAPE, "X, Y or the workspace is not 16-byte aligned");
+  const lsw_linear& L = c->lin[size_t(lin_index)];
+  if (int64_t(T) * L.in * 2 >= (int64_t(1) << 31) || int64_t(ceil_div(T, kMfmaTileRows)) * kMfmaTileRows * L.out * 2 >= (int64_t(1) << 31))
+    return fail(LSW_ERR_SHAPE, "T=%d: X and Y (rows rounded up to %d) must stay below 2^31 bytes each", T, kMfmaTileRows);
+  if (k == 0) return LSW_OK;                  // no expert selected: nothing to add
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const int N = c->E * c->r, zs = z_stride_of(c);
+  const int n_slices = adapter_slices(T, L.in);
+  float* Upart = static_cast<float*>(workspace);
+  float* Z = Upart + size_t(n_slices) * size_t(T) * size_t(N);
+  hipError_t e = launch_adapter_down(static_cast<const uint16_t*>(X_bf16), c->d_adapter + c->atk_off[size_t(lin_index)], Upart, T, L.in, N, c->qp, s);
+  if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "down-projection launch failed: %s", hipGetErrorString(e));
+  e = launch_adapter_gate(Upart, n_slices, ids_dev, gates_dev, k, T, c->E, c->r, c->scale, Z, zs, c->d_err, s);
+  if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "gate launch failed: %s", hipGetErrorString(e));
+  // the up-projection: the matrix-core switch kernels with rows = tokens and the row operand read from Z
+  const int n_groups = c->E * (c->r / 8);
+  const bool bigk = n_groups > 8;
+  const int tc = bigk ? 512 : 256;
+  Terms t;
+  std::memset(&t, 0, sizeof(t));
+  t.n = c->E;                                // sizes the launch: E * r / 8 groups of the fused rank
+  LinDesc one{};
+  one.W = static_cast<uint16_t*>(Y_bf16);
+  one.Apk = c->d_adapter + c->bpk_off[size_t(lin_index)];
+  one.out = T;
+  one.in = L.out;
+  const int64_t n_items = int64_t(ceil_div(T, kMfmaTileRows)) * ceil_div(L.out, tc);
+  LaunchPlan lp{nullptr, nullptr, nullptr, 1, int32_t(n_items), tc, c->opt_xcd, 0, Z, zs, one};
+  const int grid = std::max(8, (c->n_cu / 8) * 8);
+  e = bigk ? launch_switch_mfma_bigk(lp, t, nullptr, c->r, c->qp, grid, s) : launch_switch_mfma(lp, t, nullptr, c->r, c->qp, grid, s);
+  if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "up-projection launch failed: %s", hipGetErrorString(e));
+  return LSW_OK;
+}
+
 extern "C" lsw_status lsw_dev_status(lsw_ctx* c, int32_t* flags) {
   if (!c || !flags) return fail(LSW_ERR_ARG, "null argument");
   LSW_HIP(hipMemcpy(flags, c->d_err, sizeof(int32_t), hipMemcpyDeviceToHost));     // waits for earlier work on the null stream only
@@ -592,7 +700,7 @@ extern "C" lsw_status lsw_probe_inplace(lsw_ctx* c, int32_t waves_per_cu, void* 
   DevicePlan* dp = nullptr;
   lsw_status st = get_plan(c, 3, c->opt_tile_cols, std::vector<int32_t>(), &dp);
   if (st != LSW_OK) return st;
-  LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, c->opt_tile_cols, c->opt_xcd, 0};
+  LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, c->opt_tile_cols, c->opt_xcd, 0, nullptr, 0, LinDesc{}};
   hipError_t e = launch_probe_inplace(lp, c->n_cu * waves_per_cu, static_cast<hipStream_t>(hip_stream));
   if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "probe launch failed: %s", hipGetErrorString(e));
   return LSW_OK;
@@ -622,7 +730,7 @@ extern "C" lsw_status lsw_merged_gemv_all(lsw_ctx* c, const void* x_all_bf16, fl
   DevicePlan* dp = nullptr;
   lsw_status st = get_plan(c, 4, 1 << 30, std::vector<int32_t>(), &dp);   // items: blocks of rows, whole rows wide
   if (st != LSW_OK) return st;
-  LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, 1 << 30, c->opt_xcd, 0};
+  LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, 1 << 30, c->opt_xcd, 0, nullptr, 0, LinDesc{}};
   int grid = c->opt_gemv_grid > 0 ? c->opt_gemv_grid : c->n_cu * 2;
   grid = std::max(8, (grid / 8) * 8);
   hipError_t e = launch_gemv_all(lp, static_cast<const uint16_t*>(x_all_bf16), y_all_fp32, grid,

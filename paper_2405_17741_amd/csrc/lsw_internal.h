@@ -82,6 +82,13 @@ struct LaunchPlan {             // device pointers + counts for one launch
   int32_t tile_cols;            // columns of one work item (matrix-core kernel: a multiple of kApkBlockCols)
   int32_t xcd_remap;            // 1: each XCD takes a contiguous eighth of every grid-wide round of items
   int32_t from_base;            // 1: the switch kernels read Wbase instead of W (and still write W): lsw_rebase
+  // Adapter-path mode of the matrix-core kernels (Z != null): ONE matrix, described by `one` (W = the [T, out]
+  // activations to add to, Apk = the packed B^T of the linear, out = T, in = out features); lin/sel/first are unused.
+  // The row operand is not coeff * B but row t of Z (fp32 [T, z_stride]: the gated down-projection of token t, all
+  // experts side by side), and the fused rank runs over all E * r columns of Z.
+  const float* Z;
+  int32_t z_stride;
+  LinDesc one;
 };
 
 // Kernel launchers (lsw_kernels.hip).  All return the hipError of the launch.
@@ -90,11 +97,19 @@ struct LaunchPlan {             // device pointers + counts for one launch
 hipError_t launch_switch_valu(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int qp, int grid, hipStream_t s);
 hipError_t launch_switch_mfma(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int qp, int grid, hipStream_t s);
 hipError_t launch_switch_mfma_bigk(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int qp, int grid, hipStream_t s);
-hipError_t launch_route(const float* logits, int E, int k, int32_t* ids, float* gates, int32_t* err, hipStream_t s);
+hipError_t launch_route(const float* logits, int n_tokens, int E, int k, int32_t* ids, float* gates, int32_t* err, hipStream_t s);
 hipError_t launch_build_terms(const int32_t* old_ids, const float* old_gates, int k_old, const int32_t* new_ids,
                               const float* new_gates, int k_new, int E, float scale, Terms* out, int32_t* err, hipStream_t s);
 hipError_t launch_probe_inplace(const LaunchPlan& p, int grid, hipStream_t s);
-hipError_t launch_pack_A(const void* A, uint16_t* Apk, int E, int r, int in, int qp, hipStream_t s);
+// transposed = 0: source A [E][r][in] (columns = in);  1: source B [E][out][r] read as B^T [E][r][out] (columns = out)
+hipError_t launch_pack_A(const void* A, uint16_t* Apk, int E, int r, int in, int qp, int transposed, hipStream_t s);
+// adapter path (Eq. 2 for many tokens)
+int64_t adapter_atk_elems(int E, int r, int in, int qp);          // bf16 elements of the down-projection layout of one linear
+int adapter_slices(int T, int in);                                // partial sums the down-projection is cut into
+hipError_t launch_pack_Atk(const void* A, uint16_t* Atk, int E, int r, int in, int qp, hipStream_t s);
+hipError_t launch_adapter_down(const uint16_t* X, const uint16_t* Atk, float* Upart, int T, int in, int N, int qp, hipStream_t s);
+hipError_t launch_adapter_gate(const float* Upart, int n_slices, const int32_t* ids, const float* gates, int k, int T, int E, int r,
+                               float scale, float* Z, int z_stride, int32_t* err, hipStream_t s);
 hipError_t launch_gemv(const uint16_t* W, const uint16_t* x, float* y, int out, int in, int grid_cap, hipStream_t s);
 hipError_t launch_gemv_all(const LaunchPlan& p, const uint16_t* x_all, float* y_all, int grid, hipStream_t s);
 

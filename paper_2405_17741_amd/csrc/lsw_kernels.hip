@@ -122,7 +122,9 @@ __device__ __forceinline__ T* uniform(T* ptr) {
 // parts at [..][b][1][n][.]; bf16 factors (QP = 1) are exact in the one part (columns past `in` hold zeros).  A matrix-core lane wants 8 consecutive k of one column; in this
 // order the 32 lanes of one access (n = 0..31, fixed b) read 512 contiguous bytes.
 // ---------------------------------------------------------------------------
-template <int QP>
+// TRANSPOSED: the source is B [E][out][r] read as B^T [E][r][out] (`in` is then the number of its columns, out): the
+// Q operand of the un-merged adapter path, whose matrix rows are tokens and whose columns are output features.
+template <int QP, bool TRANSPOSED>
 __global__ __launch_bounds__(256) void k_pack_A(const void* __restrict__ A, uint16_t* __restrict__ Apk,
                                                 int E, int r, int in) {
   const int gpr = r >> 3;
@@ -139,7 +141,8 @@ __global__ __launch_bounds__(256) void k_pack_A(const void* __restrict__ A, uint
     for (int q = 0; q < 8; ++q) x[q] = 0.0f;
     if (j < in) {
 #pragma unroll
-      for (int q = 0; q < 8; ++q) x[q] = load1<QP>(A, ((long long)e * r + 8 * g + q) * in + j);
+      for (int q = 0; q < 8; ++q)
+        x[q] = load1<QP>(A, TRANSPOSED ? ((long long)e * in + j) * r + 8 * g + q : ((long long)e * r + 8 * g + q) * in + j);
     }
     u32x4 hi, lo;
 #pragma unroll
@@ -157,11 +160,13 @@ __global__ __launch_bounds__(256) void k_pack_A(const void* __restrict__ A, uint
   }
 }
 
-hipError_t launch_pack_A(const void* A, uint16_t* Apk, int E, int r, int in, int qp, hipStream_t s) {
+hipError_t launch_pack_A(const void* A, uint16_t* Apk, int E, int r, int in, int qp, int transposed, hipStream_t s) {
   const long long total = (long long)E * (r / 8) * (ceil_div(in, kApkBlockCols) * kApkBlockCols);
   int grid = int(std::min<long long>((total + 255) / 256, 1 << 16));
-  if (qp == 2) hipLaunchKernelGGL(k_pack_A<2>, dim3(grid), dim3(256), 0, s, A, Apk, E, r, in);
-  else hipLaunchKernelGGL(k_pack_A<1>, dim3(grid), dim3(256), 0, s, A, Apk, E, r, in);
+  if (qp == 2 && !transposed) hipLaunchKernelGGL((k_pack_A<2, false>), dim3(grid), dim3(256), 0, s, A, Apk, E, r, in);
+  else if (qp == 2) hipLaunchKernelGGL((k_pack_A<2, true>), dim3(grid), dim3(256), 0, s, A, Apk, E, r, in);
+  else if (!transposed) hipLaunchKernelGGL((k_pack_A<1, false>), dim3(grid), dim3(256), 0, s, A, Apk, E, r, in);
+  else hipLaunchKernelGGL((k_pack_A<1, true>), dim3(grid), dim3(256), 0, s, A, Apk, E, r, in);
   return hipGetLastError();
 }
 
@@ -329,19 +334,32 @@ __device__ __forceinline__ void mfma_load_item(const LaunchPlan& p, int item, in
                                                const int (&term_e)[NKS], const int (&term_g)[NKS],
                                                const float (&term_c)[NKS], MfmaItem<NKS>& it,
                                                int tile_rows, int row_shift) {
-  const int seg = uniform(find_segment(p.first, p.n_sel, item));
-  const LinDesc* Lp = p.lin + uniform(p.sel[seg]);
+  const bool adapter = p.Z != nullptr;          // adapter-path mode: one matrix, rows = tokens, row operand = rows of Z
   LinDesc L;
-  L.W = uniform(Lp->W);
-  L.B = uniform(Lp->B);
-  L.Apk = uniform(Lp->Apk);
-  L.out = uniform(Lp->out);
-  L.in = uniform(Lp->in);
+  int local = item;
+  if (adapter) {
+    L.W = p.one.W;
+    L.B = nullptr;
+    L.Apk = p.one.Apk;
+    L.Wbase = nullptr;
+    L.out = p.one.out;
+    L.in = p.one.in;
+  } else {
+    const int seg = uniform(find_segment(p.first, p.n_sel, item));
+    const LinDesc* Lp = p.lin + uniform(p.sel[seg]);
+    L.W = uniform(Lp->W);
+    L.B = uniform(Lp->B);
+    L.Apk = uniform(Lp->Apk);
+    L.Wbase = p.from_base ? uniform(Lp->Wbase) : nullptr;
+    L.out = uniform(Lp->out);
+    L.in = uniform(Lp->in);
+    local = uniform(item - p.first[seg]);
+  }
   int row0, col0;
-  decode_item(uniform(item - p.first[seg]), L.in, tile_rows, p.tile_cols, &row0, &col0);
+  decode_item(local, L.in, tile_rows, p.tile_cols, &row0, &col0);
   row0 += row_shift;          // the calling wave's 32 rows inside a taller item (may lie past the last row)
   it.W = L.W;
-  it.Wsrc = p.from_base ? uniform(Lp->Wbase) : L.W;
+  it.Wsrc = p.from_base ? L.Wbase : L.W;
   it.wbytes = L.out * L.in * 2;
   it.Apk = L.Apk;
   it.ncb = ceil_div(L.in, MT_STEP);
@@ -354,7 +372,8 @@ __device__ __forceinline__ void mfma_load_item(const LaunchPlan& p, int item, in
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks) {
     float b[8];
-    load8<QP>(L.B, ((long long)term_e[ks] * L.out + prow) * r + 8 * term_g[ks], b);
+    if (adapter) load8<2>(p.Z, (long long)prow * p.z_stride + 8 * (term_e[ks] * gpr + term_g[ks]), b);
+    else load8<QP>(L.B, ((long long)term_e[ks] * L.out + prow) * r + 8 * term_g[ks], b);
     const float c = prow_ok ? term_c[ks] : 0.0f;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -562,6 +581,7 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma(LaunchPlan p, Ter
   const int gpr = r >> 3;
   const int n_groups = n_terms * gpr;
   const int grid = gridDim.x;
+  const bool adapter = p.Z != nullptr;      // adapter-path mode: the "terms" are all experts 0..n_terms-1, coefficient 1
   int term_e[NKS], term_g[NKS];
   float term_c[NKS];
 #pragma unroll
@@ -569,9 +589,9 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma(LaunchPlan p, Ter
     const int G = 2 * ks + h;
     const bool valid = G < n_groups;
     const int c = valid ? G / gpr : 0;
-    term_e[ks] = s_e[c];
+    term_e[ks] = adapter ? c : s_e[c];
     term_g[ks] = valid ? G - c * gpr : 0;
-    term_c[ks] = valid ? s_coeff[c] : 0.0f;
+    term_c[ks] = valid ? (adapter ? 1.0f : s_coeff[c]) : 0.0f;
   }
 
   int item = p.xcd_remap ? xcd_contiguous_block(blockIdx.x, grid) : int(blockIdx.x);
@@ -879,10 +899,11 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
     const bool valid = G < n_groups;
     const int c = valid ? G / gpr : 0;
     const int g = valid ? G - c * gpr : 0;
-    s_e[G] = s_te[c];
+    const int e = p.Z ? c : s_te[c];          // adapter-path mode: all experts in order, coefficient 1
+    s_e[G] = e;
     s_g[G] = g;
-    s_eg[G] = s_te[c] * gpr + g;
-    s_c[G] = valid ? s_tc[c] : 0.0f;
+    s_eg[G] = e * gpr + g;
+    s_c[G] = valid ? (p.Z ? 1.0f : s_tc[c]) : 0.0f;
   }
   __syncthreads();
 
@@ -900,21 +921,35 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
   const int first_item = p.xcd_remap ? xcd_contiguous_block(blockIdx.x, grid) : int(blockIdx.x);
   int buf = 0;
   for (int item = first_item; item < p.n_items; item += grid) {       // uniform over the workgroup
-    const int seg = uniform(find_segment(p.first, p.n_sel, item));
-    const LinDesc* Lp = p.lin + uniform(p.sel[seg]);
-    const void* B = uniform(Lp->B);
-    const int out = uniform(Lp->out), in = uniform(Lp->in);
+    const bool adapter = p.Z != nullptr;
+    LinDesc L;
+    int local = item;
+    if (adapter) {
+      L = p.one;
+    } else {
+      const int seg = uniform(find_segment(p.first, p.n_sel, item));
+      const LinDesc* Lp = p.lin + uniform(p.sel[seg]);
+      L.W = uniform(Lp->W);
+      L.B = uniform(Lp->B);
+      L.Apk = uniform(Lp->Apk);
+      L.Wbase = p.from_base ? uniform(Lp->Wbase) : nullptr;
+      L.out = uniform(Lp->out);
+      L.in = uniform(Lp->in);
+      local = uniform(item - p.first[seg]);
+    }
+    const void* B = L.B;
+    const int out = L.out, in = L.in;
     int row0, col0;
-    decode_item(uniform(item - p.first[seg]), in, kMfmaTileRows, p.tile_cols, &row0, &col0);
+    decode_item(local, in, kMfmaTileRows, p.tile_cols, &row0, &col0);
     row0 += 32 * wave;
     const int col_end = min(in, col0 + p.tile_cols);
     const int ncb = ceil_div(in, MT_STEP);
-    w.W = uniform(Lp->W);
-    w.Wsrc = p.from_base ? uniform(Lp->Wbase) : w.W;
+    w.W = L.W;
+    w.Wsrc = p.from_base ? L.Wbase : w.W;
     w.wbytes = out * in * 2;
     w.stride = uint32_t(in) * 2u;
     // the packed A of the linear, advanced to this wave's two blocks inside a column block
-    w.Apk = uniform(reinterpret_cast<const uint16_t*>(reinterpret_cast<const char*>(Lp->Apk) + wave * (1024 * QP)));
+    w.Apk = uniform(reinterpret_cast<const uint16_t*>(reinterpret_cast<const char*>(L.Apk) + wave * (1024 * QP)));
     w.eg_bytes = ncb * (4096 * QP);
     const uint32_t row0_byte = uint32_t(row0) * w.stride;
 
@@ -926,7 +961,8 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
       for (int ks = 0; ks < NKS; ++ks) {
         const int G = 2 * ks + h;
         float b[8];
-        load8<QP>(B, ((long long)s_e[G] * out + prow) * r + 8 * s_g[G], b);
+        if (adapter) load8<2>(p.Z, (long long)prow * p.z_stride + 8 * s_eg[G], b);
+        else load8<QP>(B, ((long long)s_e[G] * out + prow) * r + 8 * s_g[G], b);
         const float c = prow_ok ? s_c[G] : 0.0f;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -1040,6 +1076,9 @@ hipError_t launch_switch_mfma_bigk(const LaunchPlan& p, const Terms& t, const Te
 __global__ __launch_bounds__(64) void k_route(const float* __restrict__ logits, int E, int k, int32_t* __restrict__ ids,
                                               float* __restrict__ gates, int32_t* __restrict__ err) {
   const int lane = threadIdx.x;
+  logits += (long long)blockIdx.x * E;       // one workgroup per token
+  ids += (long long)blockIdx.x * k;
+  gates += (long long)blockIdx.x * k;
   bool nan = false;
   for (int i = lane; i < E; i += 64) nan |= (logits[i] != logits[i]);
   if (__any(nan)) {
@@ -1087,8 +1126,8 @@ __global__ __launch_bounds__(64) void k_route(const float* __restrict__ logits, 
   }
 }
 
-hipError_t launch_route(const float* logits, int E, int k, int32_t* ids, float* gates, int32_t* err, hipStream_t s) {
-  hipLaunchKernelGGL(k_route, dim3(1), dim3(64), 0, s, logits, E, k, ids, gates, err);
+hipError_t launch_route(const float* logits, int n_tokens, int E, int k, int32_t* ids, float* gates, int32_t* err, hipStream_t s) {
+  hipLaunchKernelGGL(k_route, dim3(n_tokens), dim3(64), 0, s, logits, E, k, ids, gates, err);
   return hipGetLastError();
 }
 
@@ -1132,6 +1171,185 @@ __global__ __launch_bounds__(64) void k_build_terms(const int32_t* __restrict__ 
 hipError_t launch_build_terms(const int32_t* old_ids, const float* old_gates, int k_old, const int32_t* new_ids,
                               const float* new_gates, int k_new, int E, float scale, Terms* out, int32_t* err, hipStream_t s) {
   hipLaunchKernelGGL(k_build_terms, dim3(1), dim3(64), 0, s, old_ids, old_gates, k_old, new_ids, new_gates, k_new, E, scale, out, err);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Un-merged adapter path for many tokens (Eq. 2: y = f(x) + sum_i G(x1)_i E_i(x), E_i(x) = W_up (W_down x)).
+//
+// Three launches per linear.  (1) k_adapter_down: U = X A_all^T on the matrix cores, all E*r down-projection rows of
+// all experts at once (N = E*r is at most 256, so computing the unselected experts too costs nothing next to the
+// traffic), the long contraction over `in` cut into slices whose partial sums go to Upart[slice][T][N].
+// (2) k_adapter_gate: Z[t][e*r+rho] = scale * g(t,e) * sum_slices Upart (zero for experts token t did not select):
+// the gather of the token's experts is a multiplication by a mostly-zero gate table.  (3) the matrix-core switch
+// kernels in adapter mode: Y[T,out] <- rne(Y + Z B_all^T), rows = tokens, the row operand read from Z, the shared
+// operand B^T packed like A (k_pack_A, transposed source).
+//
+// k_adapter_down.  A workgroup is one wave: 32 tokens x one slice of `in`.  X is bf16 and needs no split; A is
+// split into bf16 high + low (two passes).  The contraction index inside a 64-column chunk u is laid out so that a
+// lane reads 64 contiguous bytes of its token's row: k-step s (0..3), lane half h, element i  <->  column
+// 64u + 32h + 8s + i.  The A operand comes from a re-laid-out copy built once (k_pack_Atk):
+//   Atk bf16 [N/32 blocks][in/64 chunks][4 k-steps][parts][64 lanes][8]
+// holding for lane (h, n) the 8 values A_all[32*block + n][64u + 32h + 8s + i]: one operand load of a wave is 1 KB
+// contiguous.  Rows of A_all past E*r and columns past `in` hold zeros.
+// ---------------------------------------------------------------------------
+constexpr int AD_CHUNK = 64;        // columns of `in` per chunk (4 k-steps of 16)
+
+int64_t adapter_atk_elems(int E, int r, int in, int qp) {
+  return int64_t(ceil_div(E * r, 32)) * ceil_div(in, AD_CHUNK) * 4 * qp * 64 * 8;
+}
+
+// chunks one wave contracts: about 1024 waves per launch, at least one chunk each
+static int adapter_chunks_per_slice(int T, int in) {
+  const int nch = ceil_div(in, AD_CHUNK);
+  const long long tiles = ceil_div(T, 32);
+  return int(std::max<long long>(1, std::min<long long>(nch, (nch * tiles + 1023) / 1024)));
+}
+
+int adapter_slices(int T, int in) { return ceil_div(ceil_div(in, AD_CHUNK), adapter_chunks_per_slice(T, in)); }
+
+template <int QP>
+__global__ __launch_bounds__(256) void k_pack_Atk(const void* __restrict__ A, uint16_t* __restrict__ Atk, int N, int in) {
+  const int nb_count = ceil_div(N, 32), nch = ceil_div(in, AD_CHUNK);
+  const long long total = (long long)nb_count * nch * 4 * 64;
+  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (long long)gridDim.x * blockDim.x) {
+    const int lane = int(idx & 63), s4 = int((idx >> 6) & 3);
+    const long long bu = idx >> 8;
+    const int u = int(bu % nch), nb = int(bu / nch);
+    const int row = 32 * nb + (lane & 31), j = AD_CHUNK * u + 32 * (lane >> 5) + 8 * s4;
+    float x[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = (row < N && j < in) ? load1<QP>(A, (long long)row * in + j + i) : 0.0f;   // in % 8 == 0: all 8 or none
+    u32x4 hi, lo;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      uint32_t hh, ll;
+      split2(x[2 * q], x[2 * q + 1], &hh, &ll);
+      hi[q] = hh;
+      lo[q] = ll;
+    }
+    const long long base = (((long long)(nb * nch + u) * 4 + s4) * QP * 64 + lane) * 8;
+    *reinterpret_cast<u32x4*>(Atk + base) = hi;
+    if constexpr (QP == 2) *reinterpret_cast<u32x4*>(Atk + base + 64 * 8) = lo;
+  }
+}
+
+hipError_t launch_pack_Atk(const void* A, uint16_t* Atk, int E, int r, int in, int qp, hipStream_t s) {
+  const long long total = (long long)ceil_div(E * r, 32) * ceil_div(in, AD_CHUNK) * 4 * 64;
+  const int grid = int(std::min<long long>((total + 255) / 256, 1 << 16));
+  if (qp == 2) hipLaunchKernelGGL(k_pack_Atk<2>, dim3(grid), dim3(256), 0, s, A, Atk, E * r, in);
+  else hipLaunchKernelGGL(k_pack_Atk<1>, dim3(grid), dim3(256), 0, s, A, Atk, E * r, in);
+  return hipGetLastError();
+}
+
+template <int NB, int QP>
+__global__ __launch_bounds__(64) void k_adapter_down(const uint16_t* __restrict__ X, const uint16_t* __restrict__ Atk,
+                                                     float* __restrict__ Upart, int T, int in, int N, int cps) {
+  const int lane = threadIdx.x, n = lane & 31, h = lane >> 5;
+  const int tile = blockIdx.x, slice = blockIdx.y;
+  const int nch = ceil_div(in, AD_CHUNK);
+  const int u0 = slice * cps, u1 = min(nch, u0 + cps);
+  // X through a buffer resource: token rows past T lie outside it and read as zeros
+  const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(X), 0, T * in * 2, 0x00020000);
+  const uint32_t row_off = uint32_t(32 * tile + n) * uint32_t(in) * 2u;
+  f32x16 acc[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[nb][v] = 0.0f;
+  const LSW_GLOBAL u32x4* q0 = (const LSW_GLOBAL u32x4*)Atk + lane;
+  for (int u = u0; u < u1; ++u) {
+    u32x4 xp[4];
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) {
+      const int j = AD_CHUNK * u + 32 * h + 8 * s4;
+      xp[s4] = __builtin_amdgcn_raw_buffer_load_b128(xres, j < in ? row_off + uint32_t(j) * 2u : kOutOfRange, 0, 0);
+    }
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const LSW_GLOBAL u32x4* q = q0 + ((long long)(nb * nch + u) * 4) * QP * 64;
+      u32x4 qv[4][QP];
+#pragma unroll
+      for (int s4 = 0; s4 < 4; ++s4)
+#pragma unroll
+        for (int hl = 0; hl < QP; ++hl) qv[s4][hl] = q[(s4 * QP + hl) * 64];
+#pragma unroll
+      for (int s4 = 0; s4 < 4; ++s4)
+#pragma unroll
+        for (int hl = QP - 1; hl >= 0; --hl)       // the small (low-part) products first
+          acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xp[s4]),
+                                                            __builtin_bit_cast(bf16x8, qv[s4][hl]), acc[nb], 0, 0, 0);
+    }
+  }
+  // acc[nb][v] is U[token 32*tile + 8*(v/4) + 4h + v%4][column 32*nb + n]
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    const int col = 32 * nb + n;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int t = 32 * tile + 8 * (v >> 2) + 4 * h + (v & 3);
+      if (t < T && col < N) Upart[((long long)slice * T + t) * N + col] = acc[nb][v];
+    }
+  }
+}
+
+hipError_t launch_adapter_down(const uint16_t* X, const uint16_t* Atk, float* Upart, int T, int in, int N, int qp, hipStream_t s) {
+  const int cps = adapter_chunks_per_slice(T, in);
+  const dim3 grid(ceil_div(T, 32), adapter_slices(T, in));
+  const int nb = ceil_div(N, 32);
+#define LSW_AD(NB_)                                                                                              \
+  do {                                                                                                           \
+    if (qp == 2) hipLaunchKernelGGL((k_adapter_down<NB_, 2>), grid, dim3(64), 0, s, X, Atk, Upart, T, in, N, cps); \
+    else hipLaunchKernelGGL((k_adapter_down<NB_, 1>), grid, dim3(64), 0, s, X, Atk, Upart, T, in, N, cps);         \
+  } while (0)
+  if (nb <= 1) LSW_AD(1);
+  else if (nb <= 2) LSW_AD(2);
+  else if (nb <= 4) LSW_AD(4);
+  else if (nb <= 8) LSW_AD(8);
+  else return hipErrorInvalidValue;
+#undef LSW_AD
+  return hipGetLastError();
+}
+
+// Z[t][col] = scale * g(t, expert of col) * sum over the slices of Upart[.][t][col]; columns N..z_stride-1 are zeroed.
+// A token's list is checked as the switch's lists are: an id outside [0, E), a duplicate id or a non-finite gate
+// raises the sticky error word (flag 2) and gives that token an all-zero row (its output stays what it was).
+__global__ __launch_bounds__(256) void k_adapter_gate(const float* __restrict__ Upart, int n_slices, const int32_t* __restrict__ ids,
+                                                      const float* __restrict__ gates, int k, int T, int E, int r, float scale,
+                                                      float* __restrict__ Z, int z_stride, int32_t* __restrict__ err) {
+  const int N = E * r;
+  const long long total = (long long)T * z_stride;
+  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (long long)gridDim.x * blockDim.x) {
+    const int t = int(idx / z_stride), col = int(idx - (long long)t * z_stride);
+    float z = 0.0f;
+    if (col < N) {
+      const int e = col / r;
+      bool ok = true;
+      float coeff = 0.0f;
+      for (int c = 0; c < k; ++c) {
+        const int id = ids[(long long)t * k + c];
+        const float g = gates[(long long)t * k + c];
+        ok &= (id >= 0 && id < E) && (g - g == 0.0f);
+        for (int d = 0; d < c; ++d) ok &= (ids[(long long)t * k + d] != id);
+        if (id == e) coeff = __fmul_rn(scale, g);
+      }
+      if (!ok) {
+        if (col == 0) atomicOr(err, 2);
+      } else if (coeff != 0.0f) {
+        float u = 0.0f;
+        for (int s = 0; s < n_slices; ++s) u += Upart[((long long)s * T + t) * N + col];
+        z = coeff * u;
+      }
+    }
+    Z[idx] = z;
+  }
+}
+
+hipError_t launch_adapter_gate(const float* Upart, int n_slices, const int32_t* ids, const float* gates, int k, int T, int E, int r,
+                               float scale, float* Z, int z_stride, int32_t* err, hipStream_t s) {
+  const long long total = (long long)T * z_stride;
+  const int grid = int(std::min<long long>((total + 255) / 256, 1 << 16));
+  hipLaunchKernelGGL(k_adapter_gate, dim3(grid), dim3(256), 0, s, Upart, n_slices, ids, gates, k, T, E, r, scale, Z, z_stride, err);
   return hipGetLastError();
 }
 

@@ -1,0 +1,138 @@
+"""GPU parity of the un-merged adapter path over many tokens (lsw_adapter_forward, Eq. 2) against the CPU oracle.
+
+Bar: every output within 1 bf16 ulp of oracle.adapter_forward, or within one bf16 ulp at the largest magnitude that
+entered its sum (oracle/compare.py, the same two-clause rule as for the switch); the batch router bit-exact in its ids
+and within 1 fp32 ulp in its gates."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import compare as C
+from oracle import lsw_oracle as O
+from paper_2405_17741_amd import binding as L
+from paper_2405_17741_amd import inputs as I
+from tests.gpu_harness import DeviceStack, bf16_factor_stack, bits_to_device, device_to_bits
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # T, out, in, E, r, k
+    (1, 8, 8, 2, 8, 1), (37, 264, 72, 4, 8, 2), (130, 520, 1032, 8, 8, 2), (300, 256, 4096, 8, 8, 2),
+    (64, 1048, 136, 3, 16, 3), (100, 776, 264, 16, 16, 2), (33, 264, 200, 4, 64, 2), (257, 136, 520, 5, 24, 2),
+]
+
+
+def _tokens(rng, T, E, k, inn, out):
+    X = I.f32_to_bf16_bits(rng.normal(0, 1, (T, inn)).astype(np.float32))
+    Y = I.f32_to_bf16_bits(rng.normal(0, 0.5, (T, out)).astype(np.float32))
+    logits = rng.normal(0, 1, (T, E)).astype(np.float32)
+    routes = [O.route(l, k) for l in logits]
+    ids = np.stack([r[0] for r in routes]).astype(np.int32).reshape(T, k)
+    gates = np.stack([r[1] for r in routes]).astype(np.float32).reshape(T, k)
+    return X, Y, logits, ids, gates
+
+
+def _run(ds, p, X, Y, ids, gates, k):
+    T = X.shape[0]
+    Xd, Yd = bits_to_device(X), bits_to_device(Y)
+    idd, gd = torch.from_numpy(ids).cuda(), torch.from_numpy(gates).cuda()
+    ws = torch.empty(L.lsw_adapter_workspace_bytes(ds.ctx, p, T) // 4 + 64, dtype=torch.float32, device="cuda")
+    ws.fill_(float("nan"))              # the workspace may hold anything
+    L.lsw_adapter_forward(ds.ctx, p, Xd.data_ptr(), T, idd.data_ptr(), gd.data_ptr(), k, Yd.data_ptr(), ws.data_ptr(),
+                          torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    return device_to_bits(Yd)
+
+
+@pytest.mark.parametrize("bf16_factors", [False, True])
+@pytest.mark.parametrize("case", CASES)
+def test_adapter_forward_against_oracle(case, bf16_factors):
+    T, out, inn, E, r, k = case
+    rng = np.random.default_rng(T * 131 + out + inn + r)
+    host = [I.host_linear(rng, out, inn, E, r, 0.02, 1 / np.sqrt(inn), 0.05)]
+    if bf16_factors:
+        host = bf16_factor_stack(host)
+    (_, A, B), = host
+    ds = DeviceStack.from_host(host, [(0, 0, out, inn)], E, r, scale=0.5, bf16_factors=bf16_factors)
+    with pytest.raises(L.LswError) as e:
+        L.lsw_adapter_forward(ds.ctx, 0, 16, 1, 16, 16, 1, 16, 16)
+    assert e.value.status == L.LSW_ERR_STATE
+    L.lsw_enable_adapter_path(ds.ctx)
+    L.lsw_enable_adapter_path(ds.ctx)        # idempotent
+    X, Y, _, ids, gates = _tokens(rng, T, E, k, inn, out)
+    got = _run(ds, 0, X, Y, ids, gates, k)
+    want = O.adapter_forward(Y, X, A, B, ids, gates, 0.5)
+    S = O.adapter_magnitude(X, A, B, ids, gates, 0.5)
+    rep = C.switch_parity(got, want, Y, S)
+    assert rep["fail"] == 0, {k_: v for k_, v in rep.items() if k_ != "fail_mask"}
+    assert rep["exact"] > 0.995 * rep["n"]
+    assert (got != Y).mean() > 0.2, "the adapter term must have changed a good part of Y"
+    assert L.lsw_dev_status(ds.ctx) == 0
+    ds.close()
+
+
+def test_batch_router_and_bad_lists():
+    rng = np.random.default_rng(77)
+    T, out, inn, E, r, k = 70, 136, 264, 8, 8, 2
+    host = [I.host_linear(rng, out, inn, E, r, 0.02, 1 / 16, 0.05)]
+    (_, A, B), = host
+    ds = DeviceStack.from_host(host, [(0, 0, out, inn)], E, r)
+    L.lsw_enable_adapter_path(ds.ctx)
+    X, Y, logits, ids, gates = _tokens(rng, T, E, k, inn, out)
+    logits[3, :] = 0.25                       # ties: lowest indices first
+    logits[4, [1, 6]] = [0.0, -0.0]
+    ld = torch.from_numpy(logits).cuda()
+    idd = torch.zeros(T, k, dtype=torch.int32, device="cuda")
+    gd = torch.zeros(T, k, dtype=torch.float32, device="cuda")
+    L.lsw_route_batch_dev(ds.ctx, ld.data_ptr(), T, k, idd.data_ptr(), gd.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    gi, gg = idd.cpu().numpy(), gd.cpu().numpy()
+    for t in range(T):
+        oi, og = O.route(logits[t], k)
+        assert gi[t].tolist() == oi.tolist(), t
+        assert (np.abs(gg[t].view(np.int32).astype(np.int64) - og.view(np.int32)) <= 1).all(), t
+    # the device-routed lists drive the adapter path
+    got = _run(ds, 0, X, Y, gi, gg, k)
+    rep = C.switch_parity(got, O.adapter_forward(Y, X, A, B, gi, gg), Y, O.adapter_magnitude(X, A, B, gi, gg))
+    assert rep["fail"] == 0
+    # a bad list leaves that token's row untouched and raises the flag; the other tokens are unaffected
+    bad_ids, bad_gates = gi.copy(), gg.copy()
+    bad_ids[5] = [E, 0]
+    bad_ids[9] = [2, 2]
+    bad_gates[11, 1] = np.nan
+    got = _run(ds, 0, X, Y, bad_ids, bad_gates, k)
+    assert L.lsw_dev_status(ds.ctx) & 2
+    for t in (5, 9, 11):
+        assert (got[t] == Y[t]).all()
+    keep = np.setdiff1d(np.arange(T), [5, 9, 11])
+    rep = C.switch_parity(got[keep], O.adapter_forward(Y[keep], X[keep], A, B, gi[keep], gg[keep]), Y[keep],
+                          O.adapter_magnitude(X[keep], A, B, gi[keep], gg[keep]))
+    assert rep["fail"] == 0
+    # k = 0: nothing to add
+    assert (_run(ds, 0, X, Y, np.zeros((T, 0), np.int32), np.zeros((T, 0), np.float32), 0) == Y).all()
+    ds.close()
+
+
+def test_adapter_path_then_merged_decode_agree():
+    """Eq. 2 == Eq. 3 on the device: the adapter path on the base weights and the decode through the merged weights give
+    the same output up to the bf16 rounding of the merged weights and of Y."""
+    rng = np.random.default_rng(78)
+    out, inn, E, r, k = 264, 520, 8, 8, 2
+    host = [I.host_linear(rng, out, inn, E, r, 0.02, 1 / 16, 0.05)]
+    (W0, A, B), = host
+    ds = DeviceStack.from_host(host, [(0, 0, out, inn)], E, r)
+    L.lsw_enable_adapter_path(ds.ctx)
+    X, _, _, ids, gates = _tokens(rng, 1, E, k, inn, out)
+    base = O.gemv(W0, X[0])                                  # f(x) on the base weights, fp64
+    Y = O.f64_to_bf16_bits(base)[None, :]
+    y_adapter = O.bf16_bits_to_f64(_run(ds, 0, X, Y, ids, gates, k))[0]
+    none = (np.zeros(0, np.int32), np.zeros(0, np.float32))
+    ds.switch(none, (ids[0], gates[0]))
+    y = torch.empty(out, dtype=torch.float32, device="cuda")
+    L.lsw_merged_gemv(ds.ctx, 0, bits_to_device(X[0]).data_ptr(), y.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    y_merged = y.cpu().numpy().astype(np.float64)
+    xv = np.abs(O.bf16_bits_to_f64(X[0]))
+    slack = (0.5 * C.bf16_ulp_at(np.abs(O.bf16_bits_to_f64(ds.rows(0)))) * xv[None, :]).sum(1) \
+        + 1.5 * C.bf16_ulp_at(np.abs(y_merged)) + 1e-5 * (np.abs(O.bf16_bits_to_f64(W0)) @ xv)
+    assert (np.abs(y_merged - y_adapter) <= slack).all()
+    ds.close()

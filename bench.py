@@ -79,6 +79,7 @@ def main():
     ap.add_argument("--xcd", type=int, default=-1)
     ap.add_argument("--factor-dtype", choices=("fp32", "bf16"), default="fp32",
                     help="storage type of the LoRA factors (fp32 is what the workloads prescribe)")
+    ap.add_argument("--prefill-tokens", type=int, default=2048, help="prompt length of the adapter-path timing")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 4 GiB device copy (a known-size reference for HBM byte counters)")
@@ -237,6 +238,41 @@ def main():
         torch.cuda.synchronize()
         del base
 
+    # the un-merged adapter path a prompt takes (Eq. 2): 2048 tokens through the 7 linears of one layer
+    adapter = None
+    if wl.rank % 8 == 0 and wl.experts * wl.rank <= 256:
+        T = args.prefill_tokens
+        L.lsw_enable_adapter_path(ctx)
+        lg = torch.randn(T, wl.experts, device="cuda")
+        idd = torch.zeros(T, wl.top_k, dtype=torch.int32, device="cuda")
+        gd = torch.zeros(T, wl.top_k, dtype=torch.float32, device="cuda")
+        L.lsw_route_batch_dev(ctx, lg.data_ptr(), T, wl.top_k, idd.data_ptr(), gd.data_ptr(), stream)
+        layer0 = [(p, o, n) for p, (layer, _, o, n) in enumerate(wl.linear_shapes()) if layer == 0]
+        xs = {n: torch.randn(T, n, device="cuda").to(torch.bfloat16) for _, _, n in layer0}
+        ys = {o: torch.randn(T, o, device="cuda").to(torch.bfloat16) for _, o, _ in layer0}
+        ws = torch.empty(max(L.lsw_adapter_workspace_bytes(ctx, p, T) for p, _, _ in layer0) // 4, dtype=torch.float32, device="cuda")
+
+        def prefill_layer():
+            for p, o, n in layer0:
+                L.lsw_adapter_forward(ctx, p, xs[n].data_ptr(), T, idd.data_ptr(), gd.data_ptr(), wl.top_k, ys[o].data_ptr(),
+                                      ws.data_ptr(), stream)
+        prefill_layer()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(10):
+            prefill_layer()
+        b.record()
+        b.synchronize()
+        ad_us = a.elapsed_time(b) * 1e3 / 10
+        fb = 2 if bf16_factors else 4
+        ad_bytes = sum(T * n * 2 + 2 * T * o * 2 + fb * wl.experts * wl.rank * (n + o) for _, o, n in layer0)
+        adapter = {"tokens": T, "linears": len(layer0), "us_per_layer": round(ad_us, 1), "GBps": round(ad_bytes / (ad_us * 1e-6) / 1e9, 1),
+                   "frac_of_hbm_peak": round(ad_bytes / (ad_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4), "error_flags": L.lsw_dev_status(ctx),
+                   "note": "lsw_adapter_forward over the linears of one layer: X read, Y read and written (bf16), every factor once; "
+                           "three launches per linear"}
+        del xs, ys, ws
+
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
@@ -280,6 +316,7 @@ def main():
         "device_routing": {"us_per_token": round(dev_us, 1), "tokens": n_dev, "error_flags": dev_flags,
                            "note": "lsw_route_dev + lsw_switch_dev per token, lists resident on the device, no host round trip; "
                                    "launches sized for k_old + k_new terms"},
+        "adapter_prefill": adapter,
         "layer_subset": subset,
         "rebase": rebase,
         "inplace_probe": {**probe, "note": "lsw_probe_inplace on the same weights: in-place bf16 read+write only; "

@@ -66,6 +66,34 @@ def cpu_baseline(wl, steps=3):
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
 
 
+def probe_pitch(torch, L):
+    """What an in-place pass sustains on this part as a function of the row pitch of the matrix: the switch kernel's
+    access pattern (32 rows x 512 bytes per wave and step) with no factor traffic and no matrix work."""
+    stream = torch.cuda.current_stream().cuda_stream
+    print("columns  row pitch [B]   GB/s (2 waves/CU)   GB/s (4 waves/CU)")
+    for cols in (1024, 2048, 3072, 4096, 5120, 6144, 8192, 11008, 12288, 13824, 16384, 16640, 20480, 24576, 28672, 32768, 49152):
+        rows = ((1 << 30) // (2 * cols)) // 128 * 128          # four matrices of 1 GiB (one W must stay below 2 GiB)
+        Ws = [torch.zeros(rows, cols, dtype=torch.bfloat16, device="cuda") for _ in range(4)]
+        A = torch.zeros(1, 8, cols, dtype=torch.float32, device="cuda")
+        B = torch.zeros(1, rows, 8, dtype=torch.float32, device="cuda")
+        ctx = L.lsw_create_adapters([(W.data_ptr(), A.data_ptr(), B.data_ptr(), rows, cols, i, 0) for i, W in enumerate(Ws)], 1, 8)
+        rates = []
+        for wpc in (2, 4):
+            L.lsw_probe_inplace(ctx, wpc, stream)
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(4):
+                L.lsw_probe_inplace(ctx, wpc, stream)
+            b.record()
+            b.synchronize()
+            rates.append(4.0 * 4 * rows * cols / (a.elapsed_time(b) / 4 * 1e-3) / 1e9)
+        print(f"{cols:7d}  {2 * cols:13d}   {rates[0]:17.1f}   {rates[1]:17.1f}", flush=True)
+        torch.cuda.synchronize()
+        L.lsw_destroy(ctx)
+        del Ws, A, B
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -80,6 +108,11 @@ def main():
     ap.add_argument("--factor-dtype", choices=("fp32", "bf16"), default="fp32",
                     help="storage type of the LoRA factors (fp32 is what the workloads prescribe)")
     ap.add_argument("--prefill-tokens", type=int, default=2048, help="prompt length of the adapter-path timing")
+    ap.add_argument("--probe-pitch", action="store_true",
+                    help="instead of the benchmark: in-place read+write bandwidth (lsw_probe_inplace) of 4 GiB of matrices "
+                         "as a function of its row pitch; prints a table")
+    ap.add_argument("--switch-only", action="store_true",
+                    help="time the switch launches only (profiling runs: every launch of the switch kernel is then a timed one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 4 GiB device copy (a known-size reference for HBM byte counters)")
@@ -97,8 +130,11 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
-    wl = I.WORKLOADS[args.workload]
     torch.cuda.set_device(0)
+    if args.probe_pitch:
+        probe_pitch(torch, L)
+        return
+    wl = I.WORKLOADS[args.workload]
     bf16_factors = args.factor_dtype == "bf16"
     stack = I.device_stack(wl, factor_dtype=torch.bfloat16 if bf16_factors else torch.float32)
     ctx = L.create_from_tensors(stack, wl.linear_shapes(), wl.experts, wl.rank)
@@ -150,128 +186,131 @@ def main():
     achieved = (sum(launch_bytes) / len(launch_bytes)) / (avg_ms * 1e-3) / 1e9
     ms_per_step = wall * 1e3 / args.steps
 
-    # yardstick: the same tensors, the same access pattern, no factor traffic and no matrix work
-    probe = {}
-    for wpc in (2, 4):
-        L.lsw_probe_inplace(ctx, wpc, stream)
+    probe, subset, rebase, adapter = {}, None, None, None
+    gemv_ms = gemv_gbps = dev_us = float("nan")
+    n_dev, dev_flags = 0, 0
+    if not args.switch_only:
+        # yardstick: the same tensors, the same access pattern, no factor traffic and no matrix work
+        for wpc in (2, 4):
+            L.lsw_probe_inplace(ctx, wpc, stream)
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(5):
+                L.lsw_probe_inplace(ctx, wpc, stream)
+            b.record()
+            b.synchronize()
+            probe[f"{wpc}_waves_per_cu_GBps"] = round(4.0 * wl.w_elements() / (a.elapsed_time(b) / 5 * 1e-3) / 1e9, 1)
+
+        # the decode that follows the switch (timed separately): every merged linear once, batch 1
+        nx, ny = L.lsw_query(ctx, L.LSW_Q_GEMV_X_ELEMS), L.lsw_query(ctx, L.LSW_Q_GEMV_Y_ELEMS)
+        xg = torch.randn(nx, device="cuda").to(torch.bfloat16)
+        yg = torch.empty(ny, device="cuda", dtype=torch.float32)
+        L.lsw_merged_gemv_all(ctx, xg.data_ptr(), yg.data_ptr(), stream)
         torch.cuda.synchronize()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
         for _ in range(5):
-            L.lsw_probe_inplace(ctx, wpc, stream)
+            L.lsw_merged_gemv_all(ctx, xg.data_ptr(), yg.data_ptr(), stream)
         b.record()
         b.synchronize()
-        probe[f"{wpc}_waves_per_cu_GBps"] = round(4.0 * wl.w_elements() / (a.elapsed_time(b) / 5 * 1e-3) / 1e9, 1)
+        gemv_ms = a.elapsed_time(b) / 5
+        gemv_gbps = 2.0 * wl.w_elements() / (gemv_ms * 1e-3) / 1e9
+        del xg, yg
 
-    # the decode that follows the switch (timed separately): every merged linear once, batch 1
-    nx, ny = L.lsw_query(ctx, L.LSW_Q_GEMV_X_ELEMS), L.lsw_query(ctx, L.LSW_Q_GEMV_Y_ELEMS)
-    xg = torch.randn(nx, device="cuda").to(torch.bfloat16)
-    yg = torch.empty(ny, device="cuda", dtype=torch.float32)
-    L.lsw_merged_gemv_all(ctx, xg.data_ptr(), yg.data_ptr(), stream)
-    torch.cuda.synchronize()
-    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    a.record()
-    for _ in range(5):
-        L.lsw_merged_gemv_all(ctx, xg.data_ptr(), yg.data_ptr(), stream)
-    b.record()
-    b.synchronize()
-    gemv_ms = a.elapsed_time(b) / 5
-    gemv_gbps = 2.0 * wl.w_elements() / (gemv_ms * 1e-3) / 1e9
-    del xg, yg
+        # the same token step with the token's (ids, gates) resident on the device: router, term list and switch are
+        # all launched without a value coming back to the host (lsw_route_dev + lsw_switch_dev)
+        n_dev = min(args.steps, 32)
+        logits_d = torch.from_numpy(logits[:n_dev + 1].copy()).cuda()
+        bufs = [(torch.zeros(wl.top_k, dtype=torch.int32, device="cuda"), torch.zeros(wl.top_k, dtype=torch.float32, device="cuda"))
+                for _ in range(2)]
+        bufs[1][0].copy_(torch.from_numpy(old[0])); bufs[1][1].copy_(torch.from_numpy(old[1]))     # what is merged now
 
-    # the same token step with the token's (ids, gates) resident on the device: router, term list and switch are
-    # all launched without a value coming back to the host (lsw_route_dev + lsw_switch_dev)
-    n_dev = min(args.steps, 32)
-    logits_d = torch.from_numpy(logits[:n_dev + 1].copy()).cuda()
-    bufs = [(torch.zeros(wl.top_k, dtype=torch.int32, device="cuda"), torch.zeros(wl.top_k, dtype=torch.float32, device="cuda"))
-            for _ in range(2)]
-    bufs[1][0].copy_(torch.from_numpy(old[0])); bufs[1][1].copy_(torch.from_numpy(old[1]))     # what is merged now
+        def dev_token(t):
+            new, prv = bufs[t % 2], bufs[(t + 1) % 2]
+            L.lsw_route_dev(ctx, logits_d[t].data_ptr(), wl.top_k, new[0].data_ptr(), new[1].data_ptr(), stream)
+            L.lsw_switch_dev(ctx, prv[0].data_ptr(), prv[1].data_ptr(), wl.top_k, new[0].data_ptr(), new[1].data_ptr(), wl.top_k, stream=stream)
 
-    def dev_token(t):
-        new, prv = bufs[t % 2], bufs[(t + 1) % 2]
-        L.lsw_route_dev(ctx, logits_d[t].data_ptr(), wl.top_k, new[0].data_ptr(), new[1].data_ptr(), stream)
-        L.lsw_switch_dev(ctx, prv[0].data_ptr(), prv[1].data_ptr(), wl.top_k, new[0].data_ptr(), new[1].data_ptr(), wl.top_k, stream=stream)
+        dev_token(0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for t in range(1, n_dev + 1):
+            dev_token(t)
+        torch.cuda.synchronize()
+        dev_us = (time.perf_counter() - t0) * 1e6 / n_dev
+        dev_flags = L.lsw_dev_status(ctx)
 
-    dev_token(0)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for t in range(1, n_dev + 1):
-        dev_token(t)
-    torch.cuda.synchronize()
-    dev_us = (time.perf_counter() - t0) * 1e6 / n_dev
-    dev_flags = L.lsw_dev_status(ctx)
-
-    # a partial layer set (the `layers` argument): the first half of the layers, there and back
-    half = list(range(wl.layers // 2)) or [0]
-    other = L.lsw_route(logits[0], wl.top_k)
-    sub_bytes = algorithmic_bytes(wl, len(L.lsw_build_terms(old[0], old[1], other[0], other[1], wl.experts)[0]),
-                                  2 if bf16_factors else 4) * len(half) / wl.layers
-    L.lsw_switch(ctx, old[0], old[1], other[0], other[1], layers=half, stream=stream)
-    L.lsw_switch(ctx, other[0], other[1], old[0], old[1], layers=half, stream=stream)
-    torch.cuda.synchronize()
-    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    a.record()
-    for _ in range(3):
+        # a partial layer set (the `layers` argument): the first half of the layers, there and back
+        half = list(range(wl.layers // 2)) or [0]
+        other = L.lsw_route(logits[0], wl.top_k)
+        sub_bytes = algorithmic_bytes(wl, len(L.lsw_build_terms(old[0], old[1], other[0], other[1], wl.experts)[0]),
+                                      2 if bf16_factors else 4) * len(half) / wl.layers
         L.lsw_switch(ctx, old[0], old[1], other[0], other[1], layers=half, stream=stream)
         L.lsw_switch(ctx, other[0], other[1], old[0], old[1], layers=half, stream=stream)
-    b.record()
-    b.synchronize()
-    sub_us = a.elapsed_time(b) * 1e3 / 6
-    subset = {"layers": len(half), "us": round(sub_us, 1), "GBps": round(sub_bytes / (sub_us * 1e-6) / 1e9, 1)}
-
-    # drift control: rebuild every weight from a base copy with the current set merged (reads the copy, writes W)
-    rebase = None
-    if 2 * 2 * wl.w_elements() < 200e9:
-        base = [W.clone() for W, _, _ in stack]
-        L.lsw_set_base(ctx, [t.data_ptr() for t in base])
-        L.lsw_rebase(ctx, old[0], old[1], stream=stream)
         torch.cuda.synchronize()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
-        for _ in range(5):
+        for _ in range(3):
+            L.lsw_switch(ctx, old[0], old[1], other[0], other[1], layers=half, stream=stream)
+            L.lsw_switch(ctx, other[0], other[1], old[0], old[1], layers=half, stream=stream)
+        b.record()
+        b.synchronize()
+        sub_us = a.elapsed_time(b) * 1e3 / 6
+        subset = {"layers": len(half), "us": round(sub_us, 1), "GBps": round(sub_bytes / (sub_us * 1e-6) / 1e9, 1)}
+
+        # drift control: rebuild every weight from a base copy with the current set merged (reads the copy, writes W)
+        rebase = None
+        if 2 * 2 * wl.w_elements() < 200e9:
+            base = [W.clone() for W, _, _ in stack]
+            L.lsw_set_base(ctx, [t.data_ptr() for t in base])
             L.lsw_rebase(ctx, old[0], old[1], stream=stream)
-        b.record()
-        b.synchronize()
-        rb_us = a.elapsed_time(b) * 1e3 / 5
-        rebase = {"us": round(rb_us, 1), "GBps": round(algorithmic_bytes(wl, len(old[0]), 2 if bf16_factors else 4) / (rb_us * 1e-6) / 1e9, 1),
-                  "note": "lsw_rebase: W <- rne(W_base + current set), base copy read, W written, one launch"}
-        torch.cuda.synchronize()
-        del base
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(5):
+                L.lsw_rebase(ctx, old[0], old[1], stream=stream)
+            b.record()
+            b.synchronize()
+            rb_us = a.elapsed_time(b) * 1e3 / 5
+            rebase = {"us": round(rb_us, 1), "GBps": round(algorithmic_bytes(wl, len(old[0]), 2 if bf16_factors else 4) / (rb_us * 1e-6) / 1e9, 1),
+                      "note": "lsw_rebase: W <- rne(W_base + current set), base copy read, W written, one launch"}
+            torch.cuda.synchronize()
+            del base
 
-    # the un-merged adapter path a prompt takes (Eq. 2): 2048 tokens through the 7 linears of one layer
-    adapter = None
-    if wl.rank % 8 == 0 and wl.experts * wl.rank <= 256:
-        T = args.prefill_tokens
-        L.lsw_enable_adapter_path(ctx)
-        lg = torch.randn(T, wl.experts, device="cuda")
-        idd = torch.zeros(T, wl.top_k, dtype=torch.int32, device="cuda")
-        gd = torch.zeros(T, wl.top_k, dtype=torch.float32, device="cuda")
-        L.lsw_route_batch_dev(ctx, lg.data_ptr(), T, wl.top_k, idd.data_ptr(), gd.data_ptr(), stream)
-        layer0 = [(p, o, n) for p, (layer, _, o, n) in enumerate(wl.linear_shapes()) if layer == 0]
-        xs = {n: torch.randn(T, n, device="cuda").to(torch.bfloat16) for _, _, n in layer0}
-        ys = {o: torch.randn(T, o, device="cuda").to(torch.bfloat16) for _, o, _ in layer0}
-        ws = torch.empty(max(L.lsw_adapter_workspace_bytes(ctx, p, T) for p, _, _ in layer0) // 4, dtype=torch.float32, device="cuda")
+        # the un-merged adapter path a prompt takes (Eq. 2): 2048 tokens through the 7 linears of one layer
+        adapter = None
+        if wl.rank % 8 == 0 and wl.experts * wl.rank <= 256:
+            T = args.prefill_tokens
+            L.lsw_enable_adapter_path(ctx)
+            lg = torch.randn(T, wl.experts, device="cuda")
+            idd = torch.zeros(T, wl.top_k, dtype=torch.int32, device="cuda")
+            gd = torch.zeros(T, wl.top_k, dtype=torch.float32, device="cuda")
+            L.lsw_route_batch_dev(ctx, lg.data_ptr(), T, wl.top_k, idd.data_ptr(), gd.data_ptr(), stream)
+            layer0 = [(p, o, n) for p, (layer, _, o, n) in enumerate(wl.linear_shapes()) if layer == 0]
+            xs = {n: torch.randn(T, n, device="cuda").to(torch.bfloat16) for _, _, n in layer0}
+            ys = {o: torch.randn(T, o, device="cuda").to(torch.bfloat16) for _, o, _ in layer0}
+            ws = torch.empty(max(L.lsw_adapter_workspace_bytes(ctx, p, T) for p, _, _ in layer0) // 4, dtype=torch.float32, device="cuda")
 
-        def prefill_layer():
-            for p, o, n in layer0:
-                L.lsw_adapter_forward(ctx, p, xs[n].data_ptr(), T, idd.data_ptr(), gd.data_ptr(), wl.top_k, ys[o].data_ptr(),
-                                      ws.data_ptr(), stream)
-        prefill_layer()
-        torch.cuda.synchronize()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for _ in range(10):
+            def prefill_layer():
+                for p, o, n in layer0:
+                    L.lsw_adapter_forward(ctx, p, xs[n].data_ptr(), T, idd.data_ptr(), gd.data_ptr(), wl.top_k, ys[o].data_ptr(),
+                                          ws.data_ptr(), stream)
             prefill_layer()
-        b.record()
-        b.synchronize()
-        ad_us = a.elapsed_time(b) * 1e3 / 10
-        fb = 2 if bf16_factors else 4
-        ad_bytes = sum(T * n * 2 + 2 * T * o * 2 + fb * wl.experts * wl.rank * (n + o) for _, o, n in layer0)
-        adapter = {"tokens": T, "linears": len(layer0), "us_per_layer": round(ad_us, 1), "GBps": round(ad_bytes / (ad_us * 1e-6) / 1e9, 1),
-                   "frac_of_hbm_peak": round(ad_bytes / (ad_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4), "error_flags": L.lsw_dev_status(ctx),
-                   "note": "lsw_adapter_forward over the linears of one layer: X read, Y read and written (bf16), every factor once; "
-                           "three launches per linear"}
-        del xs, ys, ws
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(10):
+                prefill_layer()
+            b.record()
+            b.synchronize()
+            ad_us = a.elapsed_time(b) * 1e3 / 10
+            fb = 2 if bf16_factors else 4
+            ad_bytes = sum(T * n * 2 + 2 * T * o * 2 + fb * wl.experts * wl.rank * (n + o) for _, o, n in layer0)
+            adapter = {"tokens": T, "linears": len(layer0), "us_per_layer": round(ad_us, 1), "GBps": round(ad_bytes / (ad_us * 1e-6) / 1e9, 1),
+                       "frac_of_hbm_peak": round(ad_bytes / (ad_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4), "error_flags": L.lsw_dev_status(ctx),
+                       "note": "lsw_adapter_forward over the linears of one layer: X read, Y read and written (bf16), every factor once; "
+                               "three launches per linear"}
+            del xs, ys, ws
 
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
@@ -310,19 +349,22 @@ def main():
                                  "median": round(sorted(launch_ms)[len(launch_ms) // 2] * 1e3, 1)}},
         "achieved_hbm_GBps": round(achieved, 1),
         "roofline": roofline,
-        "merged_gemv": {"us": round(gemv_ms * 1e3, 1), "GBps": round(gemv_gbps, 1), "frac_of_hbm_peak": round(gemv_gbps / HBM_PEAK_GBPS, 4),
-                        "note": "lsw_merged_gemv_all: batch-1 bf16 decode through every merged linear in one launch, "
-                                "2 bytes per weight, timed separately from the switch"},
-        "device_routing": {"us_per_token": round(dev_us, 1), "tokens": n_dev, "error_flags": dev_flags,
-                           "note": "lsw_route_dev + lsw_switch_dev per token, lists resident on the device, no host round trip; "
-                                   "launches sized for k_old + k_new terms"},
-        "adapter_prefill": adapter,
-        "layer_subset": subset,
-        "rebase": rebase,
-        "inplace_probe": {**probe, "note": "lsw_probe_inplace on the same weights: in-place bf16 read+write only; "
-                                           "the practical ceiling of the switch's access pattern",
-                          "switch_over_best_probe": round(achieved / max(probe.values()), 4)},
     }
+    if not args.switch_only:
+        out.update({
+            "merged_gemv": {"us": round(gemv_ms * 1e3, 1), "GBps": round(gemv_gbps, 1), "frac_of_hbm_peak": round(gemv_gbps / HBM_PEAK_GBPS, 4),
+                            "note": "lsw_merged_gemv_all: batch-1 bf16 decode through every merged linear in one launch, "
+                                    "2 bytes per weight, timed separately from the switch"},
+            "device_routing": {"us_per_token": round(dev_us, 1), "tokens": n_dev, "error_flags": dev_flags,
+                               "note": "lsw_route_dev + lsw_switch_dev per token, lists resident on the device, no host round trip; "
+                                       "launches sized for k_old + k_new terms"},
+            "adapter_prefill": adapter,
+            "layer_subset": subset,
+            "rebase": rebase,
+            "inplace_probe": {**probe, "note": "lsw_probe_inplace on the same weights: in-place bf16 read+write only; "
+                                               "the practical ceiling of the switch's access pattern",
+                              "switch_over_best_probe": round(achieved / max(probe.values()), 4)},
+        })
     torch.cuda.synchronize()
     L.lsw_destroy(ctx)
     del stack

@@ -324,9 +324,9 @@ def main():
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic}
     mean_terms = sum(terms) / len(terms)
     if max(kernels) == 2 and mean_terms * wl.rank > 64:
-        # fused ranks above 64: three bf16 passes (two with bf16-stored factors) of 2*K flop per weight take longer on
-        # the matrix cores than the W traffic takes on HBM, so that is the roofline of this launch
-        passes = 2.0 if bf16_factors else 3.0
+        # fused ranks above 64: three bf16 passes (two, or one, with bf16-stored factors) of 2*K flop per weight take
+        # longer on the matrix cores than the W traffic takes on HBM, so that is the roofline of this launch
+        passes = (1.0 if wl.rank % 16 == 0 else 2.0) if bf16_factors else 3.0    # exact bf16 factors of such a rank: one pass
         flops = [passes * 2.0 * n * wl.rank * wl.w_elements() for n, k in zip(terms, kernels) if k != 0]
         tf = (sum(flops) / len(flops)) / (avg_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",

@@ -281,7 +281,10 @@ enum {
   LSW_OPT_GRID = 3,          /* workgroups per launch; 0 = automatic (one matrix-core workgroup per CU) */
   LSW_OPT_TILE_COLS = 4,     /* matrix-core kernel: columns per work item, a multiple of 256 (tuning knob) */
   LSW_OPT_XCD_REMAP = 5,     /* 1 (default): each XCD takes a contiguous share of every round of items */
-  LSW_OPT_GEMV_GRID = 6      /* workgroups of the merged-decode launches; 0 = automatic (2 per CU) */
+  LSW_OPT_GEMV_GRID = 6,     /* workgroups of the merged-decode launches; 0 = automatic (2 per CU) */
+  LSW_OPT_ONE_PASS = 7       /* 1 (default): bf16-stored factors of a rank that is a multiple of 16 run ONE matrix-core pass
+                                when the fused rank exceeds 64 (bare B A products, gates applied in fp32 between the terms);
+                                0: two passes with the gate folded into B (what every other rank gets) */
 };
 enum {
   LSW_Q_N_LINEARS = 1, LSW_Q_N_LAYERS = 2,

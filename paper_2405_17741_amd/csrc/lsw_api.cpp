@@ -84,7 +84,7 @@ struct lsw_ctx {
   int64_t owned_bytes = 0;
   int64_t x_elems = 0, y_elems = 0;          // sizes of the back-to-back x and y of lsw_merged_gemv_all
   std::map<PlanKey, DevicePlan> plans;
-  int opt_kernel = 0, opt_strict = 0, opt_grid = 0, opt_tile_cols = kMfmaTileCols, opt_tile_cols_bigk = kMfmaBigkTileCols, opt_xcd = 1, opt_gemv_grid = 0;
+  int opt_kernel = 0, opt_strict = 0, opt_grid = 0, opt_tile_cols = kMfmaTileCols, opt_tile_cols_bigk = kMfmaBigkTileCols, opt_xcd = 1, opt_gemv_grid = 0, opt_one_pass = 1;
   int last_kernel = 0, last_items = 0, last_grid = 0;
 };
 
@@ -422,7 +422,7 @@ static lsw_status launch_switch(lsw_ctx* c, const std::vector<int32_t>& sel_laye
     const int tc = kernel >= 2 ? (bigk ? c->opt_tile_cols_bigk : c->opt_tile_cols) : kValuTileCols;
     lsw_status st = get_plan(c, kernel, tc, sel_layers, &dp);
     if (st != LSW_OK) return st;
-    LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, tc, c->opt_xcd, from_base ? 1 : 0, nullptr, 0, LinDesc{}};
+    LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, tc, c->opt_xcd, from_base ? 1 : 0, c->opt_one_pass, nullptr, 0, LinDesc{}};
     int grid = c->opt_grid;
     if (grid <= 0) grid = (kernel == 2) ? c->n_cu : c->n_cu * 2;   // matrix-core: one workgroup per CU
     grid = std::max(8, (grid / 8) * 8);     // a multiple of the 8 XCDs (the kernels' block remap assumes it)
@@ -667,7 +667,7 @@ extern "C" lsw_status lsw_adapter_forward(lsw_ctx* c, int32_t lin_index, const v
   one.out = T;
   one.in = L.out;
   const int64_t n_items = int64_t(ceil_div(T, kMfmaTileRows)) * ceil_div(L.out, tc);
-  LaunchPlan lp{nullptr, nullptr, nullptr, 1, int32_t(n_items), tc, c->opt_xcd, 0, Z, zs, one};
+  LaunchPlan lp{nullptr, nullptr, nullptr, 1, int32_t(n_items), tc, c->opt_xcd, 0, 0, Z, zs, one};
   const int grid = std::max(8, (c->n_cu / 8) * 8);
   e = bigk ? launch_switch_mfma_bigk(lp, t, nullptr, c->r, c->qp, grid, s) : launch_switch_mfma(lp, t, nullptr, c->r, c->qp, grid, s);
   if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "up-projection launch failed: %s", hipGetErrorString(e));
@@ -700,7 +700,7 @@ extern "C" lsw_status lsw_probe_inplace(lsw_ctx* c, int32_t waves_per_cu, void* 
   DevicePlan* dp = nullptr;
   lsw_status st = get_plan(c, 3, c->opt_tile_cols, std::vector<int32_t>(), &dp);
   if (st != LSW_OK) return st;
-  LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, c->opt_tile_cols, c->opt_xcd, 0, nullptr, 0, LinDesc{}};
+  LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, c->opt_tile_cols, c->opt_xcd, 0, 0, nullptr, 0, LinDesc{}};
   hipError_t e = launch_probe_inplace(lp, c->n_cu * waves_per_cu, static_cast<hipStream_t>(hip_stream));
   if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "probe launch failed: %s", hipGetErrorString(e));
   return LSW_OK;
@@ -730,7 +730,7 @@ extern "C" lsw_status lsw_merged_gemv_all(lsw_ctx* c, const void* x_all_bf16, fl
   DevicePlan* dp = nullptr;
   lsw_status st = get_plan(c, 4, 1 << 30, std::vector<int32_t>(), &dp);   // items: blocks of rows, whole rows wide
   if (st != LSW_OK) return st;
-  LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, 1 << 30, c->opt_xcd, 0, nullptr, 0, LinDesc{}};
+  LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, 1 << 30, c->opt_xcd, 0, 0, nullptr, 0, LinDesc{}};
   int grid = c->opt_gemv_grid > 0 ? c->opt_gemv_grid : c->n_cu * 2;
   grid = std::max(8, (grid / 8) * 8);
   hipError_t e = launch_gemv_all(lp, static_cast<const uint16_t*>(x_all_bf16), y_all_fp32, grid,
@@ -774,6 +774,9 @@ extern "C" lsw_status lsw_set_option(lsw_ctx* c, int32_t option, int64_t value) 
       return LSW_OK;
     case LSW_OPT_XCD_REMAP:
       c->opt_xcd = value != 0;
+      return LSW_OK;
+    case LSW_OPT_ONE_PASS:
+      c->opt_one_pass = value != 0;
       return LSW_OK;
     case LSW_OPT_GEMV_GRID:
       if (value < 0 || value > (1 << 20)) return fail(LSW_ERR_ARG, "grid option out of range");

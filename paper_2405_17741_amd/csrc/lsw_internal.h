@@ -82,6 +82,7 @@ struct LaunchPlan {             // device pointers + counts for one launch
   int32_t tile_cols;            // columns of one work item (matrix-core kernel: a multiple of kApkBlockCols)
   int32_t xcd_remap;            // 1: each XCD takes a contiguous eighth of every grid-wide round of items
   int32_t from_base;            // 1: the switch kernels read Wbase instead of W (and still write W): lsw_rebase
+  int32_t exact_one_pass;       // 1: bf16-stored factors of a rank that is a multiple of 16 run one matrix-core pass (chunked kernel)
   // Adapter-path mode of the matrix-core kernels (Z != null): ONE matrix, described by `one` (W = the [T, out]
   // activations to add to, Apk = the packed B^T of the linear, out = T, in = out features); lin/sel/first are unused.
   // The row operand is not coeff * B but row t of Z (fp32 [T, z_stride]: the gated down-projection of token t, all

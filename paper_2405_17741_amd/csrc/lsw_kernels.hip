@@ -732,10 +732,17 @@ __device__ __forceinline__ void bk_for_each_group(F& f, std::integer_sequence<in
 // matrix instructions (pair q outermost, k-step kk inside).  FIRST: widen the W words of pair q+1
 // during pair q (pair 0 is widened by the caller).  LAST: round pair q-1 during pair q (pair 3 by the
 // caller).  COPY: issue the 16 LDS-copy instructions of `cp` along with the first 8 groups.
-template <bool FIRST, bool LAST, bool COPY, int QP>
+//
+// H (exact factors, one pass): with bf16-stored factors and a rank that is a multiple of 16 every k-step belongs to ONE
+// term, and B and A are exact matrix-core operands.  The accumulators then start at zero and collect the bare products
+// B_c A_c; the gate enters in fp32 BETWEEN the terms (Horner: before the first k-step of term c the accumulators are
+// multiplied by rho = coeff_{c-1} / coeff_c, terms sorted by rising |coeff| so that |rho| <= 1) and W joins at the very end,
+// W + coeff_last * acc, rounded once.  One matrix instruction per block and k-step instead of two, no low part of P.
+template <bool FIRST, bool LAST, bool COPY, int QP, bool H>
 __device__ __forceinline__ void bk_chunk(const u32x4* p_hi, const u32x4* p_lo /* the chunk's BK_KC entries */,
                                          const u32x4* qbuf /* LDS: slot 0 of the chunk's buffer + lane */,
-                                         f32x16 (&a0)[4], f32x16 (&a1)[4], u32x4 (&wcur)[16], const BkCopy& cp) {
+                                         f32x16 (&a0)[4], f32x16 (&a1)[4], u32x4 (&wcur)[16], const BkCopy& cp,
+                                         const float* rho /* H: the chunk's BK_KC Horner factors (uniform) */, float coeff_last) {
   u32x4 qr[2][2][QP];          // [parity][block of the pair][high, low]
   auto fetch = [&](int idx) {
     const int q = idx / BK_KC, kk = idx % BK_KC;
@@ -757,21 +764,34 @@ __device__ __forceinline__ void bk_chunk(const u32x4* p_hi, const u32x4* p_lo /*
 #pragma unroll
     for (int v = kk * kRowsPer; v < (kk + 1) * kRowsPer; ++v) {
       if constexpr (FIRST && q + 1 < 4) {
-        a0[q + 1][v] = bf16_lo(wcur[v][q + 1]);
-        a1[q + 1][v] = bf16_hi(wcur[v][q + 1]);
+        a0[q + 1][v] = H ? 0.0f : bf16_lo(wcur[v][q + 1]);
+        a1[q + 1][v] = H ? 0.0f : bf16_hi(wcur[v][q + 1]);
       }
       if constexpr (LAST && q > 0) {
-        uint32_t w = pack_bf16(a0[q - 1][v], a1[q - 1][v]);   // the one rounding
+        uint32_t w = H ? pack_bf16(fmaf(coeff_last, a0[q - 1][v], bf16_lo(wcur[v][q - 1])),
+                                   fmaf(coeff_last, a1[q - 1][v], bf16_hi(wcur[v][q - 1])))
+                       : pack_bf16(a0[q - 1][v], a1[q - 1][v]);   // the one rounding
         asm volatile("" : "+v"(w));
         wcur[v][q - 1] = w;
+      }
+    }
+    if constexpr (H) {
+      if (rho[kk] != 1.0f) {          // a new term starts with this k-step (uniform)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          a0[q][v] *= rho[kk];
+          a1[q][v] *= rho[kk];
+        }
       }
     }
     const bf16x8 ph = __builtin_bit_cast(bf16x8, p_hi[kk]);
     const bf16x8 pl = __builtin_bit_cast(bf16x8, p_lo[kk]);
     const bf16x8 h0 = __builtin_bit_cast(bf16x8, qr[idx & 1][0][0]);
     const bf16x8 h1 = __builtin_bit_cast(bf16x8, qr[idx & 1][1][0]);
-    a0[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl, h0, a0[q], 0, 0, 0);
-    a1[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl, h1, a1[q], 0, 0, 0);
+    if constexpr (!H) {
+      a0[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl, h0, a0[q], 0, 0, 0);
+      a1[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl, h1, a1[q], 0, 0, 0);
+    }
     if constexpr (QP == 2) {
       const bf16x8 l0 = __builtin_bit_cast(bf16x8, qr[idx & 1][0][QP - 1]);
       const bf16x8 l1 = __builtin_bit_cast(bf16x8, qr[idx & 1][1][QP - 1]);
@@ -780,11 +800,13 @@ __device__ __forceinline__ void bk_chunk(const u32x4* p_hi, const u32x4* p_lo /*
     }
     a0[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, h0, a0[q], 0, 0, 0);
     a1[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, h1, a1[q], 0, 0, 0);
-    __builtin_amdgcn_sched_group_barrier(0x100, 2 * QP, 0);     // the next group's LDS reads first
+    if constexpr (!H) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 2 * QP, 0);     // the next group's LDS reads first
 #pragma unroll
-    for (int i = 0; i < 2 + 2 * QP; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        // one matrix instruction
-      __builtin_amdgcn_sched_group_barrier(0x002, (FIRST || LAST) ? 2 : 0, 0);   // a few vector instructions
+      for (int i = 0; i < 2 + 2 * QP; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        // one matrix instruction
+        __builtin_amdgcn_sched_group_barrier(0x002, (FIRST || LAST) ? 2 : 0, 0);   // a few vector instructions
+      }
     }
     __builtin_amdgcn_sched_barrier(0);
   };
@@ -812,6 +834,8 @@ template <int NCH>
 struct BkWave {             // per-wave state of the chunked kernel that outlives a step
   u32x4 p_hi[BK_KC * NCH], p_lo[BK_KC * NCH];
   int32_t eg[2][BK_KC * NCH];       // expert * (r/8) + rank group of lane half h, k-step ks (uniform: scalar registers)
+  float rho[BK_KC * NCH];           // exact-factor mode: Horner factor applied before k-step ks (1 = none), uniform
+  float coeff_last;                 // exact-factor mode: coefficient of the last term, applied with W at the end
   int32_t eg_bytes;                 // bytes of one (expert, rank group) slab of the linear's packed A: column blocks * 4 KB * Q parts (uniform)
   const uint16_t* Apk;
   const uint16_t* W;
@@ -835,7 +859,7 @@ __device__ __forceinline__ BkCopy bk_copy_desc(const BkWave<NCH>& w, int cs, int
 
 // One 32 x 256 step of a wave.  wcur holds the tile to update (loaded one step ago); wprev holds the finished
 // tile of the previous step: it is stored, then reloaded with the tile of the next step.
-template <int NCH, int QP>
+template <int NCH, int QP, bool H>
 __device__ __forceinline__ void bk_step(const BkWave<NCH>& w, int cs, bool more, int lane, int& buf, uint32_t prev_off,
                                         uint32_t next_off, u32x4 (&wcur)[16], u32x4 (&wprev)[16]) {
   const __amdgpu_buffer_rsrc_t res = w_resource(w.W, w.wbytes);
@@ -854,10 +878,10 @@ __device__ __forceinline__ void bk_step(const BkWave<NCH>& w, int cs, bool more,
       wprev[v] = __builtin_amdgcn_raw_buffer_load_b128(res_src, next_off + uint32_t(8 * (v >> 2) + (v & 3)) * w.stride, 0, /*nt*/ 2);
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      a0[0][v] = bf16_lo(wcur[v][0]);
-      a1[0][v] = bf16_hi(wcur[v][0]);
+      a0[0][v] = H ? 0.0f : bf16_lo(wcur[v][0]);
+      a1[0][v] = H ? 0.0f : bf16_hi(wcur[v][0]);
     }
-    bk_chunk<true, false, false, QP>(w.p_hi, w.p_lo, wg_lds + buf * (kBkBufBytes<QP> / 16) + lane, a0, a1, wcur, cp);
+    bk_chunk<true, false, false, QP, H>(w.p_hi, w.p_lo, wg_lds + buf * (kBkBufBytes<QP> / 16) + lane, a0, a1, wcur, cp, w.rho, w.coeff_last);
     bk_drain_and_barrier<32>();
     buf ^= 1;
   }
@@ -866,21 +890,27 @@ __device__ __forceinline__ void bk_step(const BkWave<NCH>& w, int cs, bool more,
     // the following chunk's Q (after the last chunk: chunk 0 of the next step; after the last step a harmless re-read)
     const BkCopy cp = bk_copy_desc<NCH, QP>(w, (ch + 1 < NCH || !more) ? cs : cs + MT_STEP, (ch + 1) % NCH, buf ^ 1);
     if (ch + 1 < NCH) {
-      bk_chunk<false, false, true, QP>(w.p_hi + ch * BK_KC, w.p_lo + ch * BK_KC, wg_lds + buf * (kBkBufBytes<QP> / 16) + lane, a0, a1, wcur, cp);
+      bk_chunk<false, false, true, QP, H>(w.p_hi + ch * BK_KC, w.p_lo + ch * BK_KC, wg_lds + buf * (kBkBufBytes<QP> / 16) + lane, a0, a1, wcur, cp,
+                                          w.rho + ch * BK_KC, w.coeff_last);
     } else {
-      bk_chunk<false, true, true, QP>(w.p_hi + ch * BK_KC, w.p_lo + ch * BK_KC, wg_lds + buf * (kBkBufBytes<QP> / 16) + lane, a0, a1, wcur, cp);
+      bk_chunk<false, true, true, QP, H>(w.p_hi + ch * BK_KC, w.p_lo + ch * BK_KC, wg_lds + buf * (kBkBufBytes<QP> / 16) + lane, a0, a1, wcur, cp,
+                                         w.rho + ch * BK_KC, w.coeff_last);
 #pragma unroll
-      for (int v = 0; v < 16; ++v) wcur[v][3] = pack_bf16(a0[3][v], a1[3][v]);
+      for (int v = 0; v < 16; ++v)
+        wcur[v][3] = H ? pack_bf16(fmaf(w.coeff_last, a0[3][v], bf16_lo(wcur[v][3])), fmaf(w.coeff_last, a1[3][v], bf16_hi(wcur[v][3])))
+                       : pack_bf16(a0[3][v], a1[3][v]);
     }
     bk_drain_and_barrier<0>();
     buf ^= 1;
   }
 }
 
-template <int NCH, int QP>
+template <int NCH, int QP, bool H>
 __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t, const Terms* t_dev, int r) {
   constexpr int NKS = BK_KC * NCH;
   static_assert(NCH >= 2 && 2 * NKS <= BK_MAX_GROUPS, "chunks per step");
+  static_assert(!H || QP == 1, "the one-pass mode needs exact (bf16-stored) factors");
+  __shared__ float s_rho[BK_KC * 4];
   __shared__ int32_t s_te[kMaxTerms];
   __shared__ float s_tc[kMaxTerms];
   __shared__ int32_t s_e[BK_MAX_GROUPS], s_g[BK_MAX_GROUPS], s_eg[BK_MAX_GROUPS];
@@ -894,6 +924,22 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
   if (n_terms == 0) return;             // nothing to merge or unmerge (device-built lists only): W stays untouched
   const int n_groups = n_terms * gpr;
   __syncthreads();
+  if constexpr (H) {
+    // terms by rising |coeff| (the sum does not depend on their order), then the Horner factor of every k-step
+    if (threadIdx.x == 0) {
+      for (int a = 1; a < n_terms; ++a)
+        for (int b = a; b > 0 && fabsf(s_tc[b]) < fabsf(s_tc[b - 1]); --b) {
+          const float tc = s_tc[b]; s_tc[b] = s_tc[b - 1]; s_tc[b - 1] = tc;
+          const int32_t te = s_te[b]; s_te[b] = s_te[b - 1]; s_te[b - 1] = te;
+        }
+      const int kpt = r >> 4;                  // k-steps per term
+      for (int ks = 0; ks < NKS; ++ks) {
+        const int c = ks / kpt;
+        s_rho[ks] = (ks > 0 && ks % kpt == 0 && c < n_terms) ? s_tc[c - 1] / s_tc[c] : 1.0f;
+      }
+    }
+    __syncthreads();
+  }
   if (threadIdx.x < BK_MAX_GROUPS) {           // group G of the fused rank: (expert, 8-rank group, coefficient); padding gets 0
     const int G = threadIdx.x;
     const bool valid = G < n_groups;
@@ -915,7 +961,9 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
   for (int ks = 0; ks < NKS; ++ks) {
     w.eg[0][ks] = uniform(s_eg[2 * ks]);
     w.eg[1][ks] = uniform(s_eg[2 * ks + 1]);
+    w.rho[ks] = H ? __builtin_bit_cast(float, uniform(__builtin_bit_cast(int, s_rho[ks]))) : 1.0f;
   }
+  w.coeff_last = H ? __builtin_bit_cast(float, uniform(__builtin_bit_cast(int, s_tc[n_terms - 1]))) : 1.0f;
 
   const int grid = gridDim.x;
   const int first_item = p.xcd_remap ? xcd_contiguous_block(blockIdx.x, grid) : int(blockIdx.x);
@@ -960,16 +1008,23 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
 #pragma unroll
       for (int ks = 0; ks < NKS; ++ks) {
         const int G = 2 * ks + h;
-        float b[8];
-        if (adapter) load8<2>(p.Z, (long long)prow * p.z_stride + 8 * s_eg[G], b);
-        else load8<QP>(B, ((long long)s_e[G] * out + prow) * r + 8 * s_g[G], b);
-        const float c = prow_ok ? s_c[G] : 0.0f;
+        if constexpr (H) {       // B as stored: an exact operand; rows past the end and padding groups contribute zeros
+          const u32x4 raw = *(const LSW_GLOBAL u32x4*)(reinterpret_cast<const uint16_t*>(B) + ((long long)s_e[G] * out + prow) * r + 8 * s_g[G]);
+          const bool on = prow_ok && s_c[G] != 0.0f;
+          w.p_hi[ks] = on ? raw : u32x4{0u, 0u, 0u, 0u};
+          w.p_lo[ks] = u32x4{0u, 0u, 0u, 0u};
+        } else {
+          float b[8];
+          if (adapter) load8<2>(p.Z, (long long)prow * p.z_stride + 8 * s_eg[G], b);
+          else load8<QP>(B, ((long long)s_e[G] * out + prow) * r + 8 * s_g[G], b);
+          const float c = prow_ok ? s_c[G] : 0.0f;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          uint32_t hi, lo;
-          split2(c * b[2 * q], c * b[2 * q + 1], &hi, &lo);
-          w.p_hi[ks][q] = hi;
-          w.p_lo[ks][q] = lo;
+          for (int q = 0; q < 4; ++q) {
+            uint32_t hi, lo;
+            split2(c * b[2 * q], c * b[2 * q + 1], &hi, &lo);
+            w.p_hi[ks][q] = hi;
+            w.p_lo[ks][q] = lo;
+          }
         }
       }
     }
@@ -999,7 +1054,7 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
       bool more = uniform(int(cs + MT_STEP < col_end)) != 0;
       {
         const uint32_t nxt = more ? lane_offset(cs + MT_STEP) : kOutOfRange;
-        bk_step<NCH, QP>(w, cs, more, lane, buf, off_b, nxt, wa, wb);     // stores wb (previous tile), reloads it, updates wa
+        bk_step<NCH, QP, H>(w, cs, more, lane, buf, off_b, nxt, wa, wb);     // stores wb (previous tile), reloads it, updates wa
         off_b = nxt;
       }
       last_in_a = true;
@@ -1008,7 +1063,7 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
       more = uniform(int(cs + MT_STEP < col_end)) != 0;
       {
         const uint32_t nxt = more ? lane_offset(cs + MT_STEP) : kOutOfRange;
-        bk_step<NCH, QP>(w, cs, more, lane, buf, off_a, nxt, wb, wa);
+        bk_step<NCH, QP, H>(w, cs, more, lane, buf, off_a, nxt, wb, wa);
         off_a = nxt;
       }
       last_in_a = false;
@@ -1031,33 +1086,36 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
   }
 }
 
-template <int NCH, int QP>
+template <int NCH, int QP, bool H>
 static hipError_t launch_bigk(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int grid, hipStream_t s) {
   const size_t lds = size_t(2) * kBkBufBytes<QP>;     // 2 x 64 KB (2 x 32 KB for bf16 factors)
   static bool configured = false;
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_switch_mfma_bigk<NCH, QP>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_switch_mfma_bigk<NCH, QP, H>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
     if (e != hipSuccess) return e;
     configured = true;
   }
-  hipLaunchKernelGGL((k_switch_mfma_bigk<NCH, QP>), dim3(grid), dim3(256), lds, s, p, t, t_dev, r);
+  hipLaunchKernelGGL((k_switch_mfma_bigk<NCH, QP, H>), dim3(grid), dim3(256), lds, s, p, t, t_dev, r);
   return hipGetLastError();
 }
 
-template <int QP>
+template <int QP, bool H>
 static hipError_t launch_bigk_qp(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int grid, hipStream_t s) {
   const int n_groups = t.n * (r / 8);
   switch ((n_groups + 2 * BK_KC - 1) / (2 * BK_KC)) {
-    case 2: return launch_bigk<2, QP>(p, t, t_dev, r, grid, s);
-    case 3: return launch_bigk<3, QP>(p, t, t_dev, r, grid, s);
-    case 4: return launch_bigk<4, QP>(p, t, t_dev, r, grid, s);
+    case 2: return launch_bigk<2, QP, H>(p, t, t_dev, r, grid, s);
+    case 3: return launch_bigk<3, QP, H>(p, t, t_dev, r, grid, s);
+    case 4: return launch_bigk<4, QP, H>(p, t, t_dev, r, grid, s);
     default: return hipErrorInvalidValue;
   }
 }
 
 hipError_t launch_switch_mfma_bigk(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int qp, int grid, hipStream_t s) {
-  return qp == 2 ? launch_bigk_qp<2>(p, t, t_dev, r, grid, s) : launch_bigk_qp<1>(p, t, t_dev, r, grid, s);
+  if (qp == 2) return launch_bigk_qp<2, false>(p, t, t_dev, r, grid, s);
+  // exact factors: one pass when every k-step of 16 ranks belongs to one term (not in adapter mode: Z is fp32)
+  if (r % 16 == 0 && p.Z == nullptr && p.exact_one_pass) return launch_bigk_qp<1, true>(p, t, t_dev, r, grid, s);
+  return launch_bigk_qp<1, false>(p, t, t_dev, r, grid, s);
 }
 
 // ---------------------------------------------------------------------------

@@ -34,14 +34,21 @@ def _sequence(rng, E, r, steps=6):
     return seq
 
 
-@pytest.mark.parametrize("kernel", [L.KERNEL_VALU, L.KERNEL_MFMA])
+@pytest.mark.parametrize("kernel", [L.KERNEL_VALU, L.KERNEL_MFMA, "mfma-two-pass"])
 @pytest.mark.parametrize("shape", SHAPES)
 def test_bf16_factors_ragged_shapes(shape, kernel):
     out, inn, E, r = shape
+    two_pass = kernel == "mfma-two-pass"      # ranks that are multiples of 16 run one pass above 64 fused ranks by default
+    if two_pass:
+        if r < 32 or r % 16:
+            pytest.skip("the one-pass mode does not apply to this rank")
+        kernel = L.KERNEL_MFMA
     rng = np.random.default_rng(out * 977 + inn + r)
     host = bf16_factor_stack([I.host_linear(rng, out, inn, E, r, 0.02, 1 / 16, 0.01)])
     (W, A, B), = host
     ds = DeviceStack.from_host(host, [(0, 0, out, inn)], E, r, scale=0.5, bf16_factors=True)
+    if two_pass:
+        L.lsw_set_option(ds.ctx, L.LSW_OPT_ONE_PASS, 0)
     prev = ds.rows(0)
     reports, used = [], set()
     seq = _sequence(rng, E, r)

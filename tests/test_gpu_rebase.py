@@ -103,3 +103,39 @@ def test_set_base_rejects_what_it_documents():
         L.lsw_rebase(ds.ctx, [9], [1.0])
     assert e.value.status == L.LSW_ERR_ARG
     ds.close()
+
+
+def test_saved_weights_and_state_resume_bit_for_bit():
+    """The merged W means something only together with the set merged into it (Eq. 7 needs it for the next switch):
+    (W, lsw_get_state) saved after some switches and loaded into a fresh context continue exactly like the run that was
+    never interrupted."""
+    wl = I.Workload("mini", 2, 64, 136, 32, 6, 8, 2, 8, 0.02, 1 / 8, 0.01, 4245)
+    shapes = wl.linear_shapes()
+    host = I.host_stack(wl)
+    routes = [O.route(l, wl.top_k) for l in I.router_logits(wl, wl.steps)]
+    a = DeviceStack.from_host(host, shapes, wl.experts, wl.rank)
+    old = NONE
+    for new in routes[:4]:
+        a.switch(old, new)
+        old = new
+    saved_W = [a.rows(p) for p in range(len(shapes))]
+    saved_state = L.lsw_get_state(a.ctx, 0)
+    assert saved_state[0].tolist() == old[0].tolist() and saved_state[1].tolist() == old[1].tolist()
+    for new in routes[4:]:
+        a.switch(old, new)
+        old = new
+    # a new process would do exactly this: upload the saved weights, create a context, continue from the saved state
+    b = DeviceStack.from_host([(W, A, B) for W, (_, A, B) in zip(saved_W, host)], shapes, wl.experts, wl.rank)
+    L.lsw_set_option(b.ctx, L.LSW_OPT_STRICT_STATE, 1)
+    with pytest.raises(L.LswError) as e:            # the fresh context believes nothing is merged
+        b.switch(saved_state, routes[4])
+    assert e.value.status == L.LSW_ERR_STATE
+    L.lsw_set_option(b.ctx, L.LSW_OPT_STRICT_STATE, 0)
+    old_b = saved_state
+    for new in routes[4:]:
+        b.switch(old_b, new)
+        old_b = new
+    for p in range(len(shapes)):
+        assert (a.rows(p) == b.rows(p)).all()
+    a.close()
+    b.close()

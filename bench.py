@@ -324,13 +324,15 @@ def main():
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic}
     mean_terms = sum(terms) / len(terms)
     if max(kernels) == 2 and mean_terms * wl.rank > 64:
-        # fused ranks above 64: three bf16 passes (two, or one, with bf16-stored factors) of 2*K flop per weight take
-        # longer on the matrix cores than the W traffic takes on HBM, so that is the roofline of this launch
+        # fused ranks above 64: three bf16 passes (two, or one, with bf16-stored factors) of 2*K flop per weight; whichever
+        # of the two floors (matrix work at the bf16 peak, algorithmic bytes at the HBM peak) is longer is the roofline
         passes = (1.0 if wl.rank % 16 == 0 else 2.0) if bf16_factors else 3.0    # exact bf16 factors of such a rank: one pass
         flops = [passes * 2.0 * n * wl.rank * wl.w_elements() for n, k in zip(terms, kernels) if k != 0]
-        tf = (sum(flops) / len(flops)) / (avg_ms * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic}
+        mean_flops, mean_bytes = sum(flops) / len(flops), sum(launch_bytes) / len(launch_bytes)
+        if mean_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12) > mean_bytes / (HBM_PEAK_GBPS * 1e9):
+            tf = mean_flops / (avg_ms * 1e-3) / 1e12
+            roofline = {"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                        "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic}
 
     out = {
         "metric": "switch latency us/token (all layers) + achieved HBM GB/s, 7B-shaped adapters",

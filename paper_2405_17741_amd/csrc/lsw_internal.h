@@ -47,7 +47,7 @@ struct Item {
   int32_t col0;
 };
 
-LSW_HD inline int32_t ceil_div(int32_t a, int32_t b) { return (a + b - 1) / b; }
+LSW_HD inline int32_t ceil_div(int32_t a, int32_t b) { return a / b + (a % b != 0); }   // a >= 0, b > 0; no overflow near 2^31
 
 // Largest s with first[s] <= item  (first[] is non-decreasing, first[0] == 0, item < first[n_sel]).
 LSW_HD inline int32_t find_segment(const int32_t* first, int32_t n_sel, int32_t item) {

@@ -118,8 +118,9 @@ def main():
                     help="also run one plain 4 GiB device copy (a known-size reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (the switch needs no collective; see DESIGN.md "
-              "for how it would shard). Re-run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU only: the switch needs no collective (every weight element depends on "
+              "its own row of B, its own column of A and the token's ids and gates), so more GPUs would each run this "
+              "same launch on their share of the layers. Re-run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

@@ -1,7 +1,8 @@
-// Device code of liblsw for gfx950 (MI355X): the fused adapter switch in two
-// flavours (matrix-core and fp32 vector-ALU), the A re-layout kernel and the
-// merged GEMV.  Sec. 3.3-3.4 of LoRA-Switch define what is computed; the tiling,
-// data movement and launch shape are this library's own.
+// Device code of liblsw for gfx950 (MI355X): the fused adapter switch (two matrix-core kernels, for fused ranks up
+// to 64 and up to 256, and an fp32 vector-ALU kernel for any rank), the operand re-layout kernels, the device-side
+// router and term-list builder, the in-place bandwidth probe, the merged-decode GEMVs, and the un-merged adapter path
+// for prompts.  Sec. 3.2-3.4 of LoRA-Switch define what is computed; the tiling, data movement and launch shapes are
+// this library's own.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>

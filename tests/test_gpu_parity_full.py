@@ -3,7 +3,8 @@
 The 7B-shaped stack (32 layers x 7 linears, 6.48e9 weights) is switched 64 times; on steps
 1, 2, 3, 32 and 64 sampled rows of EVERY linear are compared, teacher-forced, with the oracle
 (elements are independent, so sampling rows is sound), and two whole linears are compared in
-full at step 1.  The other workloads run with their true shapes on a reduced layer count."""
+full at step 1.  The 13B-, 70B- and rank-64 stacks run the same way at their full size for a few steps
+(fewer sampled rows), and on a reduced layer count for more steps."""
 import os
 
 import numpy as np
@@ -93,3 +94,31 @@ def test_7b_rank64_one_layer():
     reports, kernels = _run_sampled(wl, {1, 2, 3}, n_random_rows=13)
     assert kernels == {L.KERNEL_MFMA}          # fused ranks 64..256: the chunked matrix-core kernel
     assert all(r["exact_frac"] > 0.999 for r in reports)
+
+
+def test_13b_full_size_sampled_rows_every_linear():
+    """All 40 layers of the 13B-shaped stack (12.7e9 weights, every row pitch off the fast ones, forced expert reuse)."""
+    wl = I.Workload(**{**I.WORKLOADS["13b"].__dict__, "steps": 6})
+    reports, kernels = _run_sampled(wl, {1, 2, 6}, n_random_rows=13)
+    assert kernels == {L.KERNEL_MFMA}
+    assert len(reports) == 3 and all(r["exact_frac"] > 0.999 for r in reports)
+
+
+def test_7b_rank64_full_size_sampled_rows_every_linear():
+    """All 32 layers with rank-64 experts: the chunked matrix-core kernel over the whole stack."""
+    wl = I.Workload(**{**I.WORKLOADS["7b_r64"].__dict__, "steps": 3})
+    reports, kernels = _run_sampled(wl, {1, 2, 3}, n_random_rows=13)
+    assert kernels == {L.KERNEL_MFMA}
+    assert len(reports) == 3 and all(r["exact_frac"] > 0.998 for r in reports)
+
+
+def test_70b_full_size_sampled_rows_every_linear():
+    """All 80 layers of the 70B-shaped stack: 68.5e9 weights (137 GB) in one launch, element offsets far beyond 32 bits
+    across the stack, 4.2 million work items."""
+    free, _ = torch.cuda.mem_get_info()
+    if free < 160e9:
+        pytest.skip("needs 160 GB of free device memory")
+    wl = I.Workload(**{**I.WORKLOADS["70b"].__dict__, "steps": 2})
+    reports, kernels = _run_sampled(wl, {1, 2}, n_random_rows=5)
+    assert kernels == {L.KERNEL_MFMA}
+    assert len(reports) == 2 and all(r["exact_frac"] > 0.999 for r in reports)

@@ -255,6 +255,37 @@ def test_merged_gemv_against_oracle():
         ds.close()
 
 
+def test_merged_decode_after_many_switches_stays_within_the_predicted_drift():
+    """Eq. 2 == Eq. 3 after T free-running switches: decode through the merged weights against W0 x + sum_c g_c B_c (A_c x)
+    in fp64 from the BASE weights.  They differ by the rounding drift of the merged weights alone: per weight a random
+    walk of about 0.29 * sqrt(T) ulp, so |err_i| is about 0.29 * sqrt(T) * 2^-8 * sqrt(sum_j W_ij^2 x_j^2); gated at 6x."""
+    wl = I.Workload("mini", 1, 256, 520, 64, 8, 8, 2, 24, 0.02, 1 / 16, 0.01, 4246)
+    host = I.host_stack(wl)
+    ds = DeviceStack.from_host(host, wl.linear_shapes(), wl.experts, wl.rank)
+    routes = _route_stream(wl, wl.steps)
+    old = (np.zeros(0, np.int32), np.zeros(0, np.float32))
+    for new in routes:
+        ds.switch(old, new)
+        old = new
+    rng = np.random.default_rng(12)
+    worst = 0.0
+    for p, (W0, A, B) in enumerate(host):
+        out, inn = W0.shape
+        x = I.f32_to_bf16_bits(rng.normal(0, 1, inn).astype(np.float32))
+        y = torch.empty(out, dtype=torch.float32, device="cuda")
+        L.lsw_merged_gemv(ds.ctx, p, bits_to_device(x).data_ptr(), y.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        xv, w0 = O.bf16_bits_to_f64(x), O.bf16_bits_to_f64(W0)
+        want = w0 @ xv + O.gated_lowrank_sum(A, B, old[0], old[1]) @ xv
+        wm = O.bf16_bits_to_f64(ds.rows(p))
+        predicted = 0.29 * np.sqrt(wl.steps) * 2.0 ** -8 * np.sqrt((wm ** 2) @ (xv ** 2))
+        err = np.abs(y.cpu().numpy().astype(np.float64) - want)
+        assert (err <= 6 * predicted + 1e-5 * (np.abs(wm) @ np.abs(xv))).all(), (p, float((err / predicted).max()))
+        worst = max(worst, float(np.median(err / predicted)))
+        assert np.median(err / predicted) > 0.2, "the drift should be visible: it is what lsw_rebase removes"
+    print(f"\n[merged decode after {wl.steps} switches] median error / predicted drift up to {worst:.2f}")
+    ds.close()
+
+
 def test_merged_gemv_all_linears_in_one_launch():
     """Every linear of a small ragged stack decoded by ONE launch; each output row against the fp64 oracle."""
     rng = np.random.default_rng(11)

@@ -311,6 +311,11 @@ constexpr int MT_STEP = kApkBlockCols;
 constexpr int WG_WAVES = 4;
 constexpr int WG_ROWS = kMfmaTileRows;
 constexpr uint32_t kOutOfRange = 0x80000000u;   // byte offset beyond any W (out*in*2 < 2^31 is checked at create)
+// Cache-policy bits of the W accesses (buffer instruction aux operand on gfx950: 1 = sc0, 2 = nt, 16 = sc1): non-temporal
+// both ways.  Stores that are also written through at device scope (nt + sc1) make a bare in-place pass 1-3 % faster,
+// but the switch kernels 2-3 % slower (measured on the 7B and 13B stacks), so they are not used.
+constexpr int kWLoadAux = 2;
+constexpr int kWStoreAux = 2;
 extern __shared__ u32x4 wg_lds[];               // [2 buffers][NKS][8 blocks][high, low][64 lanes]
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t w_resource(const uint16_t* W, int wbytes) {
@@ -401,7 +406,7 @@ __device__ __forceinline__ void mfma_load_w(const MfmaItem<NKS>& it, uint32_t la
 #pragma unroll
   for (int v = 0; v < 16; ++v)
     wbuf[v] = __builtin_amdgcn_raw_buffer_load_b128(
-        res, lane_off + uint32_t(8 * (v >> 2) + (v & 3)) * it.stride_byte, 0, /*nt*/ 2);
+        res, lane_off + uint32_t(8 * (v >> 2) + (v & 3)) * it.stride_byte, 0, kWLoadAux);
 }
 
 template <int NKS, int QP>
@@ -541,12 +546,12 @@ __device__ __forceinline__ bool wg_step(const LaunchPlan& p, int grid, int n, in
 #pragma unroll
   for (int v = 0; v < 16; ++v)
     __builtin_amdgcn_raw_buffer_store_b128(
-        wprev[v], prev_res, prev_off + uint32_t(8 * (v >> 2) + (v & 3)) * prev_stride, 0, /*nt*/ 2);
+        wprev[v], prev_res, prev_off + uint32_t(8 * (v >> 2) + (v & 3)) * prev_stride, 0, kWStoreAux);
   asm volatile("" : "+v"(nlane_off) : "v"(prev_off));      // keep the loads after the stores that free their registers
 #pragma unroll
   for (int v = 0; v < 16; ++v)
     wprev[v] = __builtin_amdgcn_raw_buffer_load_b128(
-        nres, nlane_off + uint32_t(8 * (v >> 2) + (v & 3)) * nstride, 0, /*nt*/ 2);
+        nres, nlane_off + uint32_t(8 * (v >> 2) + (v & 3)) * nstride, 0, kWLoadAux);
 
   wg_compute<NKS, QP>(cur.p_hi, cur.p_lo, wg_lds + buf * kBufSlots + lane, wcur);
 
@@ -624,12 +629,12 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma(LaunchPlan p, Ter
 #pragma unroll
     for (int v = 0; v < 16; ++v)
       __builtin_amdgcn_raw_buffer_store_b128(
-          wa[v], prev_res, prev_off + uint32_t(8 * (v >> 2) + (v & 3)) * prev_stride, 0, /*nt*/ 2);
+          wa[v], prev_res, prev_off + uint32_t(8 * (v >> 2) + (v & 3)) * prev_stride, 0, kWStoreAux);
   } else {
 #pragma unroll
     for (int v = 0; v < 16; ++v)
       __builtin_amdgcn_raw_buffer_store_b128(
-          wb[v], prev_res, prev_off + uint32_t(8 * (v >> 2) + (v & 3)) * prev_stride, 0, /*nt*/ 2);
+          wb[v], prev_res, prev_off + uint32_t(8 * (v >> 2) + (v & 3)) * prev_stride, 0, kWStoreAux);
   }
 }
 
@@ -872,11 +877,11 @@ __device__ __forceinline__ void bk_step(const BkWave<NCH>& w, int cs, bool more,
     __builtin_amdgcn_sched_barrier(0);                    // keep the W requests younger than the Q copy
 #pragma unroll
     for (int v = 0; v < 16; ++v)
-      __builtin_amdgcn_raw_buffer_store_b128(wprev[v], res, prev_off + uint32_t(8 * (v >> 2) + (v & 3)) * w.stride, 0, /*nt*/ 2);
+      __builtin_amdgcn_raw_buffer_store_b128(wprev[v], res, prev_off + uint32_t(8 * (v >> 2) + (v & 3)) * w.stride, 0, kWStoreAux);
     asm volatile("" : "+v"(next_off) : "v"(prev_off));      // keep the loads after the stores that free their registers
 #pragma unroll
     for (int v = 0; v < 16; ++v)
-      wprev[v] = __builtin_amdgcn_raw_buffer_load_b128(res_src, next_off + uint32_t(8 * (v >> 2) + (v & 3)) * w.stride, 0, /*nt*/ 2);
+      wprev[v] = __builtin_amdgcn_raw_buffer_load_b128(res_src, next_off + uint32_t(8 * (v >> 2) + (v & 3)) * w.stride, 0, kWLoadAux);
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       a0[0][v] = H ? 0.0f : bf16_lo(wcur[v][0]);
@@ -1043,7 +1048,7 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
       bk_copy_range<0, 8 * QP, QP>(cp);
 #pragma unroll
       for (int v = 0; v < 16; ++v)
-        wa[v] = __builtin_amdgcn_raw_buffer_load_b128(res, off_a + uint32_t(8 * (v >> 2) + (v & 3)) * w.stride, 0, /*nt*/ 2);
+        wa[v] = __builtin_amdgcn_raw_buffer_load_b128(res, off_a + uint32_t(8 * (v >> 2) + (v & 3)) * w.stride, 0, kWLoadAux);
 #pragma unroll
       for (int v = 0; v < 16; ++v) wb[v] = u32x4{0u, 0u, 0u, 0u};
       bk_drain_and_barrier<0>();
@@ -1077,11 +1082,11 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
       if (last_in_a) {
 #pragma unroll
         for (int v = 0; v < 16; ++v)
-          __builtin_amdgcn_raw_buffer_store_b128(wa[v], res, cs_off + uint32_t(8 * (v >> 2) + (v & 3)) * w.stride, 0, /*nt*/ 2);
+          __builtin_amdgcn_raw_buffer_store_b128(wa[v], res, cs_off + uint32_t(8 * (v >> 2) + (v & 3)) * w.stride, 0, kWStoreAux);
       } else {
 #pragma unroll
         for (int v = 0; v < 16; ++v)
-          __builtin_amdgcn_raw_buffer_store_b128(wb[v], res, cs_off + uint32_t(8 * (v >> 2) + (v & 3)) * w.stride, 0, /*nt*/ 2);
+          __builtin_amdgcn_raw_buffer_store_b128(wb[v], res, cs_off + uint32_t(8 * (v >> 2) + (v & 3)) * w.stride, 0, kWStoreAux);
       }
     }
   }
@@ -1503,7 +1508,7 @@ __global__ __launch_bounds__(64) void k_probe_inplace(LaunchPlan p) {
 #pragma unroll
             for (int q = 0; q < 4; ++q)
               o[q] = pack_bf16(bf16_lo(buf[half][v][q]) + 0.0f, bf16_hi(buf[half][v][q]) + 0.0f);
-            __builtin_amdgcn_raw_buffer_store_b128(o, res, off[half] + uint32_t(8 * (v >> 2) + (v & 3)) * stride, 0, 2);
+            __builtin_amdgcn_raw_buffer_store_b128(o, res, off[half] + uint32_t(8 * (v >> 2) + (v & 3)) * stride, 0, kWStoreAux);
           }
         }
       }

@@ -136,3 +136,66 @@ def test_adapter_path_then_merged_decode_agree():
         + 1.5 * C.bf16_ulp_at(np.abs(y_merged)) + 1e-5 * (np.abs(O.bf16_bits_to_f64(W0)) @ xv)
     assert (np.abs(y_merged - y_adapter) <= slack).all()
     ds.close()
+
+
+def test_prompt_step_recorded_in_a_graph_and_replayed():
+    """Batch router + adapter path of one linear recorded in a HIP graph (they allocate nothing and clear nothing with a
+    memset) and replayed with fresh prompts, eager work and synchronisations in between; every replay against the eager
+    result bit for bit and against the oracle."""
+    rng = np.random.default_rng(79)
+    T, out, inn, E, r, k = 96, 264, 520, 8, 8, 2
+    host = [I.host_linear(rng, out, inn, E, r, 0.02, 1 / 16, 0.05)]
+    (_, A, B), = host
+    ds = DeviceStack.from_host(host, [(0, 0, out, inn)], E, r)
+    L.lsw_enable_adapter_path(ds.ctx)
+    stream = torch.cuda.current_stream().cuda_stream
+    logits = torch.zeros(T, E, device="cuda")
+    X = torch.zeros(T, inn, dtype=torch.bfloat16, device="cuda")
+    Y0 = torch.zeros(T, out, dtype=torch.bfloat16, device="cuda")
+    ws_bytes = L.lsw_adapter_workspace_bytes(ds.ctx, 0, T)
+
+    class Path:
+        def __init__(self):
+            self.ids = torch.zeros(T, k, dtype=torch.int32, device="cuda")
+            self.gates = torch.zeros(T, k, dtype=torch.float32, device="cuda")
+            self.Y = torch.zeros(T, out, dtype=torch.bfloat16, device="cuda")
+            self.ws = torch.empty(ws_bytes // 4, dtype=torch.float32, device="cuda")
+
+        def run(self, s):
+            self.Y.copy_(Y0)            # a copy kernel, not a memset
+            L.lsw_route_batch_dev(ds.ctx, logits.data_ptr(), T, k, self.ids.data_ptr(), self.gates.data_ptr(), s)
+            L.lsw_adapter_forward(ds.ctx, 0, X.data_ptr(), T, self.ids.data_ptr(), self.gates.data_ptr(), k, self.Y.data_ptr(),
+                                  self.ws.data_ptr(), s)
+
+    def fresh():
+        logits.copy_(torch.randn(T, E, device="cuda"))
+        X.copy_(torch.randn(T, inn, device="cuda").to(torch.bfloat16))
+        Y0.copy_((0.5 * torch.randn(T, out, device="cuda")).to(torch.bfloat16))
+
+    eager, graphed = Path(), Path()
+    fresh()
+    eager.run(stream)
+    graphed.run(stream)                  # first use outside the recording: kernel attributes are set then
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        graphed.run(torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    for _ in range(4):
+        fresh()                          # eager work between the replays
+        eager.run(stream)
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(eager.ids, graphed.ids) and torch.equal(eager.gates, graphed.gates)
+        assert torch.equal(eager.Y.view(torch.int16), graphed.Y.view(torch.int16))
+        ids, gates = graphed.ids.cpu().numpy(), graphed.gates.cpu().numpy()
+        lg = logits.cpu().numpy()
+        for t in range(0, T, 7):
+            assert ids[t].tolist() == O.route(lg[t], k)[0].tolist()
+        Xb, Yb = device_to_bits(X), device_to_bits(Y0)
+        rep = C.switch_parity(device_to_bits(graphed.Y), O.adapter_forward(Yb, Xb, A, B, ids, gates), Yb,
+                              O.adapter_magnitude(Xb, A, B, ids, gates))
+        assert rep["fail"] == 0
+    assert L.lsw_dev_status(ds.ctx) == 0
+    ds.close()

@@ -283,9 +283,12 @@ enum {
   LSW_OPT_TILE_COLS = 4,     /* matrix-core kernel: columns per work item, a multiple of 256 (tuning knob) */
   LSW_OPT_XCD_REMAP = 5,     /* 1 (default): each XCD takes a contiguous share of every round of items */
   LSW_OPT_GEMV_GRID = 6,     /* workgroups of the merged-decode launches; 0 = automatic (2 per CU) */
-  LSW_OPT_ONE_PASS = 7       /* 1 (default): bf16-stored factors of a rank that is a multiple of 16 run ONE matrix-core pass
+  LSW_OPT_ONE_PASS = 7,      /* 1 (default): bf16-stored factors of a rank that is a multiple of 16 run ONE matrix-core pass
                                 when the fused rank exceeds 64 (bare B A products, gates applied in fp32 between the terms);
                                 0: two passes with the gate folded into B (what every other rank gets) */
+  LSW_OPT_RESIDENT_Q = 8     /* matrix-core kernel for fused ranks up to 64: 1 (default) = where the A operand of one work
+                                item fits LDS it is kept there across the items of a column panel and each XCD walks its
+                                own eighth of the items; 0 = always the kernel that streams it per step */
 };
 enum {
   LSW_Q_N_LINEARS = 1, LSW_Q_N_LAYERS = 2,

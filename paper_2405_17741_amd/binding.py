@@ -13,7 +13,7 @@ import numpy as np
 
 LSW_OK, LSW_ERR_ARG, LSW_ERR_SHAPE, LSW_ERR_STATE, LSW_ERR_NOMEM, LSW_ERR_DEVICE = range(6)
 LSW_MAX_K = 8
-LSW_OPT_KERNEL, LSW_OPT_STRICT_STATE, LSW_OPT_GRID, LSW_OPT_TILE_COLS, LSW_OPT_XCD_REMAP, LSW_OPT_GEMV_GRID, LSW_OPT_ONE_PASS = 1, 2, 3, 4, 5, 6, 7
+LSW_OPT_KERNEL, LSW_OPT_STRICT_STATE, LSW_OPT_GRID, LSW_OPT_TILE_COLS, LSW_OPT_XCD_REMAP, LSW_OPT_GEMV_GRID, LSW_OPT_ONE_PASS, LSW_OPT_RESIDENT_Q = 1, 2, 3, 4, 5, 6, 7, 8
 (LSW_Q_N_LINEARS, LSW_Q_N_LAYERS, LSW_Q_LAST_KERNEL, LSW_Q_LAST_ITEMS, LSW_Q_LAST_GRID, LSW_Q_PACKED_BYTES,
  LSW_Q_GEMV_X_ELEMS, LSW_Q_GEMV_Y_ELEMS) = range(1, 9)
 KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2

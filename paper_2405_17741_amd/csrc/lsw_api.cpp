@@ -84,7 +84,7 @@ struct lsw_ctx {
   int64_t owned_bytes = 0;
   int64_t x_elems = 0, y_elems = 0;          // sizes of the back-to-back x and y of lsw_merged_gemv_all
   std::map<PlanKey, DevicePlan> plans;
-  int opt_kernel = 0, opt_strict = 0, opt_grid = 0, opt_tile_cols = kMfmaTileCols, opt_tile_cols_bigk = kMfmaBigkTileCols, opt_xcd = 1, opt_gemv_grid = 0, opt_one_pass = 1;
+  int opt_kernel = 0, opt_strict = 0, opt_grid = 0, opt_tile_cols = kMfmaTileCols, opt_tile_cols_bigk = kMfmaBigkTileCols, opt_xcd = 1, opt_gemv_grid = 0, opt_one_pass = 1, opt_resident = 1;
   int last_kernel = 0, last_items = 0, last_grid = 0;
 };
 
@@ -420,6 +420,10 @@ static lsw_status launch_switch(lsw_ctx* c, const std::vector<int32_t>& sel_laye
   if (t.n > 0) {
     DevicePlan* dp = nullptr;
     const int tc = kernel >= 2 ? (bigk ? c->opt_tile_cols_bigk : c->opt_tile_cols) : kValuTileCols;
+    // the Q of one item (8 KB per 256 columns, k-step and Q part) fits LDS: the resident-Q kernel, else the streaming one
+    // (fp32-stored factors only: with bf16-stored ones, half the Q bytes, the streaming kernel measured 1.3 % faster)
+    const bool resident = kernel == 2 && !bigk && c->opt_resident && c->qp == 2 &&
+                          (tc / kApkBlockCols) * ((n_groups + 1) / 2) * 8 * c->qp * 1024 <= kResidentLdsBytes;
     lsw_status st = get_plan(c, kernel, tc, sel_layers, &dp);
     if (st != LSW_OK) return st;
     LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, tc, c->opt_xcd, from_base ? 1 : 0, c->opt_one_pass, nullptr, 0, LinDesc{}};
@@ -427,7 +431,8 @@ static lsw_status launch_switch(lsw_ctx* c, const std::vector<int32_t>& sel_laye
     if (grid <= 0) grid = (kernel == 2) ? c->n_cu : c->n_cu * 2;   // matrix-core: one workgroup per CU
     grid = std::max(8, (grid / 8) * 8);     // a multiple of the 8 XCDs (the kernels' block remap assumes it)
     hipError_t e = (kernel == 2) ? (bigk ? launch_switch_mfma_bigk(lp, t, t_dev, c->r, c->qp, grid, s)
-                                         : launch_switch_mfma(lp, t, t_dev, c->r, c->qp, grid, s))
+                                  : resident ? launch_switch_mfma_res(lp, t, t_dev, c->r, c->qp, grid, s)
+                                             : launch_switch_mfma(lp, t, t_dev, c->r, c->qp, grid, s))
                                  : launch_switch_valu(lp, t, t_dev, c->r, c->qp, grid, s);
     if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "switch launch failed: %s", hipGetErrorString(e));
     c->last_kernel = kernel;
@@ -774,6 +779,9 @@ extern "C" lsw_status lsw_set_option(lsw_ctx* c, int32_t option, int64_t value) 
       return LSW_OK;
     case LSW_OPT_XCD_REMAP:
       c->opt_xcd = value != 0;
+      return LSW_OK;
+    case LSW_OPT_RESIDENT_Q:
+      c->opt_resident = value != 0;
       return LSW_OK;
     case LSW_OPT_ONE_PASS:
       c->opt_one_pass = value != 0;

@@ -66,6 +66,8 @@ LSW_HD inline void decode_item(int32_t local, int32_t in, int32_t tile_rows, int
   *col0 = (local % ncc) * tile_cols;
 }
 
+constexpr int kResidentLdsBytes = 128 * 1024;   // LDS the resident-Q matrix-core kernel may use for one item's Q
+
 // Tile shapes of the two switch kernels (rows x columns of one work item).
 constexpr int kValuTileRows = 64,  kValuTileCols = 128;
 constexpr int kMfmaTileRows = 128, kMfmaTileCols = 1024;   // 4 waves x 32 rows; default item width (LSW_OPT_TILE_COLS overrides)
@@ -97,6 +99,7 @@ struct LaunchPlan {             // device pointers + counts for one launch
 // qp: 2 = fp32-stored factors (split into two bf16 parts on the matrix cores), 1 = bf16-stored factors
 hipError_t launch_switch_valu(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int qp, int grid, hipStream_t s);
 hipError_t launch_switch_mfma(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int qp, int grid, hipStream_t s);
+hipError_t launch_switch_mfma_res(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int qp, int grid, hipStream_t s);
 hipError_t launch_switch_mfma_bigk(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int qp, int grid, hipStream_t s);
 hipError_t launch_route(const float* logits, int n_tokens, int E, int k, int32_t* ids, float* gates, int32_t* err, hipStream_t s);
 hipError_t launch_build_terms(const int32_t* old_ids, const float* old_gates, int k_old, const int32_t* new_ids,

@@ -142,6 +142,33 @@ def test_ragged_shapes_and_term_counts(shape, kernel):
     ds.close()
 
 
+@pytest.mark.parametrize("shape", [(100, 264, 5, 8), (130, 1048, 6, 8), (33, 2056, 3, 8), (260, 4104, 4, 8)])
+def test_streaming_matrix_core_kernel_with_the_resident_one_switched_off(shape):
+    """Fused ranks up to 32 with fp32 factors normally run the resident-A kernel; LSW_OPT_RESIDENT_Q = 0 sends the same
+    launches to the kernel that streams A per step.  Both must meet the bar, and they compute the same sums in the same
+    order: bit-identical results."""
+    out, inn, E, r = shape
+    rng = np.random.default_rng(out * 31 + inn)
+    W, A, B = I.host_linear(rng, out, inn, E, r, 0.02, 1 / 16, 0.01)
+    a = DeviceStack.from_host([(W, A, B)], [(0, 0, out, inn)], E, r, kernel=L.KERNEL_MFMA)
+    b = DeviceStack.from_host([(W, A, B)], [(0, 0, out, inn)], E, r, kernel=L.KERNEL_MFMA)
+    L.lsw_set_option(b.ctx, L.LSW_OPT_RESIDENT_Q, 0)
+    none = (np.zeros(0, np.int32), np.zeros(0, np.float32))
+    seq = [none, (np.array([1, 2], np.int32), np.array([0.7, 0.3], np.float32)),
+           (np.array([2, 0], np.int32), np.array([0.45, 0.55], np.float32)), (np.array([1], np.int32), np.array([1.0], np.float32)), none]
+    prev = a.rows(0)
+    for old, new in zip(seq[:-1], seq[1:]):
+        a.switch(old, new)
+        b.switch(old, new)
+        ga, gb = a.rows(0), b.rows(0)
+        assert (ga == gb).all()
+        rep, _ = check_step(prev, gb, A, B, old, new)
+        assert rep["fail"] == 0
+        prev = gb
+    a.close()
+    b.close()
+
+
 @pytest.mark.parametrize("kernel", KERNELS)
 def test_stack_with_layer_subsets_guard_bands_and_state(kernel):
     wl = I.Workload("mini", 3, 64, 136, 32, 6, 8, 2, 4, 0.02, 1 / 8, 0.01, 4242)

@@ -281,14 +281,16 @@ enum {
   LSW_OPT_STRICT_STATE = 2,  /* 1: lsw_switch rejects an `old` that differs from the tracked state of a layer */
   LSW_OPT_GRID = 3,          /* workgroups per launch; 0 = automatic (one matrix-core workgroup per CU) */
   LSW_OPT_TILE_COLS = 4,     /* matrix-core kernel: columns per work item, a multiple of 256 (tuning knob) */
-  LSW_OPT_XCD_REMAP = 5,     /* 1 (default): each XCD takes a contiguous share of every round of items */
+  LSW_OPT_XCD_REMAP = 5,     /* 1 (default): each XCD takes a contiguous share of every round of items (the resident-A
+                                kernel always gives each XCD its own eighth of the whole item list) */
   LSW_OPT_GEMV_GRID = 6,     /* workgroups of the merged-decode launches; 0 = automatic (2 per CU) */
   LSW_OPT_ONE_PASS = 7,      /* 1 (default): bf16-stored factors of a rank that is a multiple of 16 run ONE matrix-core pass
                                 when the fused rank exceeds 64 (bare B A products, gates applied in fp32 between the terms);
                                 0: two passes with the gate folded into B (what every other rank gets) */
-  LSW_OPT_RESIDENT_Q = 8     /* matrix-core kernel for fused ranks up to 64: 1 (default) = where the A operand of one work
-                                item fits LDS it is kept there across the items of a column panel and each XCD walks its
-                                own eighth of the items; 0 = always the kernel that streams it per step */
+  LSW_OPT_RESIDENT_Q = 8     /* matrix-core kernel for fused ranks up to 64 and fp32-stored factors: 1 (default) = where the A
+                                operand of one work item fits LDS and most weights lie in matrices of 4, 8, 16 or 32 column
+                                panels, A is kept in LDS across the items of a panel and each XCD walks its own eighth of
+                                the items; 0 = always the kernel that streams A per step */
 };
 enum {
   LSW_Q_N_LINEARS = 1, LSW_Q_N_LAYERS = 2,

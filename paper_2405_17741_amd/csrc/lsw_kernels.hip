@@ -641,13 +641,10 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma(LaunchPlan p, Ter
 template <int NKS, int QP>
 static hipError_t launch_wg(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int grid, hipStream_t s) {
   const size_t lds = size_t(2) * NKS * 8 * QP * 64 * sizeof(u32x4);     // 16 KB per k-step and Q part, two buffers
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_switch_mfma<NKS, QP>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  // once per process (function-local statics are initialised exactly once, also under concurrent first calls)
+  static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_switch_mfma<NKS, QP>),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
+  if (lds_ok != hipSuccess) return lds_ok;
   hipLaunchKernelGGL((k_switch_mfma<NKS, QP>), dim3(grid), dim3(64 * WG_WAVES), lds, s, p, t, t_dev, r);
   return hipGetLastError();
 }
@@ -904,13 +901,10 @@ template <int NKS, int QP>
 static hipError_t launch_res(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int grid, hipStream_t s) {
   const size_t lds = size_t(p.tile_cols / MT_STEP) * NKS * 8 * QP * 64 * sizeof(u32x4);     // 8 KB per column step, k-step and Q part
   if (lds > size_t(kResidentLdsBytes) || p.Z != nullptr) return hipErrorInvalidValue;
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_switch_mfma_res<NKS, QP>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kResidentLdsBytes);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  // once per process (function-local statics are initialised exactly once, also under concurrent first calls)
+  static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_switch_mfma_res<NKS, QP>),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, kResidentLdsBytes);
+  if (lds_ok != hipSuccess) return lds_ok;
   hipLaunchKernelGGL((k_switch_mfma_res<NKS, QP>), dim3(grid), dim3(64 * WG_WAVES), lds, s, p, t, t_dev, r);
   return hipGetLastError();
 }
@@ -1356,13 +1350,10 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
 template <int NCH, int QP, bool H>
 static hipError_t launch_bigk(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int grid, hipStream_t s) {
   const size_t lds = size_t(2) * kBkBufBytes<QP>;     // 2 x 64 KB (2 x 32 KB for bf16 factors)
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_switch_mfma_bigk<NCH, QP, H>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  // once per process (function-local statics are initialised exactly once, also under concurrent first calls)
+  static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_switch_mfma_bigk<NCH, QP, H>),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
+  if (lds_ok != hipSuccess) return lds_ok;
   hipLaunchKernelGGL((k_switch_mfma_bigk<NCH, QP, H>), dim3(grid), dim3(256), lds, s, p, t, t_dev, r);
   return hipGetLastError();
 }

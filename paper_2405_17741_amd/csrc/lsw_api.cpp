@@ -420,9 +420,12 @@ static lsw_status launch_switch(lsw_ctx* c, const std::vector<int32_t>& sel_laye
   if (t.n > 0) {
     DevicePlan* dp = nullptr;
     const int tc = kernel >= 2 ? (bigk ? c->opt_tile_cols_bigk : c->opt_tile_cols) : kValuTileCols;
+    int grid = c->opt_grid;
+    if (grid <= 0) grid = (kernel == 2) ? c->n_cu : c->n_cu * 2;   // matrix-core: one workgroup per CU
+    grid = std::max(8, (grid / 8) * 8);     // a multiple of the 8 XCDs (the kernels' block remap assumes it)
     // The resident-Q kernel pays where (a) the Q of one item (8 KB per 256 columns, k-step and Q part) fits LDS and (b) at
-    // least half of the selected weights lie in linears whose column panels per row block divide the 32 workgroups of an
-    // XCD, so that a workgroup's next item is in the panel it already holds.  fp32-stored factors only: with bf16-stored
+    // least half of the selected weights lie in linears whose column panels per row block divide the workgroups of one
+    // XCD (32), so that a workgroup's next item is in the panel it already holds.  fp32-stored factors only: with bf16-stored
     // ones (half the Q bytes) the streaming kernel measured 1.3 % faster; and not at half the item width to make K = 48-64
     // fit: on the 70B shape that gained 5 % on 3-term launches and lost as much on 4-term ones.
     bool resident = false;
@@ -433,16 +436,13 @@ static lsw_status launch_switch(lsw_ctx* c, const std::vector<int32_t>& sel_laye
         if (!sel_layers.empty() && !std::binary_search(sel_layers.begin(), sel_layers.end(), L.layer)) continue;
         const int64_t w = int64_t(L.out) * L.in;
         total += w;
-        if (32 % ceil_div(L.in, tc) == 0) reuse += w;
+        if ((grid / 8) % ceil_div(L.in, tc) == 0) reuse += w;
       }
       resident = 2 * reuse >= total;
     }
     lsw_status st = get_plan(c, kernel, tc, sel_layers, &dp);
     if (st != LSW_OK) return st;
     LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, tc, c->opt_xcd, from_base ? 1 : 0, c->opt_one_pass, nullptr, 0, LinDesc{}};
-    int grid = c->opt_grid;
-    if (grid <= 0) grid = (kernel == 2) ? c->n_cu : c->n_cu * 2;   // matrix-core: one workgroup per CU
-    grid = std::max(8, (grid / 8) * 8);     // a multiple of the 8 XCDs (the kernels' block remap assumes it)
     hipError_t e = (kernel == 2) ? (bigk ? launch_switch_mfma_bigk(lp, t, t_dev, c->r, c->qp, grid, s)
                                   : resident ? launch_switch_mfma_res(lp, t, t_dev, c->r, c->qp, grid, s)
                                              : launch_switch_mfma(lp, t, t_dev, c->r, c->qp, grid, s))

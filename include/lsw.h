@@ -287,10 +287,13 @@ enum {
   LSW_OPT_ONE_PASS = 7,      /* 1 (default): bf16-stored factors of a rank that is a multiple of 16 run ONE matrix-core pass
                                 when the fused rank exceeds 64 (bare B A products, gates applied in fp32 between the terms);
                                 0: two passes with the gate folded into B (what every other rank gets) */
-  LSW_OPT_RESIDENT_Q = 8     /* matrix-core kernel for fused ranks up to 64 and fp32-stored factors: 1 (default) = where the A
+  LSW_OPT_RESIDENT_Q = 8,    /* matrix-core kernel for fused ranks up to 64 and fp32-stored factors: 1 (default) = where the A
                                 operand of one work item fits LDS and most weights lie in matrices of 4, 8, 16 or 32 column
                                 panels, A is kept in LDS across the items of a panel and each XCD walks its own eighth of
                                 the items; 0 = always the kernel that streams A per step */
+  LSW_OPT_XCD_POOL = 9       /* that kernel: 1 (default) = the last sixteenth of every XCD's items forms a pool that workgroups
+                                draw from once their own share is done (XCDs differ in speed by 2-3 %); 0 = all items dealt
+                                statically; n >= 2 = the last 1/n instead.  The result is the same bit for bit */
 };
 enum {
   LSW_Q_N_LINEARS = 1, LSW_Q_N_LAYERS = 2,
@@ -299,7 +302,9 @@ enum {
   LSW_Q_LAST_GRID = 5,       /* workgroups of the last launch */
   LSW_Q_PACKED_BYTES = 6,    /* bytes of device memory the context owns */
   LSW_Q_GEMV_X_ELEMS = 7,    /* elements of lsw_merged_gemv_all's x_all (sum of in over the linears) */
-  LSW_Q_GEMV_Y_ELEMS = 8     /* elements of its y_all (sum of out) */
+  LSW_Q_GEMV_Y_ELEMS = 8,    /* elements of its y_all (sum of out) */
+  LSW_Q_LAST_VARIANT = 9     /* which matrix-core kernel the last launch was: 0 none / vector-ALU, 1 A streamed per step,
+                                2 A resident in LDS, 3 chunked (fused rank above 64) */
 };
 lsw_status lsw_set_option(lsw_ctx* ctx, int32_t option, int64_t value);
 int64_t    lsw_query(const lsw_ctx* ctx, int32_t what);   /* -1 on a bad argument */

@@ -13,9 +13,9 @@ import numpy as np
 
 LSW_OK, LSW_ERR_ARG, LSW_ERR_SHAPE, LSW_ERR_STATE, LSW_ERR_NOMEM, LSW_ERR_DEVICE = range(6)
 LSW_MAX_K = 8
-LSW_OPT_KERNEL, LSW_OPT_STRICT_STATE, LSW_OPT_GRID, LSW_OPT_TILE_COLS, LSW_OPT_XCD_REMAP, LSW_OPT_GEMV_GRID, LSW_OPT_ONE_PASS, LSW_OPT_RESIDENT_Q = 1, 2, 3, 4, 5, 6, 7, 8
+LSW_OPT_KERNEL, LSW_OPT_STRICT_STATE, LSW_OPT_GRID, LSW_OPT_TILE_COLS, LSW_OPT_XCD_REMAP, LSW_OPT_GEMV_GRID, LSW_OPT_ONE_PASS, LSW_OPT_RESIDENT_Q, LSW_OPT_XCD_POOL = 1, 2, 3, 4, 5, 6, 7, 8, 9
 (LSW_Q_N_LINEARS, LSW_Q_N_LAYERS, LSW_Q_LAST_KERNEL, LSW_Q_LAST_ITEMS, LSW_Q_LAST_GRID, LSW_Q_PACKED_BYTES,
- LSW_Q_GEMV_X_ELEMS, LSW_Q_GEMV_Y_ELEMS) = range(1, 9)
+ LSW_Q_GEMV_X_ELEMS, LSW_Q_GEMV_Y_ELEMS, LSW_Q_LAST_VARIANT) = range(1, 10)
 KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
 LSW_FACTOR_F32, LSW_FACTOR_BF16 = 0, 1
 

@@ -84,8 +84,8 @@ struct lsw_ctx {
   int64_t owned_bytes = 0;
   int64_t x_elems = 0, y_elems = 0;          // sizes of the back-to-back x and y of lsw_merged_gemv_all
   std::map<PlanKey, DevicePlan> plans;
-  int opt_kernel = 0, opt_strict = 0, opt_grid = 0, opt_tile_cols = kMfmaTileCols, opt_tile_cols_bigk = kMfmaBigkTileCols, opt_xcd = 1, opt_gemv_grid = 0, opt_one_pass = 1, opt_resident = 1;
-  int last_kernel = 0, last_items = 0, last_grid = 0;
+  int opt_kernel = 0, opt_strict = 0, opt_grid = 0, opt_tile_cols = kMfmaTileCols, opt_tile_cols_bigk = kMfmaBigkTileCols, opt_xcd = 1, opt_gemv_grid = 0, opt_one_pass = 1, opt_resident = 1, opt_pool = 1;
+  int last_kernel = 0, last_variant = 0, last_items = 0, last_grid = 0;
 };
 
 static int layer_slot(const lsw_ctx* c, int32_t layer) {
@@ -415,6 +415,7 @@ static lsw_status launch_switch(lsw_ctx* c, const std::vector<int32_t>& sel_laye
   if (kernel >= 2 && !mfma_fits)
     return fail(LSW_ERR_ARG, "matrix-core kernel needs r %% 8 == 0 and a fused rank <= 256 (r=%d, terms=%d)", c->r, t.n);
   c->last_kernel = 0;
+  c->last_variant = 0;
   c->last_items = 0;
   c->last_grid = 0;
   if (t.n > 0) {
@@ -442,13 +443,15 @@ static lsw_status launch_switch(lsw_ctx* c, const std::vector<int32_t>& sel_laye
     }
     lsw_status st = get_plan(c, kernel, tc, sel_layers, &dp);
     if (st != LSW_OK) return st;
-    LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, tc, c->opt_xcd, from_base ? 1 : 0, c->opt_one_pass, nullptr, 0, LinDesc{}};
+    LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, tc, c->opt_xcd, from_base ? 1 : 0, c->opt_one_pass, nullptr, 0, LinDesc{},
+                  c->opt_pool ? c->d_err + 2 : nullptr, c->opt_pool == 1 ? 16 : c->opt_pool};
     hipError_t e = (kernel == 2) ? (bigk ? launch_switch_mfma_bigk(lp, t, t_dev, c->r, c->qp, grid, s)
                                   : resident ? launch_switch_mfma_res(lp, t, t_dev, c->r, c->qp, grid, s)
                                              : launch_switch_mfma(lp, t, t_dev, c->r, c->qp, grid, s))
                                  : launch_switch_valu(lp, t, t_dev, c->r, c->qp, grid, s);
     if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "switch launch failed: %s", hipGetErrorString(e));
     c->last_kernel = kernel;
+    c->last_variant = kernel == 2 ? (bigk ? 3 : resident ? 2 : 1) : 0;
     c->last_items = dp->n_items;
     c->last_grid = grid;
   }
@@ -796,6 +799,10 @@ extern "C" lsw_status lsw_set_option(lsw_ctx* c, int32_t option, int64_t value) 
     case LSW_OPT_RESIDENT_Q:
       c->opt_resident = value != 0;
       return LSW_OK;
+    case LSW_OPT_XCD_POOL:
+      if (value < 0 || value > (1 << 20)) return fail(LSW_ERR_ARG, "pool option out of range");
+      c->opt_pool = int(value);
+      return LSW_OK;
     case LSW_OPT_ONE_PASS:
       c->opt_one_pass = value != 0;
       return LSW_OK;
@@ -819,6 +826,7 @@ extern "C" int64_t lsw_query(const lsw_ctx* c, int32_t what) {
     case LSW_Q_PACKED_BYTES: return c->owned_bytes;
     case LSW_Q_GEMV_X_ELEMS: return c->x_elems;
     case LSW_Q_GEMV_Y_ELEMS: return c->y_elems;
+    case LSW_Q_LAST_VARIANT: return c->last_variant;
     default: return -1;
   }
 }

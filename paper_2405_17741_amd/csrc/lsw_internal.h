@@ -92,6 +92,10 @@ struct LaunchPlan {             // device pointers + counts for one launch
   const float* Z;
   int32_t z_stride;
   LinDesc one;
+  // Resident-Q kernel: two zeroed counters in device memory ([0] items claimed from the shared pool, [1] workgroups
+  // finished; the kernel leaves both at zero), or null for a purely static split of the items.
+  int32_t* pool;
+  int32_t pool_div;             // every XCD range gives its last 1/pool_div to the pool
 };
 
 // Kernel launchers (lsw_kernels.hip).  All return the hipError of the launch.

@@ -685,6 +685,14 @@ hipError_t launch_switch_mfma(const LaunchPlan& p, const Terms& t, const Terms* 
 // Per step a wave stores the previous tile, requests the next one (the first tile of the following item at an item
 // boundary, with the B rows of that item right behind it), updates the current tile, and at an item boundary turns the
 // B rows into the next P.
+//
+// Balance.  The XCDs do not run this kernel equally fast (on the machines measured every second one needs 2-3 % longer
+// for the same share, whichever share it is given), so an equal static split leaves the fast ones idle at the end.
+// With a pool counter (LaunchPlan::pool) the last sixteenth of every XCD's range is therefore not dealt statically:
+// those items form a pool that a workgroup draws from, one item at a time through an atomic counter, once its own
+// column is done.  Wave 0 claims one item ahead (the answer has a whole item's time to arrive) and hands the claim to
+// the other waves through LDS at the barrier that precedes the Q copy.  The last workgroup to finish resets the
+// counters, so every launch finds them at zero.
 // ---------------------------------------------------------------------------
 struct ResItem {            // one work item (128 rows x tile_cols columns of one linear); every field is uniform
   const uint16_t* W;
@@ -750,10 +758,42 @@ __device__ __forceinline__ void res_fetch_q(const LaunchPlan& p, const ResItem& 
     wg_fetch_q<NKS, QP>(c.Apk, ncb, (cb0 + j) * MT_STEP, n, gpr, wave, term_e, term_g, wg_lds + j * kStepSlots);
 }
 
+// Where a workgroup's items come from: its own column of the XCD's statically dealt range, then the pool.
+struct ResWalk {              // every field is uniform over the workgroup
+  int step;                   // workgroups per XCD: the distance of a workgroup's consecutive static items
+  int static_end;             // end of this XCD's statically dealt items
+  int per;                    // items per XCD range (the last range may be shorter)
+  int n_items;
+  int pool_len;               // items every XCD range gives to the pool (its last ones); 0 = no pool
+  int32_t* pool;              // [0] claims made so far, [1] workgroups that have finished
+  int after;                  // the item after nxt when that is a static one, else -1
+  bool after_pool;            // the item after nxt comes from the pool: wave 0 holds the claim for it
+};
+
+__shared__ int32_t s_res_claim;           // wave 0's claim, for the other waves
+
+// pool claim g -> item: claims go round the eight ranges, position g / 8 of the range's pool part; -1 when the pool is empty
+__device__ __forceinline__ int res_pool_item(const ResWalk& w, int g) {
+  if (g >= 8 * w.pool_len) return -1;
+  return min(w.n_items, ((g & 7) + 1) * w.per) - w.pool_len + (g >> 3);
+}
+
+// after `item` has become nxt: where the item after it comes from (wave 0 claims it now if it is a pool item)
+__device__ __forceinline__ void res_plan_after(ResWalk& w, int item, bool item_from_pool, int wave, int lane, int& claim) {
+  w.after = -1;
+  w.after_pool = false;
+  if (!item_from_pool && item + w.step < w.static_end) {
+    w.after = item + w.step;
+  } else if (w.pool_len > 0) {
+    w.after_pool = true;
+    if (wave == 0 && lane == 0) claim = __hip_atomic_fetch_add(w.pool, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
 template <int NKS, int QP>
 __device__ __forceinline__ bool res_step(const LaunchPlan& p, int n, int h, int lane, int wave, int gpr, int r,
                                          const int (&term_e)[NKS], const int (&term_g)[NKS], const float (&term_c)[NKS],
-                                         ResItem& cur, ResItem& nxt, bool& have_nxt_io, int item_step, int item_end,
+                                         ResItem& cur, ResItem& nxt, bool& have_nxt_io, ResWalk& walk, int& claim,
                                          int& cs, uint32_t& lane_off,
                                          __amdgpu_buffer_rsrc_t& prev_res, uint32_t& prev_off, uint32_t& prev_stride,
                                          u32x4 (&p_hi)[NKS], u32x4 (&p_lo)[NKS], u32x4 (&wcur)[16], u32x4 (&wprev)[16]) {
@@ -797,16 +837,26 @@ __device__ __forceinline__ bool res_step(const LaunchPlan& p, int n, int h, int 
   if (last) {                      // item boundary (uniform over the workgroup: all four waves walk the same items)
     if (!have_nxt) return false;
     res_make_p<NKS>(nxt, wave, n, term_c, braw, p_hi, p_lo);
-    const bool new_panel = uniform(int(nxt.seg != cur.seg || nxt.col0 != cur.col0)) != 0;
+    const bool via_pool = walk.after_pool;       // the item after nxt is the one wave 0 claimed a boundary ago
+    const bool new_panel = uniform(int(via_pool || nxt.seg != cur.seg || nxt.col0 != cur.col0)) != 0;
     cur = nxt;
-    const int following = cur.item + item_step;
-    have_nxt_io = following < item_end;
-    if (have_nxt_io) res_item_at(p, following, nxt);
-    if (new_panel) {
-      wg_drain_and_barrier();      // every wave has finished with the old panel's Q
-      res_fetch_q<NKS, QP>(p, cur, n, gpr, wave, term_e, term_g);
-      wg_drain_and_barrier();      // the new one is complete
+    int following = walk.after;
+    if (!via_pool) {
+      have_nxt_io = following >= 0;
+      if (have_nxt_io) res_item_at(p, following, nxt);
     }
+    if (new_panel) {
+      if (via_pool && wave == 0) s_res_claim = __builtin_amdgcn_readfirstlane(claim);
+      wg_drain_and_barrier();      // every wave has finished with the old panel's Q (and sees wave 0's claim)
+      if (via_pool) {
+        following = res_pool_item(walk, uniform(s_res_claim));
+        have_nxt_io = following >= 0;
+        if (have_nxt_io) res_item_at(p, following, nxt);
+      }
+      res_fetch_q<NKS, QP>(p, cur, n, gpr, wave, term_e, term_g);
+      wg_drain_and_barrier();      // the new one is complete (and every wave has read the claim)
+    }
+    if (have_nxt_io) res_plan_after(walk, following, via_pool, wave, lane, claim);
   }
   return true;
 }
@@ -838,16 +888,29 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma_res(LaunchPlan p,
   }
 
   // XCD x (workgroups x, x + 8, ...: the hardware deals workgroups round-robin) owns items [x * per, (x + 1) * per)
-  const int wgs_per_xcd = int(gridDim.x) >> 3;
-  const int per = ceil_div(p.n_items, 8), xcd = int(blockIdx.x) & 7;
-  const int item_end = min(p.n_items, (xcd + 1) * per);
-  const int item0 = xcd * per + (int(blockIdx.x) >> 3);
-  if (item0 >= item_end) return;        // uniform over the workgroup
+  ResWalk walk;
+  walk.step = int(gridDim.x) >> 3;
+  walk.per = ceil_div(p.n_items, 8);
+  walk.n_items = p.n_items;
+  walk.pool = p.pool;
+  // a pool only where every workgroup of every XCD keeps at least two static items (the same answer in all workgroups)
+  walk.pool_len = walk.per / max(1, p.pool_div);
+  if (p.pool == nullptr || p.n_items - 7 * walk.per - walk.pool_len < 2 * walk.step) walk.pool_len = 0;
+  const int xcd = int(blockIdx.x) & 7;
+  walk.static_end = min(p.n_items, (xcd + 1) * walk.per) - walk.pool_len;
+  const int item0 = xcd * walk.per + (int(blockIdx.x) >> 3);
+  if (item0 >= walk.static_end) return; // uniform over the workgroup (never with a pool)
   ResItem cur, nxt;
   res_item_at(p, item0, cur);
   nxt = cur;
-  bool have_nxt = item0 + wgs_per_xcd < item_end;
-  if (have_nxt) res_item_at(p, item0 + wgs_per_xcd, nxt);
+  bool have_nxt = item0 + walk.step < walk.static_end;
+  int claim = 0;
+  walk.after = -1;
+  walk.after_pool = false;
+  if (have_nxt) {
+    res_item_at(p, item0 + walk.step, nxt);
+    res_plan_after(walk, nxt.item, false, wave, lane, claim);
+  }
   u32x4 p_hi[NKS], p_lo[NKS];
   {
     float braw[NKS][8];
@@ -879,9 +942,9 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma_res(LaunchPlan p,
 
   bool a_is_cur = true;
   while (true) {
-    if (!res_step<NKS, QP>(p, n, h, lane, wave, gpr, r, term_e, term_g, term_c, cur, nxt, have_nxt, wgs_per_xcd, item_end, cs, lane_off,
+    if (!res_step<NKS, QP>(p, n, h, lane, wave, gpr, r, term_e, term_g, term_c, cur, nxt, have_nxt, walk, claim, cs, lane_off,
                            prev_res, prev_off, prev_stride, p_hi, p_lo, wa, wb)) { a_is_cur = true; break; }
-    if (!res_step<NKS, QP>(p, n, h, lane, wave, gpr, r, term_e, term_g, term_c, cur, nxt, have_nxt, wgs_per_xcd, item_end, cs, lane_off,
+    if (!res_step<NKS, QP>(p, n, h, lane, wave, gpr, r, term_e, term_g, term_c, cur, nxt, have_nxt, walk, claim, cs, lane_off,
                            prev_res, prev_off, prev_stride, p_hi, p_lo, wb, wa)) { a_is_cur = false; break; }
   }
   if (a_is_cur) {
@@ -894,6 +957,15 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma_res(LaunchPlan p,
     for (int v = 0; v < 16; ++v)
       __builtin_amdgcn_raw_buffer_store_b128(
           wb[v], prev_res, prev_off + uint32_t(8 * (v >> 2) + (v & 3)) * prev_stride, 0, kWStoreAux);
+  }
+  // Only wave 0 touches the pool counters and its last claim has been answered (an empty pool is how it got here),
+  // so when the count of finished workgroups is complete nobody will claim again in this launch.
+  if (walk.pool_len > 0 && threadIdx.x == 0) {
+    const int done = __hip_atomic_fetch_add(walk.pool + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (done == int(gridDim.x) - 1) {
+      __hip_atomic_store(walk.pool, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(walk.pool + 1, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
   }
 }
 

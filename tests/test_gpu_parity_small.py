@@ -169,6 +169,57 @@ def test_streaming_matrix_core_kernel_with_the_resident_one_switched_off(shape):
     b.close()
 
 
+def test_resident_kernel_item_pool_against_the_static_split():
+    """The resident-A kernel deals the last sixteenth of every XCD's items through an atomic pool counter
+    (LSW_OPT_XCD_POOL, on by default) when a launch has enough items; 256-column items and a 64-workgroup grid make a
+    42-million-weight stack qualify.  Every item must be taken exactly once (a second application of an in-place update
+    would show), launch after launch (the kernel resets its own counters): same bits as the static split, and the
+    oracle's bar."""
+    E, r, grid = 4, 8, 64
+    dims = [(2048, 2048), (4096, 1024), (1000, 2048), (3000, 512), (520, 2056), (1536, 1024),
+            (4096, 2048), (130, 1032), (777, 1024), (2048, 2048), (8192, 1024), (2560, 2048)]
+    rng = np.random.default_rng(9090)
+    host = [I.host_linear(rng, o, n, E, r, 0.02, 1 / 16, 0.01) for o, n in dims]
+    shapes = [(p // 3, p % 3, o, n) for p, (o, n) in enumerate(dims)]
+    a = DeviceStack.from_host(host, shapes, E, r, kernel=L.KERNEL_MFMA)
+    b = DeviceStack.from_host(host, shapes, E, r, kernel=L.KERNEL_MFMA)
+    for ds in (a, b):
+        L.lsw_set_option(ds.ctx, L.LSW_OPT_GRID, grid)
+        L.lsw_set_option(ds.ctx, L.LSW_OPT_TILE_COLS, 256)
+    L.lsw_set_option(b.ctx, L.LSW_OPT_XCD_POOL, 0)
+    none = (np.zeros(0, np.int32), np.zeros(0, np.float32))
+    seq = [none, (np.array([1, 2], np.int32), np.array([0.7, 0.3], np.float32)),
+           (np.array([2, 0], np.int32), np.array([0.45, 0.55], np.float32)),
+           (np.array([3, 1], np.int32), np.array([0.5, 0.5], np.float32)), none]
+    prev = [a.rows(p) for p in range(len(dims))]
+
+    def both(old, new, layers, expect_pool=True):
+        a.switch(old, new, layers=layers)
+        b.switch(old, new, layers=layers)
+        assert L.lsw_query(a.ctx, L.LSW_Q_LAST_VARIANT) == 2 and L.lsw_query(b.ctx, L.LSW_Q_LAST_VARIANT) == 2
+        n_items = L.lsw_query(a.ctx, L.LSW_Q_LAST_ITEMS)
+        per = -(-n_items // 8)
+        if expect_pool:
+            assert per // 16 > 0 and n_items - 7 * per - per // 16 >= 2 * (grid // 8), "this launch would not use the pool"
+        for p, (layer, _, _, _) in enumerate(shapes):
+            ga, gb = a.rows(p), b.rows(p)
+            assert (ga == gb).all(), (layers, p)
+            if layers is None or layer in layers:
+                rep, _ = check_step(prev[p], ga, host[p][1], host[p][2], old, new)
+                assert rep["fail"] == 0, (layers, p)
+            else:
+                assert (ga == prev[p]).all()
+            prev[p] = ga
+
+    both(seq[0], seq[1], None)
+    both(seq[1], seq[2], None)
+    both(seq[2], seq[3], [0, 2])          # subset launches (fewer items, other pool size) between full ones
+    both(seq[2], seq[3], [1, 3])
+    both(seq[3], seq[4], None)
+    a.close()
+    b.close()
+
+
 @pytest.mark.parametrize("kernel", KERNELS)
 def test_stack_with_layer_subsets_guard_bands_and_state(kernel):
     wl = I.Workload("mini", 3, 64, 136, 32, 6, 8, 2, 4, 0.02, 1 / 8, 0.01, 4242)

@@ -281,8 +281,11 @@ enum {
   LSW_OPT_STRICT_STATE = 2,  /* 1: lsw_switch rejects an `old` that differs from the tracked state of a layer */
   LSW_OPT_GRID = 3,          /* workgroups per launch; 0 = automatic (one matrix-core workgroup per CU) */
   LSW_OPT_TILE_COLS = 4,     /* matrix-core kernel: columns per work item, a multiple of 256 (tuning knob) */
-  LSW_OPT_XCD_REMAP = 5,     /* 1 (default): each XCD takes a contiguous share of every round of items (the resident-A
-                                kernel always gives each XCD its own eighth of the whole item list) */
+  LSW_OPT_XCD_REMAP = 5,     /* order of the work items over the 8 XCDs: 0 = workgroup b takes items b, b + grid, ...; 1 = each
+                                XCD takes a contiguous share of every round of items; 2 = matrix-core kernel for fused ranks
+                                up to 64: each XCD walks its own eighth of the whole item list (the resident-A kernel
+                                always does); 3 (default) = 2 where most weights lie in matrices of 4, 8, 16 or 32 column
+                                panels, else 1 */
   LSW_OPT_GEMV_GRID = 6,     /* workgroups of the merged-decode launches; 0 = automatic (2 per CU) */
   LSW_OPT_ONE_PASS = 7,      /* 1 (default): bf16-stored factors of a rank that is a multiple of 16 run ONE matrix-core pass
                                 when the fused rank exceeds 64 (bare B A products, gates applied in fp32 between the terms);

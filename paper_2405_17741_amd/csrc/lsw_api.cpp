@@ -84,7 +84,7 @@ struct lsw_ctx {
   int64_t owned_bytes = 0;
   int64_t x_elems = 0, y_elems = 0;          // sizes of the back-to-back x and y of lsw_merged_gemv_all
   std::map<PlanKey, DevicePlan> plans;
-  int opt_kernel = 0, opt_strict = 0, opt_grid = 0, opt_tile_cols = kMfmaTileCols, opt_tile_cols_bigk = kMfmaBigkTileCols, opt_xcd = 1, opt_gemv_grid = 0, opt_one_pass = 1, opt_resident = 1, opt_pool = 1;
+  int opt_kernel = 0, opt_strict = 0, opt_grid = 0, opt_tile_cols = kMfmaTileCols, opt_tile_cols_bigk = kMfmaBigkTileCols, opt_xcd = 3, opt_gemv_grid = 0, opt_one_pass = 1, opt_resident = 1, opt_pool = 1;
   int last_kernel = 0, last_variant = 0, last_items = 0, last_grid = 0;
 };
 
@@ -424,14 +424,14 @@ static lsw_status launch_switch(lsw_ctx* c, const std::vector<int32_t>& sel_laye
     int grid = c->opt_grid;
     if (grid <= 0) grid = (kernel == 2) ? c->n_cu : c->n_cu * 2;   // matrix-core: one workgroup per CU
     grid = std::max(8, (grid / 8) * 8);     // a multiple of the 8 XCDs (the kernels' block remap assumes it)
-    // The resident-Q kernel pays where (a) the Q of one item (8 KB per 256 columns, k-step and Q part) fits LDS and (b) at
-    // least half of the selected weights lie in linears whose column panels per row block divide the workgroups of one
-    // XCD (32), so that a workgroup's next item is in the panel it already holds.  fp32-stored factors only: with bf16-stored
-    // ones (half the Q bytes) the streaming kernel measured 1.3 % faster; and not at half the item width to make K = 48-64
-    // fit: on the 70B shape that gained 5 % on 3-term launches and lost as much on 4-term ones.
-    bool resident = false;
-    if (kernel == 2 && !bigk && c->opt_resident && c->qp == 2 &&
-        (tc / kApkBlockCols) * ((n_groups + 1) / 2) * 8 * c->qp * 1024 <= kResidentLdsBytes) {
+    // Per-XCD order (each XCD walks its own eighth of the item list, the tail of every eighth dealt through the pool)
+    // pays where at least half of the selected weights lie in linears whose column panels per row block divide the
+    // workgroups of one XCD (32): a workgroup's consecutive items then lie in the same panel, the region an XCD updates
+    // stays compact, and each packed A is fetched into one L2 instead of eight.  Measured: 70B shape 47.4 against
+    // 50.2 ms, 7B with bf16-stored factors 4,076 against 4,121 us; 13B shape (5 and 13.5 panels) 9,300 against 9,180 us
+    // on a fresh machine, so it keeps the round-wise order.
+    bool per_xcd = false;
+    if (kernel == 2 && !bigk) {
       int64_t reuse = 0, total = 0;
       for (const lsw_linear& L : c->lin) {
         if (!sel_layers.empty() && !std::binary_search(sel_layers.begin(), sel_layers.end(), L.layer)) continue;
@@ -439,11 +439,19 @@ static lsw_status launch_switch(lsw_ctx* c, const std::vector<int32_t>& sel_laye
         total += w;
         if ((grid / 8) % ceil_div(L.in, tc) == 0) reuse += w;
       }
-      resident = 2 * reuse >= total;
+      per_xcd = 2 * reuse >= total;
     }
+    // The resident-Q kernel on top of that where the Q of one item (8 KB per 256 columns, k-step and Q part) fits LDS.
+    // fp32-stored factors only: with bf16-stored ones (half the Q bytes) the streaming kernel measured 1.3 % faster; and
+    // not at half the item width to make K = 48-64 fit: on the 70B shape that gained 5 % on 3-term launches and lost as
+    // much on 4-term ones.
+    const bool resident = per_xcd && c->opt_resident && c->qp == 2 &&
+                          (tc / kApkBlockCols) * ((n_groups + 1) / 2) * 8 * c->qp * 1024 <= kResidentLdsBytes;
+    // LSW_OPT_XCD_REMAP: 3 = automatic
+    const int xcd_mode = c->opt_xcd == 3 ? (bigk || kernel != 2 ? 1 : per_xcd ? 2 : 1) : c->opt_xcd;
     lsw_status st = get_plan(c, kernel, tc, sel_layers, &dp);
     if (st != LSW_OK) return st;
-    LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, tc, c->opt_xcd, from_base ? 1 : 0, c->opt_one_pass, nullptr, 0, LinDesc{},
+    LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, tc, xcd_mode, from_base ? 1 : 0, c->opt_one_pass, nullptr, 0, LinDesc{},
                   c->opt_pool ? c->d_err + 2 : nullptr, c->opt_pool == 1 ? 16 : c->opt_pool};
     hipError_t e = (kernel == 2) ? (bigk ? launch_switch_mfma_bigk(lp, t, t_dev, c->r, c->qp, grid, s)
                                   : resident ? launch_switch_mfma_res(lp, t, t_dev, c->r, c->qp, grid, s)
@@ -688,7 +696,7 @@ extern "C" lsw_status lsw_adapter_forward(lsw_ctx* c, int32_t lin_index, const v
   one.out = T;
   one.in = L.out;
   const int64_t n_items = int64_t(ceil_div(T, kMfmaTileRows)) * ceil_div(L.out, tc);
-  LaunchPlan lp{nullptr, nullptr, nullptr, 1, int32_t(n_items), tc, c->opt_xcd, 0, 0, Z, zs, one};
+  LaunchPlan lp{nullptr, nullptr, nullptr, 1, int32_t(n_items), tc, c->opt_xcd ? 1 : 0, 0, 0, Z, zs, one};
   const int grid = std::max(8, (c->n_cu / 8) * 8);
   e = bigk ? launch_switch_mfma_bigk(lp, t, nullptr, c->r, c->qp, grid, s) : launch_switch_mfma(lp, t, nullptr, c->r, c->qp, grid, s);
   if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "up-projection launch failed: %s", hipGetErrorString(e));
@@ -721,7 +729,7 @@ extern "C" lsw_status lsw_probe_inplace(lsw_ctx* c, int32_t waves_per_cu, void* 
   DevicePlan* dp = nullptr;
   lsw_status st = get_plan(c, 3, c->opt_tile_cols, std::vector<int32_t>(), &dp);
   if (st != LSW_OK) return st;
-  LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, c->opt_tile_cols, c->opt_xcd, 0, 0, nullptr, 0, LinDesc{}};
+  LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, c->opt_tile_cols, c->opt_xcd ? 1 : 0, 0, 0, nullptr, 0, LinDesc{}};
   hipError_t e = launch_probe_inplace(lp, c->n_cu * waves_per_cu, static_cast<hipStream_t>(hip_stream));
   if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "probe launch failed: %s", hipGetErrorString(e));
   return LSW_OK;
@@ -751,7 +759,7 @@ extern "C" lsw_status lsw_merged_gemv_all(lsw_ctx* c, const void* x_all_bf16, fl
   DevicePlan* dp = nullptr;
   lsw_status st = get_plan(c, 4, 1 << 30, std::vector<int32_t>(), &dp);   // items: blocks of rows, whole rows wide
   if (st != LSW_OK) return st;
-  LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, 1 << 30, c->opt_xcd, 0, 0, nullptr, 0, LinDesc{}};
+  LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, 1 << 30, c->opt_xcd ? 1 : 0, 0, 0, nullptr, 0, LinDesc{}};
   int grid = c->opt_gemv_grid > 0 ? c->opt_gemv_grid : c->n_cu * 2;
   grid = std::max(8, (grid / 8) * 8);
   hipError_t e = launch_gemv_all(lp, static_cast<const uint16_t*>(x_all_bf16), y_all_fp32, grid,
@@ -794,7 +802,8 @@ extern "C" lsw_status lsw_set_option(lsw_ctx* c, int32_t option, int64_t value) 
       c->opt_tile_cols_bigk = int(value);
       return LSW_OK;
     case LSW_OPT_XCD_REMAP:
-      c->opt_xcd = value != 0;
+      if (value < 0 || value > 3) return fail(LSW_ERR_ARG, "XCD order must be 0..3");
+      c->opt_xcd = int(value);
       return LSW_OK;
     case LSW_OPT_RESIDENT_Q:
       c->opt_resident = value != 0;

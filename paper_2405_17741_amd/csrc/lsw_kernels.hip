@@ -513,15 +513,111 @@ __device__ __forceinline__ void wg_drain_and_barrier() {
   __builtin_amdgcn_sched_barrier(0);
 }
 
+// ---------------------------------------------------------------------------
+// The order in which the workgroups of a matrix-core launch take the work items.
+//
+// Global order: workgroup b takes items b', b' + grid, ... (b' = b, or b's place in the XCD-contiguous numbering).
+// Per-XCD order: XCD x (workgroups x, x + 8, ...: the hardware deals workgroups round-robin) owns items
+// [x * per, (x + 1) * per), its grid / 8 workgroups taking consecutive items per round.  The XCDs do not run these
+// kernels equally fast then (on the machines measured every second one needs 2-3 % longer for the same share,
+// whichever share it is given), so with a pool counter (LaunchPlan::pool) the last 1 / pool_div of every XCD's range
+// is not dealt statically: those items form a pool that a workgroup draws from, one item at a time through an atomic
+// counter, once its own column is done.  Wave 0 claims one item ahead (the answer has a whole item's time to arrive)
+// and hands the claim to the other waves through LDS at a workgroup barrier.  Nothing waits for another workgroup.
+// The last workgroup to finish resets the counters, so every launch finds them at zero.
+// ---------------------------------------------------------------------------
+struct ItemWalk {             // every field is uniform over the workgroup
+  int step;                   // distance of a workgroup's consecutive static items
+  int static_end;             // end of the statically dealt items this workgroup draws from
+  int per;                    // items per XCD range (the last range may be shorter)
+  int n_items;
+  int pool_len;               // items every XCD range gives to the pool (its last ones); 0 = no pool
+  int32_t* pool;              // [0] claims made so far, [1] workgroups that have finished
+  int after;                  // the item after the next one when that is a static one, else -1
+  bool after_pool;            // the item after the next one comes from the pool: wave 0 holds the claim for it
+  int slot;                   // which of the two LDS words the next claim is handed over in
+};
+
+// Wave 0's claims, for the other waves.  Two words used in turn: with one-step items a wave may still be reading the
+// claim handed over at the last barrier while wave 0 already writes the next one.
+__shared__ int32_t s_walk_claim[2];
+
+// pool claim g -> item: claims go round the eight ranges, position g / 8 of the range's pool part; -1 when the pool is empty
+__device__ __forceinline__ int walk_pool_item(const ItemWalk& w, int g) {
+  if (g >= 8 * w.pool_len) return -1;
+  return min(w.n_items, ((g & 7) + 1) * w.per) - w.pool_len + (g >> 3);
+}
+
+// wave 0, before the barrier that precedes walk_take_claim: hand the answered claim to the workgroup
+__device__ __forceinline__ void walk_publish_claim(const ItemWalk& w, int wave, int claim) {
+  if (wave == 0) s_walk_claim[w.slot] = __builtin_amdgcn_readfirstlane(claim);
+}
+
+// every wave, after that barrier: the claimed item, or -1 when the pool was empty
+__device__ __forceinline__ int walk_take_claim(ItemWalk& w) {
+  const int item = walk_pool_item(w, uniform(s_walk_claim[w.slot]));
+  w.slot ^= 1;
+  w.after_pool = false;       // until walk_plan_after says otherwise
+  return item;
+}
+
+// Sets up the walk and returns the workgroup's first item (none if it is not below static_end: never with a pool).
+__device__ __forceinline__ int walk_init(const LaunchPlan& p, bool per_xcd, ItemWalk& w) {
+  w.n_items = p.n_items;
+  w.pool = p.pool;
+  w.pool_len = 0;
+  w.after = -1;
+  w.after_pool = false;
+  w.slot = 0;
+  if (!per_xcd) {
+    w.step = int(gridDim.x);
+    w.per = p.n_items;
+    w.static_end = p.n_items;
+    return p.xcd_remap ? xcd_contiguous_block(blockIdx.x, gridDim.x) : int(blockIdx.x);
+  }
+  w.step = int(gridDim.x) >> 3;
+  w.per = ceil_div(p.n_items, 8);
+  // a pool only where every workgroup of every XCD keeps at least two static items (the same answer in all workgroups)
+  w.pool_len = w.per / max(1, p.pool_div);
+  if (p.pool == nullptr || p.n_items - 7 * w.per - w.pool_len < 2 * w.step) w.pool_len = 0;
+  const int xcd = int(blockIdx.x) & 7;
+  w.static_end = min(p.n_items, (xcd + 1) * w.per) - w.pool_len;
+  return xcd * w.per + (int(blockIdx.x) >> 3);
+}
+
+// after `item` has become the next one: where the item after it comes from (wave 0 claims it now if it is a pool item)
+__device__ __forceinline__ void walk_plan_after(ItemWalk& w, int item, bool item_from_pool, int wave, int lane, int& claim) {
+  w.after = -1;
+  w.after_pool = false;
+  if (!item_from_pool && item + w.step < w.static_end) {
+    w.after = item + w.step;
+  } else if (w.pool_len > 0) {
+    w.after_pool = true;
+    if (wave == 0 && lane == 0) claim = __hip_atomic_fetch_add(w.pool, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
+// End of the kernel.  Only wave 0 touches the pool counters and its last claim has been answered (an empty pool is how
+// it got here), so when the count of finished workgroups is complete nobody will claim again in this launch.
+__device__ __forceinline__ void walk_finish(const ItemWalk& w) {
+  if (w.pool_len > 0 && threadIdx.x == 0) {
+    const int done = __hip_atomic_fetch_add(w.pool + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (done == int(gridDim.x) - 1) {
+      __hip_atomic_store(w.pool, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(w.pool + 1, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+}
+
 // One step of a wave: start the copy of the next step's Q quarter into the idle LDS buffer, store
 // the previous step's tile, request the next tile into the freed registers, update the current
 // tile, then drain and meet the workgroup.  Everything requested at the top has the whole compute
 // phase to arrive.  Returns false after the last tile of the workgroup.
 template <int NKS, int QP>
-__device__ __forceinline__ bool wg_step(const LaunchPlan& p, int grid, int n, int h, int lane, int wave, int gpr, int r,
+__device__ __forceinline__ bool wg_step(const LaunchPlan& p, int n, int h, int lane, int wave, int gpr, int r,
                                         const int (&term_e)[NKS], const int (&term_g)[NKS],
                                         const float (&term_c)[NKS], MfmaItem<NKS>& cur, MfmaItem<NKS>& nxt,
-                                        bool& have_nxt, int& item, int& cs, uint32_t& lane_off,
+                                        bool& have_nxt, ItemWalk& walk, int& claim, int& cs, uint32_t& lane_off,
                                         __amdgpu_buffer_rsrc_t& prev_res, uint32_t& prev_off, uint32_t& prev_stride,
                                         u32x4 (&wcur)[16], u32x4 (&wprev)[16], int buf) {
   constexpr int kBufSlots = NKS * 8 * QP * 64;
@@ -555,6 +651,7 @@ __device__ __forceinline__ bool wg_step(const LaunchPlan& p, int grid, int n, in
 
   wg_compute<NKS, QP>(cur.p_hi, cur.p_lo, wg_lds + buf * kBufSlots + lane, wcur);
 
+  if (last && walk.after_pool) walk_publish_claim(walk, wave, claim);
   wg_drain_and_barrier();
 
   prev_res = w_resource(cur.W, cur.wbytes);
@@ -565,9 +662,13 @@ __device__ __forceinline__ bool wg_step(const LaunchPlan& p, int grid, int n, in
   if (last) {                      // item boundary: rare, and the only branch of the step (uniform over the workgroup)
     if (!have_nxt) return false;
     cur = nxt;
-    item += grid;
-    have_nxt = item + grid < p.n_items;
-    if (have_nxt) mfma_load_item<NKS, QP>(p, item + grid, n, gpr, r, term_e, term_g, term_c, nxt, WG_ROWS, 32 * wave);
+    const bool via_pool = walk.after_pool;
+    const int following = via_pool ? walk_take_claim(walk) : walk.after;
+    have_nxt = following >= 0;
+    if (have_nxt) {
+      mfma_load_item<NKS, QP>(p, following, n, gpr, r, term_e, term_g, term_c, nxt, WG_ROWS, 32 * wave);
+      walk_plan_after(walk, following, via_pool, wave, lane, claim);
+    }
   }
   return true;
 }
@@ -586,7 +687,6 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma(LaunchPlan p, Ter
   const int n = lane & 31, h = lane >> 5;
   const int gpr = r >> 3;
   const int n_groups = n_terms * gpr;
-  const int grid = gridDim.x;
   const bool adapter = p.Z != nullptr;      // adapter-path mode: the "terms" are all experts 0..n_terms-1, coefficient 1
   int term_e[NKS], term_g[NKS];
   float term_c[NKS];
@@ -600,13 +700,19 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma(LaunchPlan p, Ter
     term_c[ks] = valid ? (adapter ? 1.0f : s_coeff[c]) : 0.0f;
   }
 
-  int item = p.xcd_remap ? xcd_contiguous_block(blockIdx.x, grid) : int(blockIdx.x);
-  if (item >= p.n_items) return;        // uniform over the workgroup
+  ItemWalk walk;
+  const int item0 = walk_init(p, p.xcd_remap == 2, walk);
+  if (item0 >= walk.static_end) return; // uniform over the workgroup (never with a pool)
   MfmaItem<NKS> cur, nxt;
-  mfma_load_item<NKS, QP>(p, item, n, gpr, r, term_e, term_g, term_c, cur, WG_ROWS, 32 * wave);
-  bool have_nxt = item + grid < p.n_items;
-  if (have_nxt) mfma_load_item<NKS, QP>(p, item + grid, n, gpr, r, term_e, term_g, term_c, nxt, WG_ROWS, 32 * wave);
-  else nxt = cur;
+  mfma_load_item<NKS, QP>(p, item0, n, gpr, r, term_e, term_g, term_c, cur, WG_ROWS, 32 * wave);
+  bool have_nxt = item0 + walk.step < walk.static_end;
+  int claim = 0;
+  if (have_nxt) {
+    mfma_load_item<NKS, QP>(p, item0 + walk.step, n, gpr, r, term_e, term_g, term_c, nxt, WG_ROWS, 32 * wave);
+    walk_plan_after(walk, item0 + walk.step, false, wave, lane, claim);
+  } else {
+    nxt = cur;
+  }
   int cs = cur.col0;
   uint32_t lane_off = mfma_lane_offset<NKS>(cur, cs, n, h);
   u32x4 wa[16], wb[16];
@@ -620,9 +726,9 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma(LaunchPlan p, Ter
 
   bool a_is_cur = true;
   while (true) {
-    if (!wg_step<NKS, QP>(p, grid, n, h, lane, wave, gpr, r, term_e, term_g, term_c, cur, nxt, have_nxt, item, cs, lane_off,
+    if (!wg_step<NKS, QP>(p, n, h, lane, wave, gpr, r, term_e, term_g, term_c, cur, nxt, have_nxt, walk, claim, cs, lane_off,
                       prev_res, prev_off, prev_stride, wa, wb, 0)) { a_is_cur = true; break; }
-    if (!wg_step<NKS, QP>(p, grid, n, h, lane, wave, gpr, r, term_e, term_g, term_c, cur, nxt, have_nxt, item, cs, lane_off,
+    if (!wg_step<NKS, QP>(p, n, h, lane, wave, gpr, r, term_e, term_g, term_c, cur, nxt, have_nxt, walk, claim, cs, lane_off,
                       prev_res, prev_off, prev_stride, wb, wa, 1)) { a_is_cur = false; break; }
   }
   if (a_is_cur) {
@@ -636,6 +742,7 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma(LaunchPlan p, Ter
       __builtin_amdgcn_raw_buffer_store_b128(
           wb[v], prev_res, prev_off + uint32_t(8 * (v >> 2) + (v & 3)) * prev_stride, 0, kWStoreAux);
   }
+  walk_finish(walk);
 }
 
 template <int NKS, int QP>
@@ -686,13 +793,7 @@ hipError_t launch_switch_mfma(const LaunchPlan& p, const Terms& t, const Terms* 
 // boundary, with the B rows of that item right behind it), updates the current tile, and at an item boundary turns the
 // B rows into the next P.
 //
-// Balance.  The XCDs do not run this kernel equally fast (on the machines measured every second one needs 2-3 % longer
-// for the same share, whichever share it is given), so an equal static split leaves the fast ones idle at the end.
-// With a pool counter (LaunchPlan::pool) the last sixteenth of every XCD's range is therefore not dealt statically:
-// those items form a pool that a workgroup draws from, one item at a time through an atomic counter, once its own
-// column is done.  Wave 0 claims one item ahead (the answer has a whole item's time to arrive) and hands the claim to
-// the other waves through LDS at the barrier that precedes the Q copy.  The last workgroup to finish resets the
-// counters, so every launch finds them at zero.
+// Balance.  The last sixteenth of every XCD's range goes through the item pool (see ItemWalk); pool items reload Q.
 // ---------------------------------------------------------------------------
 struct ResItem {            // one work item (128 rows x tile_cols columns of one linear); every field is uniform
   const uint16_t* W;
@@ -758,42 +859,10 @@ __device__ __forceinline__ void res_fetch_q(const LaunchPlan& p, const ResItem& 
     wg_fetch_q<NKS, QP>(c.Apk, ncb, (cb0 + j) * MT_STEP, n, gpr, wave, term_e, term_g, wg_lds + j * kStepSlots);
 }
 
-// Where a workgroup's items come from: its own column of the XCD's statically dealt range, then the pool.
-struct ResWalk {              // every field is uniform over the workgroup
-  int step;                   // workgroups per XCD: the distance of a workgroup's consecutive static items
-  int static_end;             // end of this XCD's statically dealt items
-  int per;                    // items per XCD range (the last range may be shorter)
-  int n_items;
-  int pool_len;               // items every XCD range gives to the pool (its last ones); 0 = no pool
-  int32_t* pool;              // [0] claims made so far, [1] workgroups that have finished
-  int after;                  // the item after nxt when that is a static one, else -1
-  bool after_pool;            // the item after nxt comes from the pool: wave 0 holds the claim for it
-};
-
-__shared__ int32_t s_res_claim;           // wave 0's claim, for the other waves
-
-// pool claim g -> item: claims go round the eight ranges, position g / 8 of the range's pool part; -1 when the pool is empty
-__device__ __forceinline__ int res_pool_item(const ResWalk& w, int g) {
-  if (g >= 8 * w.pool_len) return -1;
-  return min(w.n_items, ((g & 7) + 1) * w.per) - w.pool_len + (g >> 3);
-}
-
-// after `item` has become nxt: where the item after it comes from (wave 0 claims it now if it is a pool item)
-__device__ __forceinline__ void res_plan_after(ResWalk& w, int item, bool item_from_pool, int wave, int lane, int& claim) {
-  w.after = -1;
-  w.after_pool = false;
-  if (!item_from_pool && item + w.step < w.static_end) {
-    w.after = item + w.step;
-  } else if (w.pool_len > 0) {
-    w.after_pool = true;
-    if (wave == 0 && lane == 0) claim = __hip_atomic_fetch_add(w.pool, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
-}
-
 template <int NKS, int QP>
 __device__ __forceinline__ bool res_step(const LaunchPlan& p, int n, int h, int lane, int wave, int gpr, int r,
                                          const int (&term_e)[NKS], const int (&term_g)[NKS], const float (&term_c)[NKS],
-                                         ResItem& cur, ResItem& nxt, bool& have_nxt_io, ResWalk& walk, int& claim,
+                                         ResItem& cur, ResItem& nxt, bool& have_nxt_io, ItemWalk& walk, int& claim,
                                          int& cs, uint32_t& lane_off,
                                          __amdgpu_buffer_rsrc_t& prev_res, uint32_t& prev_off, uint32_t& prev_stride,
                                          u32x4 (&p_hi)[NKS], u32x4 (&p_lo)[NKS], u32x4 (&wcur)[16], u32x4 (&wprev)[16]) {
@@ -846,17 +915,17 @@ __device__ __forceinline__ bool res_step(const LaunchPlan& p, int n, int h, int 
       if (have_nxt_io) res_item_at(p, following, nxt);
     }
     if (new_panel) {
-      if (via_pool && wave == 0) s_res_claim = __builtin_amdgcn_readfirstlane(claim);
+      if (via_pool) walk_publish_claim(walk, wave, claim);
       wg_drain_and_barrier();      // every wave has finished with the old panel's Q (and sees wave 0's claim)
       if (via_pool) {
-        following = res_pool_item(walk, uniform(s_res_claim));
+        following = walk_take_claim(walk);
         have_nxt_io = following >= 0;
         if (have_nxt_io) res_item_at(p, following, nxt);
       }
       res_fetch_q<NKS, QP>(p, cur, n, gpr, wave, term_e, term_g);
       wg_drain_and_barrier();      // the new one is complete (and every wave has read the claim)
     }
-    if (have_nxt_io) res_plan_after(walk, following, via_pool, wave, lane, claim);
+    if (have_nxt_io) walk_plan_after(walk, following, via_pool, wave, lane, claim);
   }
   return true;
 }
@@ -888,28 +957,17 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma_res(LaunchPlan p,
   }
 
   // XCD x (workgroups x, x + 8, ...: the hardware deals workgroups round-robin) owns items [x * per, (x + 1) * per)
-  ResWalk walk;
-  walk.step = int(gridDim.x) >> 3;
-  walk.per = ceil_div(p.n_items, 8);
-  walk.n_items = p.n_items;
-  walk.pool = p.pool;
-  // a pool only where every workgroup of every XCD keeps at least two static items (the same answer in all workgroups)
-  walk.pool_len = walk.per / max(1, p.pool_div);
-  if (p.pool == nullptr || p.n_items - 7 * walk.per - walk.pool_len < 2 * walk.step) walk.pool_len = 0;
-  const int xcd = int(blockIdx.x) & 7;
-  walk.static_end = min(p.n_items, (xcd + 1) * walk.per) - walk.pool_len;
-  const int item0 = xcd * walk.per + (int(blockIdx.x) >> 3);
+  ItemWalk walk;
+  const int item0 = walk_init(p, true, walk);
   if (item0 >= walk.static_end) return; // uniform over the workgroup (never with a pool)
   ResItem cur, nxt;
   res_item_at(p, item0, cur);
   nxt = cur;
   bool have_nxt = item0 + walk.step < walk.static_end;
   int claim = 0;
-  walk.after = -1;
-  walk.after_pool = false;
   if (have_nxt) {
     res_item_at(p, item0 + walk.step, nxt);
-    res_plan_after(walk, nxt.item, false, wave, lane, claim);
+    walk_plan_after(walk, nxt.item, false, wave, lane, claim);
   }
   u32x4 p_hi[NKS], p_lo[NKS];
   {
@@ -958,15 +1016,7 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma_res(LaunchPlan p,
       __builtin_amdgcn_raw_buffer_store_b128(
           wb[v], prev_res, prev_off + uint32_t(8 * (v >> 2) + (v & 3)) * prev_stride, 0, kWStoreAux);
   }
-  // Only wave 0 touches the pool counters and its last claim has been answered (an empty pool is how it got here),
-  // so when the count of finished workgroups is complete nobody will claim again in this launch.
-  if (walk.pool_len > 0 && threadIdx.x == 0) {
-    const int done = __hip_atomic_fetch_add(walk.pool + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (done == int(gridDim.x) - 1) {
-      __hip_atomic_store(walk.pool, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_store(walk.pool + 1, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-  }
+  walk_finish(walk);
 }
 
 template <int NKS, int QP>

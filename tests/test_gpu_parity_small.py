@@ -169,8 +169,10 @@ def test_streaming_matrix_core_kernel_with_the_resident_one_switched_off(shape):
     b.close()
 
 
-def test_resident_kernel_item_pool_against_the_static_split():
-    """The resident-A kernel deals the last sixteenth of every XCD's items through an atomic pool counter
+@pytest.mark.parametrize("variant", [2, 1])
+def test_item_pool_against_the_static_split(variant):
+    """With each XCD on its own eighth of the items (the resident-A kernel always; the streaming kernel, variant 1, where
+    the host chooses that order or LSW_OPT_XCD_REMAP = 2 forces it) the kernel deals the last sixteenth of every XCD's items through an atomic pool counter
     (LSW_OPT_XCD_POOL, on by default) when a launch has enough items; 256-column items and a 64-workgroup grid make a
     42-million-weight stack qualify.  Every item must be taken exactly once (a second application of an in-place update
     would show), launch after launch (the kernel resets its own counters): same bits as the static split, and the
@@ -186,6 +188,9 @@ def test_resident_kernel_item_pool_against_the_static_split():
     for ds in (a, b):
         L.lsw_set_option(ds.ctx, L.LSW_OPT_GRID, grid)
         L.lsw_set_option(ds.ctx, L.LSW_OPT_TILE_COLS, 256)
+        if variant == 1:
+            L.lsw_set_option(ds.ctx, L.LSW_OPT_RESIDENT_Q, 0)
+            L.lsw_set_option(ds.ctx, L.LSW_OPT_XCD_REMAP, 2)
     L.lsw_set_option(b.ctx, L.LSW_OPT_XCD_POOL, 0)
     none = (np.zeros(0, np.int32), np.zeros(0, np.float32))
     seq = [none, (np.array([1, 2], np.int32), np.array([0.7, 0.3], np.float32)),
@@ -196,7 +201,7 @@ def test_resident_kernel_item_pool_against_the_static_split():
     def both(old, new, layers, expect_pool=True):
         a.switch(old, new, layers=layers)
         b.switch(old, new, layers=layers)
-        assert L.lsw_query(a.ctx, L.LSW_Q_LAST_VARIANT) == 2 and L.lsw_query(b.ctx, L.LSW_Q_LAST_VARIANT) == 2
+        assert L.lsw_query(a.ctx, L.LSW_Q_LAST_VARIANT) == variant and L.lsw_query(b.ctx, L.LSW_Q_LAST_VARIANT) == variant
         n_items = L.lsw_query(a.ctx, L.LSW_Q_LAST_ITEMS)
         per = -(-n_items // 8)
         if expect_pool:

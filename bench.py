@@ -106,6 +106,7 @@ def main():
     ap.add_argument("--tile-cols", type=int, default=0)
     ap.add_argument("--xcd", type=int, default=-1)
     ap.add_argument("--resident-q", type=int, default=-1, help="0: always stream the A operand per step (tuning knob)")
+    ap.add_argument("--panel-group", type=int, default=-1, help="column panels per group in the item order of wide matrices (tuning knob)")
     ap.add_argument("--xcd-pool", type=int, default=-1, help="0: resident-A kernel deals every item statically (tuning knob)")
     ap.add_argument("--factor-dtype", choices=("fp32", "bf16"), default="fp32",
                     help="storage type of the LoRA factors (fp32 is what the workloads prescribe)")
@@ -153,6 +154,8 @@ def main():
         L.lsw_set_option(ctx, L.LSW_OPT_RESIDENT_Q, args.resident_q)
     if args.xcd_pool >= 0:
         L.lsw_set_option(ctx, L.LSW_OPT_XCD_POOL, args.xcd_pool)
+    if args.panel_group >= 0:
+        L.lsw_set_option(ctx, L.LSW_OPT_PANEL_GROUP, args.panel_group)
     stream = torch.cuda.current_stream().cuda_stream
 
     n_tokens = args.warmup + args.steps

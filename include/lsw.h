@@ -294,9 +294,12 @@ enum {
                                 operand of one work item fits LDS and most weights lie in matrices of 4, 8, 16 or 32 column
                                 panels, A is kept in LDS across the items of a panel and each XCD walks its own eighth of
                                 the items; 0 = always the kernel that streams A per step */
-  LSW_OPT_XCD_POOL = 9       /* that kernel: 1 (default) = the last sixteenth of every XCD's items forms a pool that workgroups
+  LSW_OPT_XCD_POOL = 9,      /* that kernel: 1 (default) = the last sixteenth of every XCD's items forms a pool that workgroups
                                 draw from once their own share is done (XCDs differ in speed by 2-3 %); 0 = all items dealt
                                 statically; n >= 2 = the last 1/n instead.  The result is the same bit for bit */
+  LSW_OPT_PANEL_GROUP = 10   /* matrix-core kernels for fused ranks up to 64: order of the items inside a matrix with many
+                                column panels (lsw_worklist_item_grouped); -1 (default) = chosen per launch so that the
+                                packed A operand of one group stays within 2 MB, 0 = rows outermost, n = groups of n */
 };
 enum {
   LSW_Q_N_LINEARS = 1, LSW_Q_N_LAYERS = 2,
@@ -323,6 +326,12 @@ int64_t    lsw_worklist_size(const int32_t* out, const int32_t* in, int32_t n_li
 lsw_status lsw_worklist_item(const int32_t* out, const int32_t* in, int32_t n_lin,
                              int32_t tile_rows, int32_t tile_cols, int64_t item,
                              int32_t* lin, int32_t* row0, int32_t* n_rows, int32_t* col0, int32_t* n_cols);
+/* The same with the column panels of a linear taken in groups of panel_group (LSW_OPT_PANEL_GROUP): inside a linear
+ * that has more panels than that, all row blocks of the first panel_group panels come first (rows outermost), then
+ * those of the next group, and so on; the last group may be narrower.  panel_group = 0 is lsw_worklist_item. */
+lsw_status lsw_worklist_item_grouped(const int32_t* out, const int32_t* in, int32_t n_lin,
+                                     int32_t tile_rows, int32_t tile_cols, int32_t panel_group, int64_t item,
+                                     int32_t* lin, int32_t* row0, int32_t* n_rows, int32_t* col0, int32_t* n_cols);
 
 void        lsw_destroy(lsw_ctx* ctx);       /* frees what the library owns; NULL is allowed */
 const char* lsw_last_error(void);            /* message of the last failing call on this thread */

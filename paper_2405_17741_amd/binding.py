@@ -13,7 +13,7 @@ import numpy as np
 
 LSW_OK, LSW_ERR_ARG, LSW_ERR_SHAPE, LSW_ERR_STATE, LSW_ERR_NOMEM, LSW_ERR_DEVICE = range(6)
 LSW_MAX_K = 8
-LSW_OPT_KERNEL, LSW_OPT_STRICT_STATE, LSW_OPT_GRID, LSW_OPT_TILE_COLS, LSW_OPT_XCD_REMAP, LSW_OPT_GEMV_GRID, LSW_OPT_ONE_PASS, LSW_OPT_RESIDENT_Q, LSW_OPT_XCD_POOL = 1, 2, 3, 4, 5, 6, 7, 8, 9
+LSW_OPT_KERNEL, LSW_OPT_STRICT_STATE, LSW_OPT_GRID, LSW_OPT_TILE_COLS, LSW_OPT_XCD_REMAP, LSW_OPT_GEMV_GRID, LSW_OPT_ONE_PASS, LSW_OPT_RESIDENT_Q, LSW_OPT_XCD_POOL, LSW_OPT_PANEL_GROUP = 1, 2, 3, 4, 5, 6, 7, 8, 9, 10
 (LSW_Q_N_LINEARS, LSW_Q_N_LAYERS, LSW_Q_LAST_KERNEL, LSW_Q_LAST_ITEMS, LSW_Q_LAST_GRID, LSW_Q_PACKED_BYTES,
  LSW_Q_GEMV_X_ELEMS, LSW_Q_GEMV_Y_ELEMS, LSW_Q_LAST_VARIANT) = range(1, 10)
 KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
@@ -21,7 +21,7 @@ LSW_FACTOR_F32, LSW_FACTOR_BF16 = 0, 1
 
 EXPORTS = (
     "lsw_create_adapters", "lsw_switch", "lsw_merged_gemv", "lsw_route", "lsw_build_terms",
-    "lsw_get_state", "lsw_set_option", "lsw_query", "lsw_worklist_size", "lsw_worklist_item",
+    "lsw_get_state", "lsw_set_option", "lsw_query", "lsw_worklist_size", "lsw_worklist_item", "lsw_worklist_item_grouped",
     "lsw_destroy", "lsw_last_error", "lsw_probe_inplace", "lsw_merged_gemv_all",
     "lsw_route_dev", "lsw_switch_dev", "lsw_dev_status", "lsw_gemv_bf16", "lsw_create_adapters_ex",
     "lsw_set_base", "lsw_rebase", "lsw_enable_adapter_path", "lsw_adapter_workspace_bytes", "lsw_route_batch_dev",
@@ -86,6 +86,8 @@ def lib() -> C.CDLL:
         L.lsw_worklist_size.restype = C.c_int64
         L.lsw_worklist_item.argtypes = [_i32p, _i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int64,
                                         _i32p, _i32p, _i32p, _i32p, _i32p]
+        L.lsw_worklist_item_grouped.argtypes = [_i32p, _i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int64,
+                                                _i32p, _i32p, _i32p, _i32p, _i32p]
         L.lsw_probe_inplace.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         L.lsw_destroy.argtypes = [C.c_void_p]
         L.lsw_destroy.restype = None
@@ -264,6 +266,14 @@ def lsw_worklist_item(out, inn, tile_rows: int, tile_cols: int, item: int):
     ia, ip, _ = _i32(inn)
     v = [C.c_int32(0) for _ in range(5)]
     _check(lib().lsw_worklist_item(op, ip, n, tile_rows, tile_cols, item, *[C.byref(x) for x in v]))
+    return tuple(x.value for x in v)   # lin, row0, n_rows, col0, n_cols
+
+
+def lsw_worklist_item_grouped(out, inn, tile_rows: int, tile_cols: int, panel_group: int, item: int):
+    oa, op, n = _i32(out)
+    ia, ip, _ = _i32(inn)
+    v = [C.c_int32(0) for _ in range(5)]
+    _check(lib().lsw_worklist_item_grouped(op, ip, n, tile_rows, tile_cols, panel_group, item, *[C.byref(x) for x in v]))
     return tuple(x.value for x in v)   # lin, row0, n_rows, col0, n_cols
 
 

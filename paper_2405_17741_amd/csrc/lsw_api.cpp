@@ -84,7 +84,7 @@ struct lsw_ctx {
   int64_t owned_bytes = 0;
   int64_t x_elems = 0, y_elems = 0;          // sizes of the back-to-back x and y of lsw_merged_gemv_all
   std::map<PlanKey, DevicePlan> plans;
-  int opt_kernel = 0, opt_strict = 0, opt_grid = 0, opt_tile_cols = kMfmaTileCols, opt_tile_cols_bigk = kMfmaBigkTileCols, opt_xcd = 3, opt_gemv_grid = 0, opt_one_pass = 1, opt_resident = 1, opt_pool = 1;
+  int opt_kernel = 0, opt_strict = 0, opt_grid = 0, opt_tile_cols = kMfmaTileCols, opt_tile_cols_bigk = kMfmaBigkTileCols, opt_xcd = 3, opt_gemv_grid = 0, opt_one_pass = 1, opt_resident = 1, opt_pool = 1, opt_panel_group = -1;
   int last_kernel = 0, last_variant = 0, last_items = 0, last_grid = 0;
 };
 
@@ -194,11 +194,11 @@ extern "C" int64_t lsw_worklist_size(const int32_t* out, const int32_t* in, int3
   return n;
 }
 
-extern "C" lsw_status lsw_worklist_item(const int32_t* out, const int32_t* in, int32_t n_lin,
-                                        int32_t tile_rows, int32_t tile_cols, int64_t item,
-                                        int32_t* lin, int32_t* row0, int32_t* n_rows, int32_t* col0,
-                                        int32_t* n_cols) {
-  if (!shapes_ok(out, in, n_lin, tile_rows, tile_cols) || !lin || !row0 || !n_rows || !col0 || !n_cols)
+extern "C" lsw_status lsw_worklist_item_grouped(const int32_t* out, const int32_t* in, int32_t n_lin,
+                                                int32_t tile_rows, int32_t tile_cols, int32_t panel_group, int64_t item,
+                                                int32_t* lin, int32_t* row0, int32_t* n_rows, int32_t* col0,
+                                                int32_t* n_cols) {
+  if (!shapes_ok(out, in, n_lin, tile_rows, tile_cols) || panel_group < 0 || !lin || !row0 || !n_rows || !col0 || !n_cols)
     return fail(LSW_ERR_ARG, "lsw_worklist_item: bad argument");
   std::vector<int32_t> first(size_t(n_lin) + 1, 0);
   int64_t total = 0;
@@ -210,13 +210,20 @@ extern "C" lsw_status lsw_worklist_item(const int32_t* out, const int32_t* in, i
   if (item < 0 || item >= total) return fail(LSW_ERR_ARG, "item %lld outside [0,%lld)", (long long)item, (long long)total);
   int32_t s = find_segment(first.data(), n_lin, int32_t(item));
   int32_t r0, c0;
-  decode_item(int32_t(item) - first[s], in[s], tile_rows, tile_cols, &r0, &c0);
+  decode_item(int32_t(item) - first[s], out[s], in[s], tile_rows, tile_cols, panel_group, &r0, &c0);
   *lin = s;
   *row0 = r0;
   *col0 = c0;
   *n_rows = std::min(tile_rows, out[s] - r0);
   *n_cols = std::min(tile_cols, in[s] - c0);
   return LSW_OK;
+}
+
+extern "C" lsw_status lsw_worklist_item(const int32_t* out, const int32_t* in, int32_t n_lin,
+                                        int32_t tile_rows, int32_t tile_cols, int64_t item,
+                                        int32_t* lin, int32_t* row0, int32_t* n_rows, int32_t* col0,
+                                        int32_t* n_cols) {
+  return lsw_worklist_item_grouped(out, in, n_lin, tile_rows, tile_cols, 0, item, lin, row0, n_rows, col0, n_cols);
 }
 
 // ---------------------------------------------------------------------------
@@ -430,16 +437,25 @@ static lsw_status launch_switch(lsw_ctx* c, const std::vector<int32_t>& sel_laye
     // stays compact, and each packed A is fetched into one L2 instead of eight.  Measured: 70B shape 47.4 against
     // 50.2 ms, 7B with bf16-stored factors 4,076 against 4,121 us; 13B shape (5 and 13.5 panels) 9,300 against 9,180 us
     // on a fresh machine, so it keeps the round-wise order.
+    // Item order inside wide matrices (LSW_OPT_PANEL_GROUP): rows outermost, unless the launch runs in per-XCD order and
+    // the packed A a row of items needs (fused rank x in x 2 bytes x Q parts) exceeds 1.5 MB in some matrix: then an XCD's
+    // 32 concurrent items would pull more of it through the 4 MB L2 per round than survives next to the W stream (the
+    // 70B `down`, 28 panels of 256 KB at 4 terms, fetched 3.57 GB where 1.92 GB are needed), and the panels are taken
+    // in groups of 4.  Measured on the 70B shape: 4-term launches 48.4 against 50.0 ms.  Not for smaller operands (7B:
+    // 0.8 % slower) and not in the round-wise order (13B: 2-4 % slower).
     bool per_xcd = false;
+    int panel_group = 0;
     if (kernel == 2 && !bigk) {
-      int64_t reuse = 0, total = 0;
+      int64_t reuse = 0, total = 0, widest_q = 0;
       for (const lsw_linear& L : c->lin) {
         if (!sel_layers.empty() && !std::binary_search(sel_layers.begin(), sel_layers.end(), L.layer)) continue;
         const int64_t w = int64_t(L.out) * L.in;
         total += w;
         if ((grid / 8) % ceil_div(L.in, tc) == 0) reuse += w;
+        widest_q = std::max(widest_q, int64_t(n_groups) * 8 * L.in * 2 * c->qp);
       }
       per_xcd = 2 * reuse >= total;
+      panel_group = c->opt_panel_group >= 0 ? c->opt_panel_group : (per_xcd && widest_q > (3 << 19)) ? 4 : 0;
     }
     // The resident-Q kernel on top of that where the Q of one item (8 KB per 256 columns, k-step and Q part) fits LDS.
     // fp32-stored factors only: with bf16-stored ones (half the Q bytes) the streaming kernel measured 1.3 % faster; and
@@ -452,7 +468,7 @@ static lsw_status launch_switch(lsw_ctx* c, const std::vector<int32_t>& sel_laye
     lsw_status st = get_plan(c, kernel, tc, sel_layers, &dp);
     if (st != LSW_OK) return st;
     LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, tc, xcd_mode, from_base ? 1 : 0, c->opt_one_pass, nullptr, 0, LinDesc{},
-                  c->opt_pool ? c->d_err + 2 : nullptr, c->opt_pool == 1 ? 16 : c->opt_pool};
+                  c->opt_pool ? c->d_err + 2 : nullptr, c->opt_pool == 1 ? 16 : c->opt_pool, panel_group};
     hipError_t e = (kernel == 2) ? (bigk ? launch_switch_mfma_bigk(lp, t, t_dev, c->r, c->qp, grid, s)
                                   : resident ? launch_switch_mfma_res(lp, t, t_dev, c->r, c->qp, grid, s)
                                              : launch_switch_mfma(lp, t, t_dev, c->r, c->qp, grid, s))
@@ -807,6 +823,10 @@ extern "C" lsw_status lsw_set_option(lsw_ctx* c, int32_t option, int64_t value) 
       return LSW_OK;
     case LSW_OPT_RESIDENT_Q:
       c->opt_resident = value != 0;
+      return LSW_OK;
+    case LSW_OPT_PANEL_GROUP:
+      if (value < -1 || value > 1024) return fail(LSW_ERR_ARG, "panel group out of range");
+      c->opt_panel_group = int(value);
       return LSW_OK;
     case LSW_OPT_XCD_POOL:
       if (value < 0 || value > (1 << 20)) return fail(LSW_ERR_ARG, "pool option out of range");

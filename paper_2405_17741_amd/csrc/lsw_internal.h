@@ -59,11 +59,24 @@ LSW_HD inline int32_t find_segment(const int32_t* first, int32_t n_sel, int32_t 
   return lo;
 }
 
-LSW_HD inline void decode_item(int32_t local, int32_t in, int32_t tile_rows, int32_t tile_cols,
+// Item `local` of a linear -> its first row and column.  Row-major over (row block, column panel) by default.  With
+// group > 0 and more than `group` column panels the panels are taken in groups of `group` (the last one may be
+// narrower): all row blocks of one group, row-major, before the next group, so that the part of the packed A operand
+// a run of consecutive items needs stays small.
+LSW_HD inline void decode_item(int32_t local, int32_t out, int32_t in, int32_t tile_rows, int32_t tile_cols, int32_t group,
                                int32_t* row0, int32_t* col0) {
-  int32_t ncc = ceil_div(in, tile_cols);
-  *row0 = (local / ncc) * tile_rows;
-  *col0 = (local % ncc) * tile_cols;
+  const int32_t ncc = ceil_div(in, tile_cols);
+  if (group <= 0 || ncc <= group) {
+    *row0 = (local / ncc) * tile_rows;
+    *col0 = (local % ncc) * tile_cols;
+    return;
+  }
+  const int32_t per_group = ceil_div(out, tile_rows) * group;      // items of a full group
+  const int32_t g = local / per_group;
+  const int32_t width = (ncc - g * group < group) ? ncc - g * group : group;
+  const int32_t l = local - g * per_group;
+  *row0 = (l / width) * tile_rows;
+  *col0 = (g * group + l % width) * tile_cols;
 }
 
 constexpr int kResidentLdsBytes = 128 * 1024;   // LDS the resident-Q matrix-core kernel may use for one item's Q
@@ -96,6 +109,7 @@ struct LaunchPlan {             // device pointers + counts for one launch
   // finished; the kernel leaves both at zero), or null for a purely static split of the items.
   int32_t* pool;
   int32_t pool_div;             // every XCD range gives its last 1/pool_div to the pool
+  int32_t panel_group;          // column panels per group in the item order of a linear (see decode_item); 0 = row-major
 };
 
 // Kernel launchers (lsw_kernels.hip).  All return the hipError of the launch.

@@ -199,7 +199,7 @@ __global__ __launch_bounds__(256) void k_switch_valu(LaunchPlan p, Terms t, cons
     const int s = find_segment(p.first, p.n_sel, item);
     const LinDesc L = p.lin[p.sel[s]];
     int row0, col0;
-    decode_item(item - p.first[s], L.in, VT_ROWS, VT_COLS, &row0, &col0);
+    decode_item(item - p.first[s], L.out, L.in, VT_ROWS, VT_COLS, 0, &row0, &col0);
 
     float acc[4][8];
 #pragma unroll
@@ -362,7 +362,7 @@ __device__ __forceinline__ void mfma_load_item(const LaunchPlan& p, int item, in
     local = uniform(item - p.first[seg]);
   }
   int row0, col0;
-  decode_item(local, L.in, tile_rows, p.tile_cols, &row0, &col0);
+  decode_item(local, L.out, L.in, tile_rows, p.tile_cols, p.panel_group, &row0, &col0);
   row0 += row_shift;          // the calling wave's 32 rows inside a taller item (may lie past the last row)
   it.W = L.W;
   it.Wsrc = p.from_base ? L.Wbase : L.W;
@@ -816,7 +816,7 @@ __device__ __forceinline__ void res_item_at(const LaunchPlan& p, int item, ResIt
   c.out = uniform(Lp->out);
   c.in = uniform(Lp->in);
   c.item = item;
-  decode_item(uniform(item - p.first[c.seg]), c.in, kMfmaTileRows, p.tile_cols, &c.row0, &c.col0);
+  decode_item(uniform(item - p.first[c.seg]), c.out, c.in, kMfmaTileRows, p.tile_cols, p.panel_group, &c.row0, &c.col0);
 }
 
 // the B rows of this lane's row of item c (its half of every k-step), as stored
@@ -1371,7 +1371,7 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
     const void* B = L.B;
     const int out = L.out, in = L.in;
     int row0, col0;
-    decode_item(local, in, kMfmaTileRows, p.tile_cols, &row0, &col0);
+    decode_item(local, out, in, kMfmaTileRows, p.tile_cols, 0, &row0, &col0);
     row0 += 32 * wave;
     const int col_end = min(in, col0 + p.tile_cols);
     const int ncb = ceil_div(in, MT_STEP);
@@ -1852,7 +1852,7 @@ __global__ __launch_bounds__(64) void k_probe_inplace(LaunchPlan p) {
     const LinDesc* Lp = p.lin + uniform(p.sel[seg]);
     const int out = uniform(Lp->out), in = uniform(Lp->in);
     int row0, col0;
-    decode_item(uniform(item - p.first[seg]), in, 32, p.tile_cols, &row0, &col0);
+    decode_item(uniform(item - p.first[seg]), out, in, 32, p.tile_cols, 0, &row0, &col0);
     const int col_end = min(in, col0 + p.tile_cols);
     const __amdgpu_buffer_rsrc_t res = w_resource(uniform(Lp->W), out * in * 2);
     const uint32_t stride = uint32_t(in) * 2u;

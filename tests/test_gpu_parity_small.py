@@ -225,6 +225,41 @@ def test_item_pool_against_the_static_split(variant):
     b.close()
 
 
+@pytest.mark.parametrize("resident", [1, 0])
+@pytest.mark.parametrize("group", [1, 3, 4])
+def test_panel_groups_change_the_item_order_and_nothing_else(resident, group):
+    """LSW_OPT_PANEL_GROUP takes the column panels of a wide matrix in groups (all row blocks of one group before the
+    next); the launch must still touch every tile exactly once: same bits as the rows-outermost order, and the oracle's bar."""
+    E, r = 4, 8
+    dims = [(260, 4104), (520, 2056), (130, 256), (300, 1288)]          # 17, 9, 1 and 6 panels of 256 columns
+    rng = np.random.default_rng(515 + group)
+    host = [I.host_linear(rng, o, n, E, r, 0.02, 1 / 16, 0.01) for o, n in dims]
+    shapes = [(0, p, o, n) for p, (o, n) in enumerate(dims)]
+    a = DeviceStack.from_host(host, shapes, E, r, kernel=L.KERNEL_MFMA)
+    b = DeviceStack.from_host(host, shapes, E, r, kernel=L.KERNEL_MFMA)
+    for ds in (a, b):
+        L.lsw_set_option(ds.ctx, L.LSW_OPT_TILE_COLS, 256)
+        L.lsw_set_option(ds.ctx, L.LSW_OPT_RESIDENT_Q, resident)
+        L.lsw_set_option(ds.ctx, L.LSW_OPT_XCD_REMAP, 2)
+    L.lsw_set_option(a.ctx, L.LSW_OPT_PANEL_GROUP, group)
+    L.lsw_set_option(b.ctx, L.LSW_OPT_PANEL_GROUP, 0)
+    none = (np.zeros(0, np.int32), np.zeros(0, np.float32))
+    seq = [none, (np.array([1, 2], np.int32), np.array([0.7, 0.3], np.float32)),
+           (np.array([2, 0], np.int32), np.array([0.45, 0.55], np.float32)), none]
+    prev = [a.rows(p) for p in range(len(dims))]
+    for old, new in zip(seq[:-1], seq[1:]):
+        a.switch(old, new)
+        b.switch(old, new)
+        for p in range(len(dims)):
+            ga, gb = a.rows(p), b.rows(p)
+            assert (ga == gb).all(), p
+            rep, _ = check_step(prev[p], ga, host[p][1], host[p][2], old, new)
+            assert rep["fail"] == 0, p
+            prev[p] = ga
+    a.close()
+    b.close()
+
+
 @pytest.mark.parametrize("kernel", KERNELS)
 def test_stack_with_layer_subsets_guard_bands_and_state(kernel):
     wl = I.Workload("mini", 3, 64, 136, 32, 6, 8, 2, 4, 0.02, 1 / 8, 0.01, 4242)

@@ -136,6 +136,33 @@ def test_worklist_partitions_every_weight_exactly_once(tile):
     assert L.lsw_worklist_size(out, inn, 0, tc) == -1
 
 
+@pytest.mark.parametrize("group", [1, 2, 3, 4, 8])
+def test_grouped_worklist_is_a_permutation_of_the_plain_one(group):
+    """Panels in groups: inside a linear with more panels than the group size, all row blocks of one group of panels come
+    before the next group; the set of tiles is the same as in the plain order, each exactly once."""
+    tr, tc = 32, 256
+    out = np.array([256, 100, 33, 64, 1, 96], np.int32)
+    inn = np.array([256, 1048, 8, 2000, 136, 2816], np.int32)      # 1, 5, 1, 8, 1, 11 panels
+    n = L.lsw_worklist_size(out, inn, tr, tc)
+    plain = {L.lsw_worklist_item(out, inn, tr, tc, it) for it in range(n)}
+    seen = []
+    for it in range(n):
+        seen.append(L.lsw_worklist_item_grouped(out, inn, tr, tc, group, it))
+    assert len(set(seen)) == n and set(seen) == plain
+    assert [s[0] for s in seen] == sorted(s[0] for s in seen)                       # still linear by linear
+    for lin in range(len(out)):
+        mine = [s for s in seen if s[0] == lin]
+        panels = -(-int(inn[lin]) // tc)
+        if panels <= group:                                                           # few panels: the plain order
+            assert mine == sorted(mine, key=lambda s: (s[1], s[3]))
+        else:                                                                         # group of the panel never decreases; rows outermost inside
+            keys = [(s[3] // tc // group, s[1], s[3]) for s in mine]
+            assert keys == sorted(keys)
+    assert L.lsw_worklist_item_grouped(out, inn, tr, tc, 0, 7) == L.lsw_worklist_item(out, inn, tr, tc, 7)
+    with pytest.raises(L.LswError):
+        L.lsw_worklist_item_grouped(out, inn, tr, tc, -1, 0)
+
+
 def test_worklist_counts_of_the_7b_workload():
     shapes = I.WORKLOADS["7b"].linear_shapes()
     out = np.array([s[2] for s in shapes], np.int32)

@@ -333,6 +333,18 @@ lsw_status lsw_worklist_item_grouped(const int32_t* out, const int32_t* in, int3
                                      int32_t tile_rows, int32_t tile_cols, int32_t panel_group, int64_t item,
                                      int32_t* lin, int32_t* row0, int32_t* n_rows, int32_t* col0, int32_t* n_cols);
 
+/*
+ * Which work items a workgroup of a per-XCD launch (LSW_OPT_XCD_REMAP) takes, as a pure function of the counts; host
+ * helpers, no device; the kernels use the same routines.  XCD x = workgroups x, x + 8, ... owns items
+ * [x * per, (x + 1) * per), per = ceil(n_items / 8); workgroup `block` takes first, first + step, ... below static_end;
+ * the last pool_len items of every range go to the pool, where claim number g (an atomic counter at run time) stands
+ * for lsw_walk_pool_item(g), or for nothing (-1) once the pool is empty.  pool_div <= 0 = no pool.
+ * share = {first, step, static_end, per, pool_len}.  LSW_ERR_ARG unless n_items >= 0, grid a positive multiple of 8
+ * and 0 <= block < grid.
+ */
+lsw_status lsw_walk_share(int32_t n_items, int32_t grid, int32_t block, int32_t pool_div, int32_t share[5]);
+int32_t    lsw_walk_pool_item(int32_t n_items, int32_t grid, int32_t pool_div, int32_t claim);
+
 void        lsw_destroy(lsw_ctx* ctx);       /* frees what the library owns; NULL is allowed */
 const char* lsw_last_error(void);            /* message of the last failing call on this thread */
 

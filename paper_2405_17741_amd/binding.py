@@ -21,7 +21,7 @@ LSW_FACTOR_F32, LSW_FACTOR_BF16 = 0, 1
 
 EXPORTS = (
     "lsw_create_adapters", "lsw_switch", "lsw_merged_gemv", "lsw_route", "lsw_build_terms",
-    "lsw_get_state", "lsw_set_option", "lsw_query", "lsw_worklist_size", "lsw_worklist_item", "lsw_worklist_item_grouped",
+    "lsw_get_state", "lsw_set_option", "lsw_query", "lsw_worklist_size", "lsw_worklist_item", "lsw_worklist_item_grouped", "lsw_walk_share", "lsw_walk_pool_item",
     "lsw_destroy", "lsw_last_error", "lsw_probe_inplace", "lsw_merged_gemv_all",
     "lsw_route_dev", "lsw_switch_dev", "lsw_dev_status", "lsw_gemv_bf16", "lsw_create_adapters_ex",
     "lsw_set_base", "lsw_rebase", "lsw_enable_adapter_path", "lsw_adapter_workspace_bytes", "lsw_route_batch_dev",
@@ -88,6 +88,9 @@ def lib() -> C.CDLL:
                                         _i32p, _i32p, _i32p, _i32p, _i32p]
         L.lsw_worklist_item_grouped.argtypes = [_i32p, _i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int64,
                                                 _i32p, _i32p, _i32p, _i32p, _i32p]
+        L.lsw_walk_share.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, _i32p]
+        L.lsw_walk_pool_item.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+        L.lsw_walk_pool_item.restype = C.c_int32
         L.lsw_probe_inplace.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         L.lsw_destroy.argtypes = [C.c_void_p]
         L.lsw_destroy.restype = None
@@ -275,6 +278,16 @@ def lsw_worklist_item_grouped(out, inn, tile_rows: int, tile_cols: int, panel_gr
     v = [C.c_int32(0) for _ in range(5)]
     _check(lib().lsw_worklist_item_grouped(op, ip, n, tile_rows, tile_cols, panel_group, item, *[C.byref(x) for x in v]))
     return tuple(x.value for x in v)   # lin, row0, n_rows, col0, n_cols
+
+
+def lsw_walk_share(n_items: int, grid: int, block: int, pool_div: int):
+    v = (C.c_int32 * 5)()
+    _check(lib().lsw_walk_share(n_items, grid, block, pool_div, v))
+    return tuple(v)          # first, step, static_end, per, pool_len
+
+
+def lsw_walk_pool_item(n_items: int, grid: int, pool_div: int, claim: int) -> int:
+    return int(lib().lsw_walk_pool_item(n_items, grid, pool_div, claim))
 
 
 def lsw_probe_inplace(ctx: int, waves_per_cu: int, stream: int = 0) -> None:

@@ -219,6 +219,24 @@ extern "C" lsw_status lsw_worklist_item_grouped(const int32_t* out, const int32_
   return LSW_OK;
 }
 
+extern "C" lsw_status lsw_walk_share(int32_t n_items, int32_t grid, int32_t block, int32_t pool_div, int32_t share[5]) {
+  if (n_items < 0 || grid <= 0 || grid % 8 != 0 || block < 0 || block >= grid || !share)
+    return fail(LSW_ERR_ARG, "lsw_walk_share: bad argument");
+  const WalkShare w = walk_share(n_items, grid, block, pool_div > 0, pool_div);
+  share[0] = w.first;
+  share[1] = w.step;
+  share[2] = w.static_end;
+  share[3] = w.per;
+  share[4] = w.pool_len;
+  return LSW_OK;
+}
+
+extern "C" int32_t lsw_walk_pool_item(int32_t n_items, int32_t grid, int32_t pool_div, int32_t claim) {
+  if (n_items < 0 || grid <= 0 || grid % 8 != 0) return -1;
+  const WalkShare w = walk_share(n_items, grid, 0, pool_div > 0, pool_div);
+  return walk_pool_item(n_items, w.per, w.pool_len, claim);
+}
+
 extern "C" lsw_status lsw_worklist_item(const int32_t* out, const int32_t* in, int32_t n_lin,
                                         int32_t tile_rows, int32_t tile_cols, int64_t item,
                                         int32_t* lin, int32_t* row0, int32_t* n_rows, int32_t* col0,

@@ -79,6 +79,38 @@ LSW_HD inline void decode_item(int32_t local, int32_t out, int32_t in, int32_t t
   *col0 = (g * group + l % width) * tile_cols;
 }
 
+// Per-XCD order of a matrix-core launch: XCD x (workgroups x, x + 8, ...: the hardware deals workgroups round-robin)
+// owns items [x * per, (x + 1) * per); its grid / 8 workgroups take consecutive items per round, except that the last
+// pool_len items of every range form a pool dealt out one by one through an atomic counter (claim g -> walk_pool_item).
+// A pool only where every workgroup of every XCD keeps at least two static items (the same answer in all workgroups).
+struct WalkShare {
+  int32_t first;        // the workgroup's first item (none if it is not below static_end: never with a pool)
+  int32_t step;         // distance of its consecutive static items
+  int32_t static_end;   // end of the statically dealt part of its XCD's range
+  int32_t per;          // items per range (the last range may be shorter)
+  int32_t pool_len;     // items every range gives to the pool (its last ones); 0 = no pool
+};
+
+LSW_HD inline WalkShare walk_share(int32_t n_items, int32_t grid, int32_t block, bool pool, int32_t pool_div) {
+  WalkShare w;
+  w.step = grid >> 3;
+  w.per = ceil_div(n_items, 8);
+  w.pool_len = w.per / (pool_div > 1 ? pool_div : 1);
+  if (!pool || n_items - 7 * w.per - w.pool_len < 2 * w.step) w.pool_len = 0;
+  const int32_t xcd = block & 7;
+  const int32_t range_end = (xcd + 1) * w.per < n_items ? (xcd + 1) * w.per : n_items;
+  w.static_end = range_end - w.pool_len;
+  w.first = xcd * w.per + (block >> 3);
+  return w;
+}
+
+// pool claim g -> item: claims go round the eight ranges, position g / 8 of the range's pool part; -1 when the pool is empty
+LSW_HD inline int32_t walk_pool_item(int32_t n_items, int32_t per, int32_t pool_len, int32_t g) {
+  if (g < 0 || g >= 8 * pool_len) return -1;
+  const int32_t range_end = ((g & 7) + 1) * per < n_items ? ((g & 7) + 1) * per : n_items;
+  return range_end - pool_len + (g >> 3);
+}
+
 constexpr int kResidentLdsBytes = 128 * 1024;   // LDS the resident-Q matrix-core kernel may use for one item's Q
 
 // Tile shapes of the two switch kernels (rows x columns of one work item).

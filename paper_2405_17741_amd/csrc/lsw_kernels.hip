@@ -542,12 +542,6 @@ struct ItemWalk {             // every field is uniform over the workgroup
 // claim handed over at the last barrier while wave 0 already writes the next one.
 __shared__ int32_t s_walk_claim[2];
 
-// pool claim g -> item: claims go round the eight ranges, position g / 8 of the range's pool part; -1 when the pool is empty
-__device__ __forceinline__ int walk_pool_item(const ItemWalk& w, int g) {
-  if (g >= 8 * w.pool_len) return -1;
-  return min(w.n_items, ((g & 7) + 1) * w.per) - w.pool_len + (g >> 3);
-}
-
 // wave 0, before the barrier that precedes walk_take_claim: hand the answered claim to the workgroup
 __device__ __forceinline__ void walk_publish_claim(const ItemWalk& w, int wave, int claim) {
   if (wave == 0) s_walk_claim[w.slot] = __builtin_amdgcn_readfirstlane(claim);
@@ -555,7 +549,7 @@ __device__ __forceinline__ void walk_publish_claim(const ItemWalk& w, int wave, 
 
 // every wave, after that barrier: the claimed item, or -1 when the pool was empty
 __device__ __forceinline__ int walk_take_claim(ItemWalk& w) {
-  const int item = walk_pool_item(w, uniform(s_walk_claim[w.slot]));
+  const int item = walk_pool_item(w.n_items, w.per, w.pool_len, uniform(s_walk_claim[w.slot]));
   w.slot ^= 1;
   w.after_pool = false;       // until walk_plan_after says otherwise
   return item;
@@ -575,14 +569,12 @@ __device__ __forceinline__ int walk_init(const LaunchPlan& p, bool per_xcd, Item
     w.static_end = p.n_items;
     return p.xcd_remap ? xcd_contiguous_block(blockIdx.x, gridDim.x) : int(blockIdx.x);
   }
-  w.step = int(gridDim.x) >> 3;
-  w.per = ceil_div(p.n_items, 8);
-  // a pool only where every workgroup of every XCD keeps at least two static items (the same answer in all workgroups)
-  w.pool_len = w.per / max(1, p.pool_div);
-  if (p.pool == nullptr || p.n_items - 7 * w.per - w.pool_len < 2 * w.step) w.pool_len = 0;
-  const int xcd = int(blockIdx.x) & 7;
-  w.static_end = min(p.n_items, (xcd + 1) * w.per) - w.pool_len;
-  return xcd * w.per + (int(blockIdx.x) >> 3);
+  const WalkShare sh = walk_share(p.n_items, int(gridDim.x), int(blockIdx.x), p.pool != nullptr, p.pool_div);
+  w.step = sh.step;
+  w.per = sh.per;
+  w.pool_len = sh.pool_len;
+  w.static_end = sh.static_end;
+  return sh.first;
 }
 
 // after `item` has become the next one: where the item after it comes from (wave 0 claims it now if it is a pool item)

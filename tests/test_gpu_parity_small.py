@@ -221,6 +221,22 @@ def test_item_pool_against_the_static_split(variant):
     both(seq[2], seq[3], [0, 2])          # subset launches (fewer items, other pool size) between full ones
     both(seq[2], seq[3], [1, 3])
     both(seq[3], seq[4], None)
+
+    # the pool counters are reset by the kernel itself, so recorded launches replay correctly: merge and unmerge of one
+    # set, each recorded once, replayed in turn, against the same switches launched eagerly with the static split
+    graphs = []
+    for old, new in ((seq[0], seq[1]), (seq[1], seq[0])):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            a.switch(old, new)                # recorded, not run
+        graphs.append((g, old, new))
+    for _ in range(2):
+        for g, old, new in graphs:
+            g.replay()
+            b.switch(old, new)
+            torch.cuda.synchronize()
+            for p in range(len(dims)):
+                assert (a.rows(p) == b.rows(p)).all(), p
     a.close()
     b.close()
 

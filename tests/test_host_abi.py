@@ -163,6 +163,38 @@ def test_grouped_worklist_is_a_permutation_of_the_plain_one(group):
         L.lsw_worklist_item_grouped(out, inn, tr, tc, -1, 0)
 
 
+@pytest.mark.parametrize("n_items,grid,pool_div", [(49408, 256, 16), (49408, 256, 0), (1299, 64, 16), (614, 64, 16), (141, 64, 16),
+                                                  (5, 256, 16), (0, 8, 16), (4096, 256, 3), (12345, 248, 16), (263, 16, 2)])
+def test_per_xcd_walk_hands_out_every_item_exactly_once(n_items, grid, pool_div):
+    """Static columns of all workgroups plus the pool claims cover [0, n_items) exactly once; with a pool every workgroup
+    keeps at least two static items; claims beyond the pool stand for nothing."""
+    taken = np.zeros(n_items, np.int32)
+    pool_len = None
+    for block in range(grid):
+        first, step, static_end, per, pl = L.lsw_walk_share(n_items, grid, block, pool_div)
+        assert step == grid // 8 and per == -(-n_items // 8)
+        pool_len = pl if pool_len is None else pool_len
+        assert pl == pool_len                                  # the same decision in every workgroup
+        mine = list(range(first, static_end, step))
+        if pl > 0:
+            assert len(mine) >= 2
+        for it in mine:
+            taken[it] += 1
+    if pool_div <= 0:
+        assert pool_len == 0
+    for g in range(8 * pool_len):
+        it = L.lsw_walk_pool_item(n_items, grid, pool_div, g)
+        assert 0 <= it < n_items
+        taken[it] += 1
+    assert (taken == 1).all()
+    for g in (8 * pool_len, 8 * pool_len + 1, 8 * pool_len + 255, -1):
+        assert L.lsw_walk_pool_item(n_items, grid, pool_div, g) == -1
+    with pytest.raises(L.LswError):
+        L.lsw_walk_share(n_items, grid + 1, 0, pool_div)
+    with pytest.raises(L.LswError):
+        L.lsw_walk_share(n_items, grid, grid, pool_div)
+
+
 def test_worklist_counts_of_the_7b_workload():
     shapes = I.WORKLOADS["7b"].linear_shapes()
     out = np.array([s[2] for s in shapes], np.int32)

@@ -476,9 +476,9 @@ static lsw_status launch_switch(lsw_ctx* c, const std::vector<int32_t>& sel_laye
       panel_group = c->opt_panel_group >= 0 ? c->opt_panel_group : (per_xcd && widest_q > (3 << 19)) ? 4 : 0;
     }
     // The resident-Q kernel on top of that where the Q of one item (8 KB per 256 columns, k-step and Q part) fits LDS.
-    // fp32-stored factors only: with bf16-stored ones (half the Q bytes) the streaming kernel measured 1.3 % faster; and
-    // not at half the item width to make K = 48-64 fit: on the 70B shape that gained 5 % on 3-term launches and lost as
-    // much on 4-term ones.
+    // fp32-stored factors only: with bf16-stored ones (half the Q bytes) the streaming kernel is as fast or faster; and
+    // not at half the item width to make K = 48-64 fit: on the 70B shape that gained 1.4 % on 3-term launches and lost
+    // 11 % on 4-term ones (the kernel spills registers at 4 k-steps).
     const bool resident = per_xcd && c->opt_resident && c->qp == 2 &&
                           (tc / kApkBlockCols) * ((n_groups + 1) / 2) * 8 * c->qp * 1024 <= kResidentLdsBytes;
     // LSW_OPT_XCD_REMAP: 3 = automatic

@@ -127,7 +127,8 @@ struct LaunchPlan {             // device pointers + counts for one launch
   int32_t n_sel;
   int32_t n_items;
   int32_t tile_cols;            // columns of one work item (matrix-core kernel: a multiple of kApkBlockCols)
-  int32_t xcd_remap;            // 1: each XCD takes a contiguous eighth of every grid-wide round of items
+  int32_t xcd_remap;            // 0: workgroup b takes items b, b + grid, ...; 1: each XCD takes a contiguous eighth of every
+                                // grid-wide round of items; 2 (k_switch_mfma): each XCD walks its own eighth of the list
   int32_t from_base;            // 1: the switch kernels read Wbase instead of W (and still write W): lsw_rebase
   int32_t exact_one_pass;       // 1: bf16-stored factors of a rank that is a multiple of 16 run one matrix-core pass (chunked kernel)
   // Adapter-path mode of the matrix-core kernels (Z != null): ONE matrix, described by `one` (W = the [T, out]
@@ -137,7 +138,7 @@ struct LaunchPlan {             // device pointers + counts for one launch
   const float* Z;
   int32_t z_stride;
   LinDesc one;
-  // Resident-Q kernel: two zeroed counters in device memory ([0] items claimed from the shared pool, [1] workgroups
+  // Per-XCD order of k_switch_mfma / k_switch_mfma_res: two zeroed counters in device memory ([0] items claimed from the shared pool, [1] workgroups
   // finished; the kernel leaves both at zero), or null for a purely static split of the items.
   int32_t* pool;
   int32_t pool_div;             // every XCD range gives its last 1/pool_div to the pool

@@ -20,15 +20,26 @@ pytestmark = pytest.mark.gpu
 NONE = (np.zeros(0, np.int32), np.zeros(0, np.float32))
 
 
-def _run_sampled(wl, check_steps, full_linears=(), n_random_rows=61, kernel=L.KERNEL_AUTO):
+def _run_sampled(wl, check_steps, full_linears=(), n_random_rows=61, kernel=L.KERNEL_AUTO, factor_dtype=torch.float32,
+                 device_routed=False):
+    """factor_dtype bf16: the factors are stored as bf16 (the oracle gets exactly those values).  device_routed: every
+    token's (ids, gates) comes from lsw_route_dev and stays on the device, the switch is lsw_switch_dev (term list built
+    on the device, launches sized for k_old + k_new terms); ids must equal the oracle router's, the gates it produced are
+    what the oracle's switch is given."""
     shapes = wl.linear_shapes()
-    stack = I.device_stack(wl)
+    stack = I.device_stack(wl, factor_dtype=factor_dtype)
     ds = DeviceStack(stack, shapes, wl.experts, wl.rank, kernel=kernel)
     rng = np.random.default_rng(wl.seed + 1)
     rows = [I.sample_rows(rng, o, n_random_rows) for _, _, o, _ in shapes]
-    A_host = [A.cpu().numpy() for _, A, _ in stack]
-    B_rows = [B.index_select(1, torch.as_tensor(r, device=B.device)).cpu().numpy() for (_, _, B), r in zip(stack, rows)]
-    routes = [O.route(l, wl.top_k) for l in I.router_logits(wl)]
+    A_host = [A.float().cpu().numpy() for _, A, _ in stack]
+    B_rows = [B.index_select(1, torch.as_tensor(r, device=B.device)).float().cpu().numpy() for (_, _, B), r in zip(stack, rows)]
+    logits = I.router_logits(wl)
+    routes = [O.route(l, wl.top_k) for l in logits]
+    stream = torch.cuda.current_stream().cuda_stream
+    if device_routed:
+        logits_d = torch.from_numpy(logits.copy()).cuda()
+        bufs = [(torch.zeros(wl.top_k, dtype=torch.int32, device="cuda"), torch.zeros(wl.top_k, dtype=torch.float32, device="cuda"))
+                for _ in range(2)]
     old = NONE
     reports, kernels = [], set()
     for t, new in enumerate(routes, start=1):
@@ -36,7 +47,15 @@ def _run_sampled(wl, check_steps, full_linears=(), n_random_rows=61, kernel=L.KE
         if checked:
             before = [ds.rows(p, rows[p]) for p in range(len(shapes))]
             full_before = {p: ds.rows(p) for p in full_linears} if t == 1 else {}
-        ds.switch(old, new)
+        if device_routed:
+            (oi, og), (ni, ng) = bufs[t % 2], bufs[(t + 1) % 2]
+            L.lsw_route_dev(ds.ctx, logits_d[t - 1].data_ptr(), wl.top_k, ni.data_ptr(), ng.data_ptr(), stream)
+            L.lsw_switch_dev(ds.ctx, oi.data_ptr(), og.data_ptr(), 0 if t == 1 else wl.top_k, ni.data_ptr(), ng.data_ptr(), wl.top_k,
+                             stream=stream)
+            assert ni.cpu().numpy().tolist() == new[0].tolist(), t           # the selection: bit-exact
+            new = (new[0], ng.cpu().numpy().copy())                          # the device router's own gates
+        else:
+            ds.switch(old, new)
         kernels.add(L.lsw_query(ds.ctx, L.LSW_Q_LAST_KERNEL))
         if checked:
             step_reports = []
@@ -56,6 +75,8 @@ def _run_sampled(wl, check_steps, full_linears=(), n_random_rows=61, kernel=L.KE
                   f"clause2={tot['needed_clause2']} maxdist={tot['max_dist']} kernels={sorted(kernels)}", flush=True)
             reports.append(tot)
         old = new
+    if device_routed:
+        assert L.lsw_dev_status(ds.ctx) == 0
     ds.close()
     return reports, kernels
 
@@ -67,6 +88,24 @@ def test_7b_full_size_sampled_rows_every_linear():
     reports, kernels = _run_sampled(wl, {1, 2, 3, 32, 64}, full_linears=full)
     assert kernels <= {L.KERNEL_MFMA}
     assert len(reports) == 5 and all(r["exact_frac"] > 0.999 for r in reports)
+
+
+def test_7b_full_size_factors_stored_as_bf16():
+    """The launch configuration `bench.py --factor-dtype bf16` times: the streaming kernel, each XCD on its own eighth of the
+    items, the tail of every eighth dealt through the pool."""
+    wl = I.Workload(**{**I.WORKLOADS["7b"].__dict__, "steps": 8})
+    reports, kernels = _run_sampled(wl, {1, 2, 8}, n_random_rows=13, factor_dtype=torch.bfloat16)
+    assert kernels == {L.KERNEL_MFMA}
+    assert len(reports) == 3 and all(r["exact_frac"] > 0.999 for r in reports)
+
+
+def test_7b_full_size_device_routed_token_steps():
+    """lsw_route_dev + lsw_switch_dev over the whole stack: the kernels are sized for four terms and read a list of three
+    or four from device memory."""
+    wl = I.Workload(**{**I.WORKLOADS["7b"].__dict__, "steps": 8})
+    reports, kernels = _run_sampled(wl, {1, 2, 3, 8}, n_random_rows=13, device_routed=True)
+    assert kernels == {L.KERNEL_MFMA}
+    assert len(reports) == 4 and all(r["exact_frac"] > 0.999 for r in reports)
 
 
 def test_13b_shape_with_forced_reuse_two_layers():

@@ -1,0 +1,230 @@
+// liblsw device code (gfx950): the un-merged adapter path for prompts (down-projection, gate table).
+#include "lsw_device.h"
+#include "lsw_mfma.h"
+
+namespace lsw {
+
+// ---------------------------------------------------------------------------
+// Un-merged adapter path for many tokens (Eq. 2: y = f(x) + sum_i G(x1)_i E_i(x), E_i(x) = W_up (W_down x)).
+//
+// Three launches per linear.  (1) k_adapter_down: U = X A_all^T on the matrix cores, all E*r down-projection rows of
+// all experts at once (N = E*r is at most 256, so computing the unselected experts too costs nothing next to the
+// traffic), the long contraction over `in` cut into slices whose partial sums go to Upart[slice][T][N].
+// (2) k_adapter_gate: Z[t][e*r+rho] = scale * g(t,e) * sum_slices Upart (zero for experts token t did not select):
+// the gather of the token's experts is a multiplication by a mostly-zero gate table.  (3) the matrix-core switch
+// kernels in adapter mode: Y[T,out] <- rne(Y + Z B_all^T), rows = tokens, the row operand read from Z, the shared
+// operand B^T packed like A (k_pack_A, transposed source).
+//
+// k_adapter_down.  A workgroup is 32 tokens x one slice of `in`, its four waves sharing the slice.  X is bf16 and needs no split; A is
+// split into bf16 high + low (two passes).  The contraction index inside a 64-column chunk u is laid out so that a
+// lane reads 64 contiguous bytes of its token's row: k-step s (0..3), lane half h, element i  <->  column
+// 64u + 32h + 8s + i.  The A operand comes from a re-laid-out copy built once (k_pack_Atk):
+//   Atk bf16 [N/32 blocks][in/64 chunks][4 k-steps][parts][64 lanes][8]
+// holding for lane (h, n) the 8 values A_all[32*block + n][64u + 32h + 8s + i]: one operand load of a wave is 1 KB
+// contiguous.  Rows of A_all past E*r and columns past `in` hold zeros.
+// ---------------------------------------------------------------------------
+constexpr int AD_CHUNK = 64;        // columns of `in` per chunk (4 k-steps of 16)
+
+// 32-row blocks of A_all the layout holds: more than 4 are rounded up to 8 (the kernel takes them in two groups of 4)
+__host__ __device__ static inline int adapter_blocks_dev(int N) { const int nb = ceil_div(N, 32); return nb > 4 ? 8 : nb; }
+static int adapter_blocks(int N) { return adapter_blocks_dev(N); }
+
+int64_t adapter_atk_elems(int E, int r, int in, int qp) {
+  return int64_t(adapter_blocks(E * r)) * ceil_div(in, AD_CHUNK) * 4 * qp * 64 * 8;
+}
+
+// 64-column chunks one workgroup (4 waves, chunks dealt round-robin to the waves) contracts: about 512 workgroups per
+// launch, at least 4 chunks each (one per wave) unless the matrix has fewer
+static int adapter_chunks_per_slice(int T, int in) {
+  const int nch = ceil_div(in, AD_CHUNK);
+  const long long tiles = ceil_div(T, 32);
+  const long long cps = std::max<long long>(4, (nch * tiles + 511) / 512);
+  return int(std::min<long long>(nch, cps));
+}
+
+int adapter_slices(int T, int in) { return ceil_div(ceil_div(in, AD_CHUNK), adapter_chunks_per_slice(T, in)); }
+
+template <int QP>
+__global__ __launch_bounds__(256) void k_pack_Atk(const void* __restrict__ A, uint16_t* __restrict__ Atk, int N, int in) {
+  const int nb_count = adapter_blocks_dev(N), nch = ceil_div(in, AD_CHUNK);
+  const long long total = (long long)nb_count * nch * 4 * 64;
+  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (long long)gridDim.x * blockDim.x) {
+    const int lane = int(idx & 63), s4 = int((idx >> 6) & 3);
+    const long long bu = idx >> 8;
+    const int u = int(bu % nch), nb = int(bu / nch);
+    const int row = 32 * nb + (lane & 31), j = AD_CHUNK * u + 32 * (lane >> 5) + 8 * s4;
+    float x[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = (row < N && j < in) ? load1<QP>(A, (long long)row * in + j + i) : 0.0f;   // in % 8 == 0: all 8 or none
+    u32x4 hi, lo;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      uint32_t hh, ll;
+      split2(x[2 * q], x[2 * q + 1], &hh, &ll);
+      hi[q] = hh;
+      lo[q] = ll;
+    }
+    const long long base = (((long long)(nb * nch + u) * 4 + s4) * QP * 64 + lane) * 8;
+    *reinterpret_cast<u32x4*>(Atk + base) = hi;
+    if constexpr (QP == 2) *reinterpret_cast<u32x4*>(Atk + base + 64 * 8) = lo;
+  }
+}
+
+hipError_t launch_pack_Atk(const void* A, uint16_t* Atk, int E, int r, int in, int qp, hipStream_t s) {
+  const long long total = (long long)adapter_blocks(E * r) * ceil_div(in, AD_CHUNK) * 4 * 64;
+  const int grid = int(std::min<long long>((total + 255) / 256, 1 << 16));
+  if (qp == 2) hipLaunchKernelGGL(k_pack_Atk<2>, dim3(grid), dim3(256), 0, s, A, Atk, E * r, in);
+  else hipLaunchKernelGGL(k_pack_Atk<1>, dim3(grid), dim3(256), 0, s, A, Atk, E * r, in);
+  return hipGetLastError();
+}
+
+template <int NB, int QP>
+struct AdChunk {            // the operands of one 64-column chunk: this lane's 64 bytes of X and its pieces of A
+  u32x4 xp[4];
+  u32x4 qv[NB][4][QP];
+};
+
+template <int NB, int QP>
+__device__ __forceinline__ void ad_load_chunk(AdChunk<NB, QP>& c, __amdgpu_buffer_rsrc_t xres, uint32_t row_off, int in, int nch,
+                                              int u, int h, const LSW_GLOBAL u32x4* q0) {
+#pragma unroll
+  for (int s4 = 0; s4 < 4; ++s4) {
+    const int j = AD_CHUNK * u + 32 * h + 8 * s4;
+    c.xp[s4] = __builtin_amdgcn_raw_buffer_load_b128(xres, (u < nch && j < in) ? row_off + uint32_t(j) * 2u : kOutOfRange, 0, 0);
+  }
+  const int uq = min(u, nch - 1);       // past the last chunk: X reads zeros, A re-reads a valid chunk
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    const LSW_GLOBAL u32x4* q = q0 + ((long long)(nb * nch + uq) * 4) * QP * 64;      // q0 is block 0 of this workgroup's group
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4)
+#pragma unroll
+      for (int hl = 0; hl < QP; ++hl) c.qv[nb][s4][hl] = q[(s4 * QP + hl) * 64];
+  }
+}
+
+template <int NB, int QP>
+__device__ __forceinline__ void ad_compute_chunk(const AdChunk<NB, QP>& c, f32x16 (&acc)[NB]) {
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4)
+#pragma unroll
+      for (int hl = QP - 1; hl >= 0; --hl)       // the small (low-part) products first
+        acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, c.xp[s4]),
+                                                          __builtin_bit_cast(bf16x8, c.qv[nb][s4][hl]), acc[nb], 0, 0, 0);
+}
+
+// A workgroup = 32 tokens x one slice of `in` (cps chunks); its 4 waves take the chunks u0 + w, u0 + w + 4, ... with the
+// operands of the next chunk requested before the current one is multiplied, then add their accumulators through LDS.
+template <int NB, int QP>
+__global__ __launch_bounds__(256) void k_adapter_down(const uint16_t* __restrict__ X, const uint16_t* __restrict__ Atk,
+                                                      float* __restrict__ Upart, int T, int in, int N, int cps) {
+  __shared__ float red[3][NB][16][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = lane & 31, h = lane >> 5;
+  const int tile = blockIdx.x, slice = blockIdx.y;
+  const int nch = ceil_div(in, AD_CHUNK);
+  const int u0 = slice * cps, u1 = min(nch, u0 + cps);
+  // X through a buffer resource: token rows past T lie outside it and read as zeros
+  const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(X), 0, T * in * 2, 0x00020000);
+  const uint32_t row_off = uint32_t(32 * tile + n) * uint32_t(in) * 2u;
+  f32x16 acc[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[nb][v] = 0.0f;
+  const int nb0 = blockIdx.z * NB;       // N above 128: the 32-column blocks are split over blockIdx.z
+  const LSW_GLOBAL u32x4* q0 = (const LSW_GLOBAL u32x4*)Atk + (long long)nb0 * nch * 4 * QP * 64 + lane;
+  AdChunk<NB, QP> ca, cb;
+  int u = u0 + wave;
+  if (u < u1) ad_load_chunk<NB, QP>(ca, xres, row_off, in, nch, u, h, q0);
+  while (u < u1) {                       // two chunks per trip: one in flight while the other is multiplied
+    if (u + 4 < u1) ad_load_chunk<NB, QP>(cb, xres, row_off, in, nch, u + 4, h, q0);
+    ad_compute_chunk<NB, QP>(ca, acc);
+    u += 4;
+    if (u >= u1) break;
+    if (u + 4 < u1) ad_load_chunk<NB, QP>(ca, xres, row_off, in, nch, u + 4, h, q0);
+    ad_compute_chunk<NB, QP>(cb, acc);
+    u += 4;
+  }
+  if (wave > 0) {
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) red[wave - 1][nb][v][lane] = acc[nb][v];
+  }
+  __syncthreads();
+  if (wave > 0) return;
+  // acc[nb][v] is U[token 32*tile + 8*(v/4) + 4h + v%4][column 32*nb + n]
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    const int col = 32 * (nb0 + nb) + n;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int t = 32 * tile + 8 * (v >> 2) + 4 * h + (v & 3);
+      const float sum = ((acc[nb][v] + red[0][nb][v][lane]) + red[1][nb][v][lane]) + red[2][nb][v][lane];
+      if (t < T && col < N) Upart[((long long)slice * T + t) * N + col] = sum;
+    }
+  }
+}
+
+hipError_t launch_adapter_down(const uint16_t* X, const uint16_t* Atk, float* Upart, int T, int in, int N, int qp, hipStream_t s) {
+  const int cps = adapter_chunks_per_slice(T, in);
+  const int nb = ceil_div(N, 32);
+  const dim3 grid(ceil_div(T, 32), adapter_slices(T, in), nb > 4 ? 2 : 1);
+#define LSW_AD(NB_)                                                                                              \
+  do {                                                                                                           \
+    if (qp == 2) hipLaunchKernelGGL((k_adapter_down<NB_, 2>), grid, dim3(256), 0, s, X, Atk, Upart, T, in, N, cps); \
+    else hipLaunchKernelGGL((k_adapter_down<NB_, 1>), grid, dim3(256), 0, s, X, Atk, Upart, T, in, N, cps);         \
+  } while (0)
+  if (nb <= 1) LSW_AD(1);
+  else if (nb <= 2) LSW_AD(2);
+  else if (nb <= 8) LSW_AD(4);            // 5..8 blocks: two groups of 4 (the packed layout is padded to whole groups)
+  else return hipErrorInvalidValue;
+#undef LSW_AD
+  return hipGetLastError();
+}
+
+// Z[t][col] = scale * g(t, expert of col) * sum over the slices of Upart[.][t][col]; columns N..z_stride-1 are zeroed.
+// A token's list is checked as the switch's lists are: an id outside [0, E), a duplicate id or a non-finite gate
+// raises the sticky error word (flag 2) and gives that token an all-zero row (its output stays what it was).
+__global__ __launch_bounds__(256) void k_adapter_gate(const float* __restrict__ Upart, int n_slices, const int32_t* __restrict__ ids,
+                                                      const float* __restrict__ gates, int k, int T, int E, int r, float scale,
+                                                      float* __restrict__ Z, int z_stride, int32_t* __restrict__ err) {
+  const int N = E * r;
+  const long long total = (long long)T * z_stride;
+  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (long long)gridDim.x * blockDim.x) {
+    const int t = int(idx / z_stride), col = int(idx - (long long)t * z_stride);
+    float z = 0.0f;
+    if (col < N) {
+      const int e = col / r;
+      bool ok = true;
+      float coeff = 0.0f;
+      for (int c = 0; c < k; ++c) {
+        const int id = ids[(long long)t * k + c];
+        const float g = gates[(long long)t * k + c];
+        ok &= (id >= 0 && id < E) && (g - g == 0.0f);
+        for (int d = 0; d < c; ++d) ok &= (ids[(long long)t * k + d] != id);
+        if (id == e) coeff = __fmul_rn(scale, g);
+      }
+      if (!ok) {
+        if (col == 0) atomicOr(err, 2);
+      } else if (coeff != 0.0f) {
+        float u = 0.0f;
+        for (int s = 0; s < n_slices; ++s) u += Upart[((long long)s * T + t) * N + col];
+        z = coeff * u;
+      }
+    }
+    Z[idx] = z;
+  }
+}
+
+hipError_t launch_adapter_gate(const float* Upart, int n_slices, const int32_t* ids, const float* gates, int k, int T, int E, int r,
+                               float scale, float* Z, int z_stride, int32_t* err, hipStream_t s) {
+  const long long total = (long long)T * z_stride;
+  const int grid = int(std::min<long long>((total + 255) / 256, 1 << 16));
+  hipLaunchKernelGGL(k_adapter_gate, dim3(grid), dim3(256), 0, s, Upart, n_slices, ids, gates, k, T, E, r, scale, Z, z_stride, err);
+  return hipGetLastError();
+}
+
+}  // namespace lsw

@@ -145,7 +145,7 @@ struct LaunchPlan {             // device pointers + counts for one launch
   int32_t panel_group;          // column panels per group in the item order of a linear (see decode_item); 0 = row-major
 };
 
-// Kernel launchers (lsw_kernels.hip).  All return the hipError of the launch.
+// Kernel launchers (one .hip file per kernel family).  All return the hipError of the launch.
 // t.n sizes the launch; with t_dev != null the kernels read the list (possibly shorter, or empty) from device memory
 // qp: 2 = fp32-stored factors (split into two bf16 parts on the matrix cores), 1 = bf16-stored factors
 hipError_t launch_switch_valu(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int qp, int grid, hipStream_t s);

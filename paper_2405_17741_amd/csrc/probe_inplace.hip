@@ -1,0 +1,67 @@
+// liblsw device code (gfx950): the in-place bandwidth probe.
+#include "lsw_device.h"
+#include "lsw_mfma.h"
+
+namespace lsw {
+
+// ---------------------------------------------------------------------------
+// Bandwidth probe: the switch kernel's W traffic and nothing else.  A persistent grid of
+// single-wave workgroups walks 32-row x tile_cols items in 32 x 256 steps (the same 512-byte row
+// segments, non-temporal 16-byte accesses and one-step-ahead requests as the switch), widens each
+// bf16 to fp32, adds +0.0f, rounds back and stores in place: every finite value is unchanged (a
+// negative zero becomes +0).  What this sustains is the ceiling of the in-place access pattern on
+// the given matrices, without factor traffic or matrix work.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void k_probe_inplace(LaunchPlan p) {
+  const int lane = threadIdx.x, n = lane & 31, h = lane >> 5;
+  const int grid = gridDim.x;
+  const int first_item = p.xcd_remap ? xcd_contiguous_block(blockIdx.x, grid) : int(blockIdx.x);
+  for (int item = first_item; item < p.n_items; item += grid) {
+    const int seg = uniform(find_segment(p.first, p.n_sel, item));
+    const LinDesc* Lp = p.lin + uniform(p.sel[seg]);
+    const int out = uniform(Lp->out), in = uniform(Lp->in);
+    int row0, col0;
+    decode_item(uniform(item - p.first[seg]), out, in, 32, p.tile_cols, 0, &row0, &col0);
+    const int col_end = min(in, col0 + p.tile_cols);
+    const __amdgpu_buffer_rsrc_t res = w_resource(uniform(Lp->W), out * in * 2);
+    const uint32_t stride = uint32_t(in) * 2u;
+    auto offset = [&](int cs) {
+      const int col = cs + 8 * n;
+      return col < col_end ? uint32_t(row0 + 4 * h) * stride + uint32_t(col) * 2u : kOutOfRange;
+    };
+    u32x4 buf[2][16];
+    uint32_t off[2];
+    off[0] = offset(col0);
+#pragma unroll
+    for (int v = 0; v < 16; ++v)
+      buf[0][v] = __builtin_amdgcn_raw_buffer_load_b128(res, off[0] + uint32_t(8 * (v >> 2) + (v & 3)) * stride, 0, 2);
+    for (int cs = col0; cs < col_end; cs += 2 * MT_STEP) {
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        const int c = cs + half * MT_STEP;
+        if (c < col_end) {
+          off[half ^ 1] = (c + MT_STEP < col_end) ? offset(c + MT_STEP) : kOutOfRange;
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            buf[half ^ 1][v] = __builtin_amdgcn_raw_buffer_load_b128(
+                res, off[half ^ 1] + uint32_t(8 * (v >> 2) + (v & 3)) * stride, 0, 2);
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            u32x4 o;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+              o[q] = pack_bf16(bf16_lo(buf[half][v][q]) + 0.0f, bf16_hi(buf[half][v][q]) + 0.0f);
+            __builtin_amdgcn_raw_buffer_store_b128(o, res, off[half] + uint32_t(8 * (v >> 2) + (v & 3)) * stride, 0, kWStoreAux);
+          }
+        }
+      }
+    }
+  }
+}
+
+hipError_t launch_probe_inplace(const LaunchPlan& p, int grid, hipStream_t s) {
+  hipLaunchKernelGGL(k_probe_inplace, dim3(grid), dim3(64), 0, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace lsw

@@ -108,6 +108,49 @@ def test_7b_full_size_device_routed_token_steps():
     assert len(reports) == 4 and all(r["exact_frac"] > 0.999 for r in reports)
 
 
+def _twin_stacks_stay_identical(wl, options_b, steps):
+    """Two copies of a stack, the second with other launch options (item order, pool, kernel choice): the orders differ,
+    the arithmetic per element does not, so after every switch EVERY weight must hold the same bits.  A skipped item or
+    one applied twice anywhere in the launch shows."""
+    shapes = wl.linear_shapes()
+    a = DeviceStack(I.device_stack(wl), shapes, wl.experts, wl.rank)
+    b = DeviceStack(I.device_stack(wl), shapes, wl.experts, wl.rank)
+    for opt, value in options_b:
+        L.lsw_set_option(b.ctx, opt, value)
+    routes = [O.route(l, wl.top_k) for l in I.router_logits(wl, steps)]
+    old = NONE
+    variants = set()
+    for t, new in enumerate(routes, start=1):
+        a.switch(old, new)
+        b.switch(old, new)
+        variants.add((L.lsw_query(a.ctx, L.LSW_Q_LAST_VARIANT), L.lsw_query(b.ctx, L.LSW_Q_LAST_VARIANT)))
+        for p in range(len(shapes)):
+            assert torch.equal(a.stack[p][0].view(torch.int16), b.stack[p][0].view(torch.int16)), (wl.name, t, p)
+        old = new
+    a.close()
+    b.close()
+    return variants
+
+
+def test_7b_full_size_pool_and_kernel_choice_leave_the_same_bits_for_64_switches():
+    """The headline launch (A resident in LDS, per-XCD order, item pool) against the streaming kernel in the round-wise
+    order on a second copy of the whole stack: all 6.5e9 weights compared after each of 64 switches."""
+    wl = I.WORKLOADS["7b"]
+    variants = _twin_stacks_stay_identical(wl, [(L.LSW_OPT_RESIDENT_Q, 0), (L.LSW_OPT_XCD_REMAP, 1)], wl.steps)
+    assert variants == {(2, 1)}
+
+
+def test_70b_shape_forty_layers_item_order_leaves_the_same_bits():
+    """Half the 70B-shaped stack twice (2 x 68 GB): per-XCD order with the pool and panel groups against the round-wise
+    order with rows outermost."""
+    free, _ = torch.cuda.mem_get_info()
+    if free < 170e9:
+        pytest.skip("needs 170 GB of free device memory")
+    wl = I.scaled(I.WORKLOADS["70b"], 40)
+    variants = _twin_stacks_stay_identical(wl, [(L.LSW_OPT_XCD_REMAP, 1), (L.LSW_OPT_PANEL_GROUP, 0), (L.LSW_OPT_RESIDENT_Q, 0)], 5)
+    assert {v[1] for v in variants} == {1}
+
+
 def test_13b_shape_with_forced_reuse_two_layers():
     wl = I.scaled(I.WORKLOADS["13b"], 2)
     reports, kernels = _run_sampled(wl, {1, 2, 3, 17, 33, 64}, n_random_rows=29)

@@ -102,7 +102,9 @@ lsw_status lsw_create_adapters_ex(const lsw_linear* lin, int32_t n_lin, int32_t 
 /*
  * The fused switch (Alg. 1 steps 2-4; Eq. 8 == Eq. 10; one launch as in Eq. 11).
  *
- *   layers, n_layers   HOST list of distinct layer numbers to switch; NULL, 0 = every layer.
+ *   layers, n_layers   HOST list of distinct layer numbers to switch; NULL, 0 = every layer.  The first call with a
+ *                      new subset (in any order) uploads a small table for it (a blocking copy; not inside a stream
+ *                      capture); the library keeps up to 256 such tables and starts over beyond that.
  *   old_ids/old_gates  HOST, k_old entries: the experts merged now (Eq. 7 removes them).  k_old = 0: none.
  *   new_ids/new_gates  HOST, k_new entries: the experts to merge (Eq. 4).  k_new = 0: restore the base weights.
  *   hip_stream         hipStream_t (NULL = default stream).  The call is asynchronous on it.

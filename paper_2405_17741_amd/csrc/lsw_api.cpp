@@ -378,11 +378,22 @@ extern "C" void lsw_destroy(lsw_ctx* c) {
 
 // ---------------------------------------------------------------------------
 // plans: which linears a launch covers and where each one's items start
+constexpr size_t kMaxPlans = 256;
 // ---------------------------------------------------------------------------
 static lsw_status get_plan(lsw_ctx* c, int kernel, int tc, const std::vector<int32_t>& layers_sorted, DevicePlan** out) {
   PlanKey key{kernel, tc, layers_sorted};
   auto it = c->plans.find(key);
   if (it != c->plans.end()) { *out = &it->second; return LSW_OK; }
+  // A caller that walks through very many different layer subsets must not grow the cache without bound: beyond
+  // kMaxPlans the tables are dropped (after the device has finished with them) and built again on demand.
+  if (c->plans.size() >= kMaxPlans) {
+    LSW_HIP(hipDeviceSynchronize());
+    for (auto& kv : c->plans) {
+      (void)hipFree(kv.second.d_sel);
+      c->owned_bytes -= int64_t(size_t(2 * kv.second.n_sel + 1) * sizeof(int32_t));
+    }
+    c->plans.clear();
+  }
   const int32_t tr = kernel == 4 ? kGemvRows : kernel == 3 ? 32 : kernel == 2 ? kMfmaTileRows : kValuTileRows;   // 3 = bandwidth probe, 4 = merged decode
   std::vector<int32_t> sel, first(1, 0);
   int64_t total = 0;

@@ -82,3 +82,41 @@ def test_longest_lists_and_smallest_shapes():
             assert rep["fail"] == 0
             prev = got
         ds.close()
+
+
+def test_many_distinct_layer_subsets_do_not_grow_the_context_without_bound():
+    """Every new layer subset gets a small device table; the library keeps at most 256 of them.  600 different subsets of a
+    10-layer stack, each merged and unmerged: the owned bytes stay bounded and the weights stay right."""
+    E, r, layers = 4, 8, 10
+    rng = np.random.default_rng(31)
+    host = [I.host_linear(rng, 64, 256, E, r, 0.02, 1 / 16, 0.01) for _ in range(layers)]
+    shapes = [(l, 0, 64, 256) for l in range(layers)]
+    ds = DeviceStack.from_host(host, shapes, E, r, kernel=L.KERNEL_MFMA)
+    base_bytes = L.lsw_query(ds.ctx, L.LSW_Q_PACKED_BYTES)
+    a = (np.array([1, 3], np.int32), np.array([0.25, 0.75], np.float32))
+    peak = 0
+    for mask in range(1, 601):
+        subset = [l for l in range(layers) if (mask >> l) & 1]
+        checked = mask % 97 == 0                             # now and then: the subset, and only it, was merged
+        if checked:
+            prev = [ds.rows(p) for p in range(layers)]
+        ds.switch(NONE, a, layers=subset)
+        if checked:
+            for p in range(layers):
+                got = ds.rows(p)
+                if p in subset:
+                    rep, _ = check_step(prev[p], got, host[p][1], host[p][2], NONE, a)
+                    assert rep["fail"] == 0
+                else:
+                    assert (got == prev[p]).all()
+        ds.switch(a, NONE, layers=subset)
+        peak = max(peak, L.lsw_query(ds.ctx, L.LSW_Q_PACKED_BYTES))
+    assert peak - base_bytes <= 257 * (2 * layers + 1) * 4
+    # merge and unmerge are not exact inverses in bf16 (one rounding each), so the state now is whatever 600 such pairs
+    # left; one more switch from it is checked like any other
+    before = [ds.rows(p) for p in range(layers)]
+    ds.switch(NONE, a)
+    for p in range(layers):
+        rep, _ = check_step(before[p], ds.rows(p), host[p][1], host[p][2], NONE, a)
+        assert rep["fail"] == 0
+    ds.close()

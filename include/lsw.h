@@ -42,7 +42,8 @@ typedef enum lsw_status {
   LSW_ERR_ARG = 1,      /* null pointer, id out of range, duplicate id, k too large, non-finite gate ... */
   LSW_ERR_SHAPE = 2,    /* unsupported shape or misaligned pointer */
   LSW_ERR_STATE = 3,    /* `old` does not match what the context knows to be merged (strict mode only); a call that needs
-                           lsw_set_base or lsw_enable_adapter_path first */
+                           lsw_set_base or lsw_enable_adapter_path first; a call made while another device than the
+                           context's (the one current at lsw_create_adapters) is the calling thread's current device */
   LSW_ERR_NOMEM = 4,    /* host or device allocation failed */
   LSW_ERR_DEVICE = 5    /* no usable HIP device, or a HIP call failed */
 } lsw_status;

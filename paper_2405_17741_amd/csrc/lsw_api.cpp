@@ -419,6 +419,15 @@ static lsw_status get_plan(lsw_ctx* c, int kernel, int tc, const std::vector<int
   return LSW_OK;
 }
 
+// A context belongs to the device that was current when it was created; its launches and copies must run there.
+static lsw_status ctx_ready(const lsw_ctx* c) {
+  if (!c) return fail(LSW_ERR_ARG, "ctx is null");
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return fail(LSW_ERR_DEVICE, "no current HIP device"); }
+  if (dev != c->device) return fail(LSW_ERR_STATE, "the context belongs to device %d, the calling thread's current device is %d", c->device, dev);
+  return LSW_OK;
+}
+
 // ---------------------------------------------------------------------------
 // the switch
 // ---------------------------------------------------------------------------
@@ -515,7 +524,7 @@ extern "C" lsw_status lsw_switch(lsw_ctx* c, const int32_t* layers, int32_t n_la
                                  const int32_t* old_ids, const float* old_gates, int32_t k_old,
                                  const int32_t* new_ids, const float* new_gates, int32_t k_new,
                                  void* hip_stream) {
-  if (!c) return fail(LSW_ERR_ARG, "ctx is null");
+  if (lsw_status ready = ctx_ready(c)) return ready;
   std::vector<int32_t> sel_layers;
   lsw_status st = select_layers(c, layers, n_layers, &sel_layers);
   if (st != LSW_OK) return st;
@@ -553,7 +562,7 @@ extern "C" lsw_status lsw_switch(lsw_ctx* c, const int32_t* layers, int32_t n_la
 // drift control: re-base the merged weights on a caller-kept copy of the base weights
 // ---------------------------------------------------------------------------
 extern "C" lsw_status lsw_set_base(lsw_ctx* c, const void* const* W_base, int32_t n_lin) {
-  if (!c) return fail(LSW_ERR_ARG, "ctx is null");
+  if (lsw_status ready = ctx_ready(c)) return ready;
   if (!W_base || n_lin != int32_t(c->lin.size())) return fail(LSW_ERR_ARG, "W_base is null or n_lin differs from the %zu registered linears", c->lin.size());
   for (int32_t p = 0; p < n_lin; ++p) {
     if (!W_base[p]) return fail(LSW_ERR_ARG, "linear %d: null base copy", p);
@@ -569,7 +578,7 @@ extern "C" lsw_status lsw_set_base(lsw_ctx* c, const void* const* W_base, int32_
 
 extern "C" lsw_status lsw_rebase(lsw_ctx* c, const int32_t* layers, int32_t n_layers,
                                  const int32_t* ids, const float* gates, int32_t k, void* hip_stream) {
-  if (!c) return fail(LSW_ERR_ARG, "ctx is null");
+  if (lsw_status ready = ctx_ready(c)) return ready;
   if (!c->have_base) return fail(LSW_ERR_STATE, "lsw_rebase: no base copies registered (lsw_set_base)");
   std::vector<int32_t> sel_layers;
   lsw_status st = select_layers(c, layers, n_layers, &sel_layers);
@@ -605,7 +614,7 @@ extern "C" lsw_status lsw_rebase(lsw_ctx* c, const int32_t* layers, int32_t n_la
 // ---------------------------------------------------------------------------
 extern "C" lsw_status lsw_route_dev(lsw_ctx* c, const float* logits_dev, int32_t k, int32_t* ids_dev, float* gates_dev,
                                     void* hip_stream) {
-  if (!c) return fail(LSW_ERR_ARG, "ctx is null");
+  if (lsw_status ready = ctx_ready(c)) return ready;
   if (k < 0 || k > LSW_MAX_K || k > c->E) return fail(LSW_ERR_ARG, "lsw_route_dev: k=%d outside 0..min(%d, E=%d)", k, int(LSW_MAX_K), c->E);
   if (!logits_dev || (k > 0 && (!ids_dev || !gates_dev))) return fail(LSW_ERR_ARG, "lsw_route_dev: null pointer");
   if (k == 0) return LSW_OK;
@@ -618,7 +627,7 @@ extern "C" lsw_status lsw_switch_dev(lsw_ctx* c, const int32_t* layers, int32_t 
                                      const int32_t* old_ids_dev, const float* old_gates_dev, int32_t k_old,
                                      const int32_t* new_ids_dev, const float* new_gates_dev, int32_t k_new,
                                      void* hip_stream) {
-  if (!c) return fail(LSW_ERR_ARG, "ctx is null");
+  if (lsw_status ready = ctx_ready(c)) return ready;
   if (c->opt_strict) return fail(LSW_ERR_STATE, "lsw_switch_dev: the host cannot check device-resident lists (strict mode is on)");
   if (k_old < 0 || k_old > LSW_MAX_K || k_old > c->E) return fail(LSW_ERR_ARG, "old: k=%d out of range", k_old);
   if (k_new < 0 || k_new > LSW_MAX_K || k_new > c->E) return fail(LSW_ERR_ARG, "new: k=%d out of range", k_new);
@@ -645,7 +654,7 @@ extern "C" lsw_status lsw_switch_dev(lsw_ctx* c, const int32_t* layers, int32_t 
 
 extern "C" lsw_status lsw_route_batch_dev(lsw_ctx* c, const float* logits_dev, int32_t n_tokens, int32_t k, int32_t* ids_dev,
                                           float* gates_dev, void* hip_stream) {
-  if (!c) return fail(LSW_ERR_ARG, "ctx is null");
+  if (lsw_status ready = ctx_ready(c)) return ready;
   if (n_tokens < 1 || n_tokens > (1 << 24)) return fail(LSW_ERR_ARG, "lsw_route_batch_dev: n_tokens=%d outside 1..2^24", n_tokens);
   if (k < 0 || k > LSW_MAX_K || k > c->E) return fail(LSW_ERR_ARG, "lsw_route_batch_dev: k=%d outside 0..min(%d, E=%d)", k, int(LSW_MAX_K), c->E);
   if (!logits_dev || (k > 0 && (!ids_dev || !gates_dev))) return fail(LSW_ERR_ARG, "lsw_route_batch_dev: null pointer");
@@ -661,7 +670,7 @@ extern "C" lsw_status lsw_route_batch_dev(lsw_ctx* c, const float* logits_dev, i
 static int z_stride_of(const lsw_ctx* c) { return ceil_div(c->E * c->r, 16) * 16; }   // whole k-steps of 16: the pad columns hold zeros
 
 extern "C" lsw_status lsw_enable_adapter_path(lsw_ctx* c) {
-  if (!c) return fail(LSW_ERR_ARG, "ctx is null");
+  if (lsw_status ready = ctx_ready(c)) return ready;
   if (c->d_adapter) return LSW_OK;
   if (c->r % 8 != 0 || c->E * c->r > 256)
     return fail(LSW_ERR_SHAPE, "the adapter path needs r %% 8 == 0 and E * r <= 256 (E=%d, r=%d)", c->E, c->r);
@@ -708,7 +717,7 @@ extern "C" int64_t lsw_adapter_workspace_bytes(const lsw_ctx* c, int32_t lin_ind
 extern "C" lsw_status lsw_adapter_forward(lsw_ctx* c, int32_t lin_index, const void* X_bf16, int32_t T,
                                           const int32_t* ids_dev, const float* gates_dev, int32_t k,
                                           void* Y_bf16, void* workspace, void* hip_stream) {
-  if (!c) return fail(LSW_ERR_ARG, "ctx is null");
+  if (lsw_status ready = ctx_ready(c)) return ready;
   if (!c->d_adapter) return fail(LSW_ERR_STATE, "lsw_adapter_forward: call lsw_enable_adapter_path first");
   if (lin_index < 0 || size_t(lin_index) >= c->lin.size()) return fail(LSW_ERR_ARG, "lin_index %d out of range", lin_index);
   if (T < 1) return fail(LSW_ERR_ARG, "T=%d < 1", T);
@@ -749,7 +758,8 @@ extern "C" lsw_status lsw_adapter_forward(lsw_ctx* c, int32_t lin_index, const v
 }
 
 extern "C" lsw_status lsw_dev_status(lsw_ctx* c, int32_t* flags) {
-  if (!c || !flags) return fail(LSW_ERR_ARG, "null argument");
+  if (!flags) return fail(LSW_ERR_ARG, "null argument");
+  if (lsw_status ready = ctx_ready(c)) return ready;
   LSW_HIP(hipMemcpy(flags, c->d_err, sizeof(int32_t), hipMemcpyDeviceToHost));     // waits for earlier work on the null stream only
   return LSW_OK;
 }
@@ -769,7 +779,7 @@ extern "C" lsw_status lsw_gemv_bf16(const void* W_bf16, const void* x_bf16, floa
 // bandwidth probe over the registered weights
 // ---------------------------------------------------------------------------
 extern "C" lsw_status lsw_probe_inplace(lsw_ctx* c, int32_t waves_per_cu, void* hip_stream) {
-  if (!c) return fail(LSW_ERR_ARG, "ctx is null");
+  if (lsw_status ready = ctx_ready(c)) return ready;
   if (waves_per_cu < 1 || waves_per_cu > 16) return fail(LSW_ERR_ARG, "waves_per_cu=%d outside 1..16", waves_per_cu);
   DevicePlan* dp = nullptr;
   lsw_status st = get_plan(c, 3, c->opt_tile_cols, std::vector<int32_t>(), &dp);
@@ -785,7 +795,7 @@ extern "C" lsw_status lsw_probe_inplace(lsw_ctx* c, int32_t waves_per_cu, void* 
 // ---------------------------------------------------------------------------
 extern "C" lsw_status lsw_merged_gemv(lsw_ctx* c, int32_t lin_index, const void* x_bf16, float* y_fp32,
                                       void* hip_stream) {
-  if (!c) return fail(LSW_ERR_ARG, "ctx is null");
+  if (lsw_status ready = ctx_ready(c)) return ready;
   if (lin_index < 0 || size_t(lin_index) >= c->lin.size()) return fail(LSW_ERR_ARG, "lin_index %d out of range", lin_index);
   if (!x_bf16 || !y_fp32) return fail(LSW_ERR_ARG, "null vector");
   if (!aligned16(x_bf16)) return fail(LSW_ERR_SHAPE, "x is not 16-byte aligned");
@@ -798,7 +808,7 @@ extern "C" lsw_status lsw_merged_gemv(lsw_ctx* c, int32_t lin_index, const void*
 }
 
 extern "C" lsw_status lsw_merged_gemv_all(lsw_ctx* c, const void* x_all_bf16, float* y_all_fp32, void* hip_stream) {
-  if (!c) return fail(LSW_ERR_ARG, "ctx is null");
+  if (lsw_status ready = ctx_ready(c)) return ready;
   if (!x_all_bf16 || !y_all_fp32) return fail(LSW_ERR_ARG, "null vector");
   if (!aligned16(x_all_bf16)) return fail(LSW_ERR_SHAPE, "x is not 16-byte aligned");
   DevicePlan* dp = nullptr;

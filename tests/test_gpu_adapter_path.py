@@ -19,6 +19,9 @@ CASES = [
     # T, out, in, E, r, k
     (1, 8, 8, 2, 8, 1), (37, 264, 72, 4, 8, 2), (130, 520, 1032, 8, 8, 2), (300, 256, 4096, 8, 8, 2),
     (64, 1048, 136, 3, 16, 3), (100, 776, 264, 16, 16, 2), (33, 264, 200, 4, 64, 2), (257, 136, 520, 5, 24, 2),
+    # longer prompts: many token tiles and slices of the down-projection, ragged last tiles; 1, 2 and 4 blocks of 32
+    # down-projection rows
+    (1100, 136, 520, 8, 8, 2), (1030, 264, 264, 4, 8, 2), (1500, 72, 328, 8, 16, 2), (4200, 136, 264, 4, 8, 2), (4130, 72, 200, 8, 8, 2),
 ]
 
 

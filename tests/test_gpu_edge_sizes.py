@@ -120,3 +120,27 @@ def test_many_distinct_layer_subsets_do_not_grow_the_context_without_bound():
         rep, _ = check_step(before[p], ds.rows(p), host[p][1], host[p][2], NONE, a)
         assert rep["fail"] == 0
     ds.close()
+
+
+def test_options_reject_values_outside_their_documented_range():
+    rng = np.random.default_rng(3)
+    host = [I.host_linear(rng, 32, 64, 2, 8, 0.02, 1 / 8, 0.01)]
+    ds = DeviceStack.from_host(host, [(0, 0, 32, 64)], 2, 8)
+    bad = [(L.LSW_OPT_KERNEL, 3), (L.LSW_OPT_GRID, -1), (L.LSW_OPT_TILE_COLS, 100), (L.LSW_OPT_TILE_COLS, 0),
+           (L.LSW_OPT_XCD_REMAP, 4), (L.LSW_OPT_XCD_REMAP, -1), (L.LSW_OPT_PANEL_GROUP, -2), (L.LSW_OPT_PANEL_GROUP, 2000),
+           (L.LSW_OPT_XCD_POOL, -1), (L.LSW_OPT_GEMV_GRID, -5), (99, 0)]
+    for opt, value in bad:
+        with pytest.raises(L.LswError) as e:
+            L.lsw_set_option(ds.ctx, opt, value)
+        assert e.value.status == L.LSW_ERR_ARG, (opt, value)
+    for opt, value in [(L.LSW_OPT_XCD_REMAP, 0), (L.LSW_OPT_XCD_REMAP, 3), (L.LSW_OPT_PANEL_GROUP, -1), (L.LSW_OPT_PANEL_GROUP, 4),
+                       (L.LSW_OPT_XCD_POOL, 0), (L.LSW_OPT_XCD_POOL, 32), (L.LSW_OPT_TILE_COLS, 512)]:
+        L.lsw_set_option(ds.ctx, opt, value)
+    assert L.lsw_query(ds.ctx, 99) == -1
+    # the stack still switches correctly under those settings
+    a = (np.array([1], np.int32), np.array([1.0], np.float32))
+    before = ds.rows(0)
+    ds.switch(NONE, a)
+    rep, _ = check_step(before, ds.rows(0), host[0][1], host[0][2], NONE, a)
+    assert rep["fail"] == 0
+    ds.close()

@@ -85,3 +85,26 @@ def merge_reports(reports):
     tot["max_dist"] = mx
     tot["exact_frac"] = tot["exact"] / max(tot["n"], 1)
     return tot
+
+
+def gate_quality(tot, label, rank=8, exact_min=None, clause2_max=None):
+    """Beyond "no failing element": how MANY elements may differ from the oracle at all, and how many may lean on the
+    second clause of the comparison rule.  A correct kernel differs from the oracle only where the exact sum lies within
+    its accumulation error of a rounding boundary, and needs the second clause only where the result cancels to within
+    2^8 times that error of zero; both rates follow from the arithmetic (three-pass split-bf16 products: about 2^-18
+    relative per product, so the error of the sum grows like sqrt(K) with the fused rank K).  Measured on the full-size
+    stacks: 0.99983-0.99994 bit-equal and 5e-6 - 1.2e-5 on the second clause at ranks 8 and 16 (K = 24-64), 0.99963-0.99974
+    and 1.6e-5 - 2.1e-5 at rank 64 (K = 192-256).  The gates sit a factor of about two beyond those; a kernel with
+    bf16-rounded factors in a single pass (97 % bit-equal) or a systematic error near zero fails them.
+    Small samples get an absolute allowance of a few elements on top (Poisson noise)."""
+    if exact_min is None:
+        exact_min = 0.9995 if rank >= 32 else 0.9998
+    if clause2_max is None:
+        clause2_max = 5e-5 if rank >= 32 else 2e-5
+    n = max(tot["n"], 1)
+    slack = 6.0 * (n ** 0.5)                      # sampling noise of the differing-element count
+    print(f"[quality {label}] n={n} exact_frac={tot['exact_frac']:.6f} (gate {exact_min}) "
+          f"clause2_rate={tot['needed_clause2'] / n:.2e} (gate {clause2_max:.0e}) max_dist={tot['max_dist']}", flush=True)
+    assert tot["fail"] == 0, (label, tot)
+    assert tot["exact"] >= exact_min * n - slack * ((1 - exact_min) ** 0.5) - 2, (label, "too few bit-equal elements", tot)
+    assert tot["needed_clause2"] <= clause2_max * n + 6.0 * (clause2_max * n) ** 0.5 + 2, (label, "too many elements on the second clause", tot)

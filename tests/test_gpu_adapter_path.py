@@ -68,6 +68,8 @@ def test_adapter_forward_against_oracle(case, bf16_factors):
     S = O.adapter_magnitude(X, A, B, ids, gates, 0.5)
     rep = C.switch_parity(got, want, Y, S)
     assert rep["fail"] == 0, {k_: v for k_, v in rep.items() if k_ != "fail_mask"}
+    print(f"[adapter quality {case} bf16={bf16_factors}] n={rep['n']} exact_frac={rep['exact'] / rep['n']:.6f} "
+          f"clause2={rep['needed_clause2']} max_dist={rep['max_dist']}", flush=True)
     assert rep["exact"] > 0.995 * rep["n"]
     assert (got != Y).mean() > 0.2, "the adapter term must have changed a good part of Y"
     assert L.lsw_dev_status(ds.ctx) == 0

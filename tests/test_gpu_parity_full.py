@@ -14,7 +14,7 @@ import torch
 from oracle import lsw_oracle as O
 from paper_2405_17741_amd import binding as L
 from paper_2405_17741_amd import inputs as I
-from tests.gpu_harness import DeviceStack, check_step, merge_reports
+from tests.gpu_harness import DeviceStack, check_step, gate_quality, merge_reports
 
 pytestmark = pytest.mark.gpu
 NONE = (np.zeros(0, np.int32), np.zeros(0, np.float32))
@@ -73,6 +73,7 @@ def _run_sampled(wl, check_steps, full_linears=(), n_random_rows=61, kernel=L.KE
             tot = merge_reports(step_reports)
             print(f"[{wl.name} step {t}] n={tot['n']} exact={tot['exact_frac']:.6f} "
                   f"clause2={tot['needed_clause2']} maxdist={tot['max_dist']} kernels={sorted(kernels)}", flush=True)
+            gate_quality(tot, f"{wl.name} step {t}", rank=wl.rank)
             reports.append(tot)
         old = new
     if device_routed:
@@ -87,7 +88,7 @@ def test_7b_full_size_sampled_rows_every_linear():
     full = (int(rng.integers(0, 32)) * 7 + 0, int(rng.integers(0, 32)) * 7 + 4)   # one 4096x4096, one 11008x4096
     reports, kernels = _run_sampled(wl, {1, 2, 3, 32, 64}, full_linears=full)
     assert kernels <= {L.KERNEL_MFMA}
-    assert len(reports) == 5 and all(r["exact_frac"] > 0.999 for r in reports)
+    assert len(reports) == 5
 
 
 def test_7b_full_size_factors_stored_as_bf16():
@@ -96,7 +97,7 @@ def test_7b_full_size_factors_stored_as_bf16():
     wl = I.Workload(**{**I.WORKLOADS["7b"].__dict__, "steps": 8})
     reports, kernels = _run_sampled(wl, {1, 2, 8}, n_random_rows=13, factor_dtype=torch.bfloat16)
     assert kernels == {L.KERNEL_MFMA}
-    assert len(reports) == 3 and all(r["exact_frac"] > 0.999 for r in reports)
+    assert len(reports) == 3
 
 
 def test_7b_full_size_device_routed_token_steps():
@@ -105,7 +106,7 @@ def test_7b_full_size_device_routed_token_steps():
     wl = I.Workload(**{**I.WORKLOADS["7b"].__dict__, "steps": 8})
     reports, kernels = _run_sampled(wl, {1, 2, 3, 8}, n_random_rows=13, device_routed=True)
     assert kernels == {L.KERNEL_MFMA}
-    assert len(reports) == 4 and all(r["exact_frac"] > 0.999 for r in reports)
+    assert len(reports) == 4
 
 
 def _twin_stacks_stay_identical(wl, options_b, steps):
@@ -155,7 +156,6 @@ def test_13b_shape_with_forced_reuse_two_layers():
     wl = I.scaled(I.WORKLOADS["13b"], 2)
     reports, kernels = _run_sampled(wl, {1, 2, 3, 17, 33, 64}, n_random_rows=29)
     assert L.KERNEL_MFMA in kernels
-    assert all(r["exact_frac"] > 0.999 for r in reports)
     # the stream really reuses experts: some steps have 3 terms (one id in both sets)
     routes = [O.route(l, 2)[0].tolist() for l in I.router_logits(wl)]
     reuse = sum(len(set(a) & set(b)) > 0 for a, b in zip(routes[:-1], routes[1:]))
@@ -167,7 +167,6 @@ def test_70b_shape_one_layer():
     wl = I.Workload(**{**wl.__dict__, "steps": 4})
     reports, kernels = _run_sampled(wl, {1, 2, 4}, n_random_rows=13)
     assert kernels == {L.KERNEL_MFMA}
-    assert all(r["exact_frac"] > 0.999 for r in reports)
 
 
 def test_7b_rank64_one_layer():
@@ -175,7 +174,6 @@ def test_7b_rank64_one_layer():
     wl = I.Workload(**{**wl.__dict__, "steps": 3})
     reports, kernels = _run_sampled(wl, {1, 2, 3}, n_random_rows=13)
     assert kernels == {L.KERNEL_MFMA}          # fused ranks 64..256: the chunked matrix-core kernel
-    assert all(r["exact_frac"] > 0.999 for r in reports)
 
 
 def test_13b_full_size_sampled_rows_every_linear():
@@ -183,7 +181,7 @@ def test_13b_full_size_sampled_rows_every_linear():
     wl = I.Workload(**{**I.WORKLOADS["13b"].__dict__, "steps": 6})
     reports, kernels = _run_sampled(wl, {1, 2, 6}, n_random_rows=13)
     assert kernels == {L.KERNEL_MFMA}
-    assert len(reports) == 3 and all(r["exact_frac"] > 0.999 for r in reports)
+    assert len(reports) == 3
 
 
 def test_7b_rank64_full_size_sampled_rows_every_linear():
@@ -191,7 +189,7 @@ def test_7b_rank64_full_size_sampled_rows_every_linear():
     wl = I.Workload(**{**I.WORKLOADS["7b_r64"].__dict__, "steps": 3})
     reports, kernels = _run_sampled(wl, {1, 2, 3}, n_random_rows=13)
     assert kernels == {L.KERNEL_MFMA}
-    assert len(reports) == 3 and all(r["exact_frac"] > 0.998 for r in reports)
+    assert len(reports) == 3
 
 
 def test_70b_full_size_sampled_rows_every_linear():
@@ -203,4 +201,4 @@ def test_70b_full_size_sampled_rows_every_linear():
     wl = I.Workload(**{**I.WORKLOADS["70b"].__dict__, "steps": 2})
     reports, kernels = _run_sampled(wl, {1, 2}, n_random_rows=5)
     assert kernels == {L.KERNEL_MFMA}
-    assert len(reports) == 2 and all(r["exact_frac"] > 0.999 for r in reports)
+    assert len(reports) == 2

@@ -90,3 +90,51 @@ def test_planted_mistakes_are_caught():
     assert O.adapter_forward(Y, X, A, B, ids, gates, 0.5).tolist() == want
     for name, f in mistakes.items():
         assert np.asarray(f()).tolist() != want, name
+
+
+def test_adapter_magnitude_bruteforce_and_closed_form():
+    # S pinned from BOTH sides: a quadruple loop over the definition sum_c |s g| sum_rho |B| sum_j |A||x| on a tiny case
+    # (mixed signs everywhere, negative scale), and a closed form where every factor has magnitude one.
+    Y, X, A, B, ids, gates = _case(15, T=3, inn=5, out=4, E=3, r=2)
+    gates = gates * np.array([[1.0, -1.0]], np.float32)          # a negative gate: only its magnitude may enter
+    S = O.adapter_magnitude(X, A, B, ids, gates, -1.5)
+    Xf = O.bf16_bits_to_f64(X)
+    for t in range(3):
+        for i in range(4):
+            s = 0.0
+            for c in range(2):
+                e = int(ids[t, c])
+                up = 0.0
+                for rho in range(2):
+                    down = sum(abs(float(A[e, rho, j])) * abs(float(Xf[t, j])) for j in range(5))
+                    up += abs(float(B[e, i, rho])) * down
+                s += 1.5 * abs(float(gates[t, c])) * up
+            assert S[t, i] == pytest.approx(s, rel=1e-14)
+    # all |values| one: S = |scale| * (sum_c |g_c|) * r * in, whatever the signs
+    T, inn, out, E, r, k = 2, 6, 3, 4, 3, 2
+    rng = np.random.default_rng(16)
+    sgn = lambda shape: rng.choice([-1.0, 1.0], size=shape).astype(np.float32)
+    X1 = I.f32_to_bf16_bits(sgn((T, inn)))
+    ids1 = np.array([[0, 3], [2, 1]], np.int32)
+    g1 = np.array([[0.25, -0.5], [1.0, 0.125]], np.float32)
+    S1 = O.adapter_magnitude(X1, sgn((E, r, inn)), sgn((E, out, r)), ids1, g1, -2.0)
+    assert (S1 == 2.0 * np.abs(g1).sum(1, keepdims=True) * r * inn).all()
+
+
+def test_a_wrong_magnitude_fails_its_pins():
+    # planted mistakes in a copy of the definition: each one leaves the brute-force value
+    Y, X, A, B, ids, gates = _case(17, T=3, inn=5, out=4, E=3, r=2)
+    S = O.adapter_magnitude(X, A, B, ids, gates, 1.5)
+    Xa = np.abs(O.bf16_bits_to_f64(X))
+    def variant(factor=1.0, abs_x=True, abs_a=True, slots=2):
+        out = np.zeros_like(S)
+        for t in range(3):
+            for c in range(slots):
+                e = int(ids[t, c])
+                Ae = np.abs(A[e]).astype(np.float64) if abs_a else A[e].astype(np.float64)
+                x = Xa[t] if abs_x else O.bf16_bits_to_f64(X)[t]
+                out[t] += factor * 1.5 * abs(float(gates[t, c])) * (np.abs(B[e]).astype(np.float64) @ (Ae @ x))
+        return out
+    assert np.allclose(variant(), S, rtol=1e-14, atol=0)
+    for kw in ({"factor": 2.0}, {"factor": 0.5}, {"abs_x": False}, {"abs_a": False}, {"slots": 1}):
+        assert not np.allclose(variant(**kw), S, rtol=1e-9, atol=0), kw

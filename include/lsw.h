@@ -24,7 +24,21 @@
  *     pointers marked HOST are ordinary host memory.  Nothing here takes
  *     ownership of caller memory.
  *   - Calls on one context are not thread-safe; work is ordered by the stream.
- *     Two switches in flight on different streams over the same weights race.
+ *     Two switches in flight on different streams over the same weights race.  Switches over
+ *     DISJOINT layer subsets may overlap on different streams: every launch of lsw_switch,
+ *     lsw_switch_dev and lsw_rebase takes its own small block of library-owned device memory (the
+ *     device-built term list and two work counters), 16 blocks per context used in turn, so at most
+ *     16 such launches of one context may be in flight at once.  A recorded HIP graph keeps the
+ *     blocks its launches took: do not replay it concurrently with itself.
+ *
+ * Limits
+ *   - One W must stay below 2 GiB counting its rows rounded up to a multiple of 128 (the kernels
+ *     address a matrix with 32-bit byte offsets): a 4096 x 262144 or a 128256 x 8192 matrix is
+ *     refused with LSW_ERR_SHAPE.  The whole stack may be of any size (the 70B-shaped one is 137 GB).
+ *   - At most 2^31 - 1 work items per launch, LSW_MAX_K experts per list, 256 distinct layer subsets
+ *     per context (see lsw_switch).
+ *
+ * Tuning knobs, diagnostics and the host hooks the tests use are declared in lsw_tuning.h.
  */
 #ifndef LSW_H
 #define LSW_H
@@ -104,8 +118,10 @@ lsw_status lsw_create_adapters_ex(const lsw_linear* lin, int32_t n_lin, int32_t 
  * The fused switch (Alg. 1 steps 2-4; Eq. 8 == Eq. 10; one launch as in Eq. 11).
  *
  *   layers, n_layers   HOST list of distinct layer numbers to switch; NULL, 0 = every layer.  The first call with a
- *                      new subset (in any order) uploads a small table for it (a blocking copy; not inside a stream
- *                      capture); the library keeps up to 256 such tables and starts over beyond that.
+ *                      new subset (in any order) allocates and uploads a small table for it (a blocking copy; not
+ *                      inside a stream capture).  A table is never moved or freed while the context lives, so launches
+ *                      in flight and recorded graphs stay valid; a context holds at most 256 of them, and a call that
+ *                      would need one more fails with LSW_ERR_STATE until lsw_drop_subset_tables has been called.
  *   old_ids/old_gates  HOST, k_old entries: the experts merged now (Eq. 7 removes them).  k_old = 0: none.
  *   new_ids/new_gates  HOST, k_new entries: the experts to merge (Eq. 4).  k_new = 0: restore the base weights.
  *   hip_stream         hipStream_t (NULL = default stream).  The call is asynchronous on it.
@@ -122,6 +138,14 @@ lsw_status lsw_switch(lsw_ctx* ctx, const int32_t* layers, int32_t n_layers,
                       void* hip_stream);
 
 /*
+ * Frees the per-subset tables of the context (they are rebuilt on demand).  Synchronises the device first.  A HIP
+ * graph recorded before this call that contains a launch over a layer subset (or any launch of this context other
+ * than over all layers) must not be replayed afterwards.  Errors: LSW_ERR_ARG, LSW_ERR_STATE (another device is
+ * current), LSW_ERR_DEVICE.
+ */
+lsw_status lsw_drop_subset_tables(lsw_ctx* ctx);
+
+/*
  * Drift control.  Eq. 7 treats the unmerge as exact; in bf16 it is not: every switch rounds once, so after T
  * switches W differs from rne(W_base + delta_current) by a random walk of about 0.3 * sqrt(T) ulp.  A caller
  * that keeps a copy of the base weights (the second copy Sec. 3.3 avoids for memory's sake; at 288 GB per GPU
@@ -134,7 +158,8 @@ lsw_status lsw_switch(lsw_ctx* ctx, const int32_t* layers, int32_t n_layers,
  * lsw_rebase     W_p <- rne_bf16(W_base_p + sum_c s*g_c*(B_c A_c)) for every linear of the selected layers
  *                (Eq. 4 applied to the base copy): the same kernels as lsw_switch, one launch, reading the base
  *                copy and writing W.  ids/gates/k: HOST, the set that is to be merged afterwards (what
- *                lsw_switch would have been given as `new`); k = 0 copies the base weights back.
+ *                lsw_switch would have been given as `new`); k = 0 copies the base weights back (one launch of a
+ *                copy kernel over the selected linears).
  *                Asynchronous on hip_stream.  The tracked state of the touched layers becomes (ids, gates).
  * Errors: LSW_ERR_ARG (null, n_lin mismatch, base copy == W, bad list or layer), LSW_ERR_SHAPE (misaligned),
  * LSW_ERR_STATE (lsw_rebase before lsw_set_base), LSW_ERR_DEVICE.
@@ -261,48 +286,16 @@ lsw_status lsw_build_terms(const int32_t* old_ids, const float* old_gates, int32
                            int32_t* terms_ids, float* terms_coeff, int32_t* n_terms);
 
 /*
- * Bandwidth probe for callers that cannot judge a switch latency without a yardstick (benchmarks):
- * one in-place pass over every registered W with the switch kernel's access pattern and no factor
- * traffic or matrix work: each bf16 is widened, has +0.0f added, is rounded back and stored, so
- * every finite value is unchanged (only a negative zero becomes +0).  `waves_per_cu` (1..16)
- * single-wave workgroups per CU are launched.  Asynchronous on hip_stream.  What it sustains
- * (4 bytes per weight / elapsed time) bounds what lsw_switch can reach on the same tensors.
- * Errors: LSW_ERR_ARG, LSW_ERR_DEVICE.
- */
-lsw_status lsw_probe_inplace(lsw_ctx* ctx, int32_t waves_per_cu, void* hip_stream);
-
-/*
  * What the context believes is merged in `layer` now (the pair Eq. 7 needs for the next
  * switch).  ids/gates HOST arrays with room for LSW_MAX_K entries; k receives the count.
  */
 lsw_status lsw_get_state(const lsw_ctx* ctx, int32_t layer, int32_t* ids, float* gates, int32_t* k);
 
-/* Options (lsw_set_option) and queries (lsw_query). */
+/* Options (lsw_set_option) and queries (lsw_query).  The tuning knobs (options 3..10) are declared in lsw_tuning.h. */
 enum {
   LSW_OPT_KERNEL = 1,        /* 0 = automatic, 1 = fp32 vector-ALU kernel (any rank), 2 = matrix-core kernels
                                 (need r % 8 == 0 and at most 256 fused ranks = terms * r per switch) */
-  LSW_OPT_STRICT_STATE = 2,  /* 1: lsw_switch rejects an `old` that differs from the tracked state of a layer */
-  LSW_OPT_GRID = 3,          /* workgroups per launch; 0 = automatic (one matrix-core workgroup per CU) */
-  LSW_OPT_TILE_COLS = 4,     /* matrix-core kernel: columns per work item, a multiple of 256 (tuning knob) */
-  LSW_OPT_XCD_REMAP = 5,     /* order of the work items over the 8 XCDs: 0 = workgroup b takes items b, b + grid, ...; 1 = each
-                                XCD takes a contiguous share of every round of items; 2 = matrix-core kernel for fused ranks
-                                up to 64: each XCD walks its own eighth of the whole item list (the resident-A kernel
-                                always does); 3 (default) = 2 where most weights lie in matrices of 4, 8, 16 or 32 column
-                                panels, else 1 */
-  LSW_OPT_GEMV_GRID = 6,     /* workgroups of the merged-decode launches; 0 = automatic (2 per CU) */
-  LSW_OPT_ONE_PASS = 7,      /* 1 (default): bf16-stored factors of a rank that is a multiple of 16 run ONE matrix-core pass
-                                when the fused rank exceeds 64 (bare B A products, gates applied in fp32 between the terms);
-                                0: two passes with the gate folded into B (what every other rank gets) */
-  LSW_OPT_RESIDENT_Q = 8,    /* matrix-core kernel for fused ranks up to 64 and fp32-stored factors: 1 (default) = where the A
-                                operand of one work item fits LDS and most weights lie in matrices of 4, 8, 16 or 32 column
-                                panels, A is kept in LDS across the items of a panel and each XCD walks its own eighth of
-                                the items; 0 = always the kernel that streams A per step */
-  LSW_OPT_XCD_POOL = 9,      /* that kernel: 1 (default) = the last sixteenth of every XCD's items forms a pool that workgroups
-                                draw from once their own share is done (XCDs differ in speed by 2-3 %); 0 = all items dealt
-                                statically; n >= 2 = the last 1/n instead.  The result is the same bit for bit */
-  LSW_OPT_PANEL_GROUP = 10   /* matrix-core kernels for fused ranks up to 64: order of the items inside a matrix with many
-                                column panels (lsw_worklist_item_grouped); -1 (default) = chosen per launch so that the
-                                packed A operand of one group stays within 2 MB, 0 = rows outermost, n = groups of n */
+  LSW_OPT_STRICT_STATE = 2   /* 1: lsw_switch rejects an `old` that differs from the tracked state of a layer */
 };
 enum {
   LSW_Q_N_LINEARS = 1, LSW_Q_N_LAYERS = 2,
@@ -317,36 +310,6 @@ enum {
 };
 lsw_status lsw_set_option(lsw_ctx* ctx, int32_t option, int64_t value);
 int64_t    lsw_query(const lsw_ctx* ctx, int32_t what);   /* -1 on a bad argument */
-
-/*
- * The work decomposition of one launch (the tiles Sec. 3.4 hands to thread blocks), as a pure
- * function of the shapes: linear p is cut into ceil(out/tile_rows) x ceil(in/tile_cols) items,
- * numbered linear by linear, rows outermost.  Host helpers, no device.  The kernels decode an
- * item number with the same routine.
- */
-int64_t    lsw_worklist_size(const int32_t* out, const int32_t* in, int32_t n_lin,
-                             int32_t tile_rows, int32_t tile_cols);            /* -1 on a bad argument */
-lsw_status lsw_worklist_item(const int32_t* out, const int32_t* in, int32_t n_lin,
-                             int32_t tile_rows, int32_t tile_cols, int64_t item,
-                             int32_t* lin, int32_t* row0, int32_t* n_rows, int32_t* col0, int32_t* n_cols);
-/* The same with the column panels of a linear taken in groups of panel_group (LSW_OPT_PANEL_GROUP): inside a linear
- * that has more panels than that, all row blocks of the first panel_group panels come first (rows outermost), then
- * those of the next group, and so on; the last group may be narrower.  panel_group = 0 is lsw_worklist_item. */
-lsw_status lsw_worklist_item_grouped(const int32_t* out, const int32_t* in, int32_t n_lin,
-                                     int32_t tile_rows, int32_t tile_cols, int32_t panel_group, int64_t item,
-                                     int32_t* lin, int32_t* row0, int32_t* n_rows, int32_t* col0, int32_t* n_cols);
-
-/*
- * Which work items a workgroup of a per-XCD launch (LSW_OPT_XCD_REMAP) takes, as a pure function of the counts; host
- * helpers, no device; the kernels use the same routines.  XCD x = workgroups x, x + 8, ... owns items
- * [x * per, (x + 1) * per), per = ceil(n_items / 8); workgroup `block` takes first, first + step, ... below static_end;
- * the last pool_len items of every range go to the pool, where claim number g (an atomic counter at run time) stands
- * for lsw_walk_pool_item(g), or for nothing (-1) once the pool is empty.  pool_div <= 0 = no pool.
- * share = {first, step, static_end, per, pool_len}.  LSW_ERR_ARG unless n_items >= 0, grid a positive multiple of 8
- * and 0 <= block < grid.
- */
-lsw_status lsw_walk_share(int32_t n_items, int32_t grid, int32_t block, int32_t pool_div, int32_t share[5]);
-int32_t    lsw_walk_pool_item(int32_t n_items, int32_t grid, int32_t pool_div, int32_t claim);
 
 void        lsw_destroy(lsw_ctx* ctx);       /* frees what the library owns; NULL is allowed */
 const char* lsw_last_error(void);            /* message of the last failing call on this thread */

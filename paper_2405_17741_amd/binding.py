@@ -25,7 +25,7 @@ EXPORTS = (
     "lsw_destroy", "lsw_last_error", "lsw_probe_inplace", "lsw_merged_gemv_all",
     "lsw_route_dev", "lsw_switch_dev", "lsw_dev_status", "lsw_gemv_bf16", "lsw_create_adapters_ex",
     "lsw_set_base", "lsw_rebase", "lsw_enable_adapter_path", "lsw_adapter_workspace_bytes", "lsw_route_batch_dev",
-    "lsw_adapter_forward",
+    "lsw_adapter_forward", "lsw_drop_subset_tables",
 )
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblsw.so")
@@ -92,6 +92,7 @@ def lib() -> C.CDLL:
         L.lsw_walk_pool_item.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32]
         L.lsw_walk_pool_item.restype = C.c_int32
         L.lsw_probe_inplace.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
+        L.lsw_drop_subset_tables.argtypes = [C.c_void_p]
         L.lsw_destroy.argtypes = [C.c_void_p]
         L.lsw_destroy.restype = None
         L.lsw_last_error.restype = C.c_char_p
@@ -292,6 +293,10 @@ def lsw_walk_pool_item(n_items: int, grid: int, pool_div: int, claim: int) -> in
 
 def lsw_probe_inplace(ctx: int, waves_per_cu: int, stream: int = 0) -> None:
     _check(lib().lsw_probe_inplace(ctx, waves_per_cu, C.c_void_p(stream)))
+
+
+def lsw_drop_subset_tables(ctx: int) -> None:
+    _check(lib().lsw_drop_subset_tables(ctx))
 
 
 def lsw_destroy(ctx: int) -> None:

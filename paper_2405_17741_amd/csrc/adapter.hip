@@ -25,8 +25,9 @@ namespace lsw {
 // ---------------------------------------------------------------------------
 constexpr int AD_CHUNK = 64;        // columns of `in` per chunk (4 k-steps of 16)
 
-// 32-row blocks of A_all the layout holds: more than 4 are rounded up to 8 (the kernel takes them in two groups of 4)
-__host__ __device__ static inline int adapter_blocks_dev(int N) { const int nb = ceil_div(N, 32); return nb > 4 ? 8 : nb; }
+// 32-row blocks of A_all the layout holds = the blocks the down-projection reads: 1, 2, 4 (3 is rounded up: the kernel
+// exists for 1, 2 and 4 blocks per workgroup) or 8 (two groups of 4); the rows past E*r hold zeros
+__host__ __device__ static inline int adapter_blocks_dev(int N) { const int nb = ceil_div(N, 32); return nb > 4 ? 8 : nb == 3 ? 4 : nb; }
 static int adapter_blocks(int N) { return adapter_blocks_dev(N); }
 
 int64_t adapter_atk_elems(int E, int r, int in, int qp) {
@@ -177,10 +178,11 @@ hipError_t launch_adapter_down(const uint16_t* X, const uint16_t* Atk, float* Up
     if (qp == 2) hipLaunchKernelGGL((k_adapter_down<NB_, 2>), grid, dim3(256), 0, s, X, Atk, Upart, T, in, N, cps); \
     else hipLaunchKernelGGL((k_adapter_down<NB_, 1>), grid, dim3(256), 0, s, X, Atk, Upart, T, in, N, cps);         \
   } while (0)
+  const int nb_read = nb <= 1 ? 1 : nb <= 2 ? 2 : 4 * int(grid.z);   // blocks of Atk the launch reads
+  if (nb > 8 || nb_read != adapter_blocks(N)) return hipErrorInvalidValue;      // never beyond what k_pack_Atk laid out
   if (nb <= 1) LSW_AD(1);
   else if (nb <= 2) LSW_AD(2);
-  else if (nb <= 8) LSW_AD(4);            // 5..8 blocks: two groups of 4 (the packed layout is padded to whole groups)
-  else return hipErrorInvalidValue;
+  else LSW_AD(4);                         // 3..4 blocks: one group of 4; 5..8: two groups of 4 (the layout is padded to whole groups)
 #undef LSW_AD
   return hipGetLastError();
 }

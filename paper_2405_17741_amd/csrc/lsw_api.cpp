@@ -79,14 +79,33 @@ struct lsw_ctx {
   uint16_t* d_apk = nullptr;                 // packed A of all linears (r % 8 == 0 only)
   uint16_t* d_adapter = nullptr;             // adapter path: per linear the down-projection layout of A, then the packed B^T
   std::vector<size_t> atk_off, bpk_off;      // element offsets of the two parts of linear p inside d_adapter
-  Terms* d_terms = nullptr;                  // term list built on the device by lsw_switch_dev, followed by the sticky error word
+  char* d_slots = nullptr;                   // the sticky error word (first kSlotBytes), then kLaunchSlots launch slots
   int32_t* d_err = nullptr;
+  int slot_next = 0;                         // the slot the next switch launch takes
   int64_t owned_bytes = 0;
   int64_t x_elems = 0, y_elems = 0;          // sizes of the back-to-back x and y of lsw_merged_gemv_all
   std::map<PlanKey, DevicePlan> plans;
   int opt_kernel = 0, opt_strict = 0, opt_grid = 0, opt_tile_cols = kMfmaTileCols, opt_tile_cols_bigk = kMfmaBigkTileCols, opt_xcd = 3, opt_gemv_grid = 0, opt_one_pass = 1, opt_resident = 1, opt_pool = 1, opt_panel_group = -1;
   int last_kernel = 0, last_variant = 0, last_items = 0, last_grid = 0;
 };
+
+// What a switch launch WRITES besides the weights: the term list lsw_switch_dev builds on the device and the two
+// counters of the item pool.  Every launch takes the next of kLaunchSlots slots in turn, so launches of one context
+// that overlap on different streams (disjoint layer subsets) do not share them; a slot is reused after kLaunchSlots
+// further launches.  The counters of a slot are zero whenever no launch is using it (the kernels leave them so).
+struct LaunchSlot {
+  Terms terms;
+  int32_t pool[2];
+};
+constexpr int kLaunchSlots = 16;
+constexpr size_t kSlotBytes = 256;
+static_assert(sizeof(LaunchSlot) <= kSlotBytes, "slot size");
+
+static LaunchSlot* take_slot(lsw_ctx* c) {
+  LaunchSlot* s = reinterpret_cast<LaunchSlot*>(c->d_slots + kSlotBytes * size_t(1 + c->slot_next));
+  c->slot_next = (c->slot_next + 1) % kLaunchSlots;
+  return s;
+}
 
 static int layer_slot(const lsw_ctx* c, int32_t layer) {
   auto it = std::lower_bound(c->layer_ids.begin(), c->layer_ids.end(), layer);
@@ -321,10 +340,10 @@ extern "C" lsw_status lsw_create_adapters_ex(const lsw_linear* lin, int32_t n_li
   auto cleanup = [raw]() {
     if (raw->d_apk) (void)hipFree(raw->d_apk);
     if (raw->d_lin) (void)hipFree(raw->d_lin);
-    if (raw->d_terms) (void)hipFree(raw->d_terms);
+    if (raw->d_slots) (void)hipFree(raw->d_slots);
     raw->d_apk = nullptr;
     raw->d_lin = nullptr;
-    raw->d_terms = nullptr;
+    raw->d_slots = nullptr;
   };
   if (pack) {
     hipError_t e = hipMalloc(reinterpret_cast<void**>(&c->d_apk), apk_elems * sizeof(uint16_t));
@@ -351,12 +370,13 @@ extern "C" lsw_status lsw_create_adapters_ex(const lsw_linear* lin, int32_t n_li
   hipError_t e = hipMalloc(reinterpret_cast<void**>(&c->d_lin), desc.size() * sizeof(LinDesc));
   if (e != hipSuccess) { (void)hipGetLastError(); cleanup(); return fail(LSW_ERR_NOMEM, "hipMalloc of the descriptor table failed"); }
   c->owned_bytes += int64_t(desc.size() * sizeof(LinDesc));
-  e = hipMalloc(reinterpret_cast<void**>(&c->d_terms), sizeof(Terms) + 16);
-  if (e != hipSuccess) { (void)hipGetLastError(); cleanup(); return fail(LSW_ERR_NOMEM, "hipMalloc of the device term list failed"); }
-  c->d_err = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(c->d_terms) + sizeof(Terms));
-  c->owned_bytes += int64_t(sizeof(Terms) + 16);
-  e = hipMemset(c->d_terms, 0, sizeof(Terms) + 16);
-  if (e != hipSuccess) { cleanup(); return fail(LSW_ERR_DEVICE, "clearing the device term list failed: %s", hipGetErrorString(e)); }
+  const size_t slot_bytes = kSlotBytes * size_t(1 + kLaunchSlots);
+  e = hipMalloc(reinterpret_cast<void**>(&c->d_slots), slot_bytes);
+  if (e != hipSuccess) { (void)hipGetLastError(); cleanup(); return fail(LSW_ERR_NOMEM, "hipMalloc of the launch slots failed"); }
+  c->d_err = reinterpret_cast<int32_t*>(c->d_slots);
+  c->owned_bytes += int64_t(slot_bytes);
+  e = hipMemset(c->d_slots, 0, slot_bytes);
+  if (e != hipSuccess) { cleanup(); return fail(LSW_ERR_DEVICE, "clearing the launch slots failed: %s", hipGetErrorString(e)); }
   e = hipMemcpy(c->d_lin, desc.data(), desc.size() * sizeof(LinDesc), hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipDeviceSynchronize();   // the pack kernels have read A
   if (e != hipSuccess) { cleanup(); return fail(LSW_ERR_DEVICE, "descriptor upload / pack failed: %s", hipGetErrorString(e)); }
@@ -372,7 +392,7 @@ extern "C" void lsw_destroy(lsw_ctx* c) {
   if (c->d_apk) (void)hipFree(c->d_apk);
   if (c->d_adapter) (void)hipFree(c->d_adapter);
   if (c->d_lin) (void)hipFree(c->d_lin);
-  if (c->d_terms) (void)hipFree(c->d_terms);
+  if (c->d_slots) (void)hipFree(c->d_slots);
   delete c;
 }
 
@@ -384,16 +404,11 @@ static lsw_status get_plan(lsw_ctx* c, int kernel, int tc, const std::vector<int
   PlanKey key{kernel, tc, layers_sorted};
   auto it = c->plans.find(key);
   if (it != c->plans.end()) { *out = &it->second; return LSW_OK; }
-  // A caller that walks through very many different layer subsets must not grow the cache without bound: beyond
-  // kMaxPlans the tables are dropped (after the device has finished with them) and built again on demand.
-  if (c->plans.size() >= kMaxPlans) {
-    LSW_HIP(hipDeviceSynchronize());
-    for (auto& kv : c->plans) {
-      (void)hipFree(kv.second.d_sel);
-      c->owned_bytes -= int64_t(size_t(2 * kv.second.n_sel + 1) * sizeof(int32_t));
-    }
-    c->plans.clear();
-  }
+  // A table stays where it is for as long as the context lives unless the caller drops them all (lsw_drop_subset_tables):
+  // launches in flight and recorded HIP graphs hold its address.  A caller that walks through very many different layer
+  // subsets therefore meets a limit, not a silent eviction.
+  if (c->plans.size() >= kMaxPlans)
+    return fail(LSW_ERR_STATE, "%zu layer-subset tables are in use (the limit per context); lsw_drop_subset_tables frees them", c->plans.size());
   const int32_t tr = kernel == 4 ? kGemvRows : kernel == 3 ? 32 : kernel == 2 ? kMfmaTileRows : kValuTileRows;   // 3 = bandwidth probe, 4 = merged decode
   std::vector<int32_t> sel, first(1, 0);
   int64_t total = 0;
@@ -416,6 +431,19 @@ static lsw_status get_plan(lsw_ctx* c, int kernel, int tc, const std::vector<int
   c->owned_bytes += int64_t(blob.size() * sizeof(int32_t));
   auto ins = c->plans.emplace(std::move(key), dp);
   *out = &ins.first->second;
+  return LSW_OK;
+}
+
+extern "C" lsw_status lsw_drop_subset_tables(lsw_ctx* c) {
+  if (!c) return fail(LSW_ERR_ARG, "ctx is null");
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev != c->device) { (void)hipGetLastError(); return fail(LSW_ERR_STATE, "the context's device is not current"); }
+  LSW_HIP(hipDeviceSynchronize());              // no launch may still be reading a table
+  for (auto& kv : c->plans) {
+    (void)hipFree(kv.second.d_sel);
+    c->owned_bytes -= int64_t(size_t(2 * kv.second.n_sel + 1) * sizeof(int32_t));
+  }
+  c->plans.clear();
   return LSW_OK;
 }
 
@@ -448,8 +476,9 @@ static lsw_status select_layers(lsw_ctx* c, const int32_t* layers, int32_t n_lay
 }
 
 // One launch over the selected layers.  t.n sizes the launch; with t_dev the kernel reads the list from device memory.
-static lsw_status launch_switch(lsw_ctx* c, const std::vector<int32_t>& sel_layers, const Terms& t, const Terms* t_dev,
-                                hipStream_t s, bool from_base = false) {
+static lsw_status launch_switch(lsw_ctx* c, const std::vector<int32_t>& sel_layers, const Terms& t, LaunchSlot* slot, bool terms_on_device,
+                                hipStream_t s, bool from_base = false, bool probe = false) {
+  const Terms* t_dev = terms_on_device ? &slot->terms : nullptr;
   // the matrix-core kernels keep the fused rank (terms x r) in registers: up to 64 in the streaming
   // kernel, up to 256 in the chunked one
   const int n_groups = (c->r % 8 == 0) ? t.n * (c->r / 8) : 0;
@@ -506,8 +535,9 @@ static lsw_status launch_switch(lsw_ctx* c, const std::vector<int32_t>& sel_laye
     lsw_status st = get_plan(c, kernel, tc, sel_layers, &dp);
     if (st != LSW_OK) return st;
     LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, tc, xcd_mode, from_base ? 1 : 0, c->opt_one_pass, nullptr, 0, LinDesc{},
-                  c->opt_pool ? c->d_err + 2 : nullptr, c->opt_pool == 1 ? 16 : c->opt_pool, panel_group};
-    hipError_t e = (kernel == 2) ? (bigk ? launch_switch_mfma_bigk(lp, t, t_dev, c->r, c->qp, grid, s)
+                  c->opt_pool ? slot->pool : nullptr, c->opt_pool == 1 ? 16 : c->opt_pool, panel_group, probe ? 1 : 0};
+    if (probe && kernel != 2) return fail(LSW_ERR_ARG, "the switch-pattern probe needs the matrix-core kernels (r %% 8 == 0)");
+    hipError_t e = (kernel == 2) ? (bigk && !probe ? launch_switch_mfma_bigk(lp, t, t_dev, c->r, c->qp, grid, s)
                                   : resident ? launch_switch_mfma_res(lp, t, t_dev, c->r, c->qp, grid, s)
                                              : launch_switch_mfma(lp, t, t_dev, c->r, c->qp, grid, s))
                                  : launch_switch_valu(lp, t, t_dev, c->r, c->qp, grid, s);
@@ -548,7 +578,7 @@ extern "C" lsw_status lsw_switch(lsw_ctx* c, const int32_t* layers, int32_t n_la
       if (!same) return fail(LSW_ERR_STATE, "layer %d: `old` differs from the merged state", layer);
     }
   }
-  st = launch_switch(c, sel_layers, t, nullptr, static_cast<hipStream_t>(hip_stream));
+  st = launch_switch(c, sel_layers, t, take_slot(c), false, static_cast<hipStream_t>(hip_stream));
   if (st != LSW_OK) return st;
   for (int32_t layer : touched) {
     LayerState& s = c->state[size_t(layer_slot(c, layer))];
@@ -593,12 +623,14 @@ extern "C" lsw_status lsw_rebase(lsw_ctx* c, const int32_t* layers, int32_t n_la
     c->last_kernel = 0;
     c->last_items = 0;
     c->last_grid = 0;
-    for (size_t p = 0; p < c->lin.size(); ++p) {
-      if (!sel_layers.empty() && !std::binary_search(sel_layers.begin(), sel_layers.end(), c->lin[p].layer)) continue;
-      LSW_HIP(hipMemcpyAsync(c->lin[p].W, c->desc[p].Wbase, size_t(c->lin[p].out) * size_t(c->lin[p].in) * 2, hipMemcpyDeviceToDevice, s));
-    }
+    DevicePlan* dp = nullptr;                  // one launch: the probe's walk over the selected linears, reading the base copy
+    st = get_plan(c, 3, c->opt_tile_cols, sel_layers, &dp);
+    if (st != LSW_OK) return st;
+    LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, c->opt_tile_cols, c->opt_xcd ? 1 : 0, 1, 0, nullptr, 0, LinDesc{}};
+    hipError_t e = launch_probe_inplace(lp, c->n_cu * 4, s);
+    if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "copy launch failed: %s", hipGetErrorString(e));
   } else {
-    st = launch_switch(c, sel_layers, t, nullptr, s, /*from_base*/ true);
+    st = launch_switch(c, sel_layers, t, take_slot(c), false, s, /*from_base*/ true);
     if (st != LSW_OK) return st;
   }
   for (int32_t layer : touched) {
@@ -640,12 +672,13 @@ extern "C" lsw_status lsw_switch_dev(lsw_ctx* c, const int32_t* layers, int32_t 
   Terms t;
   std::memset(&t, 0, sizeof(t));
   t.n = k_old + k_new;                       // the launch is sized for the longest list the device may build
+  LaunchSlot* slot = take_slot(c);
   if (t.n > 0) {
     hipError_t e = launch_build_terms(old_ids_dev, old_gates_dev, k_old, new_ids_dev, new_gates_dev, k_new, c->E, c->scale,
-                                      c->d_terms, c->d_err, s);
+                                      &slot->terms, c->d_err, s);
     if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "term builder launch failed: %s", hipGetErrorString(e));
   }
-  st = launch_switch(c, sel_layers, t, c->d_terms, s);
+  st = launch_switch(c, sel_layers, t, slot, true, s);
   if (st != LSW_OK) return st;
   const std::vector<int32_t>& touched = sel_layers.empty() ? c->layer_ids : sel_layers;
   for (int32_t layer : touched) c->state[size_t(layer_slot(c, layer))].k = -1;     // known to the device only
@@ -780,7 +813,13 @@ extern "C" lsw_status lsw_gemv_bf16(const void* W_bf16, const void* x_bf16, floa
 // ---------------------------------------------------------------------------
 extern "C" lsw_status lsw_probe_inplace(lsw_ctx* c, int32_t waves_per_cu, void* hip_stream) {
   if (lsw_status ready = ctx_ready(c)) return ready;
-  if (waves_per_cu < 1 || waves_per_cu > 16) return fail(LSW_ERR_ARG, "waves_per_cu=%d outside 1..16", waves_per_cu);
+  if (waves_per_cu < 0 || waves_per_cu > 16) return fail(LSW_ERR_ARG, "waves_per_cu=%d outside 0..16", waves_per_cu);
+  if (waves_per_cu == 0) {          // the switch kernel's own launch for a token with two old and two new experts, work taken out
+    Terms t;
+    std::memset(&t, 0, sizeof(t));
+    t.n = std::min(4, c->E);
+    return launch_switch(c, std::vector<int32_t>(), t, take_slot(c), false, static_cast<hipStream_t>(hip_stream), false, true);
+  }
   DevicePlan* dp = nullptr;
   lsw_status st = get_plan(c, 3, c->opt_tile_cols, std::vector<int32_t>(), &dp);
   if (st != LSW_OK) return st;

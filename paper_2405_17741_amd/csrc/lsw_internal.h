@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include "lsw.h"
+#include "lsw_tuning.h"
 
 #if defined(__HIPCC__) || defined(__HIP__)
 #define LSW_HD __host__ __device__
@@ -143,6 +144,8 @@ struct LaunchPlan {             // device pointers + counts for one launch
   int32_t* pool;
   int32_t pool_div;             // every XCD range gives its last 1/pool_div to the pool
   int32_t panel_group;          // column panels per group in the item order of a linear (see decode_item); 0 = row-major
+  int32_t probe;                // 1 (k_switch_mfma, k_switch_mfma_res): the kernel's walk and W traffic only, no operand loads, no
+                                // matrix work; every value is rewritten as it is (lsw_probe_inplace with waves_per_cu = 0)
 };
 
 // Kernel launchers (one .hip file per kernel family).  All return the hipError of the launch.

@@ -33,7 +33,7 @@ struct MfmaItem {           // what a wave keeps per work item
   u32x4 p_hi[NKS], p_lo[NKS];
 };
 
-template <int NKS, int QP>
+template <int NKS, int QP, bool PROBE = false>
 __device__ __forceinline__ void mfma_load_item(const LaunchPlan& p, int item, int n, int gpr, int r,
                                                const int (&term_e)[NKS], const int (&term_g)[NKS],
                                                const float (&term_c)[NKS], MfmaItem<NKS>& it,
@@ -73,6 +73,7 @@ __device__ __forceinline__ void mfma_load_item(const LaunchPlan& p, int item, in
   it.row0_byte = uint32_t(row0) * it.stride_byte;
   const int prow = min(row0 + n, L.out - 1);
   const bool prow_ok = row0 + n < L.out;       // rows past the end get a zero coefficient and an offset outside W
+  if constexpr (PROBE) return;
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks) {
     float b[8];
@@ -178,6 +179,14 @@ __device__ __forceinline__ void wg_compute(const u32x4 (&p_hi)[NKS], const u32x4
   }
 #pragma unroll
   for (int v = 0; v < 16; ++v) wcur[v][3] = pack_bf16(a0[3][v], a1[3][v]);
+}
+
+// The probe's stand-in for wg_compute: every bf16 widened, +0.0f, rounded back (finite values unchanged).
+__device__ __forceinline__ void wg_probe_compute(u32x4 (&wcur)[16]) {
+#pragma unroll
+  for (int v = 0; v < 16; ++v)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) wcur[v][q] = pack_bf16(bf16_lo(wcur[v][q]) + 0.0f, bf16_hi(wcur[v][q]) + 0.0f);
 }
 
 // This wave's quarter of the Q operand of column step `cs` (blocks 2w and 2w+1, all k-steps),

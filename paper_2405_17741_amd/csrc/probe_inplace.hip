@@ -11,7 +11,9 @@ namespace lsw {
 // bf16 to fp32, adds +0.0f, rounds back and stores in place: every finite value is unchanged (a
 // negative zero becomes +0).  What this sustains is the ceiling of the in-place access pattern on
 // the given matrices, without factor traffic or matrix work.
+// COPY (lsw_rebase with nothing to merge): the same walk reading the caller's base copy and writing W, bits unchanged.
 // ---------------------------------------------------------------------------
+template <bool COPY>
 __global__ __launch_bounds__(64) void k_probe_inplace(LaunchPlan p) {
   const int lane = threadIdx.x, n = lane & 31, h = lane >> 5;
   const int grid = gridDim.x;
@@ -24,6 +26,7 @@ __global__ __launch_bounds__(64) void k_probe_inplace(LaunchPlan p) {
     decode_item(uniform(item - p.first[seg]), out, in, 32, p.tile_cols, 0, &row0, &col0);
     const int col_end = min(in, col0 + p.tile_cols);
     const __amdgpu_buffer_rsrc_t res = w_resource(uniform(Lp->W), out * in * 2);
+    const __amdgpu_buffer_rsrc_t res_src = COPY ? w_resource(uniform(Lp->Wbase), out * in * 2) : res;
     const uint32_t stride = uint32_t(in) * 2u;
     auto offset = [&](int cs) {
       const int col = cs + 8 * n;
@@ -34,7 +37,7 @@ __global__ __launch_bounds__(64) void k_probe_inplace(LaunchPlan p) {
     off[0] = offset(col0);
 #pragma unroll
     for (int v = 0; v < 16; ++v)
-      buf[0][v] = __builtin_amdgcn_raw_buffer_load_b128(res, off[0] + uint32_t(8 * (v >> 2) + (v & 3)) * stride, 0, 2);
+      buf[0][v] = __builtin_amdgcn_raw_buffer_load_b128(res_src, off[0] + uint32_t(8 * (v >> 2) + (v & 3)) * stride, 0, 2);
     for (int cs = col0; cs < col_end; cs += 2 * MT_STEP) {
 #pragma unroll
       for (int half = 0; half < 2; ++half) {
@@ -44,13 +47,13 @@ __global__ __launch_bounds__(64) void k_probe_inplace(LaunchPlan p) {
 #pragma unroll
           for (int v = 0; v < 16; ++v)
             buf[half ^ 1][v] = __builtin_amdgcn_raw_buffer_load_b128(
-                res, off[half ^ 1] + uint32_t(8 * (v >> 2) + (v & 3)) * stride, 0, 2);
+                res_src, off[half ^ 1] + uint32_t(8 * (v >> 2) + (v & 3)) * stride, 0, 2);
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
             u32x4 o;
 #pragma unroll
             for (int q = 0; q < 4; ++q)
-              o[q] = pack_bf16(bf16_lo(buf[half][v][q]) + 0.0f, bf16_hi(buf[half][v][q]) + 0.0f);
+              o[q] = COPY ? buf[half][v][q] : pack_bf16(bf16_lo(buf[half][v][q]) + 0.0f, bf16_hi(buf[half][v][q]) + 0.0f);
             __builtin_amdgcn_raw_buffer_store_b128(o, res, off[half] + uint32_t(8 * (v >> 2) + (v & 3)) * stride, 0, kWStoreAux);
           }
         }
@@ -60,7 +63,8 @@ __global__ __launch_bounds__(64) void k_probe_inplace(LaunchPlan p) {
 }
 
 hipError_t launch_probe_inplace(const LaunchPlan& p, int grid, hipStream_t s) {
-  hipLaunchKernelGGL(k_probe_inplace, dim3(grid), dim3(64), 0, s, p);
+  if (p.from_base) hipLaunchKernelGGL(k_probe_inplace<true>, dim3(grid), dim3(64), 0, s, p);
+  else hipLaunchKernelGGL(k_probe_inplace<false>, dim3(grid), dim3(64), 0, s, p);
   return hipGetLastError();
 }
 

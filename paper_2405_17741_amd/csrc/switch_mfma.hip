@@ -44,7 +44,7 @@ namespace lsw {
 // the previous step's tile, request the next tile into the freed registers, update the current
 // tile, then drain and meet the workgroup.  Everything requested at the top has the whole compute
 // phase to arrive.  Returns false after the last tile of the workgroup.
-template <int NKS, int QP>
+template <int NKS, int QP, bool PROBE>
 __device__ __forceinline__ bool wg_step(const LaunchPlan& p, int n, int h, int lane, int wave, int gpr, int r,
                                         const int (&term_e)[NKS], const int (&term_g)[NKS],
                                         const float (&term_c)[NKS], MfmaItem<NKS>& cur, MfmaItem<NKS>& nxt,
@@ -64,7 +64,7 @@ __device__ __forceinline__ bool wg_step(const LaunchPlan& p, int n, int h, int l
     const int col = ncs + 8 * n;
     if (more && col < ncol_end) nlane_off = nrow0_byte + uint32_t(4 * h) * nstride + uint32_t(col) * 2u;
   }
-  {   // (a finished workgroup re-reads its last block, which is harmless)
+  if constexpr (!PROBE) {   // (a finished workgroup re-reads its last block, which is harmless)
     const int qcs = uniform(more ? ncs : cs);
     const uint16_t* qApk = uniform((more && last) ? nxt.Apk : cur.Apk);
     const int qncb = uniform((more && last) ? nxt.ncb : cur.ncb);
@@ -80,7 +80,8 @@ __device__ __forceinline__ bool wg_step(const LaunchPlan& p, int n, int h, int l
     wprev[v] = __builtin_amdgcn_raw_buffer_load_b128(
         nres, nlane_off + uint32_t(8 * (v >> 2) + (v & 3)) * nstride, 0, kWLoadAux);
 
-  wg_compute<NKS, QP>(cur.p_hi, cur.p_lo, wg_lds + buf * kBufSlots + lane, wcur);
+  if constexpr (PROBE) wg_probe_compute(wcur);
+  else wg_compute<NKS, QP>(cur.p_hi, cur.p_lo, wg_lds + buf * kBufSlots + lane, wcur);
 
   if (last && walk.after_pool) walk_publish_claim(walk, wave, claim);
   wg_drain_and_barrier();
@@ -97,14 +98,14 @@ __device__ __forceinline__ bool wg_step(const LaunchPlan& p, int n, int h, int l
     const int following = via_pool ? walk_take_claim(walk) : walk.after;
     have_nxt = following >= 0;
     if (have_nxt) {
-      mfma_load_item<NKS, QP>(p, following, n, gpr, r, term_e, term_g, term_c, nxt, WG_ROWS, 32 * wave);
+      mfma_load_item<NKS, QP, PROBE>(p, following, n, gpr, r, term_e, term_g, term_c, nxt, WG_ROWS, 32 * wave);
       walk_plan_after(walk, following, via_pool, wave, lane, claim);
     }
   }
   return true;
 }
 
-template <int NKS, int QP>
+template <int NKS, int QP, bool PROBE>
 __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma(LaunchPlan p, Terms t, const Terms* t_dev, int r) {
   __shared__ int32_t s_e[kMaxTerms];
   __shared__ float s_coeff[kMaxTerms];
@@ -135,11 +136,11 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma(LaunchPlan p, Ter
   const int item0 = walk_init(p, p.xcd_remap == 2, walk);
   if (item0 >= walk.static_end) return; // uniform over the workgroup (never with a pool)
   MfmaItem<NKS> cur, nxt;
-  mfma_load_item<NKS, QP>(p, item0, n, gpr, r, term_e, term_g, term_c, cur, WG_ROWS, 32 * wave);
+  mfma_load_item<NKS, QP, PROBE>(p, item0, n, gpr, r, term_e, term_g, term_c, cur, WG_ROWS, 32 * wave);
   bool have_nxt = item0 + walk.step < walk.static_end;
   int claim = 0;
   if (have_nxt) {
-    mfma_load_item<NKS, QP>(p, item0 + walk.step, n, gpr, r, term_e, term_g, term_c, nxt, WG_ROWS, 32 * wave);
+    mfma_load_item<NKS, QP, PROBE>(p, item0 + walk.step, n, gpr, r, term_e, term_g, term_c, nxt, WG_ROWS, 32 * wave);
     walk_plan_after(walk, item0 + walk.step, false, wave, lane, claim);
   } else {
     nxt = cur;
@@ -150,16 +151,16 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma(LaunchPlan p, Ter
   mfma_load_w<NKS>(cur, lane_off, wa);
 #pragma unroll
   for (int v = 0; v < 16; ++v) wb[v] = u32x4{0u, 0u, 0u, 0u};
-  wg_fetch_q<NKS, QP>(cur.Apk, cur.ncb, cs, n, gpr, wave, term_e, term_g, wg_lds);
+  if constexpr (!PROBE) wg_fetch_q<NKS, QP>(cur.Apk, cur.ncb, cs, n, gpr, wave, term_e, term_g, wg_lds);
   wg_drain_and_barrier();
   __amdgpu_buffer_rsrc_t prev_res = w_resource(cur.W, cur.wbytes);
   uint32_t prev_off = kOutOfRange, prev_stride = 0;
 
   bool a_is_cur = true;
   while (true) {
-    if (!wg_step<NKS, QP>(p, n, h, lane, wave, gpr, r, term_e, term_g, term_c, cur, nxt, have_nxt, walk, claim, cs, lane_off,
+    if (!wg_step<NKS, QP, PROBE>(p, n, h, lane, wave, gpr, r, term_e, term_g, term_c, cur, nxt, have_nxt, walk, claim, cs, lane_off,
                       prev_res, prev_off, prev_stride, wa, wb, 0)) { a_is_cur = true; break; }
-    if (!wg_step<NKS, QP>(p, n, h, lane, wave, gpr, r, term_e, term_g, term_c, cur, nxt, have_nxt, walk, claim, cs, lane_off,
+    if (!wg_step<NKS, QP, PROBE>(p, n, h, lane, wave, gpr, r, term_e, term_g, term_c, cur, nxt, have_nxt, walk, claim, cs, lane_off,
                       prev_res, prev_off, prev_stride, wb, wa, 1)) { a_is_cur = false; break; }
   }
   if (a_is_cur) {
@@ -176,14 +177,14 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma(LaunchPlan p, Ter
   walk_finish(walk);
 }
 
-template <int NKS, int QP>
+template <int NKS, int QP, bool PROBE = false>
 static hipError_t launch_wg(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int grid, hipStream_t s) {
   const size_t lds = size_t(2) * NKS * 8 * QP * 64 * sizeof(u32x4);     // 16 KB per k-step and Q part, two buffers
   // once per process (function-local statics are initialised exactly once, also under concurrent first calls)
-  static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_switch_mfma<NKS, QP>),
+  static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_switch_mfma<NKS, QP, PROBE>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
   if (lds_ok != hipSuccess) return lds_ok;
-  hipLaunchKernelGGL((k_switch_mfma<NKS, QP>), dim3(grid), dim3(64 * WG_WAVES), lds, s, p, t, t_dev, r);
+  hipLaunchKernelGGL((k_switch_mfma<NKS, QP, PROBE>), dim3(grid), dim3(64 * WG_WAVES), lds, s, p, t, t_dev, r);
   return hipGetLastError();
 }
 
@@ -202,6 +203,7 @@ static hipError_t launch_wg_qp(const LaunchPlan& p, const Terms& t, const Terms*
 // t.n sizes the kernel (k-steps kept in registers); with t_dev the kernel takes the list itself, which may
 // be shorter, from device memory
 hipError_t launch_switch_mfma(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int qp, int grid, hipStream_t s) {
+  if (p.probe) return launch_wg<1, 2, true>(p, t, t_dev, r, grid, s);
   return qp == 2 ? launch_wg_qp<2>(p, t, t_dev, r, grid, s) : launch_wg_qp<1>(p, t, t_dev, r, grid, s);
 }
 

@@ -89,7 +89,7 @@ __device__ __forceinline__ void res_fetch_q(const LaunchPlan& p, const ResItem& 
     wg_fetch_q<NKS, QP>(c.Apk, ncb, (cb0 + j) * MT_STEP, n, gpr, wave, term_e, term_g, wg_lds + j * kStepSlots);
 }
 
-template <int NKS, int QP>
+template <int NKS, int QP, bool PROBE>
 __device__ __forceinline__ bool res_step(const LaunchPlan& p, int n, int h, int lane, int wave, int gpr, int r,
                                          const int (&term_e)[NKS], const int (&term_g)[NKS], const float (&term_c)[NKS],
                                          ResItem& cur, ResItem& nxt, bool& have_nxt_io, ItemWalk& walk, int& claim,
@@ -124,9 +124,12 @@ __device__ __forceinline__ bool res_step(const LaunchPlan& p, int n, int h, int 
         nres, nlane_off + uint32_t(8 * (v >> 2) + (v & 3)) * nstride, 0, kWLoadAux);
   const bool boundary = last && have_nxt;
   float braw[NKS][8];
-  if (boundary) res_load_b<NKS, QP>(nxt, wave, n, r, term_e, term_g, braw);
-
-  wg_compute<NKS, QP>(p_hi, p_lo, wg_lds + ((cs - cur.col0) / MT_STEP) * kStepSlots + lane, wcur);
+  if constexpr (!PROBE) {
+    if (boundary) res_load_b<NKS, QP>(nxt, wave, n, r, term_e, term_g, braw);
+    wg_compute<NKS, QP>(p_hi, p_lo, wg_lds + ((cs - cur.col0) / MT_STEP) * kStepSlots + lane, wcur);
+  } else {
+    wg_probe_compute(wcur);
+  }
 
   prev_res = w_resource(cur.W, cur.out * cur.in * 2);
   prev_off = lane_off;
@@ -135,7 +138,7 @@ __device__ __forceinline__ bool res_step(const LaunchPlan& p, int n, int h, int 
   cs = ncs;
   if (last) {                      // item boundary (uniform over the workgroup: all four waves walk the same items)
     if (!have_nxt) return false;
-    res_make_p<NKS>(nxt, wave, n, term_c, braw, p_hi, p_lo);
+    if constexpr (!PROBE) res_make_p<NKS>(nxt, wave, n, term_c, braw, p_hi, p_lo);
     const bool via_pool = walk.after_pool;       // the item after nxt is the one wave 0 claimed a boundary ago
     const bool new_panel = uniform(int(via_pool || nxt.seg != cur.seg || nxt.col0 != cur.col0)) != 0;
     cur = nxt;
@@ -152,7 +155,7 @@ __device__ __forceinline__ bool res_step(const LaunchPlan& p, int n, int h, int 
         have_nxt_io = following >= 0;
         if (have_nxt_io) res_item_at(p, following, nxt);
       }
-      res_fetch_q<NKS, QP>(p, cur, n, gpr, wave, term_e, term_g);
+      if constexpr (!PROBE) res_fetch_q<NKS, QP>(p, cur, n, gpr, wave, term_e, term_g);
       wg_drain_and_barrier();      // the new one is complete (and every wave has read the claim)
     }
     if (have_nxt_io) walk_plan_after(walk, following, via_pool, wave, lane, claim);
@@ -160,7 +163,7 @@ __device__ __forceinline__ bool res_step(const LaunchPlan& p, int n, int h, int 
   return true;
 }
 
-template <int NKS, int QP>
+template <int NKS, int QP, bool PROBE>
 __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma_res(LaunchPlan p, Terms t, const Terms* t_dev, int r) {
   __shared__ int32_t s_e[kMaxTerms];
   __shared__ float s_coeff[kMaxTerms];
@@ -200,7 +203,7 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma_res(LaunchPlan p,
     walk_plan_after(walk, nxt.item, false, wave, lane, claim);
   }
   u32x4 p_hi[NKS], p_lo[NKS];
-  {
+  if constexpr (!PROBE) {
     float braw[NKS][8];
     res_load_b<NKS, QP>(cur, wave, n, r, term_e, term_g, braw);
     res_make_p<NKS>(cur, wave, n, term_c, braw, p_hi, p_lo);
@@ -223,16 +226,16 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma_res(LaunchPlan p,
   }
 #pragma unroll
   for (int v = 0; v < 16; ++v) wb[v] = u32x4{0u, 0u, 0u, 0u};
-  res_fetch_q<NKS, QP>(p, cur, n, gpr, wave, term_e, term_g);
+  if constexpr (!PROBE) res_fetch_q<NKS, QP>(p, cur, n, gpr, wave, term_e, term_g);
   wg_drain_and_barrier();
   __amdgpu_buffer_rsrc_t prev_res = w_resource(cur.W, cur.out * cur.in * 2);
   uint32_t prev_off = kOutOfRange, prev_stride = 0;
 
   bool a_is_cur = true;
   while (true) {
-    if (!res_step<NKS, QP>(p, n, h, lane, wave, gpr, r, term_e, term_g, term_c, cur, nxt, have_nxt, walk, claim, cs, lane_off,
+    if (!res_step<NKS, QP, PROBE>(p, n, h, lane, wave, gpr, r, term_e, term_g, term_c, cur, nxt, have_nxt, walk, claim, cs, lane_off,
                            prev_res, prev_off, prev_stride, p_hi, p_lo, wa, wb)) { a_is_cur = true; break; }
-    if (!res_step<NKS, QP>(p, n, h, lane, wave, gpr, r, term_e, term_g, term_c, cur, nxt, have_nxt, walk, claim, cs, lane_off,
+    if (!res_step<NKS, QP, PROBE>(p, n, h, lane, wave, gpr, r, term_e, term_g, term_c, cur, nxt, have_nxt, walk, claim, cs, lane_off,
                            prev_res, prev_off, prev_stride, p_hi, p_lo, wb, wa)) { a_is_cur = false; break; }
   }
   if (a_is_cur) {
@@ -249,15 +252,15 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma_res(LaunchPlan p,
   walk_finish(walk);
 }
 
-template <int NKS, int QP>
+template <int NKS, int QP, bool PROBE = false>
 static hipError_t launch_res(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int grid, hipStream_t s) {
   const size_t lds = size_t(p.tile_cols / MT_STEP) * NKS * 8 * QP * 64 * sizeof(u32x4);     // 8 KB per column step, k-step and Q part
   if (lds > size_t(kResidentLdsBytes) || p.Z != nullptr) return hipErrorInvalidValue;
   // once per process (function-local statics are initialised exactly once, also under concurrent first calls)
-  static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_switch_mfma_res<NKS, QP>),
+  static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_switch_mfma_res<NKS, QP, PROBE>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, kResidentLdsBytes);
   if (lds_ok != hipSuccess) return lds_ok;
-  hipLaunchKernelGGL((k_switch_mfma_res<NKS, QP>), dim3(grid), dim3(64 * WG_WAVES), lds, s, p, t, t_dev, r);
+  hipLaunchKernelGGL((k_switch_mfma_res<NKS, QP, PROBE>), dim3(grid), dim3(64 * WG_WAVES), lds, s, p, t, t_dev, r);
   return hipGetLastError();
 }
 
@@ -274,6 +277,7 @@ static hipError_t launch_res_qp(const LaunchPlan& p, const Terms& t, const Terms
 }
 
 hipError_t launch_switch_mfma_res(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int qp, int grid, hipStream_t s) {
+  if (p.probe) return launch_res<1, 2, true>(p, t, t_dev, r, grid, s);
   return qp == 2 ? launch_res_qp<2>(p, t, t_dev, r, grid, s) : launch_res_qp<1>(p, t, t_dev, r, grid, s);
 }
 

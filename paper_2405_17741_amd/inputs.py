@@ -130,26 +130,29 @@ def device_stack(wl: Workload, device="cuda", factor_dtype=torch.float32):
 def router_logits(wl: Workload, steps=None) -> np.ndarray:
     """fp32 [steps, E] router logits ~ N(0,1), one row per token.
 
-    With wl.reuse_prob > 0, a Bernoulli(reuse_prob) draw per step decides whether
-    the step must keep one of the previous step's top-k experts: if the two
-    top-k sets are disjoint, the logit of the step's last-ranked selected expert
-    is exchanged with the logit of a uniformly chosen previously selected expert.
-    The multiset of logit values of the step is unchanged.
+    With wl.reuse_prob > 0 the rows are built by rank instead of drawn in place: the step's E values are
+    sorted, and a random order of the experts says which expert receives the largest value, the second
+    largest, and so on (i.i.d. values in a uniformly random order are again i.i.d., so the distribution is
+    the same).  A Bernoulli(reuse_prob) draw per step decides whether the step must keep one of the previous
+    step's k highest-valued experts: if none of them is among this step's first k, the expert at place k-1 of
+    the order exchanges places with a uniformly chosen one of them.  Nothing here selects experts from logits:
+    the generator knows the places because it assigned them.
     """
     steps = wl.steps if steps is None else steps
     rng = np.random.default_rng(wl.seed + 7919)
     logits = rng.normal(0.0, 1.0, size=(steps, wl.experts)).astype(np.float32)
     if wl.reuse_prob > 0.0:
+        k = wl.top_k
         force = rng.random(steps) < wl.reuse_prob
-        pick = rng.integers(0, wl.top_k, size=steps)
-        prev = None
+        pick = rng.integers(0, k, size=steps)
+        values = -np.sort(-logits, axis=1)                        # descending per step
+        order = np.stack([rng.permutation(wl.experts) for _ in range(steps)])
         for t in range(steps):
-            top = np.argsort(-logits[t], kind="stable")[: wl.top_k]
-            if prev is not None and force[t] and not set(top.tolist()) & set(prev.tolist()):
-                a, b = int(top[-1]), int(prev[pick[t]])
-                logits[t, a], logits[t, b] = logits[t, b], logits[t, a]
-                top = np.argsort(-logits[t], kind="stable")[: wl.top_k]
-            prev = top
+            if t > 0 and force[t] and not set(order[t, :k].tolist()) & set(order[t - 1, :k].tolist()):
+                keep = int(order[t - 1, pick[t]])
+                at = int(np.nonzero(order[t] == keep)[0][0])
+                order[t, k - 1], order[t, at] = order[t, at], order[t, k - 1]
+            logits[t, order[t]] = values[t]
     return logits
 
 

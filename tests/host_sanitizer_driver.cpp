@@ -9,6 +9,7 @@
 #include <vector>
 
 #include "lsw.h"
+#include "lsw_tuning.h"
 
 #define EXPECT(cond)                                                         \
   do {                                                                       \
@@ -101,6 +102,7 @@ int main() {
     EXPECT(lsw_switch_dev(nullptr, nullptr, 0, nullptr, nullptr, 0, nullptr, nullptr, 0, nullptr) == LSW_ERR_ARG);
     EXPECT(lsw_rebase(nullptr, nullptr, 0, nullptr, nullptr, 0, nullptr) == LSW_ERR_ARG);
     EXPECT(lsw_set_base(nullptr, nullptr, 0) == LSW_ERR_ARG);
+    EXPECT(lsw_drop_subset_tables(nullptr) == LSW_ERR_ARG);
     EXPECT(lsw_enable_adapter_path(nullptr) == LSW_ERR_ARG);
     EXPECT(lsw_adapter_forward(nullptr, 0, nullptr, 1, nullptr, nullptr, 0, nullptr, nullptr, nullptr) == LSW_ERR_ARG);
     EXPECT(lsw_adapter_workspace_bytes(nullptr, 0, 1) == -1);

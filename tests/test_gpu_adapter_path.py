@@ -19,6 +19,8 @@ CASES = [
     # T, out, in, E, r, k
     (1, 8, 8, 2, 8, 1), (37, 264, 72, 4, 8, 2), (130, 520, 1032, 8, 8, 2), (300, 256, 4096, 8, 8, 2),
     (64, 1048, 136, 3, 16, 3), (100, 776, 264, 16, 16, 2), (33, 264, 200, 4, 64, 2), (257, 136, 520, 5, 24, 2),
+    # 3 blocks of 32 down-projection rows (E * r = 96, laid out and read as 4) and 5 (laid out and read as 8)
+    (70, 72, 520, 6, 16, 2), (45, 136, 264, 5, 32, 2),
     # longer prompts: many token tiles and slices of the down-projection, ragged last tiles; 1, 2 and 4 blocks of 32
     # down-projection rows
     (1100, 136, 520, 8, 8, 2), (1030, 264, 264, 4, 8, 2), (1500, 72, 328, 8, 16, 2), (4200, 136, 264, 4, 8, 2), (4130, 72, 200, 8, 8, 2),

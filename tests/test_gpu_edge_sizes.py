@@ -84,9 +84,11 @@ def test_longest_lists_and_smallest_shapes():
         ds.close()
 
 
-def test_many_distinct_layer_subsets_do_not_grow_the_context_without_bound():
-    """Every new layer subset gets a small device table; the library keeps at most 256 of them.  600 different subsets of a
-    10-layer stack, each merged and unmerged: the owned bytes stay bounded and the weights stay right."""
+def test_many_distinct_layer_subsets_meet_a_limit_not_an_eviction():
+    """Every new layer subset gets a small device table that is never moved or freed while the context lives (launches
+    in flight and recorded graphs hold its address); a context keeps at most 256 of them.  600 different subsets of a
+    10-layer stack, each merged and unmerged: beyond the limit the call fails with LSW_ERR_STATE and touches nothing,
+    lsw_drop_subset_tables frees the tables, the owned bytes stay bounded and the weights stay right."""
     E, r, layers = 4, 8, 10
     rng = np.random.default_rng(31)
     host = [I.host_linear(rng, 64, 256, E, r, 0.02, 1 / 16, 0.01) for _ in range(layers)]
@@ -94,13 +96,20 @@ def test_many_distinct_layer_subsets_do_not_grow_the_context_without_bound():
     ds = DeviceStack.from_host(host, shapes, E, r, kernel=L.KERNEL_MFMA)
     base_bytes = L.lsw_query(ds.ctx, L.LSW_Q_PACKED_BYTES)
     a = (np.array([1, 3], np.int32), np.array([0.25, 0.75], np.float32))
-    peak = 0
+    peak, refused = 0, 0
     for mask in range(1, 601):
         subset = [l for l in range(layers) if (mask >> l) & 1]
         checked = mask % 97 == 0                             # now and then: the subset, and only it, was merged
         if checked:
             prev = [ds.rows(p) for p in range(layers)]
-        ds.switch(NONE, a, layers=subset)
+        try:
+            ds.switch(NONE, a, layers=subset)
+        except L.LswError as e:
+            assert e.status == L.LSW_ERR_STATE and "lsw_drop_subset_tables" in str(e)
+            refused += 1
+            L.lsw_drop_subset_tables(ds.ctx)
+            assert L.lsw_query(ds.ctx, L.LSW_Q_PACKED_BYTES) == base_bytes
+            ds.switch(NONE, a, layers=subset)
         if checked:
             for p in range(layers):
                 got = ds.rows(p)
@@ -111,6 +120,7 @@ def test_many_distinct_layer_subsets_do_not_grow_the_context_without_bound():
                     assert (got == prev[p]).all()
         ds.switch(a, NONE, layers=subset)
         peak = max(peak, L.lsw_query(ds.ctx, L.LSW_Q_PACKED_BYTES))
+    assert refused == 2                                      # 600 subsets, 256 tables at a time
     assert peak - base_bytes <= 257 * (2 * layers + 1) * 4
     # merge and unmerge are not exact inverses in bf16 (one rounding each), so the state now is whatever 600 such pairs
     # left; one more switch from it is checked like any other

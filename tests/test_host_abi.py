@@ -16,7 +16,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "lsw.h")).read()
+    header = "".join(open(os.path.join(ROOT, "include", h)).read() for h in ("lsw.h", "lsw_tuning.h"))
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(lsw_[a-z0-9_]+)\s*\(", header))
     assert declared == set(L.EXPORTS)

@@ -72,7 +72,9 @@ def test_adapter_forward_against_oracle(case, bf16_factors):
     assert rep["fail"] == 0, {k_: v for k_, v in rep.items() if k_ != "fail_mask"}
     print(f"[adapter quality {case} bf16={bf16_factors}] n={rep['n']} exact_frac={rep['exact'] / rep['n']:.6f} "
           f"clause2={rep['needed_clause2']} max_dist={rep['max_dist']}", flush=True)
-    assert rep["exact"] > 0.995 * rep["n"]
+    # measured: 0.9985-0.9997 bit-equal, at most 8e-5 of the outputs on the second clause (20 of 571,200)
+    assert rep["exact"] >= 0.998 * rep["n"] - 6 * (0.002 * rep["n"]) ** 0.5 - 2
+    assert rep["needed_clause2"] <= 2e-4 * rep["n"] + 6 * (2e-4 * rep["n"]) ** 0.5 + 2
     assert (got != Y).mean() > 0.2, "the adapter term must have changed a good part of Y"
     assert L.lsw_dev_status(ds.ctx) == 0
     ds.close()

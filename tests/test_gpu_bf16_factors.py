@@ -63,7 +63,7 @@ def test_bf16_factors_ragged_shapes(shape, kernel):
         assert rep["fail"] == 0, (old, new, {k: v for k, v in rep.items() if k != "fail_mask"})
         reports.append(rep)
         prev = got
-    gate_quality(merge_reports(reports), f"bf16 factors ragged {shape} kernel={kernel}", exact_min=0.995, clause2_max=1e-3)
+    gate_quality(merge_reports(reports), f"bf16 factors ragged {shape} kernel={kernel}", exact_min=0.999, clause2_max=1.5e-4)
     if kernel == L.KERNEL_MFMA and r >= 32:
         assert L.KERNEL_MFMA in used
     ds.close()
@@ -113,7 +113,7 @@ def test_bf16_factors_tiny_workload_every_step():
         assert rep["fail"] == 0
         reports.append(rep)
         prev, old = got, new
-    gate_quality(merge_reports(reports), "bf16 factors tiny", exact_min=0.999, clause2_max=1e-3)
+    gate_quality(merge_reports(reports), "bf16 factors tiny", exact_min=0.999, clause2_max=1.5e-4)
     ds.close()
 
 

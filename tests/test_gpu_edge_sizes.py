@@ -38,7 +38,7 @@ def test_largest_single_weight(kernel):
         assert rep["fail"] == 0, {k: v for k, v in rep.items() if k != "fail_mask"}
         assert not torch.equal(W[-1, -8:], guard)          # the very last 16 bytes were updated
         reports.append(rep)
-    gate_quality(merge_reports(reports), "largest single weight", exact_min=0.999, clause2_max=1e-3)
+    gate_quality(merge_reports(reports), "largest single weight", exact_min=0.9998, clause2_max=2e-5)
     ds.close()
     # one more row of 128 would cross 2^31 bytes: refused at create time, before any launch
     with pytest.raises(L.LswError) as e:

@@ -15,6 +15,11 @@ from tests.gpu_harness import bf16_factor_stack, DeviceStack, bits_to_device, ch
 
 pytestmark = pytest.mark.gpu
 KERNELS = [L.KERNEL_VALU, L.KERNEL_MFMA]
+# Quality gates of the small workloads (see gpu_harness.gate_quality).  Their updates are 4 times larger against the
+# weights than those of the model-shaped stacks (A has standard deviation 1/16), so more elements sit near a rounding
+# boundary: measured 0.99996-0.999995 bit-equal and at most 2.5e-6 on the second clause with fp32 accumulation (the
+# vector-ALU kernel), 0.99934-0.99981 and at most 5.3e-5 with the three-pass split on the matrix cores.
+SMALL_GATES = {L.KERNEL_VALU: dict(exact_min=0.9999, clause2_max=1e-5), L.KERNEL_MFMA: dict(exact_min=0.999, clause2_max=1.5e-4)}
 
 
 def _route_stream(wl, steps):
@@ -46,7 +51,7 @@ def test_tiny_workload_every_step_full_matrix(kernel):
     tot = merge_reports(reports)
     print(f"\n[tiny kernel={kernel}] {tot}; free-running mismatch after {wl.steps} steps: "
           f"{(free != prev).mean():.4%}")
-    gate_quality(tot, f"tiny kernel={kernel}", exact_min=0.999, clause2_max=1e-3)
+    gate_quality(tot, f"tiny kernel={kernel}", **SMALL_GATES[kernel])
     # restore the base weights: within the drift the oracle itself predicts
     ds.switch(old, (np.zeros(0, np.int32), np.zeros(0, np.float32)))
     rep, _ = check_step(prev, ds.rows(0), A, B, old, (np.zeros(0, np.int32), np.zeros(0, np.float32)))
@@ -136,7 +141,7 @@ def test_ragged_shapes_and_term_counts(shape, kernel):
         assert rep["fail"] == 0, (old, new, {k: v for k, v in rep.items() if k != "fail_mask"})
         reports.append(rep)
         prev = got
-    gate_quality(merge_reports(reports), f"ragged {shape} kernel={kernel}", exact_min=0.995, clause2_max=1e-3)
+    gate_quality(merge_reports(reports), f"ragged {shape} kernel={kernel}", **SMALL_GATES[kernel])
     if kernel == L.KERNEL_MFMA and r >= 32:
         assert L.KERNEL_MFMA in kernels_used
     ds.close()
@@ -455,13 +460,14 @@ def test_probe_inplace_leaves_weights_unchanged():
     wl = I.Workload("mini", 2, 64, 136, 32, 4, 8, 2, 4, 0.02, 1 / 8, 0.01, 515)
     host = I.host_stack(wl)
     ds = DeviceStack.from_host(host, wl.linear_shapes(), wl.experts, wl.rank)
-    for wpc in (1, 4):
+    for wpc in (1, 4, 0):          # 0 = the switch kernel's own launch with the work taken out
         L.lsw_probe_inplace(ds.ctx, wpc, torch.cuda.current_stream().cuda_stream)
     for p_, (W, _, _) in enumerate(host):
         got = ds.rows(p_)
         neg_zero = W == 0x8000
         assert (got[~neg_zero] == W[~neg_zero]).all()
         assert (got[neg_zero] == 0).all()
-    with pytest.raises(L.LswError):
-        L.lsw_probe_inplace(ds.ctx, 0)
+    for bad in (-1, 17):
+        with pytest.raises(L.LswError):
+            L.lsw_probe_inplace(ds.ctx, bad)
     ds.close()

@@ -94,6 +94,121 @@ def probe_pitch(torch, L):
         del Ws, A, B
 
 
+def switch_roofline(wl, terms, kernels, launch_bytes, avg_ms, bf16_factors, traffic):
+    """HBM roofline of the timed launches, or the matrix-core one where the three-pass product needs longer at the bf16
+    matrix peak than the algorithmic bytes need at the HBM peak (fused ranks above 64 with fp32-stored factors)."""
+    mean_bytes = sum(launch_bytes) / len(launch_bytes)
+    achieved = mean_bytes / (avg_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic}
+    mean_terms = sum(terms) / len(terms)
+    if max(kernels) == 2 and mean_terms * wl.rank > 64:
+        # fused ranks above 64: three bf16 passes (two, or one, with bf16-stored factors) of 2*K flop per weight
+        passes = (1.0 if wl.rank % 16 == 0 else 2.0) if bf16_factors else 3.0    # exact bf16 factors of such a rank: one pass
+        flops = [passes * 2.0 * n * wl.rank * wl.w_elements() for n, k in zip(terms, kernels) if k != 0]
+        mean_flops = sum(flops) / len(flops)
+        if mean_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12) > mean_bytes / (HBM_PEAK_GBPS * 1e9):
+            tf = mean_flops / (avg_ms * 1e-3) / 1e12
+            roofline = {"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                        "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic,
+                        "hbm_GBps": round(achieved, 1), "hbm_frac": round(achieved / HBM_PEAK_GBPS, 4)}
+    return roofline, achieved
+
+
+def time_switches(torch, L, I, wl, ctx, steps, warmup, bf16_factors, old=None, stream=0):
+    """`warmup` untimed and `steps` timed token steps (route on the host, one lsw_switch over all layers), an event pair
+    around every launch.  Returns (stats dict, merged set after the last step, wall seconds of the timed region)."""
+    import numpy as np
+    logits = I.router_logits(wl, warmup + steps)
+    old = (np.zeros(0, np.int32), np.zeros(0, np.float32)) if old is None else old
+
+    def token(t, old):
+        new = L.lsw_route(logits[t], wl.top_k)                         # step a1 (host)
+        L.lsw_switch(ctx, old[0], old[1], new[0], new[1], stream=stream)   # steps a2-a6 (one launch)
+        return new
+
+    for t in range(warmup):
+        old = token(t, old)
+    torch.cuda.synchronize()
+    # accounting pass (host only, outside the timed region): how many terms each timed launch carries
+    terms, prev = [], old
+    for i in range(steps):
+        nxt = L.lsw_route(logits[warmup + i], wl.top_k)
+        terms.append(len(L.lsw_build_terms(prev[0], prev[1], nxt[0], nxt[1], wl.experts)[0]))
+        prev = nxt
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    kernels, variants = [], []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        ev[i][0].record()
+        old = token(warmup + i, old)
+        ev[i][1].record()
+        kernels.append(L.lsw_query(ctx, L.LSW_Q_LAST_KERNEL))
+        variants.append(L.lsw_query(ctx, L.LSW_Q_LAST_VARIANT))
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    fb = 2 if bf16_factors else 4
+    launch_ms = [a.elapsed_time(b) for (a, b), k in zip(ev, kernels) if k != 0]
+    launch_bytes = [algorithmic_bytes(wl, n, fb) for n, k in zip(terms, kernels) if k != 0]
+    avg_ms = sum(launch_ms) / len(launch_ms)
+    med_ms = sorted(launch_ms)[len(launch_ms) // 2]
+    rates = sorted(b / (ms * 1e-3) / 1e9 for b, ms in zip(launch_bytes, launch_ms))
+    mix = {}
+    for n, k, v, ms in zip(terms, kernels, variants, [a.elapsed_time(b) for a, b in ev]):
+        if k == 0:
+            continue
+        key = f"{n}_terms"
+        m = mix.setdefault(key, {"launches": 0, "us": 0.0, "kernel": VARIANT_NAMES.get(v, str(v))})
+        m["launches"] += 1
+        m["us"] += ms * 1e3
+    for m in mix.values():
+        m["us"] = round(m["us"] / m["launches"], 1)
+    stats = {"terms": terms, "kernels": kernels, "launch_ms": launch_ms, "launch_bytes": launch_bytes, "avg_ms": avg_ms, "med_ms": med_ms,
+             "median_GBps": rates[len(rates) // 2], "mix": mix, "grid": L.lsw_query(ctx, L.LSW_Q_LAST_GRID)}
+    return stats, old, wall
+
+
+VARIANT_NAMES = {0: "vector-ALU", 1: "matrix-core, A streamed per step", 2: "matrix-core, A resident in LDS", 3: "matrix-core, chunked fused rank"}
+
+
+def other_config(torch, L, I, name, factor_dtype, steps, warmup, traffic_table):
+    """One more workload on the same line: stack drawn, switched `steps` times, freed.  Returns its entry."""
+    wl = I.WORKLOADS[name]
+    bf16_factors = factor_dtype == "bf16"
+    need = 2 * wl.w_elements() + (2 if bf16_factors else 4) * 2 * wl.experts * wl.rank * wl.factor_dims() + (6 << 30)
+    free, _ = torch.cuda.mem_get_info()
+    if free < need:
+        return {"skipped": f"needs {need / 1e9:.0f} GB of free device memory, {free / 1e9:.0f} GB are free"}
+    t0 = time.perf_counter()
+    stack = I.device_stack(wl, factor_dtype=torch.bfloat16 if bf16_factors else torch.float32)
+    ctx = L.create_from_tensors(stack, wl.linear_shapes(), wl.experts, wl.rank)
+    stats, _, wall = time_switches(torch, L, I, wl, ctx, steps, warmup, bf16_factors, stream=torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    L.lsw_destroy(ctx)
+    del stack
+    torch.cuda.empty_cache()
+    key = name + ("_bf16_factors" if bf16_factors else "")
+    roofline, achieved = switch_roofline(wl, stats["terms"], stats["kernels"], stats["launch_bytes"], stats["avg_ms"], bf16_factors,
+                                         traffic_table.get(key))
+    return {
+        "workload": f"{wl.name}: {wl.layers} layers x 7 linears, hidden {wl.hidden}, ffn {wl.ffn}, E={wl.experts}, r={wl.rank}, "
+                    f"top-{wl.top_k}, factors stored as {factor_dtype}",
+        "steps": steps, "warmup": warmup,
+        "us": {"mean": round(stats["avg_ms"] * 1e3, 1), "median": round(stats["med_ms"] * 1e3, 1), "min": round(min(stats["launch_ms"]) * 1e3, 1),
+               "wall_per_step": round(wall * 1e6 / steps, 1)},
+        "algorithmic_bytes_mean": int(sum(stats["launch_bytes"]) / len(stats["launch_bytes"])),
+        "terms_per_step_mean": round(sum(stats["terms"]) / len(stats["terms"]), 3),
+        "launch_mix": stats["mix"],
+        "hbm_GBps": {"from_mean": round(achieved, 1), "median_of_launches": round(stats["median_GBps"], 1)},
+        "roofline": roofline,
+        "setup_s": round(time.perf_counter() - t0 - wall, 1),
+    }
+
+
+OTHER_CONFIGS = (("7b_r64", "fp32", 16), ("7b_r64", "bf16", 16), ("13b", "fp32", 16), ("70b", "fp32", 8))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -117,6 +232,11 @@ def main():
     ap.add_argument("--switch-only", action="store_true",
                     help="time the switch launches only (profiling runs: every launch of the switch kernel is then a timed one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--configs", default="all",
+                    help="'all' (default): after the headline workload also time 7b_r64 (fp32- and bf16-stored factors), 13b and 70b "
+                         "with fewer steps, one entry each under \"configs\"; 'none': the headline only")
+    ap.add_argument("--time-budget", type=float, default=420.0,
+                    help="seconds this run may take before the remaining workloads under \"configs\" are written as skipped")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 4 GiB device copy (a known-size reference for HBM byte counters)")
     args = ap.parse_args()
@@ -126,6 +246,7 @@ def main():
               "same launch on their share of the layers. Re-run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
+    t_start = time.perf_counter()
     import numpy as np
     import torch
     from paper_2405_17741_amd import binding as L
@@ -158,41 +279,9 @@ def main():
         L.lsw_set_option(ctx, L.LSW_OPT_PANEL_GROUP, args.panel_group)
     stream = torch.cuda.current_stream().cuda_stream
 
-    n_tokens = args.warmup + args.steps
-    logits = I.router_logits(wl, n_tokens)
-    old = (np.zeros(0, np.int32), np.zeros(0, np.float32))
-
-    def token(t, old):
-        new = L.lsw_route(logits[t], wl.top_k)                         # step a1 (host)
-        L.lsw_switch(ctx, old[0], old[1], new[0], new[1], stream=stream)   # steps a2-a6 (one launch)
-        return new
-
-    for t in range(args.warmup):
-        old = token(t, old)
-    torch.cuda.synchronize()
-
-    # accounting pass (host only, outside the timed region): how many terms each timed launch carries
-    terms, prev = [], old
-    for i in range(args.steps):
-        nxt = L.lsw_route(logits[args.warmup + i], wl.top_k)
-        terms.append(len(L.lsw_build_terms(prev[0], prev[1], nxt[0], nxt[1], wl.experts)[0]))
-        prev = nxt
-
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    kernels = []
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        ev[i][0].record()
-        old = token(args.warmup + i, old)
-        ev[i][1].record()
-        kernels.append(L.lsw_query(ctx, L.LSW_Q_LAST_KERNEL))
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-
-    launch_ms = [a.elapsed_time(b) for (a, b), k in zip(ev, kernels) if k != 0]
-    launch_bytes = [algorithmic_bytes(wl, n, 2 if bf16_factors else 4) for n, k in zip(terms, kernels) if k != 0]
-    avg_ms = sum(launch_ms) / len(launch_ms)
+    logits = I.router_logits(wl, args.warmup + args.steps)
+    stats, old, wall = time_switches(torch, L, I, wl, ctx, args.steps, args.warmup, bf16_factors, stream=stream)
+    terms, kernels, launch_ms, launch_bytes, avg_ms = stats["terms"], stats["kernels"], stats["launch_ms"], stats["launch_bytes"], stats["avg_ms"]
     achieved = (sum(launch_bytes) / len(launch_bytes)) / (avg_ms * 1e-3) / 1e9
     ms_per_step = wall * 1e3 / args.steps
 
@@ -201,7 +290,7 @@ def main():
     n_dev, dev_flags = 0, 0
     if not args.switch_only:
         # yardstick: the same tensors, the same access pattern, no factor traffic and no matrix work
-        for wpc in (2, 4):
+        for wpc in ((0, 2, 4) if wl.rank % 8 == 0 else (2, 4)):
             L.lsw_probe_inplace(ctx, wpc, stream)
             torch.cuda.synchronize()
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -210,7 +299,7 @@ def main():
                 L.lsw_probe_inplace(ctx, wpc, stream)
             b.record()
             b.synchronize()
-            probe[f"{wpc}_waves_per_cu_GBps"] = round(4.0 * wl.w_elements() / (a.elapsed_time(b) / 5 * 1e-3) / 1e9, 1)
+            probe["switch_pattern_GBps" if wpc == 0 else f"{wpc}_waves_per_cu_GBps"] = round(4.0 * wl.w_elements() / (a.elapsed_time(b) / 5 * 1e-3) / 1e9, 1)
 
         # the decode that follows the switch (timed separately): every merged linear once, batch 1
         nx, ny = L.lsw_query(ctx, L.LSW_Q_GEMV_X_ELEMS), L.lsw_query(ctx, L.LSW_Q_GEMV_Y_ELEMS)
@@ -322,27 +411,17 @@ def main():
                                "three launches per linear"}
             del xs, ys, ws
 
-    traffic = None
+    traffic_table = {}
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(args.workload + ("_bf16_factors" if bf16_factors else ""))
+            traffic_table = json.load(open(tpath))
         except Exception:
-            traffic = None
-
-    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic}
+            traffic_table = {}
+    roofline, _ = switch_roofline(wl, terms, kernels, launch_bytes, avg_ms, bf16_factors,
+                                  traffic_table.get(args.workload + ("_bf16_factors" if bf16_factors else "")))
+    roofline["achieved_from_median"] = round(stats["median_GBps"], 1)
     mean_terms = sum(terms) / len(terms)
-    if max(kernels) == 2 and mean_terms * wl.rank > 64:
-        # fused ranks above 64: three bf16 passes (two, or one, with bf16-stored factors) of 2*K flop per weight; whichever
-        # of the two floors (matrix work at the bf16 peak, algorithmic bytes at the HBM peak) is longer is the roofline
-        passes = (1.0 if wl.rank % 16 == 0 else 2.0) if bf16_factors else 3.0    # exact bf16 factors of such a rank: one pass
-        flops = [passes * 2.0 * n * wl.rank * wl.w_elements() for n, k in zip(terms, kernels) if k != 0]
-        mean_flops, mean_bytes = sum(flops) / len(flops), sum(launch_bytes) / len(launch_bytes)
-        if mean_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12) > mean_bytes / (HBM_PEAK_GBPS * 1e9):
-            tf = mean_flops / (avg_ms * 1e-3) / 1e12
-            roofline = {"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                        "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic}
 
     out = {
         "metric": "switch latency us/token (all layers) + achieved HBM GB/s, 7B-shaped adapters",
@@ -358,7 +437,8 @@ def main():
                    "grid": L.lsw_query(ctx, L.LSW_Q_LAST_GRID),
                    "terms_per_step_mean": round(sum(terms) / len(terms), 3),
                    "launch_us": {"mean": round(avg_ms * 1e3, 1), "min": round(min(launch_ms) * 1e3, 1),
-                                 "median": round(sorted(launch_ms)[len(launch_ms) // 2] * 1e3, 1)}},
+                                 "median": round(sorted(launch_ms)[len(launch_ms) // 2] * 1e3, 1)},
+                   "launch_mix": stats["mix"]},
         "achieved_hbm_GBps": round(achieved, 1),
         "roofline": roofline,
     }
@@ -373,13 +453,30 @@ def main():
             "adapter_prefill": adapter,
             "layer_subset": subset,
             "rebase": rebase,
-            "inplace_probe": {**probe, "note": "lsw_probe_inplace on the same weights: in-place bf16 read+write only; "
-                                               "the practical ceiling of the switch's access pattern",
+            "inplace_probe": {**probe, "note": "lsw_probe_inplace on the same weights: in-place bf16 read+write only, no factor traffic, no "
+                                               "matrix work; switch_pattern = the switch kernel's own launch (4-wave workgroups, its item "
+                                               "order and pool, its per-step schedule) with the work taken out; N_waves_per_cu = single-wave "
+                                               "workgroups walking 32-row items",
                               "switch_over_best_probe": round(achieved / max(probe.values()), 4)},
         })
     torch.cuda.synchronize()
     L.lsw_destroy(ctx)
     del stack
+    torch.cuda.empty_cache()
+    if args.configs == "all" and not args.switch_only and args.workload == "7b" and not bf16_factors:
+        # the other workload shapes, fewer steps each; the CPU baseline (about 15 s) still has to fit behind them
+        out["configs"] = {}
+        for name, fdt, steps in OTHER_CONFIGS:
+            key = name + ("_bf16_factors" if fdt == "bf16" else "")
+            spent = time.perf_counter() - t_start
+            if spent > args.time_budget - (150.0 if name == "70b" else 40.0):
+                out["configs"][key] = {"skipped": f"time budget: {spent:.0f} s of {args.time_budget:.0f} s spent before this workload"}
+                continue
+            try:
+                out["configs"][key] = other_config(torch, L, I, name, fdt, steps, 2, traffic_table)
+            except torch.cuda.OutOfMemoryError as e:
+                out["configs"][key] = {"skipped": f"out of device memory: {str(e)[:120]}"}
+                torch.cuda.empty_cache()
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.float32, device="cuda").normal_()
         dst = torch.empty_like(src)

@@ -272,6 +272,22 @@ lsw_status lsw_adapter_forward(lsw_ctx* ctx, int32_t lin_index, const void* X_bf
                                void* Y_bf16, void* workspace, void* hip_stream);
 
 /*
+ * lsw_adapter_forward for callers that can neither allocate device memory nor bring a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without the workspace, same three
+ * launches, same result bit for bit; the partial sums and the gate table live in a device array of 32 MiB that is part
+ * of the library's code object (every GPU the library runs on holds its own copy until the process ends; its address on
+ * the context's device is looked up once, at lsw_enable_adapter_path).  The call allocates and frees nothing and
+ * synchronises nothing.  T is limited by lsw_adapter_workspace_bytes(ctx, lin_index, T) <= 32 MiB (33,554,432 bytes; about
+ * 13,000 to 100,000 tokens of a 4096-wide linear, depending on E * r): beyond it LSW_ERR_SHAPE, nothing launched.  Every call on
+ * one GPU, from any context, uses the same array: calls that overlap on one GPU (two streams, two threads) race on it;
+ * order them.  Nothing in it has to be cleared between calls (the kernels write every word they later read).
+ * Other errors: as lsw_adapter_forward.
+ */
+lsw_status lsw_adapter_forward_static(lsw_ctx* ctx, int32_t lin_index, const void* X_bf16, int32_t T,
+                                      const int32_t* ids_dev, const float* gates_dev, int32_t k,
+                                      void* Y_bf16, void* hip_stream);
+
+/*
  * The signed coefficient list one switch applies (Alg. 1 steps 2-3 without moving any tensor:
  * Eq. 5 puts the gate on one factor, Eq. 9 negates the previous set): new experts with
  * +scale*g, old experts with -scale*g, an expert in both with scale*g_new - scale*g_old,

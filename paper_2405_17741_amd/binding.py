@@ -25,7 +25,7 @@ EXPORTS = (
     "lsw_destroy", "lsw_last_error", "lsw_probe_inplace", "lsw_merged_gemv_all",
     "lsw_route_dev", "lsw_switch_dev", "lsw_dev_status", "lsw_gemv_bf16", "lsw_create_adapters_ex",
     "lsw_set_base", "lsw_rebase", "lsw_enable_adapter_path", "lsw_adapter_workspace_bytes", "lsw_route_batch_dev",
-    "lsw_adapter_forward", "lsw_drop_subset_tables",
+    "lsw_adapter_forward", "lsw_drop_subset_tables", "lsw_adapter_forward_static",
 )
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblsw.so")
@@ -66,6 +66,8 @@ def lib() -> C.CDLL:
         L.lsw_route_batch_dev.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.lsw_adapter_forward.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
                                           C.c_void_p, C.c_void_p, C.c_void_p]
+        L.lsw_adapter_forward_static.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
+                                                 C.c_void_p, C.c_void_p]
         L.lsw_set_base.argtypes = [C.c_void_p, C.POINTER(C.c_void_p), C.c_int32]
         L.lsw_rebase.argtypes = [C.c_void_p, _i32p, C.c_int32, _i32p, _f32p, C.c_int32, C.c_void_p]
         L.lsw_merged_gemv.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -175,6 +177,12 @@ def lsw_adapter_forward(ctx: int, lin_index: int, X_ptr: int, T: int, ids_ptr: i
                         workspace_ptr: int, stream: int = 0) -> None:
     _check(lib().lsw_adapter_forward(ctx, lin_index, C.c_void_p(X_ptr), T, C.c_void_p(ids_ptr), C.c_void_p(gates_ptr), k,
                                      C.c_void_p(Y_ptr), C.c_void_p(workspace_ptr), C.c_void_p(stream)))
+
+
+def lsw_adapter_forward_static(ctx: int, lin_index: int, X_ptr: int, T: int, ids_ptr: int, gates_ptr: int, k: int, Y_ptr: int,
+                               stream: int = 0) -> None:
+    _check(lib().lsw_adapter_forward_static(ctx, lin_index, C.c_void_p(X_ptr), T, C.c_void_p(ids_ptr), C.c_void_p(gates_ptr), k,
+                                            C.c_void_p(Y_ptr), C.c_void_p(stream)))
 
 
 def lsw_set_base(ctx: int, base_ptrs) -> None:

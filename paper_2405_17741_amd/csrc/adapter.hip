@@ -2,7 +2,38 @@
 #include "lsw_device.h"
 #include "lsw_mfma.h"
 
+#include <mutex>
+
 namespace lsw {
+
+// ---------------------------------------------------------------------------
+// Workspace of lsw_adapter_forward_static: device memory that exists from the moment the library is loaded on a GPU
+// until the process ends, so that the call needs no allocation and no workspace from its caller.  Each GPU holds its own
+// copy at its own address; host code never uses the array's name as an address, only what hipGetSymbolAddress returned
+// for the device that was current (looked up once per device, at lsw_enable_adapter_path).
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+hipError_t adapter_static_scratch(int device, void** ptr) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* table[kMaxDevices] = {};
+  if (device < 0 || device >= kMaxDevices || !ptr) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> guard(mu);
+  if (!table[device]) {
+    int cur = -1;
+    hipError_t e = hipGetDevice(&cur);
+    if (e != hipSuccess) return e;
+    if (cur != device) return hipErrorInvalidDevice;      // the address belongs to the device that is current
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    table[device] = p;
+  }
+  *ptr = table[device];
+  return hipSuccess;
+}
 
 // ---------------------------------------------------------------------------
 // Un-merged adapter path for many tokens (Eq. 2: y = f(x) + sum_i G(x1)_i E_i(x), E_i(x) = W_up (W_down x)).

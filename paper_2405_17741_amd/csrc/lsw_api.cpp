@@ -77,6 +77,7 @@ struct lsw_ctx {
   std::vector<LinDesc> desc;                 // host copy of the descriptor table
   bool have_base = false;                    // lsw_set_base has registered the base copies
   uint16_t* d_apk = nullptr;                 // packed A of all linears (r % 8 == 0 only)
+  void* static_scratch = nullptr;            // this device's copy of the library's static workspace (lsw_adapter_forward_static)
   uint16_t* d_adapter = nullptr;             // adapter path: per linear the down-projection layout of A, then the packed B^T
   std::vector<size_t> atk_off, bpk_off;      // element offsets of the two parts of linear p inside d_adapter
   char* d_slots = nullptr;                   // the sticky error word (first kSlotBytes), then kLaunchSlots launch slots
@@ -705,6 +706,10 @@ static int z_stride_of(const lsw_ctx* c) { return ceil_div(c->E * c->r, 16) * 16
 extern "C" lsw_status lsw_enable_adapter_path(lsw_ctx* c) {
   if (lsw_status ready = ctx_ready(c)) return ready;
   if (c->d_adapter) return LSW_OK;
+  {   // the address of the static workspace on this device (the context's device is current: ctx_ready)
+    hipError_t se = adapter_static_scratch(c->device, &c->static_scratch);
+    if (se != hipSuccess) { c->static_scratch = nullptr; return fail(LSW_ERR_DEVICE, "address of the static workspace: %s", hipGetErrorString(se)); }
+  }
   if (c->r % 8 != 0 || c->E * c->r > 256)
     return fail(LSW_ERR_SHAPE, "the adapter path needs r %% 8 == 0 and E * r <= 256 (E=%d, r=%d)", c->E, c->r);
   const size_t n_lin = c->lin.size();
@@ -788,6 +793,21 @@ extern "C" lsw_status lsw_adapter_forward(lsw_ctx* c, int32_t lin_index, const v
   e = bigk ? launch_switch_mfma_bigk(lp, t, nullptr, c->r, c->qp, grid, s) : launch_switch_mfma(lp, t, nullptr, c->r, c->qp, grid, s);
   if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "up-projection launch failed: %s", hipGetErrorString(e));
   return LSW_OK;
+}
+
+extern "C" lsw_status lsw_adapter_forward_static(lsw_ctx* c, int32_t lin_index, const void* X_bf16, int32_t T,
+                                                 const int32_t* ids_dev, const float* gates_dev, int32_t k,
+                                                 void* Y_bf16, void* hip_stream) {
+  if (lsw_status ready = ctx_ready(c)) return ready;
+  if (!c->d_adapter || !c->static_scratch) return fail(LSW_ERR_STATE, "lsw_adapter_forward_static: call lsw_enable_adapter_path first");
+  if (lin_index < 0 || size_t(lin_index) >= c->lin.size()) return fail(LSW_ERR_ARG, "lin_index %d out of range", lin_index);
+  if (T < 1) return fail(LSW_ERR_ARG, "T=%d < 1", T);
+  const int64_t need = lsw_adapter_workspace_bytes(c, lin_index, T);
+  if (need < 0 || need > int64_t(kStaticScratchBytes))
+    return fail(LSW_ERR_SHAPE, "T=%d tokens need %lld bytes of workspace, the static one holds %lld: use lsw_adapter_forward with a workspace of the caller's",
+                T, (long long)need, (long long)kStaticScratchBytes);
+  // same checks, same three launches; the kernels get the device address looked up at lsw_enable_adapter_path
+  return lsw_adapter_forward(c, lin_index, X_bf16, T, ids_dev, gates_dev, k, Y_bf16, c->static_scratch, hip_stream);
 }
 
 extern "C" lsw_status lsw_dev_status(lsw_ctx* c, int32_t* flags) {

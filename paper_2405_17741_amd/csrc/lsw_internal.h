@@ -162,6 +162,8 @@ hipError_t launch_probe_inplace(const LaunchPlan& p, int grid, hipStream_t s);
 // transposed = 0: source A [E][r][in] (columns = in);  1: source B [E][out][r] read as B^T [E][r][out] (columns = out)
 hipError_t launch_pack_A(const void* A, uint16_t* Apk, int E, int r, int in, int qp, int transposed, hipStream_t s);
 // adapter path (Eq. 2 for many tokens)
+constexpr size_t kStaticScratchBytes = size_t(32) << 20;          // workspace limit of lsw_adapter_forward_static (a device array of this size per GPU)
+hipError_t adapter_static_scratch(int device, void** ptr);        // its address on `device`, which must be the current device
 int64_t adapter_atk_elems(int E, int r, int in, int qp);          // bf16 elements of the down-projection layout of one linear
 int adapter_slices(int T, int in);                                // partial sums the down-projection is cut into
 hipError_t launch_pack_Atk(const void* A, uint16_t* Atk, int E, int r, int in, int qp, hipStream_t s);

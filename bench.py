@@ -94,6 +94,14 @@ def probe_pitch(torch, L):
         del Ws, A, B
 
 
+def fast_pitch(n_cols: int) -> int:
+    """The next leading dimension (elements) at which rows are 4, 8, 16 or 32 KB apart, or a multiple of 32 KB beyond."""
+    for ld in (2048, 4096, 8192, 16384):
+        if n_cols <= ld:
+            return ld
+    return -(-n_cols // 16384) * 16384
+
+
 def switch_roofline(wl, terms, kernels, launch_bytes, avg_ms, bf16_factors, traffic):
     """HBM roofline of the timed launches, or the matrix-core one where the three-pass product needs longer at the bf16
     matrix peak than the algorithmic bytes need at the HBM peak (fused ranks above 64 with fp32-stored factors)."""
@@ -172,28 +180,31 @@ def time_switches(torch, L, I, wl, ctx, steps, warmup, bf16_factors, old=None, s
 VARIANT_NAMES = {0: "vector-ALU", 1: "matrix-core, A streamed per step", 2: "matrix-core, A resident in LDS", 3: "matrix-core, chunked fused rank"}
 
 
-def other_config(torch, L, I, name, factor_dtype, steps, warmup, traffic_table):
+def other_config(torch, L, I, name, factor_dtype, steps, warmup, traffic_table, pad_pitch=False):
     """One more workload on the same line: stack drawn, switched `steps` times, freed.  Returns its entry."""
     wl = I.WORKLOADS[name]
     bf16_factors = factor_dtype == "bf16"
-    need = 2 * wl.w_elements() + (2 if bf16_factors else 4) * 2 * wl.experts * wl.rank * wl.factor_dims() + (6 << 30)
+    w_alloc = sum(o * (fast_pitch(n) if pad_pitch else n) for _, _, o, n in wl.linear_shapes())
+    need = 2 * w_alloc + (2 if bf16_factors else 4) * 2 * wl.experts * wl.rank * wl.factor_dims() + (6 << 30)
     free, _ = torch.cuda.mem_get_info()
     if free < need:
         return {"skipped": f"needs {need / 1e9:.0f} GB of free device memory, {free / 1e9:.0f} GB are free"}
     t0 = time.perf_counter()
-    stack = I.device_stack(wl, factor_dtype=torch.bfloat16 if bf16_factors else torch.float32)
+    stack = I.device_stack(wl, factor_dtype=torch.bfloat16 if bf16_factors else torch.float32, ld_of=fast_pitch if pad_pitch else None)
     ctx = L.create_from_tensors(stack, wl.linear_shapes(), wl.experts, wl.rank)
     stats, _, wall = time_switches(torch, L, I, wl, ctx, steps, warmup, bf16_factors, stream=torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()
     L.lsw_destroy(ctx)
     del stack
     torch.cuda.empty_cache()
-    key = name + ("_bf16_factors" if bf16_factors else "")
+    key = name + ("_bf16_factors" if bf16_factors else "") + ("_pitch_padded" if pad_pitch else "")
     roofline, achieved = switch_roofline(wl, stats["terms"], stats["kernels"], stats["launch_bytes"], stats["avg_ms"], bf16_factors,
                                          traffic_table.get(key))
     return {
         "workload": f"{wl.name}: {wl.layers} layers x 7 linears, hidden {wl.hidden}, ffn {wl.ffn}, E={wl.experts}, r={wl.rank}, "
-                    f"top-{wl.top_k}, factors stored as {factor_dtype}",
+                    f"top-{wl.top_k}, factors stored as {factor_dtype}"
+                    + (", every weight stored at a row pitch of 4, 8, 16 or 32 KB (lsw_linear::ld; same algorithmic bytes, "
+                       f"{2 * w_alloc / 1e9:.1f} GB allocated for {2 * wl.w_elements() / 1e9:.1f} GB of weights)" if pad_pitch else ""),
         "steps": steps, "warmup": warmup,
         "us": {"mean": round(stats["avg_ms"] * 1e3, 1), "median": round(stats["med_ms"] * 1e3, 1), "min": round(min(stats["launch_ms"]) * 1e3, 1),
                "wall_per_step": round(wall * 1e6 / steps, 1)},
@@ -206,7 +217,8 @@ def other_config(torch, L, I, name, factor_dtype, steps, warmup, traffic_table):
     }
 
 
-OTHER_CONFIGS = (("7b_r64", "fp32", 16), ("7b_r64", "bf16", 16), ("13b", "fp32", 16), ("70b", "fp32", 8))
+OTHER_CONFIGS = (("7b_r64", "fp32", 16, False), ("7b_r64", "bf16", 16, False), ("13b", "fp32", 16, False), ("70b", "fp32", 8, False),
+                 ("7b", "fp32", 16, True), ("13b", "fp32", 16, True))
 
 
 def main():
@@ -231,6 +243,9 @@ def main():
                          "as a function of its row pitch; prints a table")
     ap.add_argument("--switch-only", action="store_true",
                     help="time the switch launches only (profiling runs: every launch of the switch kernel is then a timed one)")
+    ap.add_argument("--pad-pitch", action="store_true",
+                    help="store every weight whose rows are not 4, 8, 16 or 32 KB apart at the next such leading dimension "
+                         "(lsw_linear::ld; the padding columns are never touched): an in-place pass runs fastest at those pitches")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--configs", default="all",
                     help="'all' (default): after the headline workload also time 7b_r64 (fp32- and bf16-stored factors), 13b and 70b "
@@ -261,7 +276,7 @@ def main():
         return
     wl = I.WORKLOADS[args.workload]
     bf16_factors = args.factor_dtype == "bf16"
-    stack = I.device_stack(wl, factor_dtype=torch.bfloat16 if bf16_factors else torch.float32)
+    stack = I.device_stack(wl, factor_dtype=torch.bfloat16 if bf16_factors else torch.float32, ld_of=fast_pitch if args.pad_pitch else None)
     ctx = L.create_from_tensors(stack, wl.linear_shapes(), wl.experts, wl.rank)
     if args.kernel:
         L.lsw_set_option(ctx, L.LSW_OPT_KERNEL, args.kernel)
@@ -430,7 +445,8 @@ def main():
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{wl.name}: {wl.layers} layers x 7 linears, hidden {wl.hidden}, ffn {wl.ffn}, "
-                               f"E={wl.experts}, r={wl.rank}, top-{wl.top_k}, all layers per launch, factors stored as {args.factor_dtype}",
+                               f"E={wl.experts}, r={wl.rank}, top-{wl.top_k}, all layers per launch, factors stored as {args.factor_dtype}"
+                               + (", weights stored at 4/8/16/32 KB row pitch" if args.pad_pitch else ""),
                    "w_elements": wl.w_elements(),
                    "kernel": {0: "none", 1: "vector-ALU", 2: "matrix-core"}[max(kernels)],
                    "fused_rank_mean": round(mean_terms * wl.rank, 1),
@@ -466,14 +482,14 @@ def main():
     if args.configs == "all" and not args.switch_only and args.workload == "7b" and not bf16_factors:
         # the other workload shapes, fewer steps each; the CPU baseline (about 15 s) still has to fit behind them
         out["configs"] = {}
-        for name, fdt, steps in OTHER_CONFIGS:
-            key = name + ("_bf16_factors" if fdt == "bf16" else "")
+        for name, fdt, steps, pad in OTHER_CONFIGS:
+            key = name + ("_bf16_factors" if fdt == "bf16" else "") + ("_pitch_padded" if pad else "")
             spent = time.perf_counter() - t_start
             if spent > args.time_budget - (150.0 if name == "70b" else 40.0):
                 out["configs"][key] = {"skipped": f"time budget: {spent:.0f} s of {args.time_budget:.0f} s spent before this workload"}
                 continue
             try:
-                out["configs"][key] = other_config(torch, L, I, name, fdt, steps, 2, traffic_table)
+                out["configs"][key] = other_config(torch, L, I, name, fdt, steps, 2, traffic_table, pad)
             except torch.cuda.OutOfMemoryError as e:
                 out["configs"][key] = {"skipped": f"out of device memory: {str(e)[:120]}"}
                 torch.cuda.empty_cache()

@@ -40,7 +40,7 @@ class LswError(RuntimeError):
 
 class lsw_linear(C.Structure):
     _fields_ = [("W", C.c_void_p), ("A", C.c_void_p), ("B", C.c_void_p),
-                ("out", C.c_int32), ("in_", C.c_int32), ("layer", C.c_int32), ("kind", C.c_int32)]
+                ("out", C.c_int32), ("in_", C.c_int32), ("layer", C.c_int32), ("kind", C.c_int32), ("ld", C.c_int32)]
 
 
 _i32p = C.POINTER(C.c_int32)
@@ -129,15 +129,16 @@ def _f32(a):
 
 
 def lsw_create_adapters(linears, E: int, r: int, scale: float = 1.0, factor_dtype=None) -> int:
-    """linears: iterable of (W_ptr, A_ptr, B_ptr, out, in, layer, kind) with device addresses as ints.
+    """linears: iterable of (W_ptr, A_ptr, B_ptr, out, in, layer, kind[, ld]) with device addresses as ints (ld: the leading
+    dimension of W in elements, 0 or absent = dense).
 
     factor_dtype None calls lsw_create_adapters (fp32 factors); LSW_FACTOR_F32 / LSW_FACTOR_BF16 call
     lsw_create_adapters_ex.  Returns the opaque context handle (an int); release it with lsw_destroy.
     """
     linears = list(linears)
     arr = (lsw_linear * max(len(linears), 1))()
-    for i, (w, a, b, o, n, layer, kind) in enumerate(linears):
-        arr[i] = lsw_linear(w, a, b, o, n, layer, kind)
+    for i, (w, a, b, o, n, layer, kind, *ld) in enumerate(linears):
+        arr[i] = lsw_linear(w, a, b, o, n, layer, kind, ld[0] if ld else 0)
     ctx = C.c_void_p()
     if factor_dtype is None:
         _check(lib().lsw_create_adapters(arr if linears else None, len(linears), E, r, scale, C.byref(ctx)))
@@ -323,7 +324,8 @@ def create_from_tensors(stack, shapes, E: int, r: int, scale: float = 1.0) -> in
     factor_dtype = None if dtypes == {torch.float32} else LSW_FACTOR_BF16
     lin = []
     for (W, A, B), (layer, kind, o, n) in zip(stack, shapes):
-        assert W.is_contiguous() and A.is_contiguous() and B.is_contiguous()
+        # W may be a column slice [:, :in] of a wider contiguous tensor: its row stride is the leading dimension
+        assert A.is_contiguous() and B.is_contiguous() and W.stride(1) == 1 and W.stride(0) >= n
         assert tuple(W.shape) == (o, n) and tuple(A.shape) == (E, r, n) and tuple(B.shape) == (E, o, r)
-        lin.append((W.data_ptr(), A.data_ptr(), B.data_ptr(), o, n, layer, kind))
+        lin.append((W.data_ptr(), A.data_ptr(), B.data_ptr(), o, n, layer, kind, 0 if W.stride(0) == n else W.stride(0)))
     return lsw_create_adapters(lin, E, r, scale, factor_dtype)

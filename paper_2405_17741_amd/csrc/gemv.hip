@@ -26,11 +26,11 @@ __device__ __forceinline__ float gv_dot8(const u32x4 w, const u32x4 x, float acc
 }
 
 // rows row0 .. row0+GV_ROWS-1 of W (rows past `out` are clamped for the loads and not written)
-__device__ __forceinline__ void gv_rows(const uint16_t* W, const uint16_t* x, float* y, int out, int in, int row0, int lane) {
+__device__ __forceinline__ void gv_rows(const uint16_t* W, const uint16_t* x, float* y, int out, int in, int ld, int row0, int lane) {
   const LSW_GLOBAL u32x4* wrow[GV_ROWS];
 #pragma unroll
   for (int m = 0; m < GV_ROWS; ++m)
-    wrow[m] = as_global(reinterpret_cast<const u32x4*>(W + (long long)min(row0 + m, out - 1) * in));
+    wrow[m] = as_global(reinterpret_cast<const u32x4*>(W + (long long)min(row0 + m, out - 1) * ld));
   const LSW_GLOBAL u32x4* xv = as_global(reinterpret_cast<const u32x4*>(x));
   float acc[GV_ROWS];
 #pragma unroll
@@ -65,16 +65,16 @@ __device__ __forceinline__ void gv_rows(const uint16_t* W, const uint16_t* x, fl
 
 // one linear
 __global__ __launch_bounds__(256) void k_gemv(const uint16_t* __restrict__ W, const uint16_t* __restrict__ x,
-                                              float* __restrict__ y, int out, int in) {
+                                              float* __restrict__ y, int out, int in, int ld) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n_blocks = ceil_div(out, GV_ROWS);
   for (int rb = blockIdx.x * 4 + wave; rb < n_blocks; rb += gridDim.x * 4)
-    gv_rows(W, x, y, out, in, rb * GV_ROWS, lane);
+    gv_rows(W, x, y, out, in, ld, rb * GV_ROWS, lane);
 }
 
-hipError_t launch_gemv(const uint16_t* W, const uint16_t* x, float* y, int out, int in, int grid_cap, hipStream_t s) {
+hipError_t launch_gemv(const uint16_t* W, const uint16_t* x, float* y, int out, int in, int ld, int grid_cap, hipStream_t s) {
   const int grid = std::max(1, std::min(ceil_div(ceil_div(out, GV_ROWS), 4), grid_cap));
-  hipLaunchKernelGGL(k_gemv, dim3(grid), dim3(256), 0, s, W, x, y, out, in);
+  hipLaunchKernelGGL(k_gemv, dim3(grid), dim3(256), 0, s, W, x, y, out, in, ld);
   return hipGetLastError();
 }
 
@@ -86,9 +86,9 @@ __global__ __launch_bounds__(256) void k_gemv_all(LaunchPlan p, const uint16_t* 
   for (int item = vb * 4 + wave; item < p.n_items; item += gridDim.x * 4) {
     const int seg = uniform(find_segment(p.first, p.n_sel, uniform(item)));
     const LinDesc* Lp = p.lin + uniform(p.sel[seg]);
-    const int out = uniform(Lp->out), in = uniform(Lp->in);
+    const int out = uniform(Lp->out), in = uniform(Lp->in), ld = uniform(Lp->ld);
     const int row0 = uniform(item - p.first[seg]) * GV_ROWS;
-    gv_rows(uniform(Lp->W), x_all + Lp->x_off, y_all + Lp->y_off, out, in, row0, lane);
+    gv_rows(uniform(Lp->W), x_all + Lp->x_off, y_all + Lp->y_off, out, in, ld, row0, lane);
   }
 }
 

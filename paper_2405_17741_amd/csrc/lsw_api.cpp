@@ -292,9 +292,11 @@ extern "C" lsw_status lsw_create_adapters_ex(const lsw_linear* lin, int32_t n_li
     if (L.layer < 0) return fail(LSW_ERR_ARG, "linear %d: layer %d < 0", p, L.layer);
     if (L.out < 1) return fail(LSW_ERR_SHAPE, "linear %d: out=%d < 1", p, L.out);
     if (L.in < 8 || L.in % 8 != 0) return fail(LSW_ERR_SHAPE, "linear %d: in=%d is not a positive multiple of 8", p, L.in);
+    if (L.ld != 0 && (L.ld < L.in || L.ld % 8 != 0))
+      return fail(LSW_ERR_SHAPE, "linear %d: ld=%d must be 0 (dense) or a multiple of 8 that is at least in=%d", p, L.ld, L.in);
     // 32-bit byte offsets inside one W, including the rows a 128-row work item may reach past the end
-    if (int64_t(ceil_div(L.out, kMfmaTileRows)) * kMfmaTileRows * L.in * 2 >= (int64_t(1) << 31))
-      return fail(LSW_ERR_SHAPE, "linear %d: W (rows rounded up to %d) must stay below 2^31 bytes", p, kMfmaTileRows);
+    if (int64_t(ceil_div(L.out, kMfmaTileRows)) * kMfmaTileRows * (L.ld ? L.ld : L.in) * 2 >= (int64_t(1) << 31))
+      return fail(LSW_ERR_SHAPE, "linear %d: W (rows rounded up to %d, at its leading dimension) must stay below 2^31 bytes", p, kMfmaTileRows);
     // 32-bit byte offsets inside one linear's packed A (E * r * padded in * 4 bytes)
     if (r % 8 == 0 && int64_t(E) * r * ceil_div(L.in, kApkBlockCols) * kApkBlockCols * 2 * qp >= (int64_t(1) << 31))
       return fail(LSW_ERR_SHAPE, "linear %d: E * r * in * 4 must stay below 2^31 bytes", p);
@@ -363,6 +365,7 @@ extern "C" lsw_status lsw_create_adapters_ex(const lsw_linear* lin, int32_t n_li
     desc[p].Wbase = nullptr;
     desc[p].out = lin[p].out;
     desc[p].in = lin[p].in;
+    desc[p].ld = lin[p].ld ? lin[p].ld : lin[p].in;
     desc[p].x_off = c->x_elems;
     desc[p].y_off = c->y_elems;
     c->x_elems += lin[p].in;
@@ -787,6 +790,7 @@ extern "C" lsw_status lsw_adapter_forward(lsw_ctx* c, int32_t lin_index, const v
   one.Apk = c->d_adapter + c->bpk_off[size_t(lin_index)];
   one.out = T;
   one.in = L.out;
+  one.ld = L.out;
   const int64_t n_items = int64_t(ceil_div(T, kMfmaTileRows)) * ceil_div(L.out, tc);
   LaunchPlan lp{nullptr, nullptr, nullptr, 1, int32_t(n_items), tc, c->opt_xcd ? 1 : 0, 0, 0, Z, zs, one};
   const int grid = std::max(8, (c->n_cu / 8) * 8);
@@ -822,7 +826,7 @@ extern "C" lsw_status lsw_gemv_bf16(const void* W_bf16, const void* x_bf16, floa
   if (!W_bf16 || !x_bf16 || !y_fp32) return fail(LSW_ERR_ARG, "null pointer");
   if (out < 1 || in < 8 || in % 8 != 0) return fail(LSW_ERR_SHAPE, "out=%d, in=%d: in must be a positive multiple of 8", out, in);
   if (!aligned16(W_bf16) || !aligned16(x_bf16)) return fail(LSW_ERR_SHAPE, "W or x is not 16-byte aligned");
-  hipError_t e = launch_gemv(static_cast<const uint16_t*>(W_bf16), static_cast<const uint16_t*>(x_bf16), y_fp32, out, in, 512,
+  hipError_t e = launch_gemv(static_cast<const uint16_t*>(W_bf16), static_cast<const uint16_t*>(x_bf16), y_fp32, out, in, in, 512,
                              static_cast<hipStream_t>(hip_stream));
   if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "gemv launch failed: %s", hipGetErrorString(e));
   return LSW_OK;
@@ -860,7 +864,7 @@ extern "C" lsw_status lsw_merged_gemv(lsw_ctx* c, int32_t lin_index, const void*
   if (!aligned16(x_bf16)) return fail(LSW_ERR_SHAPE, "x is not 16-byte aligned");
   const lsw_linear& L = c->lin[size_t(lin_index)];
   hipError_t e = launch_gemv(static_cast<const uint16_t*>(L.W), static_cast<const uint16_t*>(x_bf16), y_fp32,
-                             L.out, L.in, c->opt_gemv_grid > 0 ? c->opt_gemv_grid : c->n_cu * 2,
+                             L.out, L.in, c->desc[size_t(lin_index)].ld, c->opt_gemv_grid > 0 ? c->opt_gemv_grid : c->n_cu * 2,
                              static_cast<hipStream_t>(hip_stream));
   if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "gemv launch failed: %s", hipGetErrorString(e));
   return LSW_OK;

@@ -27,6 +27,7 @@ struct LinDesc {
   const uint16_t* Wbase;  // caller-kept copy of the weights with nothing merged (lsw_set_base), or null
   int32_t         out;
   int32_t         in;
+  int32_t         ld;     // elements between the starts of consecutive rows of W (and of Wbase), >= in
   int64_t         x_off;  // element offset of this linear's input in the back-to-back x of lsw_merged_gemv_all
   int64_t         y_off;  // element offset of its output in the back-to-back y
 };
@@ -49,6 +50,11 @@ struct Item {
 };
 
 LSW_HD inline int32_t ceil_div(int32_t a, int32_t b) { return a / b + (a % b != 0); }   // a >= 0, b > 0; no overflow near 2^31
+
+// Bytes from the first element of a [out, in] matrix with leading dimension ld to the end of its last row: what the
+// kernels give the hardware as the size of the buffer, so that rows past the end fall outside it.  Below 2^31 (checked
+// when the linear is registered).
+LSW_HD inline int32_t w_extent_bytes(int32_t out, int32_t in, int32_t ld) { return ((out - 1) * ld + in) * 2; }
 
 // Largest s with first[s] <= item  (first[] is non-decreasing, first[0] == 0, item < first[n_sel]).
 LSW_HD inline int32_t find_segment(const int32_t* first, int32_t n_sel, int32_t item) {
@@ -170,7 +176,7 @@ hipError_t launch_pack_Atk(const void* A, uint16_t* Atk, int E, int r, int in, i
 hipError_t launch_adapter_down(const uint16_t* X, const uint16_t* Atk, float* Upart, int T, int in, int N, int qp, hipStream_t s);
 hipError_t launch_adapter_gate(const float* Upart, int n_slices, const int32_t* ids, const float* gates, int k, int T, int E, int r,
                                float scale, float* Z, int z_stride, int32_t* err, hipStream_t s);
-hipError_t launch_gemv(const uint16_t* W, const uint16_t* x, float* y, int out, int in, int grid_cap, hipStream_t s);
+hipError_t launch_gemv(const uint16_t* W, const uint16_t* x, float* y, int out, int in, int ld, int grid_cap, hipStream_t s);
 hipError_t launch_gemv_all(const LaunchPlan& p, const uint16_t* x_all, float* y_all, int grid, hipStream_t s);
 
 }  // namespace lsw

@@ -48,6 +48,7 @@ __device__ __forceinline__ void mfma_load_item(const LaunchPlan& p, int item, in
     L.Wbase = nullptr;
     L.out = p.one.out;
     L.in = p.one.in;
+    L.ld = p.one.ld;
   } else {
     const int seg = uniform(find_segment(p.first, p.n_sel, item));
     const LinDesc* Lp = p.lin + uniform(p.sel[seg]);
@@ -57,6 +58,7 @@ __device__ __forceinline__ void mfma_load_item(const LaunchPlan& p, int item, in
     L.Wbase = p.from_base ? uniform(Lp->Wbase) : nullptr;
     L.out = uniform(Lp->out);
     L.in = uniform(Lp->in);
+    L.ld = uniform(Lp->ld);
     local = uniform(item - p.first[seg]);
   }
   int row0, col0;
@@ -64,12 +66,12 @@ __device__ __forceinline__ void mfma_load_item(const LaunchPlan& p, int item, in
   row0 += row_shift;          // the calling wave's 32 rows inside a taller item (may lie past the last row)
   it.W = L.W;
   it.Wsrc = p.from_base ? L.Wbase : L.W;
-  it.wbytes = L.out * L.in * 2;
+  it.wbytes = w_extent_bytes(L.out, L.in, L.ld);
   it.Apk = L.Apk;
   it.ncb = ceil_div(L.in, MT_STEP);
   it.col0 = col0;
   it.col_end = min(L.in, col0 + p.tile_cols);
-  it.stride_byte = uint32_t(L.in) * 2u;
+  it.stride_byte = uint32_t(L.ld) * 2u;
   it.row0_byte = uint32_t(row0) * it.stride_byte;
   const int prow = min(row0 + n, L.out - 1);
   const bool prow_ok = row0 + n < L.out;       // rows past the end get a zero coefficient and an offset outside W

@@ -21,13 +21,13 @@ __global__ __launch_bounds__(64) void k_probe_inplace(LaunchPlan p) {
   for (int item = first_item; item < p.n_items; item += grid) {
     const int seg = uniform(find_segment(p.first, p.n_sel, item));
     const LinDesc* Lp = p.lin + uniform(p.sel[seg]);
-    const int out = uniform(Lp->out), in = uniform(Lp->in);
+    const int out = uniform(Lp->out), in = uniform(Lp->in), ld = uniform(Lp->ld);
     int row0, col0;
     decode_item(uniform(item - p.first[seg]), out, in, 32, p.tile_cols, 0, &row0, &col0);
     const int col_end = min(in, col0 + p.tile_cols);
-    const __amdgpu_buffer_rsrc_t res = w_resource(uniform(Lp->W), out * in * 2);
-    const __amdgpu_buffer_rsrc_t res_src = COPY ? w_resource(uniform(Lp->Wbase), out * in * 2) : res;
-    const uint32_t stride = uint32_t(in) * 2u;
+    const __amdgpu_buffer_rsrc_t res = w_resource(uniform(Lp->W), w_extent_bytes(out, in, ld));
+    const __amdgpu_buffer_rsrc_t res_src = COPY ? w_resource(uniform(Lp->Wbase), w_extent_bytes(out, in, ld)) : res;
+    const uint32_t stride = uint32_t(ld) * 2u;
     auto offset = [&](int cs) {
       const int col = cs + 8 * n;
       return col < col_end ? uint32_t(row0 + 4 * h) * stride + uint32_t(col) * 2u : kOutOfRange;

@@ -323,6 +323,7 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
       L.Wbase = p.from_base ? uniform(Lp->Wbase) : nullptr;
       L.out = uniform(Lp->out);
       L.in = uniform(Lp->in);
+      L.ld = uniform(Lp->ld);
       local = uniform(item - p.first[seg]);
     }
     const void* B = L.B;
@@ -334,8 +335,8 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
     const int ncb = ceil_div(in, MT_STEP);
     w.W = L.W;
     w.Wsrc = p.from_base ? L.Wbase : w.W;
-    w.wbytes = out * in * 2;
-    w.stride = uint32_t(in) * 2u;
+    w.wbytes = w_extent_bytes(out, in, L.ld);
+    w.stride = uint32_t(L.ld) * 2u;
     // the packed A of the linear, advanced to this wave's two blocks inside a column block
     w.Apk = uniform(reinterpret_cast<const uint16_t*>(reinterpret_cast<const char*>(L.Apk) + wave * (1024 * QP)));
     w.eg_bytes = ncb * (4096 * QP);

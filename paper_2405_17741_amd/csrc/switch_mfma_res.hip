@@ -30,7 +30,7 @@ struct ResItem {            // one work item (128 rows x tile_cols columns of on
   const uint16_t* Wsrc;     // where tiles are read from: W, or the base copy when re-basing
   const void* B;
   const uint16_t* Apk;
-  int out, in;
+  int out, in, ld;
   int seg;                  // position of the linear in the launch's selection
   int item;
   int row0, col0;
@@ -45,6 +45,7 @@ __device__ __forceinline__ void res_item_at(const LaunchPlan& p, int item, ResIt
   c.Apk = uniform(Lp->Apk);
   c.out = uniform(Lp->out);
   c.in = uniform(Lp->in);
+  c.ld = uniform(Lp->ld);
   c.item = item;
   decode_item(uniform(item - p.first[c.seg]), c.out, c.in, kMfmaTileRows, p.tile_cols, p.panel_group, &c.row0, &c.col0);
 }
@@ -102,9 +103,9 @@ __device__ __forceinline__ bool res_step(const LaunchPlan& p, int n, int h, int 
   const bool have_nxt = have_nxt_io;
   const bool more = !last || have_nxt;
   // the tile after this one: the next column step, or the first tile of the following item (scalar selects, no branch)
-  const int nout = uniform(last ? nxt.out : cur.out), nin = uniform(last ? nxt.in : cur.in);
-  const __amdgpu_buffer_rsrc_t nres = w_resource(last ? nxt.Wsrc : cur.Wsrc, nout * nin * 2);
-  const uint32_t nstride = uint32_t(nin) * 2u;
+  const int nout = uniform(last ? nxt.out : cur.out), nin = uniform(last ? nxt.in : cur.in), nld = uniform(last ? nxt.ld : cur.ld);
+  const __amdgpu_buffer_rsrc_t nres = w_resource(last ? nxt.Wsrc : cur.Wsrc, w_extent_bytes(nout, nin, nld));
+  const uint32_t nstride = uint32_t(nld) * 2u;
   const int ncs = uniform(last ? nxt.col0 : cs + MT_STEP);
   const int ncol_end = uniform(last ? min(nxt.in, nxt.col0 + p.tile_cols) : col_end);
   const uint32_t nrow0_byte = uint32_t(uniform((last ? nxt.row0 : cur.row0) + 32 * wave)) * nstride;
@@ -131,9 +132,9 @@ __device__ __forceinline__ bool res_step(const LaunchPlan& p, int n, int h, int 
     wg_probe_compute(wcur);
   }
 
-  prev_res = w_resource(cur.W, cur.out * cur.in * 2);
+  prev_res = w_resource(cur.W, w_extent_bytes(cur.out, cur.in, cur.ld));
   prev_off = lane_off;
-  prev_stride = uint32_t(cur.in) * 2u;
+  prev_stride = uint32_t(cur.ld) * 2u;
   lane_off = nlane_off;
   cs = ncs;
   if (last) {                      // item boundary (uniform over the workgroup: all four waves walk the same items)
@@ -212,23 +213,23 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma_res(LaunchPlan p,
   uint32_t lane_off = kOutOfRange;
   {
     const int col = cs + 8 * n;
-    const uint32_t stride = uint32_t(cur.in) * 2u;
+    const uint32_t stride = uint32_t(cur.ld) * 2u;
     if (col < min(cur.in, cur.col0 + p.tile_cols))
       lane_off = uint32_t(cur.row0 + 32 * wave + 4 * h) * stride + uint32_t(col) * 2u;
   }
   u32x4 wa[16], wb[16];
   {
-    const __amdgpu_buffer_rsrc_t res = w_resource(cur.Wsrc, cur.out * cur.in * 2);
+    const __amdgpu_buffer_rsrc_t res = w_resource(cur.Wsrc, w_extent_bytes(cur.out, cur.in, cur.ld));
 #pragma unroll
     for (int v = 0; v < 16; ++v)
       wa[v] = __builtin_amdgcn_raw_buffer_load_b128(
-          res, lane_off + uint32_t(8 * (v >> 2) + (v & 3)) * (uint32_t(cur.in) * 2u), 0, kWLoadAux);
+          res, lane_off + uint32_t(8 * (v >> 2) + (v & 3)) * (uint32_t(cur.ld) * 2u), 0, kWLoadAux);
   }
 #pragma unroll
   for (int v = 0; v < 16; ++v) wb[v] = u32x4{0u, 0u, 0u, 0u};
   if constexpr (!PROBE) res_fetch_q<NKS, QP>(p, cur, n, gpr, wave, term_e, term_g);
   wg_drain_and_barrier();
-  __amdgpu_buffer_rsrc_t prev_res = w_resource(cur.W, cur.out * cur.in * 2);
+  __amdgpu_buffer_rsrc_t prev_res = w_resource(cur.W, w_extent_bytes(cur.out, cur.in, cur.ld));
   uint32_t prev_off = kOutOfRange, prev_stride = 0;
 
   bool a_is_cur = true;

@@ -84,9 +84,9 @@ __global__ __launch_bounds__(256) void k_switch_valu(LaunchPlan p, Terms t, cons
       for (int m = 0; m < 4; ++m) {
         const int row = row0 + ty * 4 + m;
         if (row < L.out) {
-          u32x4* ptr = reinterpret_cast<u32x4*>(L.W + (long long)row * L.in + col);
+          u32x4* ptr = reinterpret_cast<u32x4*>(L.W + (long long)row * L.ld + col);
           const u32x4 w = __builtin_nontemporal_load(
-              p.from_base ? reinterpret_cast<const u32x4*>(L.Wbase + (long long)row * L.in + col) : ptr);
+              p.from_base ? reinterpret_cast<const u32x4*>(L.Wbase + (long long)row * L.ld + col) : ptr);
           u32x4 o;
 #pragma unroll
           for (int q = 0; q < 4; ++q)

@@ -110,17 +110,26 @@ def host_stack(wl: Workload):
             for _, _, o, i in wl.linear_shapes()]
 
 
-def device_stack(wl: Workload, device="cuda", factor_dtype=torch.float32):
+PAD_GUARD = -7.5          # what the padding columns of a W stored at a leading dimension > in are filled with
+
+
+def device_stack(wl: Workload, device="cuda", factor_dtype=torch.float32, ld_of=None):
     """Every linear of a workload drawn on the device with wl.seed.
 
     Returns a list of (W bf16 [out,in], A [E,r,in], B [E,out,r]) torch tensors; the factors are drawn in
     fp32 and stored as `factor_dtype` (fp32, or bf16: each value rounded once to the nearest bf16).
+    ld_of: optional function in -> leading dimension (elements).  Where it exceeds `in`, W is the first `in`
+    columns of an [out, ld] buffer whose other columns hold PAD_GUARD; the drawn values are the same.
     """
     g = torch.Generator(device=device)
     g.manual_seed(wl.seed)
     stack = []
     for _, _, o, i in wl.linear_shapes():
         W = (torch.randn(o, i, generator=g, device=device, dtype=torch.float32) * wl.w_std).to(torch.bfloat16)
+        if ld_of is not None and ld_of(i) > i:
+            full = torch.full((o, int(ld_of(i))), PAD_GUARD, device=device, dtype=torch.bfloat16)
+            full[:, :i] = W
+            W = full[:, :i]
         A = torch.randn(wl.experts, wl.rank, i, generator=g, device=device, dtype=torch.float32) * wl.a_std
         B = torch.randn(wl.experts, o, wl.rank, generator=g, device=device, dtype=torch.float32) * wl.b_std
         stack.append((W, A.to(factor_dtype), B.to(factor_dtype)))

@@ -94,6 +94,13 @@ int main() {
     L.in = 12;
     EXPECT(lsw_create_adapters(&L, 1, 8, 8, 1.0f, &ctx) == LSW_ERR_SHAPE);
     L.in = 64;
+    L.ld = 56;                 // a leading dimension below in, and one that leaves rows misaligned
+    EXPECT(lsw_create_adapters(&L, 1, 8, 8, 1.0f, &ctx) == LSW_ERR_SHAPE);
+    L.ld = 68;
+    EXPECT(lsw_create_adapters(&L, 1, 8, 8, 1.0f, &ctx) == LSW_ERR_SHAPE);
+    L.ld = 1 << 24;            // 64 rows rounded up to 128 x 2^24 x 2 bytes: beyond 2 GiB because of the pitch alone
+    EXPECT(lsw_create_adapters(&L, 1, 8, 8, 1.0f, &ctx) == LSW_ERR_SHAPE);
+    L.ld = 0;
     L.out = 40000000;          // 40e6 x 64 x 2 bytes: above 2 GiB
     EXPECT(lsw_create_adapters(&L, 1, 8, 8, 1.0f, &ctx) == LSW_ERR_SHAPE);
     EXPECT(lsw_create_adapters(&L, 1, 8, 8, 1.0f, nullptr) == LSW_ERR_ARG);

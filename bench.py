@@ -402,28 +402,52 @@ def main():
             L.lsw_route_batch_dev(ctx, lg.data_ptr(), T, wl.top_k, idd.data_ptr(), gd.data_ptr(), stream)
             layer0 = [(p, o, n) for p, (layer, _, o, n) in enumerate(wl.linear_shapes()) if layer == 0]
             xs = {n: torch.randn(T, n, device="cuda").to(torch.bfloat16) for _, _, n in layer0}
-            ys = {o: torch.randn(T, o, device="cuda").to(torch.bfloat16) for _, o, _ in layer0}
-            ws = torch.empty(max(L.lsw_adapter_workspace_bytes(ctx, p, T) for p, _, _ in layer0) // 4, dtype=torch.float32, device="cuda")
-
-            def prefill_layer():
-                for p, o, n in layer0:
-                    L.lsw_adapter_forward(ctx, p, xs[n].data_ptr(), T, idd.data_ptr(), gd.data_ptr(), wl.top_k, ys[o].data_ptr(),
-                                          ws.data_ptr(), stream)
-            prefill_layer()
-            torch.cuda.synchronize()
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
-            for _ in range(10):
-                prefill_layer()
-            b.record()
-            b.synchronize()
-            ad_us = a.elapsed_time(b) * 1e3 / 10
+            ys = [torch.randn(T, o, device="cuda").to(torch.bfloat16) for _, o, _ in layer0]      # one output per linear
+            ws = torch.empty(L.lsw_adapter_layer_workspace_bytes(ctx, 0, T) // 4, dtype=torch.float32, device="cuda")
             fb = 2 if bf16_factors else 4
+
+            def prefill_layer():          # all linears of the layer: three launches in all
+                L.lsw_adapter_forward_layer(ctx, 0, [xs[n].data_ptr() for _, _, n in layer0], T, idd.data_ptr(), gd.data_ptr(), wl.top_k,
+                                            [y.data_ptr() for y in ys], ws.data_ptr(), stream)
+
+            def prefill_per_linear():     # the same work as seven separate calls (three launches each)
+                for i, (p, o, n) in enumerate(layer0):
+                    L.lsw_adapter_forward(ctx, p, xs[n].data_ptr(), T, idd.data_ptr(), gd.data_ptr(), wl.top_k, ys[i].data_ptr(),
+                                          ws.data_ptr(), stream)
+
+            def timed(fn, reps=10):
+                fn()
+                torch.cuda.synchronize()
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                for _ in range(reps):
+                    fn()
+                b.record()
+                b.synchronize()
+                return a.elapsed_time(b) * 1e3 / reps
+
+            ad_us, ad_us_lin = timed(prefill_layer), timed(prefill_per_linear)
             ad_bytes = sum(T * n * 2 + 2 * T * o * 2 + fb * wl.experts * wl.rank * (n + o) for _, o, n in layer0)
             adapter = {"tokens": T, "linears": len(layer0), "us_per_layer": round(ad_us, 1), "GBps": round(ad_bytes / (ad_us * 1e-6) / 1e9, 1),
-                       "frac_of_hbm_peak": round(ad_bytes / (ad_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4), "error_flags": L.lsw_dev_status(ctx),
-                       "note": "lsw_adapter_forward over the linears of one layer: X read, Y read and written (bf16), every factor once; "
-                               "three launches per linear"}
+                       "frac_of_hbm_peak": round(ad_bytes / (ad_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+                       "us_per_layer_one_call_per_linear": round(ad_us_lin, 1), "error_flags": L.lsw_dev_status(ctx),
+                       "note": "lsw_adapter_forward_layer over the linears of one layer (three launches in all): per linear X read, Y "
+                               "read and written (bf16), every factor once; beside it the same work as one lsw_adapter_forward per linear"}
+            if T != 8192 and not args.switch_only:      # the same at a longer prompt
+                T8 = 8192
+                lg8 = torch.randn(T8, wl.experts, device="cuda")
+                id8 = torch.zeros(T8, wl.top_k, dtype=torch.int32, device="cuda")
+                g8 = torch.zeros(T8, wl.top_k, dtype=torch.float32, device="cuda")
+                L.lsw_route_batch_dev(ctx, lg8.data_ptr(), T8, wl.top_k, id8.data_ptr(), g8.data_ptr(), stream)
+                xs8 = {n: torch.randn(T8, n, device="cuda").to(torch.bfloat16) for _, _, n in layer0}
+                ys8 = [torch.randn(T8, o, device="cuda").to(torch.bfloat16) for _, o, _ in layer0]
+                ws8 = torch.empty(L.lsw_adapter_layer_workspace_bytes(ctx, 0, T8) // 4, dtype=torch.float32, device="cuda")
+                us8 = timed(lambda: L.lsw_adapter_forward_layer(ctx, 0, [xs8[n].data_ptr() for _, _, n in layer0], T8, id8.data_ptr(), g8.data_ptr(),
+                                                                wl.top_k, [y.data_ptr() for y in ys8], ws8.data_ptr(), stream), 5)
+                b8 = sum(T8 * n * 2 + 2 * T8 * o * 2 + fb * wl.experts * wl.rank * (n + o) for _, o, n in layer0)
+                adapter["tokens_8192"] = {"us_per_layer": round(us8, 1), "GBps": round(b8 / (us8 * 1e-6) / 1e9, 1),
+                                          "frac_of_hbm_peak": round(b8 / (us8 * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)}
+                del xs8, ys8, ws8
             del xs, ys, ws
 
     traffic_table = {}

@@ -266,6 +266,14 @@ lsw_status lsw_gemv_bf16(const void* W_bf16, const void* x_bf16, float* y_fp32, 
  *                          irrelevant before and after; all 16-byte aligned.  Three launches, asynchronous on
  *                          hip_stream, nothing allocated.  A token whose list is bad (id outside [0,E), duplicate id,
  *                          non-finite gate) keeps its row of Y unchanged and raises flag 2 of lsw_dev_status.
+ * lsw_adapter_forward_layer the same for EVERY linear of one layer in three launches in all (all down-projections, all
+ *                          gate tables, all up-projections), which is what a prompt of a few thousand tokens needs: one
+ *                          linear alone does not fill the chip.  X_bf16 and Y_bf16 are HOST arrays of DEVICE pointers, one
+ *                          entry per linear of `layer` in registration order (linears that read the same activations, q/k/v
+ *                          or gate/up, simply get the same X pointer; every Y is distinct); all linears see the same T tokens
+ *                          and the same per-token lists (the single router of Eq. 2).  workspace: DEVICE,
+ *                          lsw_adapter_layer_workspace_bytes(ctx, layer, T) bytes.  A layer may have at most 8 linears
+ *                          (LSW_ERR_SHAPE).  Per linear the result is bit for bit what lsw_adapter_forward gives.
  * Errors: LSW_ERR_ARG, LSW_ERR_SHAPE (misaligned, X or Y of 2 GiB or more), LSW_ERR_STATE (path not enabled),
  * LSW_ERR_NOMEM, LSW_ERR_DEVICE.
  */
@@ -276,6 +284,10 @@ lsw_status lsw_route_batch_dev(lsw_ctx* ctx, const float* logits_dev, int32_t n_
 lsw_status lsw_adapter_forward(lsw_ctx* ctx, int32_t lin_index, const void* X_bf16, int32_t T,
                                const int32_t* ids_dev, const float* gates_dev, int32_t k,
                                void* Y_bf16, void* workspace, void* hip_stream);
+int64_t    lsw_adapter_layer_workspace_bytes(const lsw_ctx* ctx, int32_t layer, int32_t T);   /* -1 on a bad argument */
+lsw_status lsw_adapter_forward_layer(lsw_ctx* ctx, int32_t layer, const void* const* X_bf16, int32_t T,
+                                     const int32_t* ids_dev, const float* gates_dev, int32_t k,
+                                     void* const* Y_bf16, void* workspace, void* hip_stream);
 
 /*
  * lsw_adapter_forward for callers that can neither allocate device memory nor bring a workspace: code under HIP graph

@@ -26,6 +26,7 @@ EXPORTS = (
     "lsw_route_dev", "lsw_switch_dev", "lsw_dev_status", "lsw_gemv_bf16", "lsw_create_adapters_ex",
     "lsw_set_base", "lsw_rebase", "lsw_enable_adapter_path", "lsw_adapter_workspace_bytes", "lsw_route_batch_dev",
     "lsw_adapter_forward", "lsw_drop_subset_tables", "lsw_adapter_forward_static",
+    "lsw_adapter_layer_workspace_bytes", "lsw_adapter_forward_layer",
 )
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblsw.so")
@@ -68,6 +69,10 @@ def lib() -> C.CDLL:
                                           C.c_void_p, C.c_void_p, C.c_void_p]
         L.lsw_adapter_forward_static.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
                                                  C.c_void_p, C.c_void_p]
+        L.lsw_adapter_layer_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+        L.lsw_adapter_layer_workspace_bytes.restype = C.c_int64
+        L.lsw_adapter_forward_layer.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_void_p), C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
+                                                C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p]
         L.lsw_set_base.argtypes = [C.c_void_p, C.POINTER(C.c_void_p), C.c_int32]
         L.lsw_rebase.argtypes = [C.c_void_p, _i32p, C.c_int32, _i32p, _f32p, C.c_int32, C.c_void_p]
         L.lsw_merged_gemv.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -99,7 +104,8 @@ def lib() -> C.CDLL:
         L.lsw_destroy.restype = None
         L.lsw_last_error.restype = C.c_char_p
         for name in EXPORTS:
-            if name not in ("lsw_query", "lsw_worklist_size", "lsw_destroy", "lsw_last_error", "lsw_adapter_workspace_bytes"):
+            if name not in ("lsw_query", "lsw_worklist_size", "lsw_destroy", "lsw_last_error", "lsw_adapter_workspace_bytes",
+                            "lsw_adapter_layer_workspace_bytes"):
                 getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -184,6 +190,23 @@ def lsw_adapter_forward_static(ctx: int, lin_index: int, X_ptr: int, T: int, ids
                                stream: int = 0) -> None:
     _check(lib().lsw_adapter_forward_static(ctx, lin_index, C.c_void_p(X_ptr), T, C.c_void_p(ids_ptr), C.c_void_p(gates_ptr), k,
                                             C.c_void_p(Y_ptr), C.c_void_p(stream)))
+
+
+def lsw_adapter_layer_workspace_bytes(ctx: int, layer: int, T: int) -> int:
+    n = int(lib().lsw_adapter_layer_workspace_bytes(ctx, layer, T))
+    if n < 0:
+        raise LswError(LSW_ERR_ARG, lsw_last_error())
+    return n
+
+
+def lsw_adapter_forward_layer(ctx: int, layer: int, X_ptrs, T: int, ids_ptr: int, gates_ptr: int, k: int, Y_ptrs,
+                              workspace_ptr: int, stream: int = 0) -> None:
+    """X_ptrs / Y_ptrs: device addresses (ints), one per linear of `layer` in registration order."""
+    X_ptrs, Y_ptrs = list(X_ptrs), list(Y_ptrs)
+    xa = (C.c_void_p * max(len(X_ptrs), 1))(*X_ptrs)
+    ya = (C.c_void_p * max(len(Y_ptrs), 1))(*Y_ptrs)
+    _check(lib().lsw_adapter_forward_layer(ctx, layer, xa, T, C.c_void_p(ids_ptr), C.c_void_p(gates_ptr), k, ya,
+                                           C.c_void_p(workspace_ptr), C.c_void_p(stream)))
 
 
 def lsw_set_base(ctx: int, base_ptrs) -> None:

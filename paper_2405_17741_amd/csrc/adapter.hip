@@ -67,7 +67,7 @@ int64_t adapter_atk_elems(int E, int r, int in, int qp) {
 
 // 64-column chunks one workgroup (4 waves, chunks dealt round-robin to the waves) contracts: about 512 workgroups per
 // launch, at least 4 chunks each (one per wave) unless the matrix has fewer
-static int adapter_chunks_per_slice(int T, int in) {
+int adapter_chunks_per_slice(int T, int in) {
   const int nch = ceil_div(in, AD_CHUNK);
   const long long tiles = ceil_div(T, 32);
   const long long cps = std::max<long long>(4, (nch * tiles + 511) / 512);
@@ -149,12 +149,20 @@ __device__ __forceinline__ void ad_compute_chunk(const AdChunk<NB, QP>& c, f32x1
 
 // A workgroup = 32 tokens x one slice of `in` (cps chunks); its 4 waves take the chunks u0 + w, u0 + w + 4, ... with the
 // operands of the next chunk requested before the current one is multiplied, then add their accumulators through LDS.
+// One launch covers every linear of the call: workgroups jobs.first[i] .. jobs.first[i+1]-1 belong to linear i and are
+// numbered (group of 4 row blocks, slice, token tile), the token tile fastest.
 template <int NB, int QP>
-__global__ __launch_bounds__(256) void k_adapter_down(const uint16_t* __restrict__ X, const uint16_t* __restrict__ Atk,
-                                                      float* __restrict__ Upart, int T, int in, int N, int cps) {
+__global__ __launch_bounds__(256) void k_adapter_down(AdJobs jobs, int N) {
   __shared__ float red[3][NB][16][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = lane & 31, h = lane >> 5;
-  const int tile = blockIdx.x, slice = blockIdx.y;
+  const int job = uniform(find_segment(jobs.first, jobs.n, int(blockIdx.x)));
+  const uint16_t* __restrict__ X = uniform(jobs.X[job]);
+  const uint16_t* __restrict__ Atk = uniform(jobs.Atk[job]);
+  float* __restrict__ Upart = uniform(jobs.Upart[job]);
+  const int T = jobs.T, in = uniform(jobs.in[job]), cps = uniform(jobs.cps[job]), n_slices = uniform(jobs.n_slices[job]);
+  const int n_tiles = ceil_div(T, 32);
+  const int local = uniform(int(blockIdx.x) - jobs.first[job]);
+  const int tile = local % n_tiles, slice = (local / n_tiles) % n_slices, zgroup = local / (n_tiles * n_slices);
   const int nch = ceil_div(in, AD_CHUNK);
   const int u0 = slice * cps, u1 = min(nch, u0 + cps);
   // X through a buffer resource: token rows past T lie outside it and read as zeros
@@ -165,7 +173,7 @@ __global__ __launch_bounds__(256) void k_adapter_down(const uint16_t* __restrict
   for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[nb][v] = 0.0f;
-  const int nb0 = blockIdx.z * NB;       // N above 128: the 32-column blocks are split over blockIdx.z
+  const int nb0 = zgroup * NB;           // N above 128: the 32-column blocks come in two groups of workgroups
   const LSW_GLOBAL u32x4* q0 = (const LSW_GLOBAL u32x4*)Atk + (long long)nb0 * nch * 4 * QP * 64 + lane;
   AdChunk<NB, QP> ca, cb;
   int u = u0 + wave;
@@ -200,17 +208,25 @@ __global__ __launch_bounds__(256) void k_adapter_down(const uint16_t* __restrict
   }
 }
 
-hipError_t launch_adapter_down(const uint16_t* X, const uint16_t* Atk, float* Upart, int T, int in, int N, int qp, hipStream_t s) {
-  const int cps = adapter_chunks_per_slice(T, in);
+hipError_t launch_adapter_down(const AdJobs& jobs_in, int N, int qp, hipStream_t s) {
+  AdJobs jobs = jobs_in;
   const int nb = ceil_div(N, 32);
-  const dim3 grid(ceil_div(T, 32), adapter_slices(T, in), nb > 4 ? 2 : 1);
-#define LSW_AD(NB_)                                                                                              \
-  do {                                                                                                           \
-    if (qp == 2) hipLaunchKernelGGL((k_adapter_down<NB_, 2>), grid, dim3(256), 0, s, X, Atk, Upart, T, in, N, cps); \
-    else hipLaunchKernelGGL((k_adapter_down<NB_, 1>), grid, dim3(256), 0, s, X, Atk, Upart, T, in, N, cps);         \
+  const int zgroups = nb > 4 ? 2 : 1;
+  const int nb_read = nb <= 1 ? 1 : nb <= 2 ? 2 : 4 * zgroups;       // blocks of Atk a workgroup row reads
+  if (jobs.n < 1 || jobs.n > kAdMaxLin || nb > 8 || nb_read != adapter_blocks(N)) return hipErrorInvalidValue;   // never beyond what k_pack_Atk laid out
+  long long total = 0;
+  for (int i = 0; i < jobs.n; ++i) {
+    jobs.first[i] = int(total);
+    total += (long long)ceil_div(jobs.T, 32) * jobs.n_slices[i] * zgroups;
+    if (total > INT32_MAX) return hipErrorInvalidValue;
+  }
+  for (int i = jobs.n; i <= kAdMaxLin; ++i) jobs.first[i] = int(total);
+  const dim3 grid{unsigned(total)};
+#define LSW_AD(NB_)                                                                                  \
+  do {                                                                                               \
+    if (qp == 2) hipLaunchKernelGGL((k_adapter_down<NB_, 2>), grid, dim3(256), 0, s, jobs, N);       \
+    else hipLaunchKernelGGL((k_adapter_down<NB_, 1>), grid, dim3(256), 0, s, jobs, N);               \
   } while (0)
-  const int nb_read = nb <= 1 ? 1 : nb <= 2 ? 2 : 4 * int(grid.z);   // blocks of Atk the launch reads
-  if (nb > 8 || nb_read != adapter_blocks(N)) return hipErrorInvalidValue;      // never beyond what k_pack_Atk laid out
   if (nb <= 1) LSW_AD(1);
   else if (nb <= 2) LSW_AD(2);
   else LSW_AD(4);                         // 3..4 blocks: one group of 4; 5..8: two groups of 4 (the layout is padded to whole groups)
@@ -221,12 +237,17 @@ hipError_t launch_adapter_down(const uint16_t* X, const uint16_t* Atk, float* Up
 // Z[t][col] = scale * g(t, expert of col) * sum over the slices of Upart[.][t][col]; columns N..z_stride-1 are zeroed.
 // A token's list is checked as the switch's lists are: an id outside [0, E), a duplicate id or a non-finite gate
 // raises the sticky error word (flag 2) and gives that token an all-zero row (its output stays what it was).
-__global__ __launch_bounds__(256) void k_adapter_gate(const float* __restrict__ Upart, int n_slices, const int32_t* __restrict__ ids,
-                                                      const float* __restrict__ gates, int k, int T, int E, int r, float scale,
-                                                      float* __restrict__ Z, int z_stride, int32_t* __restrict__ err) {
-  const int N = E * r;
-  const long long total = (long long)T * z_stride;
-  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (long long)gridDim.x * blockDim.x) {
+__global__ __launch_bounds__(256) void k_adapter_gate(AdJobs jobs, const int32_t* __restrict__ ids,
+                                                      const float* __restrict__ gates, int k, int E, int r, float scale,
+                                                      int z_stride, int32_t* __restrict__ err) {
+  const int N = E * r, T = jobs.T;
+  const long long per = (long long)T * z_stride, total = per * jobs.n;      // every linear of the call, one after the other
+  for (long long gidx = (long long)blockIdx.x * blockDim.x + threadIdx.x; gidx < total; gidx += (long long)gridDim.x * blockDim.x) {
+    const int job = int(gidx / per);
+    const long long idx = gidx - job * per;
+    const float* __restrict__ Upart = jobs.Upart[job];
+    float* __restrict__ Z = jobs.Z[job];
+    const int n_slices = jobs.n_slices[job];
     const int t = int(idx / z_stride), col = int(idx - (long long)t * z_stride);
     float z = 0.0f;
     if (col < N) {
@@ -241,7 +262,7 @@ __global__ __launch_bounds__(256) void k_adapter_gate(const float* __restrict__ 
         if (id == e) coeff = __fmul_rn(scale, g);
       }
       if (!ok) {
-        if (col == 0) atomicOr(err, 2);
+        if (col == 0 && job == 0) atomicOr(err, 2);
       } else if (coeff != 0.0f) {
         float u = 0.0f;
         for (int s = 0; s < n_slices; ++s) u += Upart[((long long)s * T + t) * N + col];
@@ -252,11 +273,11 @@ __global__ __launch_bounds__(256) void k_adapter_gate(const float* __restrict__ 
   }
 }
 
-hipError_t launch_adapter_gate(const float* Upart, int n_slices, const int32_t* ids, const float* gates, int k, int T, int E, int r,
-                               float scale, float* Z, int z_stride, int32_t* err, hipStream_t s) {
-  const long long total = (long long)T * z_stride;
+hipError_t launch_adapter_gate(const AdJobs& jobs, const int32_t* ids, const float* gates, int k, int E, int r,
+                               float scale, int z_stride, int32_t* err, hipStream_t s) {
+  const long long total = (long long)jobs.T * z_stride * jobs.n;
   const int grid = int(std::min<long long>((total + 255) / 256, 1 << 16));
-  hipLaunchKernelGGL(k_adapter_gate, dim3(grid), dim3(256), 0, s, Upart, n_slices, ids, gates, k, T, E, r, scale, Z, z_stride, err);
+  hipLaunchKernelGGL(k_adapter_gate, dim3(grid), dim3(256), 0, s, jobs, ids, gates, k, E, r, scale, z_stride, err);
   return hipGetLastError();
 }
 

@@ -451,6 +451,19 @@ extern "C" lsw_status lsw_drop_subset_tables(lsw_ctx* c) {
   return LSW_OK;
 }
 
+// the launch description over the linears of a plan, everything else zero
+static LaunchPlan plan_of(const lsw_ctx* c, const DevicePlan* dp, int tile_cols, int xcd_remap) {
+  LaunchPlan lp{};
+  lp.lin = c->d_lin;
+  lp.sel = dp->d_sel;
+  lp.first = dp->d_sel + dp->n_sel;
+  lp.n_sel = dp->n_sel;
+  lp.n_items = dp->n_items;
+  lp.tile_cols = tile_cols;
+  lp.xcd_remap = xcd_remap;
+  return lp;
+}
+
 // A context belongs to the device that was current when it was created; its launches and copies must run there.
 static lsw_status ctx_ready(const lsw_ctx* c) {
   if (!c) return fail(LSW_ERR_ARG, "ctx is null");
@@ -538,8 +551,13 @@ static lsw_status launch_switch(lsw_ctx* c, const std::vector<int32_t>& sel_laye
     const int xcd_mode = c->opt_xcd == 3 ? (bigk || kernel != 2 ? 1 : per_xcd ? 2 : 1) : c->opt_xcd;
     lsw_status st = get_plan(c, kernel, tc, sel_layers, &dp);
     if (st != LSW_OK) return st;
-    LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, tc, xcd_mode, from_base ? 1 : 0, c->opt_one_pass, nullptr, 0, LinDesc{},
-                  c->opt_pool ? slot->pool : nullptr, c->opt_pool == 1 ? 16 : c->opt_pool, panel_group, probe ? 1 : 0};
+    LaunchPlan lp = plan_of(c, dp, tc, xcd_mode);
+    lp.from_base = from_base ? 1 : 0;
+    lp.exact_one_pass = c->opt_one_pass;
+    lp.pool = c->opt_pool ? slot->pool : nullptr;
+    lp.pool_div = c->opt_pool == 1 ? 16 : c->opt_pool;
+    lp.panel_group = panel_group;
+    lp.probe = probe ? 1 : 0;
     if (probe && kernel != 2) return fail(LSW_ERR_ARG, "the switch-pattern probe needs the matrix-core kernels (r %% 8 == 0)");
     hipError_t e = (kernel == 2) ? (bigk && !probe ? launch_switch_mfma_bigk(lp, t, t_dev, c->r, c->qp, grid, s)
                                   : resident ? launch_switch_mfma_res(lp, t, t_dev, c->r, c->qp, grid, s)
@@ -630,7 +648,8 @@ extern "C" lsw_status lsw_rebase(lsw_ctx* c, const int32_t* layers, int32_t n_la
     DevicePlan* dp = nullptr;                  // one launch: the probe's walk over the selected linears, reading the base copy
     st = get_plan(c, 3, c->opt_tile_cols, sel_layers, &dp);
     if (st != LSW_OK) return st;
-    LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, c->opt_tile_cols, c->opt_xcd ? 1 : 0, 1, 0, nullptr, 0, LinDesc{}};
+    LaunchPlan lp = plan_of(c, dp, c->opt_tile_cols, c->opt_xcd ? 1 : 0);
+    lp.from_base = 1;
     hipError_t e = launch_probe_inplace(lp, c->n_cu * 4, s);
     if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "copy launch failed: %s", hipGetErrorString(e));
   } else {
@@ -746,13 +765,105 @@ extern "C" lsw_status lsw_enable_adapter_path(lsw_ctx* c) {
   return LSW_OK;
 }
 
+static int64_t adapter_ws_bytes(const lsw_ctx* c, size_t lin_index, int32_t T) {
+  const int64_t N = int64_t(c->E) * c->r;
+  return 4 * (int64_t(adapter_slices(T, c->lin[lin_index].in)) * T * N + int64_t(T) * z_stride_of(c));
+}
+
 extern "C" int64_t lsw_adapter_workspace_bytes(const lsw_ctx* c, int32_t lin_index, int32_t T) {
   if (!c || lin_index < 0 || size_t(lin_index) >= c->lin.size() || T < 1) {
     fail(LSW_ERR_ARG, "lsw_adapter_workspace_bytes: bad argument");
     return -1;
   }
-  const int64_t N = int64_t(c->E) * c->r;
-  return 4 * (int64_t(adapter_slices(T, c->lin[size_t(lin_index)].in)) * T * N + int64_t(T) * z_stride_of(c));
+  return adapter_ws_bytes(c, size_t(lin_index), T);
+}
+
+// the linears of `layer` in registration order (at most kAdMaxLin)
+static lsw_status layer_linears(const lsw_ctx* c, int32_t layer, std::vector<int32_t>* idx) {
+  idx->clear();
+  for (size_t p = 0; p < c->lin.size(); ++p)
+    if (c->lin[p].layer == layer) idx->push_back(int32_t(p));
+  if (idx->empty()) return fail(LSW_ERR_ARG, "unknown layer %d", layer);
+  if (idx->size() > size_t(kAdMaxLin)) return fail(LSW_ERR_SHAPE, "layer %d has %zu linears, one call covers at most %d", layer, idx->size(), kAdMaxLin);
+  return LSW_OK;
+}
+
+extern "C" int64_t lsw_adapter_layer_workspace_bytes(const lsw_ctx* c, int32_t layer, int32_t T) {
+  std::vector<int32_t> idx;
+  if (!c || T < 1 || layer_linears(c, layer, &idx) != LSW_OK) {
+    if (!c || T < 1) fail(LSW_ERR_ARG, "lsw_adapter_layer_workspace_bytes: bad argument");
+    return -1;
+  }
+  int64_t total = 0;
+  for (int32_t p : idx) total += adapter_ws_bytes(c, size_t(p), T);
+  return total;
+}
+
+// Eq. 2's adapter sum for n linears that see the same T tokens: three launches in all (down-projections, gate tables,
+// up-projections), the workspace cut into one block per linear in the given order.
+static lsw_status adapter_run(lsw_ctx* c, const int32_t* lin_idx, int n, const void* const* X, int32_t T, const int32_t* ids_dev,
+                              const float* gates_dev, int32_t k, void* const* Y, void* workspace, hipStream_t s) {
+  if (!c->d_adapter) return fail(LSW_ERR_STATE, "the adapter path is not enabled: call lsw_enable_adapter_path first");
+  if (T < 1) return fail(LSW_ERR_ARG, "T=%d < 1", T);
+  if (k < 0 || k > LSW_MAX_K || k > c->E) return fail(LSW_ERR_ARG, "k=%d outside 0..min(%d, E=%d)", k, int(LSW_MAX_K), c->E);
+  if (!X || !Y || !workspace || (k > 0 && (!ids_dev || !gates_dev))) return fail(LSW_ERR_ARG, "null pointer");
+  if (!aligned16(workspace)) return fail(LSW_ERR_SHAPE, "the workspace is not 16-byte aligned");
+  const int N = c->E * c->r, zs = z_stride_of(c);
+  const int n_groups = c->E * (c->r / 8);
+  const bool bigk = n_groups > 8;
+  const int tc = bigk ? 512 : 256;
+  AdJobs jobs{};
+  jobs.n = n;
+  jobs.T = T;
+  LaunchPlan lp{};
+  lp.n_sel = n;
+  lp.tile_cols = tc;
+  lp.xcd_remap = c->opt_xcd ? 1 : 0;
+  lp.z_stride = zs;
+  char* ws = static_cast<char*>(workspace);
+  int64_t n_items = 0;
+  for (int i = 0; i < n; ++i) {
+    const size_t p = size_t(lin_idx[i]);
+    const lsw_linear& L = c->lin[p];
+    if (!X[i] || !Y[i]) return fail(LSW_ERR_ARG, "linear %zu: null X or Y", p);
+    if (!aligned16(X[i]) || !aligned16(Y[i])) return fail(LSW_ERR_SHAPE, "linear %zu: X or Y is not 16-byte aligned", p);
+    if (int64_t(T) * L.in * 2 >= (int64_t(1) << 31) || int64_t(ceil_div(T, kMfmaTileRows)) * kMfmaTileRows * L.out * 2 >= (int64_t(1) << 31))
+      return fail(LSW_ERR_SHAPE, "T=%d: X and Y (rows rounded up to %d) must stay below 2^31 bytes each", T, kMfmaTileRows);
+    jobs.X[i] = static_cast<const uint16_t*>(X[i]);
+    jobs.Atk[i] = c->d_adapter + c->atk_off[p];
+    jobs.in[i] = L.in;
+    jobs.cps[i] = adapter_chunks_per_slice(T, L.in);
+    jobs.n_slices[i] = adapter_slices(T, L.in);
+    jobs.Upart[i] = reinterpret_cast<float*>(ws);
+    jobs.Z[i] = jobs.Upart[i] + size_t(jobs.n_slices[i]) * size_t(T) * size_t(N);
+    ws += adapter_ws_bytes(c, p, T);
+    LinDesc& d = lp.ad[i];
+    d.W = static_cast<uint16_t*>(Y[i]);
+    d.B = jobs.Z[i];
+    d.Apk = c->d_adapter + c->bpk_off[p];
+    d.out = T;
+    d.in = L.out;
+    d.ld = L.out;
+    lp.ad_first[i] = int32_t(n_items);
+    n_items += int64_t(ceil_div(T, kMfmaTileRows)) * ceil_div(L.out, tc);
+    if (n_items > INT32_MAX) return fail(LSW_ERR_SHAPE, "more than 2^31 work items");
+  }
+  for (int i = n; i <= kAdMaxLin; ++i) lp.ad_first[i] = int32_t(n_items);
+  lp.n_items = int32_t(n_items);
+  lp.Z = jobs.Z[0];
+  if (k == 0) return LSW_OK;                  // no expert selected: nothing to add
+  hipError_t e = launch_adapter_down(jobs, N, c->qp, s);
+  if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "down-projection launch failed: %s", hipGetErrorString(e));
+  e = launch_adapter_gate(jobs, ids_dev, gates_dev, k, c->E, c->r, c->scale, zs, c->d_err, s);
+  if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "gate launch failed: %s", hipGetErrorString(e));
+  // the up-projections: the matrix-core switch kernels with rows = tokens and the row operand read from Z
+  Terms t;
+  std::memset(&t, 0, sizeof(t));
+  t.n = c->E;                                // sizes the launch: E * r / 8 groups of the fused rank
+  const int grid = std::max(8, (c->n_cu / 8) * 8);
+  e = bigk ? launch_switch_mfma_bigk(lp, t, nullptr, c->r, c->qp, grid, s) : launch_switch_mfma(lp, t, nullptr, c->r, c->qp, grid, s);
+  if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "up-projection launch failed: %s", hipGetErrorString(e));
+  return LSW_OK;
 }
 
 extern "C" lsw_status lsw_adapter_forward(lsw_ctx* c, int32_t lin_index, const void* X_bf16, int32_t T,
@@ -761,42 +872,17 @@ extern "C" lsw_status lsw_adapter_forward(lsw_ctx* c, int32_t lin_index, const v
   if (lsw_status ready = ctx_ready(c)) return ready;
   if (!c->d_adapter) return fail(LSW_ERR_STATE, "lsw_adapter_forward: call lsw_enable_adapter_path first");
   if (lin_index < 0 || size_t(lin_index) >= c->lin.size()) return fail(LSW_ERR_ARG, "lin_index %d out of range", lin_index);
-  if (T < 1) return fail(LSW_ERR_ARG, "T=%d < 1", T);
-  if (k < 0 || k > LSW_MAX_K || k > c->E) return fail(LSW_ERR_ARG, "k=%d outside 0..min(%d, E=%d)", k, int(LSW_MAX_K), c->E);
-  if (!X_bf16 || !Y_bf16 || !workspace || (k > 0 && (!ids_dev || !gates_dev))) return fail(LSW_ERR_ARG, "null pointer");
-  if (!aligned16(X_bf16) || !aligned16(Y_bf16) || !aligned16(workspace)) return fail(LSW_ERR_SHAPE, "X, Y or the workspace is not 16-byte aligned");
-  const lsw_linear& L = c->lin[size_t(lin_index)];
-  if (int64_t(T) * L.in * 2 >= (int64_t(1) << 31) || int64_t(ceil_div(T, kMfmaTileRows)) * kMfmaTileRows * L.out * 2 >= (int64_t(1) << 31))
-    return fail(LSW_ERR_SHAPE, "T=%d: X and Y (rows rounded up to %d) must stay below 2^31 bytes each", T, kMfmaTileRows);
-  if (k == 0) return LSW_OK;                  // no expert selected: nothing to add
-  hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  const int N = c->E * c->r, zs = z_stride_of(c);
-  const int n_slices = adapter_slices(T, L.in);
-  float* Upart = static_cast<float*>(workspace);
-  float* Z = Upart + size_t(n_slices) * size_t(T) * size_t(N);
-  hipError_t e = launch_adapter_down(static_cast<const uint16_t*>(X_bf16), c->d_adapter + c->atk_off[size_t(lin_index)], Upart, T, L.in, N, c->qp, s);
-  if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "down-projection launch failed: %s", hipGetErrorString(e));
-  e = launch_adapter_gate(Upart, n_slices, ids_dev, gates_dev, k, T, c->E, c->r, c->scale, Z, zs, c->d_err, s);
-  if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "gate launch failed: %s", hipGetErrorString(e));
-  // the up-projection: the matrix-core switch kernels with rows = tokens and the row operand read from Z
-  const int n_groups = c->E * (c->r / 8);
-  const bool bigk = n_groups > 8;
-  const int tc = bigk ? 512 : 256;
-  Terms t;
-  std::memset(&t, 0, sizeof(t));
-  t.n = c->E;                                // sizes the launch: E * r / 8 groups of the fused rank
-  LinDesc one{};
-  one.W = static_cast<uint16_t*>(Y_bf16);
-  one.Apk = c->d_adapter + c->bpk_off[size_t(lin_index)];
-  one.out = T;
-  one.in = L.out;
-  one.ld = L.out;
-  const int64_t n_items = int64_t(ceil_div(T, kMfmaTileRows)) * ceil_div(L.out, tc);
-  LaunchPlan lp{nullptr, nullptr, nullptr, 1, int32_t(n_items), tc, c->opt_xcd ? 1 : 0, 0, 0, Z, zs, one};
-  const int grid = std::max(8, (c->n_cu / 8) * 8);
-  e = bigk ? launch_switch_mfma_bigk(lp, t, nullptr, c->r, c->qp, grid, s) : launch_switch_mfma(lp, t, nullptr, c->r, c->qp, grid, s);
-  if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "up-projection launch failed: %s", hipGetErrorString(e));
-  return LSW_OK;
+  return adapter_run(c, &lin_index, 1, &X_bf16, T, ids_dev, gates_dev, k, &Y_bf16, workspace, static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" lsw_status lsw_adapter_forward_layer(lsw_ctx* c, int32_t layer, const void* const* X_bf16, int32_t T,
+                                                const int32_t* ids_dev, const float* gates_dev, int32_t k,
+                                                void* const* Y_bf16, void* workspace, void* hip_stream) {
+  if (lsw_status ready = ctx_ready(c)) return ready;
+  if (!c->d_adapter) return fail(LSW_ERR_STATE, "lsw_adapter_forward_layer: call lsw_enable_adapter_path first");
+  std::vector<int32_t> idx;
+  if (lsw_status st = layer_linears(c, layer, &idx)) return st;
+  return adapter_run(c, idx.data(), int(idx.size()), X_bf16, T, ids_dev, gates_dev, k, Y_bf16, workspace, static_cast<hipStream_t>(hip_stream));
 }
 
 extern "C" lsw_status lsw_adapter_forward_static(lsw_ctx* c, int32_t lin_index, const void* X_bf16, int32_t T,
@@ -847,7 +933,7 @@ extern "C" lsw_status lsw_probe_inplace(lsw_ctx* c, int32_t waves_per_cu, void* 
   DevicePlan* dp = nullptr;
   lsw_status st = get_plan(c, 3, c->opt_tile_cols, std::vector<int32_t>(), &dp);
   if (st != LSW_OK) return st;
-  LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, c->opt_tile_cols, c->opt_xcd ? 1 : 0, 0, 0, nullptr, 0, LinDesc{}};
+  const LaunchPlan lp = plan_of(c, dp, c->opt_tile_cols, c->opt_xcd ? 1 : 0);
   hipError_t e = launch_probe_inplace(lp, c->n_cu * waves_per_cu, static_cast<hipStream_t>(hip_stream));
   if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "probe launch failed: %s", hipGetErrorString(e));
   return LSW_OK;
@@ -877,7 +963,7 @@ extern "C" lsw_status lsw_merged_gemv_all(lsw_ctx* c, const void* x_all_bf16, fl
   DevicePlan* dp = nullptr;
   lsw_status st = get_plan(c, 4, 1 << 30, std::vector<int32_t>(), &dp);   // items: blocks of rows, whole rows wide
   if (st != LSW_OK) return st;
-  LaunchPlan lp{c->d_lin, dp->d_sel, dp->d_sel + dp->n_sel, dp->n_sel, dp->n_items, 1 << 30, c->opt_xcd ? 1 : 0, 0, 0, nullptr, 0, LinDesc{}};
+  const LaunchPlan lp = plan_of(c, dp, 1 << 30, c->opt_xcd ? 1 : 0);
   int grid = c->opt_gemv_grid > 0 ? c->opt_gemv_grid : c->n_cu * 2;
   grid = std::max(8, (grid / 8) * 8);
   hipError_t e = launch_gemv_all(lp, static_cast<const uint16_t*>(x_all_bf16), y_all_fp32, grid,

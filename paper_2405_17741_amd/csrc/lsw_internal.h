@@ -127,6 +127,8 @@ constexpr int kMfmaBigkTileCols = 4096;                     // default item widt
 constexpr int kGemvRows = 4;                                // rows of one wave's block in the merged-decode kernels
 constexpr int kApkBlockCols = 256;   // column block of the packed A layout = columns per matrix-core step
 
+constexpr int kAdMaxLin = 8;    // linears one launch of the adapter path (lsw_adapter_forward_layer) covers at most
+
 struct LaunchPlan {             // device pointers + counts for one launch
   const LinDesc* lin;
   const int32_t* sel;
@@ -138,13 +140,15 @@ struct LaunchPlan {             // device pointers + counts for one launch
                                 // grid-wide round of items; 2 (k_switch_mfma): each XCD walks its own eighth of the list
   int32_t from_base;            // 1: the switch kernels read Wbase instead of W (and still write W): lsw_rebase
   int32_t exact_one_pass;       // 1: bf16-stored factors of a rank that is a multiple of 16 run one matrix-core pass (chunked kernel)
-  // Adapter-path mode of the matrix-core kernels (Z != null): ONE matrix, described by `one` (W = the [T, out]
-  // activations to add to, Apk = the packed B^T of the linear, out = T, in = out features); lin/sel/first are unused.
+  // Adapter-path mode of the matrix-core kernels (Z != null): up to kAdMaxLin matrices described by `ad` (W = the
+  // [T, out] activations to add to, Apk = the packed B^T of the linear, B = that linear's Z, out = T, in = ld = out
+  // features), ad_first[i] = number of the first work item of ad[i]; n_sel = how many; lin/sel/first are unused.
   // The row operand is not coeff * B but row t of Z (fp32 [T, z_stride]: the gated down-projection of token t, all
   // experts side by side), and the fused rank runs over all E * r columns of Z.
-  const float* Z;
+  const float* Z;               // non-null = adapter mode (the Z of ad[0])
   int32_t z_stride;
-  LinDesc one;
+  LinDesc ad[kAdMaxLin];
+  int32_t ad_first[kAdMaxLin + 1];
   // Per-XCD order of k_switch_mfma / k_switch_mfma_res: two zeroed counters in device memory ([0] items claimed from the shared pool, [1] workgroups
   // finished; the kernel leaves both at zero), or null for a purely static split of the items.
   int32_t* pool;
@@ -173,9 +177,23 @@ hipError_t adapter_static_scratch(int device, void** ptr);        // its address
 int64_t adapter_atk_elems(int E, int r, int in, int qp);          // bf16 elements of the down-projection layout of one linear
 int adapter_slices(int T, int in);                                // partial sums the down-projection is cut into
 hipError_t launch_pack_Atk(const void* A, uint16_t* Atk, int E, int r, int in, int qp, hipStream_t s);
-hipError_t launch_adapter_down(const uint16_t* X, const uint16_t* Atk, float* Upart, int T, int in, int N, int qp, hipStream_t s);
-hipError_t launch_adapter_gate(const float* Upart, int n_slices, const int32_t* ids, const float* gates, int k, int T, int E, int r,
-                               float scale, float* Z, int z_stride, int32_t* err, hipStream_t s);
+// the linears one call of the adapter path covers (all with the same T tokens, the same per-token lists)
+struct AdJobs {
+  int32_t n;                       // linears, 1..kAdMaxLin
+  int32_t T;
+  const uint16_t* X[kAdMaxLin];    // bf16 [T, in]
+  const uint16_t* Atk[kAdMaxLin];  // down-projection layout of the linear's A
+  float* Upart[kAdMaxLin];         // partial sums [n_slices][T][N]
+  float* Z[kAdMaxLin];             // gate table [T][z_stride]
+  int32_t in[kAdMaxLin];
+  int32_t cps[kAdMaxLin];          // 64-column chunks per slice
+  int32_t n_slices[kAdMaxLin];
+  int32_t first[kAdMaxLin + 1];    // first workgroup of each linear in the down-projection launch
+};
+hipError_t launch_adapter_down(const AdJobs& jobs, int N, int qp, hipStream_t s);      // fills first[] itself
+hipError_t launch_adapter_gate(const AdJobs& jobs, const int32_t* ids, const float* gates, int k, int E, int r,
+                               float scale, int z_stride, int32_t* err, hipStream_t s);
+int adapter_chunks_per_slice(int T, int in);
 hipError_t launch_gemv(const uint16_t* W, const uint16_t* x, float* y, int out, int in, int ld, int grid_cap, hipStream_t s);
 hipError_t launch_gemv_all(const LaunchPlan& p, const uint16_t* x_all, float* y_all, int grid, hipStream_t s);
 

@@ -42,13 +42,15 @@ __device__ __forceinline__ void mfma_load_item(const LaunchPlan& p, int item, in
   LinDesc L;
   int local = item;
   if (adapter) {
-    L.W = p.one.W;
-    L.B = nullptr;
-    L.Apk = p.one.Apk;
+    const int seg = uniform(find_segment(p.ad_first, p.n_sel, item));
+    L.W = uniform(p.ad[seg].W);
+    L.B = uniform(p.ad[seg].B);            // this linear's Z
+    L.Apk = uniform(p.ad[seg].Apk);
     L.Wbase = nullptr;
-    L.out = p.one.out;
-    L.in = p.one.in;
-    L.ld = p.one.ld;
+    L.out = uniform(p.ad[seg].out);
+    L.in = uniform(p.ad[seg].in);
+    L.ld = uniform(p.ad[seg].ld);
+    local = uniform(item - p.ad_first[seg]);
   } else {
     const int seg = uniform(find_segment(p.first, p.n_sel, item));
     const LinDesc* Lp = p.lin + uniform(p.sel[seg]);
@@ -79,7 +81,7 @@ __device__ __forceinline__ void mfma_load_item(const LaunchPlan& p, int item, in
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks) {
     float b[8];
-    if (adapter) load8<2>(p.Z, (long long)prow * p.z_stride + 8 * (term_e[ks] * gpr + term_g[ks]), b);
+    if (adapter) load8<2>(L.B, (long long)prow * p.z_stride + 8 * (term_e[ks] * gpr + term_g[ks]), b);
     else load8<QP>(L.B, ((long long)term_e[ks] * L.out + prow) * r + 8 * term_g[ks], b);
     const float c = prow_ok ? term_c[ks] : 0.0f;
 #pragma unroll

@@ -313,7 +313,15 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
     LinDesc L;
     int local = item;
     if (adapter) {
-      L = p.one;
+      const int seg = uniform(find_segment(p.ad_first, p.n_sel, item));
+      L.W = uniform(p.ad[seg].W);
+      L.B = uniform(p.ad[seg].B);            // this linear's Z
+      L.Apk = uniform(p.ad[seg].Apk);
+      L.Wbase = nullptr;
+      L.out = uniform(p.ad[seg].out);
+      L.in = uniform(p.ad[seg].in);
+      L.ld = uniform(p.ad[seg].ld);
+      local = uniform(item - p.ad_first[seg]);
     } else {
       const int seg = uniform(find_segment(p.first, p.n_sel, item));
       const LinDesc* Lp = p.lin + uniform(p.sel[seg]);
@@ -356,7 +364,7 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
           w.p_lo[ks] = u32x4{0u, 0u, 0u, 0u};
         } else {
           float b[8];
-          if (adapter) load8<2>(p.Z, (long long)prow * p.z_stride + 8 * s_eg[G], b);
+          if (adapter) load8<2>(B, (long long)prow * p.z_stride + 8 * s_eg[G], b);
           else load8<QP>(B, ((long long)s_e[G] * out + prow) * r + 8 * s_g[G], b);
           const float c = prow_ok ? s_c[G] : 0.0f;
 #pragma unroll

@@ -113,6 +113,9 @@ int main() {
     EXPECT(lsw_enable_adapter_path(nullptr) == LSW_ERR_ARG);
     EXPECT(lsw_adapter_forward(nullptr, 0, nullptr, 1, nullptr, nullptr, 0, nullptr, nullptr, nullptr) == LSW_ERR_ARG);
     EXPECT(lsw_adapter_workspace_bytes(nullptr, 0, 1) == -1);
+    EXPECT(lsw_adapter_layer_workspace_bytes(nullptr, 0, 1) == -1);
+    EXPECT(lsw_adapter_forward_layer(nullptr, 0, nullptr, 1, nullptr, nullptr, 0, nullptr, nullptr, nullptr) == LSW_ERR_ARG);
+    EXPECT(lsw_adapter_forward_static(nullptr, 0, nullptr, 1, nullptr, nullptr, 0, nullptr, nullptr) == LSW_ERR_ARG);
     EXPECT(lsw_route_batch_dev(nullptr, nullptr, 1, 1, nullptr, nullptr, nullptr) == LSW_ERR_ARG);
     EXPECT(lsw_get_state(nullptr, 0, nullptr, nullptr, &k) == LSW_ERR_ARG);
     EXPECT(lsw_dev_status(nullptr, &flags) == LSW_ERR_ARG);

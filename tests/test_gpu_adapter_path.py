@@ -208,3 +208,52 @@ def test_prompt_step_recorded_in_a_graph_and_replayed():
         assert rep["fail"] == 0
     assert L.lsw_dev_status(ds.ctx) == 0
     ds.close()
+
+
+@pytest.mark.parametrize("E,r,T", [(8, 8, 300), (8, 16, 130), (6, 16, 70)])
+def test_whole_layer_in_three_launches_equals_the_per_linear_calls(E, r, T):
+    """lsw_adapter_forward_layer: the seven linears of a layer (q/k/v reading one X, gate/up another) in one call; every
+    output against the oracle and, bit for bit, against lsw_adapter_forward on that linear alone.  A second layer in the
+    same context makes the layer's linears a proper subset; N = E * r of 64 runs the streaming matrix-core kernel, 128 and
+    96 the chunked one (and 96 the padded down-projection layout)."""
+    hidden, ffn, kv, k = 264, 520, 136, 2
+    dims = [(hidden, hidden), (kv, hidden), (kv, hidden), (hidden, hidden), (ffn, hidden), (ffn, hidden), (hidden, ffn)]
+    shapes = [(layer, kind, o, n) for layer in (0, 1) for kind, (o, n) in enumerate(dims)]
+    rng = np.random.default_rng(E * 100 + r + T)
+    host = [I.host_linear(rng, o, n, E, r, 0.02, 1 / np.sqrt(n), 0.05) for _, _, o, n in shapes]
+    ds = DeviceStack.from_host(host, shapes, E, r, scale=0.5)
+    L.lsw_enable_adapter_path(ds.ctx)
+    stream = torch.cuda.current_stream().cuda_stream
+    layer = 1
+    lin = [p for p, s in enumerate(shapes) if s[0] == layer]
+    x_attn, _, _, ids, gates = _tokens(rng, T, E, k, hidden, hidden)
+    x_o = I.f32_to_bf16_bits(rng.normal(0, 1, (T, hidden)).astype(np.float32))
+    x_down = I.f32_to_bf16_bits(rng.normal(0, 1, (T, ffn)).astype(np.float32))
+    Xs = [x_attn, x_attn, x_attn, x_o, x_attn, x_attn, x_down]             # q, k, v, o, gate, up, down
+    Ys = [I.f32_to_bf16_bits(rng.normal(0, 0.5, (T, o)).astype(np.float32)) for o, _ in dims]
+    xd = {id(x): bits_to_device(x) for x in Xs}
+    idd, gd = torch.from_numpy(ids).cuda(), torch.from_numpy(gates).cuda()
+    yd = [bits_to_device(y) for y in Ys]
+    ws = torch.full((L.lsw_adapter_layer_workspace_bytes(ds.ctx, layer, T) // 4 + 64,), float("nan"), dtype=torch.float32, device="cuda")
+    assert L.lsw_adapter_layer_workspace_bytes(ds.ctx, layer, T) == sum(L.lsw_adapter_workspace_bytes(ds.ctx, p, T) for p in lin)
+    L.lsw_adapter_forward_layer(ds.ctx, layer, [xd[id(x)].data_ptr() for x in Xs], T, idd.data_ptr(), gd.data_ptr(), k,
+                                [y.data_ptr() for y in yd], ws.data_ptr(), stream)
+    torch.cuda.synchronize()
+    assert torch.isnan(ws[-64:]).all(), "nothing written past the stated workspace size"
+    for i, p in enumerate(lin):
+        got = device_to_bits(yd[i])
+        alone = _run(ds, p, Xs[i], Ys[i], ids, gates, k)
+        assert (got == alone).all(), (i, "differs from the single-linear call")
+        _, A, B = host[p]
+        rep = C.switch_parity(got, O.adapter_forward(Ys[i], Xs[i], A, B, ids, gates, 0.5), Ys[i],
+                              O.adapter_magnitude(Xs[i], A, B, ids, gates, 0.5))
+        assert rep["fail"] == 0 and rep["exact"] > 0.995 * rep["n"], (i, {k_: v for k_, v in rep.items() if k_ != "fail_mask"})
+    assert L.lsw_dev_status(ds.ctx) == 0
+    # argument checks: unknown layer, a null entry
+    with pytest.raises(L.LswError) as e:
+        L.lsw_adapter_forward_layer(ds.ctx, 5, [16] * 7, T, idd.data_ptr(), gd.data_ptr(), k, [16] * 7, ws.data_ptr(), stream)
+    assert e.value.status == L.LSW_ERR_ARG
+    with pytest.raises(L.LswError) as e:
+        L.lsw_adapter_forward_layer(ds.ctx, layer, [16] * 6 + [0], T, idd.data_ptr(), gd.data_ptr(), k, [16] * 7, ws.data_ptr(), stream)
+    assert e.value.status == L.LSW_ERR_ARG
+    ds.close()

@@ -767,7 +767,7 @@ extern "C" lsw_status lsw_enable_adapter_path(lsw_ctx* c) {
 
 static int64_t adapter_ws_bytes(const lsw_ctx* c, size_t lin_index, int32_t T) {
   const int64_t N = int64_t(c->E) * c->r;
-  return 4 * (int64_t(adapter_slices(T, c->lin[lin_index].in)) * T * N + int64_t(T) * z_stride_of(c));
+  return 4 * (int64_t(adapter_slices(T, c->lin[lin_index].in, int(N))) * T * N + int64_t(T) * z_stride_of(c));
 }
 
 extern "C" int64_t lsw_adapter_workspace_bytes(const lsw_ctx* c, int32_t lin_index, int32_t T) {
@@ -811,7 +811,15 @@ static lsw_status adapter_run(lsw_ctx* c, const int32_t* lin_idx, int n, const v
   const int N = c->E * c->r, zs = z_stride_of(c);
   const int n_groups = c->E * (c->r / 8);
   const bool bigk = n_groups > 8;
-  const int tc = bigk ? 512 : 256;
+  // Up-projection items: 128 tokens x tc output columns.  The row operand (a token block's rows of Z, split) is set up
+  // once per item, so wide items are cheaper per byte; the widest that still leaves every workgroup three items or more.
+  const int grid = std::max(8, (c->n_cu / 8) * 8);
+  int tc = bigk ? 512 : 256;
+  for (int cand : {2048, 1024, 512}) {
+    int64_t items = 0;
+    for (int i = 0; i < n; ++i) items += int64_t(ceil_div(T, kMfmaTileRows)) * ceil_div(c->lin[size_t(lin_idx[i])].out, cand);
+    if (items >= 3 * int64_t(grid)) { tc = cand; break; }
+  }
   AdJobs jobs{};
   jobs.n = n;
   jobs.T = T;
@@ -832,8 +840,8 @@ static lsw_status adapter_run(lsw_ctx* c, const int32_t* lin_idx, int n, const v
     jobs.X[i] = static_cast<const uint16_t*>(X[i]);
     jobs.Atk[i] = c->d_adapter + c->atk_off[p];
     jobs.in[i] = L.in;
-    jobs.cps[i] = adapter_chunks_per_slice(T, L.in);
-    jobs.n_slices[i] = adapter_slices(T, L.in);
+    jobs.cps[i] = adapter_chunks_per_slice(T, L.in, N);
+    jobs.n_slices[i] = adapter_slices(T, L.in, N);
     jobs.Upart[i] = reinterpret_cast<float*>(ws);
     jobs.Z[i] = jobs.Upart[i] + size_t(jobs.n_slices[i]) * size_t(T) * size_t(N);
     ws += adapter_ws_bytes(c, p, T);
@@ -860,7 +868,6 @@ static lsw_status adapter_run(lsw_ctx* c, const int32_t* lin_idx, int n, const v
   Terms t;
   std::memset(&t, 0, sizeof(t));
   t.n = c->E;                                // sizes the launch: E * r / 8 groups of the fused rank
-  const int grid = std::max(8, (c->n_cu / 8) * 8);
   e = bigk ? launch_switch_mfma_bigk(lp, t, nullptr, c->r, c->qp, grid, s) : launch_switch_mfma(lp, t, nullptr, c->r, c->qp, grid, s);
   if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "up-projection launch failed: %s", hipGetErrorString(e));
   return LSW_OK;

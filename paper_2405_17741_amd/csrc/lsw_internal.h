@@ -175,7 +175,7 @@ hipError_t launch_pack_A(const void* A, uint16_t* Apk, int E, int r, int in, int
 constexpr size_t kStaticScratchBytes = size_t(32) << 20;          // workspace limit of lsw_adapter_forward_static (a device array of this size per GPU)
 hipError_t adapter_static_scratch(int device, void** ptr);        // its address on `device`, which must be the current device
 int64_t adapter_atk_elems(int E, int r, int in, int qp);          // bf16 elements of the down-projection layout of one linear
-int adapter_slices(int T, int in);                                // partial sums the down-projection is cut into
+int adapter_slices(int T, int in, int N);                         // partial sums the down-projection of N = E * r rows is cut into
 hipError_t launch_pack_Atk(const void* A, uint16_t* Atk, int E, int r, int in, int qp, hipStream_t s);
 // the linears one call of the adapter path covers (all with the same T tokens, the same per-token lists)
 struct AdJobs {
@@ -193,7 +193,7 @@ struct AdJobs {
 hipError_t launch_adapter_down(const AdJobs& jobs, int N, int qp, hipStream_t s);      // fills first[] itself
 hipError_t launch_adapter_gate(const AdJobs& jobs, const int32_t* ids, const float* gates, int k, int E, int r,
                                float scale, int z_stride, int32_t* err, hipStream_t s);
-int adapter_chunks_per_slice(int T, int in);
+int adapter_chunks_per_slice(int T, int in, int N);
 hipError_t launch_gemv(const uint16_t* W, const uint16_t* x, float* y, int out, int in, int ld, int grid_cap, hipStream_t s);
 hipError_t launch_gemv_all(const LaunchPlan& p, const uint16_t* x_all, float* y_all, int grid, hipStream_t s);
 

@@ -401,18 +401,26 @@ def main():
             gd = torch.zeros(T, wl.top_k, dtype=torch.float32, device="cuda")
             L.lsw_route_batch_dev(ctx, lg.data_ptr(), T, wl.top_k, idd.data_ptr(), gd.data_ptr(), stream)
             layer0 = [(p, o, n) for p, (layer, _, o, n) in enumerate(wl.linear_shapes()) if layer == 0]
-            xs = {n: torch.randn(T, n, device="cuda").to(torch.bfloat16) for _, _, n in layer0}
+            kinds0 = [kind for layer, kind, _, _ in wl.linear_shapes() if layer == 0]
+            # as in a decoder layer: q, k, v read one activation tensor, o another, gate and up a third, down a fourth
+            group_of = {0: "attn_in", 1: "attn_in", 2: "attn_in", 3: "o_in", 4: "ffn_in", 5: "ffn_in", 6: "down_in"}
+
+            def activations(tokens):
+                made = {}
+                return [made.setdefault((group_of[kind], n), torch.randn(tokens, n, device="cuda").to(torch.bfloat16))
+                        for kind, (_, _, n) in zip(kinds0, layer0)]
+            xs = activations(T)
             ys = [torch.randn(T, o, device="cuda").to(torch.bfloat16) for _, o, _ in layer0]      # one output per linear
             ws = torch.empty(L.lsw_adapter_layer_workspace_bytes(ctx, 0, T) // 4, dtype=torch.float32, device="cuda")
             fb = 2 if bf16_factors else 4
 
             def prefill_layer():          # all linears of the layer: three launches in all
-                L.lsw_adapter_forward_layer(ctx, 0, [xs[n].data_ptr() for _, _, n in layer0], T, idd.data_ptr(), gd.data_ptr(), wl.top_k,
+                L.lsw_adapter_forward_layer(ctx, 0, [x.data_ptr() for x in xs], T, idd.data_ptr(), gd.data_ptr(), wl.top_k,
                                             [y.data_ptr() for y in ys], ws.data_ptr(), stream)
 
             def prefill_per_linear():     # the same work as seven separate calls (three launches each)
                 for i, (p, o, n) in enumerate(layer0):
-                    L.lsw_adapter_forward(ctx, p, xs[n].data_ptr(), T, idd.data_ptr(), gd.data_ptr(), wl.top_k, ys[i].data_ptr(),
+                    L.lsw_adapter_forward(ctx, p, xs[i].data_ptr(), T, idd.data_ptr(), gd.data_ptr(), wl.top_k, ys[i].data_ptr(),
                                           ws.data_ptr(), stream)
 
             def timed(fn, reps=10):
@@ -439,10 +447,10 @@ def main():
                 id8 = torch.zeros(T8, wl.top_k, dtype=torch.int32, device="cuda")
                 g8 = torch.zeros(T8, wl.top_k, dtype=torch.float32, device="cuda")
                 L.lsw_route_batch_dev(ctx, lg8.data_ptr(), T8, wl.top_k, id8.data_ptr(), g8.data_ptr(), stream)
-                xs8 = {n: torch.randn(T8, n, device="cuda").to(torch.bfloat16) for _, _, n in layer0}
+                xs8 = activations(T8)
                 ys8 = [torch.randn(T8, o, device="cuda").to(torch.bfloat16) for _, o, _ in layer0]
                 ws8 = torch.empty(L.lsw_adapter_layer_workspace_bytes(ctx, 0, T8) // 4, dtype=torch.float32, device="cuda")
-                us8 = timed(lambda: L.lsw_adapter_forward_layer(ctx, 0, [xs8[n].data_ptr() for _, _, n in layer0], T8, id8.data_ptr(), g8.data_ptr(),
+                us8 = timed(lambda: L.lsw_adapter_forward_layer(ctx, 0, [x.data_ptr() for x in xs8], T8, id8.data_ptr(), g8.data_ptr(),
                                                                 wl.top_k, [y.data_ptr() for y in ys8], ws8.data_ptr(), stream), 5)
                 b8 = sum(T8 * n * 2 + 2 * T8 * o * 2 + fb * wl.experts * wl.rank * (n + o) for _, o, n in layer0)
                 adapter["tokens_8192"] = {"us_per_layer": round(us8, 1), "GBps": round(b8 / (us8 * 1e-6) / 1e9, 1),

@@ -200,7 +200,21 @@ def other_config(torch, L, I, name, factor_dtype, steps, warmup, traffic_table, 
     key = name + ("_bf16_factors" if bf16_factors else "") + ("_pitch_padded" if pad_pitch else "")
     roofline, achieved = switch_roofline(wl, stats["terms"], stats["kernels"], stats["launch_bytes"], stats["avg_ms"], bf16_factors,
                                          traffic_table.get(key))
+    extra = {}
+    if roofline["bound"] == "mfma":
+        # what the bare inner loop of this kernel sustains on this part (power-limited clock under matrix load):
+        # a wave's 32 x 256 tile needs K / 4 groups of six matrix instructions, the chip runs 1024 waves at once
+        ns = L.lsw_probe_matrix_loop(600, 4, 2, False)
+        ns0 = L.lsw_probe_matrix_loop(600, 4, 2, True)
+        k_max = max(stats["terms"]) * wl.rank
+        groups = wl.w_elements() / 8192.0 * (k_max / 4.0) / 1024.0
+        extra["matrix_loop"] = {"ns_per_group": round(ns, 1), "ns_per_group_zero_operands": round(ns0, 1),
+                                "cycles_per_group": 192, "loop_only_us_at_fused_rank": {str(k_max): round(groups * ns * 1e-3, 1)},
+                                "note": "lsw_probe_matrix_loop: the kernel's inner loop alone (4 LDS reads + 6 matrix instructions per group, "
+                                        "2 LDS-DMA copies riding along, no weight traffic, no barriers) on all CUs: the time it needs for "
+                                        "this launch's matrix work is the practical ceiling under the part's power limit"}
     return {
+        **extra,
         "workload": f"{wl.name}: {wl.layers} layers x 7 linears, hidden {wl.hidden}, ffn {wl.ffn}, E={wl.experts}, r={wl.rank}, "
                     f"top-{wl.top_k}, factors stored as {factor_dtype}"
                     + (", every weight stored at a row pitch of 4, 8, 16 or 32 KB (lsw_linear::ld; same algorithmic bytes, "

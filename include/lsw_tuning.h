@@ -55,6 +55,19 @@ enum {
 lsw_status lsw_probe_inplace(lsw_ctx* ctx, int32_t waves_per_cu, void* hip_stream);
 
 /*
+ * What the matrix cores sustain on the inner loop of the three-pass kernel for fused ranks above 64, with nothing around
+ * it: per group 4 LDS reads + 6 v_mfma_f32_32x32x16_bf16 (192 matrix-pipe cycles), 4 waves per workgroup, one workgroup
+ * per CU, no weight traffic, no barriers; `copies_per_group` (0..2) LDS-DMA copies of 1 KB ride along as in the kernel;
+ * zero_operands != 0 multiplies zeros (the chip then holds a higher clock).  Runs 2 + `launches` launches of `iters`
+ * chunk quadruples (64 groups each) on the current device, synchronously, and stores the mean nanoseconds per group of
+ * the timed ones in *ns_per_group.  A switch of fused rank K over n weights needs n / 8192 x K / 4 groups per CU-wave,
+ * i.e. at least n x K / (8192 x 4 x 1024 waves) x ns_per_group: the ceiling the power limit of the part sets for
+ * that kernel, below the datasheet rate.  Allocates about 5 MB of device memory for the duration of the call.
+ * Errors: LSW_ERR_ARG, LSW_ERR_NOMEM, LSW_ERR_DEVICE.
+ */
+lsw_status lsw_probe_matrix_loop(int32_t iters, int32_t launches, int32_t copies_per_group, int32_t zero_operands, double* ns_per_group);
+
+/*
  * The work decomposition of one launch, as a pure function of the shapes: linear p is cut into
  * ceil(out/tile_rows) x ceil(in/tile_cols) items, numbered linear by linear, rows outermost.  Host helpers, no
  * device.  The kernels decode an item number with the same routine.

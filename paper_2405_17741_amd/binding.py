@@ -26,7 +26,7 @@ EXPORTS = (
     "lsw_route_dev", "lsw_switch_dev", "lsw_dev_status", "lsw_gemv_bf16", "lsw_create_adapters_ex",
     "lsw_set_base", "lsw_rebase", "lsw_enable_adapter_path", "lsw_adapter_workspace_bytes", "lsw_route_batch_dev",
     "lsw_adapter_forward", "lsw_drop_subset_tables", "lsw_adapter_forward_static",
-    "lsw_adapter_layer_workspace_bytes", "lsw_adapter_forward_layer",
+    "lsw_adapter_layer_workspace_bytes", "lsw_adapter_forward_layer", "lsw_probe_matrix_loop",
 )
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblsw.so")
@@ -100,6 +100,7 @@ def lib() -> C.CDLL:
         L.lsw_walk_pool_item.restype = C.c_int32
         L.lsw_probe_inplace.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         L.lsw_drop_subset_tables.argtypes = [C.c_void_p]
+        L.lsw_probe_matrix_loop.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_double)]
         L.lsw_destroy.argtypes = [C.c_void_p]
         L.lsw_destroy.restype = None
         L.lsw_last_error.restype = C.c_char_p
@@ -325,6 +326,13 @@ def lsw_walk_pool_item(n_items: int, grid: int, pool_div: int, claim: int) -> in
 
 def lsw_probe_inplace(ctx: int, waves_per_cu: int, stream: int = 0) -> None:
     _check(lib().lsw_probe_inplace(ctx, waves_per_cu, C.c_void_p(stream)))
+
+
+def lsw_probe_matrix_loop(iters: int, launches: int, copies_per_group: int, zero_operands: bool) -> float:
+    """Nanoseconds per group of 6 matrix instructions (192 matrix-pipe cycles) in the bare three-pass loop."""
+    ns = C.c_double(0.0)
+    _check(lib().lsw_probe_matrix_loop(iters, launches, copies_per_group, 1 if zero_operands else 0, C.byref(ns)))
+    return ns.value
 
 
 def lsw_drop_subset_tables(ctx: int) -> None:

@@ -12,7 +12,7 @@ LIB = os.path.join(PKG, "liblsw.so")
 # host code of the C ABI + one translation unit per kernel family
 SOURCES = [os.path.join(PKG, "csrc", name) for name in (
     "lsw_api.cpp", "pack_a.hip", "switch_valu.hip", "switch_mfma.hip", "switch_mfma_res.hip", "switch_mfma_bigk.hip",
-    "route.hip", "adapter.hip", "probe_inplace.hip", "gemv.hip")]
+    "route.hip", "adapter.hip", "probe_inplace.hip", "probe_mfma.hip", "gemv.hip")]
 
 
 def _run(cmd, verbose):

@@ -946,6 +946,46 @@ extern "C" lsw_status lsw_probe_inplace(lsw_ctx* c, int32_t waves_per_cu, void* 
   return LSW_OK;
 }
 
+extern "C" lsw_status lsw_probe_matrix_loop(int32_t iters, int32_t launches, int32_t copies_per_group, int32_t zero_operands, double* ns_per_group) {
+  if (!ns_per_group || iters < 1 || iters > (1 << 20) || launches < 1 || launches > 1000 || copies_per_group < 0 || copies_per_group > 2)
+    return fail(LSW_ERR_ARG, "lsw_probe_matrix_loop: bad argument");
+  int dev = 0;
+  hipDeviceProp_t prop;
+  LSW_HIP(hipGetDevice(&dev));
+  LSW_HIP(hipGetDeviceProperties(&prop, dev));
+  const int grid = prop.multiProcessorCount;
+  void *out = nullptr, *pin = nullptr, *qsrc = nullptr;
+  hipEvent_t a = nullptr, b = nullptr;
+  auto release = [&]() {
+    if (out) (void)hipFree(out);
+    if (pin) (void)hipFree(pin);
+    if (qsrc) (void)hipFree(qsrc);
+    if (a) (void)hipEventDestroy(a);
+    if (b) (void)hipEventDestroy(b);
+  };
+  std::vector<uint32_t> hp(32 * 64 * 4);
+  for (size_t i = 0; i < hp.size(); ++i) hp[i] = ((uint32_t(i + 1) * 2246822519u) & 0x0fff0fffu) | 0x3c00bc00u;     // bf16 pairs near +-1
+  hipError_t e = hipMalloc(&out, size_t(grid) * 256 * 16);
+  if (e == hipSuccess) e = hipMalloc(&pin, hp.size() * 4);
+  if (e == hipSuccess) e = hipMalloc(&qsrc, size_t(4) << 20);
+  if (e != hipSuccess) { (void)hipGetLastError(); release(); return fail(LSW_ERR_NOMEM, "lsw_probe_matrix_loop: device allocation failed"); }
+  e = hipMemcpy(pin, hp.data(), hp.size() * 4, hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemset(qsrc, 0x3c, size_t(4) << 20);
+  if (e == hipSuccess) e = hipEventCreate(&a);
+  if (e == hipSuccess) e = hipEventCreate(&b);
+  for (int i = 0; i < 2 && e == hipSuccess; ++i) e = launch_probe_matrix_loop(out, pin, qsrc, grid, iters, copies_per_group, zero_operands, nullptr);
+  if (e == hipSuccess) e = hipEventRecord(a, nullptr);
+  for (int i = 0; i < launches && e == hipSuccess; ++i) e = launch_probe_matrix_loop(out, pin, qsrc, grid, iters, copies_per_group, zero_operands, nullptr);
+  if (e == hipSuccess) e = hipEventRecord(b, nullptr);
+  if (e == hipSuccess) e = hipEventSynchronize(b);
+  float ms = 0.0f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, a, b);
+  release();
+  if (e != hipSuccess) return fail(LSW_ERR_DEVICE, "lsw_probe_matrix_loop: %s", hipGetErrorString(e));
+  *ns_per_group = double(ms) * 1e6 / (double(launches) * iters * 64.0);
+  return LSW_OK;
+}
+
 // ---------------------------------------------------------------------------
 // merged decode, state, options
 // ---------------------------------------------------------------------------

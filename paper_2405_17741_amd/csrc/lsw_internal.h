@@ -169,6 +169,7 @@ hipError_t launch_route(const float* logits, int n_tokens, int E, int k, int32_t
 hipError_t launch_build_terms(const int32_t* old_ids, const float* old_gates, int k_old, const int32_t* new_ids,
                               const float* new_gates, int k_new, int E, float scale, Terms* out, int32_t* err, hipStream_t s);
 hipError_t launch_probe_inplace(const LaunchPlan& p, int grid, hipStream_t s);
+hipError_t launch_probe_matrix_loop(void* out, const void* pin, const void* qsrc, int grid, int iters, int copies, int zero_operands, hipStream_t s);
 // transposed = 0: source A [E][r][in] (columns = in);  1: source B [E][out][r] read as B^T [E][r][out] (columns = out)
 hipError_t launch_pack_A(const void* A, uint16_t* Apk, int E, int r, int in, int qp, int transposed, hipStream_t s);
 // adapter path (Eq. 2 for many tokens)

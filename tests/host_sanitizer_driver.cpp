@@ -110,6 +110,8 @@ int main() {
     EXPECT(lsw_rebase(nullptr, nullptr, 0, nullptr, nullptr, 0, nullptr) == LSW_ERR_ARG);
     EXPECT(lsw_set_base(nullptr, nullptr, 0) == LSW_ERR_ARG);
     EXPECT(lsw_drop_subset_tables(nullptr) == LSW_ERR_ARG);
+    { double ns = 0; EXPECT(lsw_probe_matrix_loop(0, 1, 0, 0, &ns) == LSW_ERR_ARG); EXPECT(lsw_probe_matrix_loop(1, 1, 3, 0, &ns) == LSW_ERR_ARG);
+      EXPECT(lsw_probe_matrix_loop(1, 1, 0, 0, nullptr) == LSW_ERR_ARG); }
     EXPECT(lsw_enable_adapter_path(nullptr) == LSW_ERR_ARG);
     EXPECT(lsw_adapter_forward(nullptr, 0, nullptr, 1, nullptr, nullptr, 0, nullptr, nullptr, nullptr) == LSW_ERR_ARG);
     EXPECT(lsw_adapter_workspace_bytes(nullptr, 0, 1) == -1);

@@ -456,6 +456,16 @@ def test_merged_gemv_all_linears_in_one_launch():
     ds.close()
 
 
+def test_matrix_loop_probe_reports_a_plausible_rate():
+    ns = L.lsw_probe_matrix_loop(50, 2, 2, False)
+    ns0 = L.lsw_probe_matrix_loop(50, 2, 0, True)
+    # 192 matrix-pipe cycles per group: 80 ns at the 2.4 GHz peak clock; anything far outside is a broken probe
+    assert 60.0 < ns0 < 400.0 and 60.0 < ns < 400.0 and ns0 <= ns * 1.1, (ns0, ns)
+    for bad in ((0, 1, 0), (10, 0, 0), (10, 1, 3)):
+        with pytest.raises(L.LswError):
+            L.lsw_probe_matrix_loop(bad[0], bad[1], bad[2], False)
+
+
 def test_probe_inplace_leaves_weights_unchanged():
     wl = I.Workload("mini", 2, 64, 136, 32, 4, 8, 2, 4, 0.02, 1 / 8, 0.01, 515)
     host = I.host_stack(wl)

@@ -2,6 +2,7 @@
 #include "lsw_device.h"
 #include "lsw_mfma.h"
 
+#include <algorithm>
 #include <mutex>
 
 namespace lsw {
@@ -46,8 +47,7 @@ hipError_t adapter_static_scratch(int device, void** ptr) {
 // kernels in adapter mode: Y[T,out] <- rne(Y + Z B_all^T), rows = tokens, the row operand read from Z, the shared
 // operand B^T packed like A (k_pack_A, transposed source).
 //
-// k_adapter_down.  A workgroup is 32 tokens x one slice of `in`, its four waves sharing the slice.  X is bf16 and needs no split; A is
-// split into bf16 high + low (two passes).  The contraction index inside a 64-column chunk u is laid out so that a
+// k_adapter_down.  X is bf16 and needs no split; A is split into bf16 high + low (two passes).  The contraction index inside a 64-column chunk u is laid out so that a
 // lane reads 64 contiguous bytes of its token's row: k-step s (0..3), lane half h, element i  <->  column
 // 64u + 32h + 8s + i.  The A operand comes from a re-laid-out copy built once (k_pack_Atk):
 //   Atk bf16 [N/32 blocks][in/64 chunks][4 k-steps][parts][64 lanes][8]
@@ -272,6 +272,21 @@ hipError_t launch_adapter_down(const AdJobs& jobs_in, int N, int qp, hipStream_t
   const int nb_read = nb <= 1 ? 1 : nb <= 2 ? 2 : 4 * zgroups;       // blocks of Atk a workgroup row reads
   if (jobs.n < 1 || jobs.n > kAdMaxLin || nb > 8 || nb_read != adapter_blocks(N)) return hipErrorInvalidValue;   // never beyond what k_pack_Atk laid out
   const int rb = adapter_token_blocks(jobs.T, N);
+  // Workgroups start in the order of their numbers and a linear's workgroups all take equally long (cps chunks): the
+  // linears with the longest slices go first, so that the launch does not end with a few long workgroups on a half-empty chip.
+  int order[kAdMaxLin];
+  for (int i = 0; i < jobs.n; ++i) order[i] = i;
+  std::stable_sort(order, order + jobs.n, [&](int a, int b) { return jobs_in.cps[a] > jobs_in.cps[b]; });
+  for (int i = 0; i < jobs.n; ++i) {
+    const int j = order[i];
+    jobs.X[i] = jobs_in.X[j];
+    jobs.Atk[i] = jobs_in.Atk[j];
+    jobs.Upart[i] = jobs_in.Upart[j];
+    jobs.Z[i] = jobs_in.Z[j];
+    jobs.in[i] = jobs_in.in[j];
+    jobs.cps[i] = jobs_in.cps[j];
+    jobs.n_slices[i] = jobs_in.n_slices[j];
+  }
   long long total = 0;
   for (int i = 0; i < jobs.n; ++i) {
     jobs.first[i] = int(total);

@@ -37,7 +37,7 @@ template <int NKS, int QP, bool PROBE = false>
 __device__ __forceinline__ void mfma_load_item(const LaunchPlan& p, int item, int n, int gpr, int r,
                                                const int (&term_e)[NKS], const int (&term_g)[NKS],
                                                const float (&term_c)[NKS], MfmaItem<NKS>& it,
-                                               int tile_rows, int row_shift) {
+                                               int tile_rows, int row_shift, int flat_end = 0) {
   const bool adapter = p.Z != nullptr;          // adapter-path mode: one matrix, rows = tokens, row operand = rows of Z
   LinDesc L;
   int local = item;
@@ -73,6 +73,9 @@ __device__ __forceinline__ void mfma_load_item(const LaunchPlan& p, int item, in
   it.ncb = ceil_div(L.in, MT_STEP);
   it.col0 = col0;
   it.col_end = min(L.in, col0 + p.tile_cols);
+  // flat numbering (flat_end = end of the workgroup's range): the item takes every unit up to the end of its row of units
+  // or of the range, whichever comes first
+  if (flat_end > 0) it.col_end = min(L.in, col0 + MT_STEP * min(ceil_div(L.in - col0, MT_STEP), flat_end - item));
   it.stride_byte = uint32_t(L.ld) * 2u;
   it.row0_byte = uint32_t(row0) * it.stride_byte;
   const int prow = min(row0 + n, L.out - 1);
@@ -287,6 +290,26 @@ __device__ __forceinline__ int walk_init(const LaunchPlan& p, bool per_xcd, Item
   w.static_end = sh.static_end;
   return sh.first;
 }
+
+// Flat numbering (LaunchPlan::flat): workgroup b takes the units [n * i / grid, n * (i + 1) / grid) where i is its place in the
+// XCD-contiguous order (XCD x = workgroups x, x + 8, ... works on one contiguous eighth of the numbering).  w.step is the
+// length of the item loaded last (mfma_item_units), set by the caller after every load.  Returns the first unit.
+__device__ __forceinline__ int walk_init_flat(const LaunchPlan& p, ItemWalk& w) {
+  w.n_items = p.n_items;
+  w.pool = nullptr;
+  w.pool_len = 0;
+  w.after = -1;
+  w.after_pool = false;
+  w.slot = 0;
+  w.per = p.n_items;
+  w.step = 1;
+  const long long g = gridDim.x, i = (long long)(blockIdx.x & 7) * (g >> 3) + (blockIdx.x >> 3);
+  w.static_end = int((long long)p.n_items * (i + 1) / g);
+  return int((long long)p.n_items * i / g);
+}
+
+template <int NKS>
+__device__ __forceinline__ int mfma_item_units(const MfmaItem<NKS>& it) { return ceil_div(it.col_end - it.col0, MT_STEP); }
 
 // after `item` has become the next one: where the item after it comes from (wave 0 claims it now if it is a pool item)
 __device__ __forceinline__ void walk_plan_after(ItemWalk& w, int item, bool item_from_pool, int wave, int lane, int& claim) {

@@ -98,7 +98,8 @@ __device__ __forceinline__ bool wg_step(const LaunchPlan& p, int n, int h, int l
     const int following = via_pool ? walk_take_claim(walk) : walk.after;
     have_nxt = following >= 0;
     if (have_nxt) {
-      mfma_load_item<NKS, QP, PROBE>(p, following, n, gpr, r, term_e, term_g, term_c, nxt, WG_ROWS, 32 * wave);
+      mfma_load_item<NKS, QP, PROBE>(p, following, n, gpr, r, term_e, term_g, term_c, nxt, WG_ROWS, 32 * wave, p.flat ? walk.static_end : 0);
+      if (p.flat) walk.step = mfma_item_units(nxt);
       walk_plan_after(walk, following, via_pool, wave, lane, claim);
     }
   }
@@ -133,15 +134,20 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma(LaunchPlan p, Ter
   }
 
   ItemWalk walk;
-  const int item0 = walk_init(p, p.xcd_remap == 2, walk);
+  const bool flat = p.flat != 0;
+  const int item0 = flat ? walk_init_flat(p, walk) : walk_init(p, p.xcd_remap == 2, walk);
   if (item0 >= walk.static_end) return; // uniform over the workgroup (never with a pool)
+  const int flat_end = flat ? walk.static_end : 0;
   MfmaItem<NKS> cur, nxt;
-  mfma_load_item<NKS, QP, PROBE>(p, item0, n, gpr, r, term_e, term_g, term_c, cur, WG_ROWS, 32 * wave);
-  bool have_nxt = item0 + walk.step < walk.static_end;
+  mfma_load_item<NKS, QP, PROBE>(p, item0, n, gpr, r, term_e, term_g, term_c, cur, WG_ROWS, 32 * wave, flat_end);
+  if (flat) walk.step = mfma_item_units(cur);
+  const int item1 = item0 + walk.step;
+  bool have_nxt = item1 < walk.static_end;
   int claim = 0;
   if (have_nxt) {
-    mfma_load_item<NKS, QP, PROBE>(p, item0 + walk.step, n, gpr, r, term_e, term_g, term_c, nxt, WG_ROWS, 32 * wave);
-    walk_plan_after(walk, item0 + walk.step, false, wave, lane, claim);
+    mfma_load_item<NKS, QP, PROBE>(p, item1, n, gpr, r, term_e, term_g, term_c, nxt, WG_ROWS, 32 * wave, flat_end);
+    if (flat) walk.step = mfma_item_units(nxt);
+    walk_plan_after(walk, item1, false, wave, lane, claim);
   } else {
     nxt = cur;
   }

@@ -192,8 +192,19 @@ def other_config(torch, L, I, name, factor_dtype, steps, warmup, traffic_table, 
     t0 = time.perf_counter()
     stack = I.device_stack(wl, factor_dtype=torch.bfloat16 if bf16_factors else torch.float32, ld_of=fast_pitch if pad_pitch else None)
     ctx = L.create_from_tensors(stack, wl.linear_shapes(), wl.experts, wl.rank)
-    stats, _, wall = time_switches(torch, L, I, wl, ctx, steps, warmup, bf16_factors, stream=torch.cuda.current_stream().cuda_stream)
+    stream = torch.cuda.current_stream().cuda_stream
+    stats, _, wall = time_switches(torch, L, I, wl, ctx, steps, warmup, bf16_factors, stream=stream)
     torch.cuda.synchronize()
+    # the ceiling of the access pattern on these tensors: the matrix-core switch launch with the work taken out
+    L.lsw_probe_inplace(ctx, 0, stream)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(3):
+        L.lsw_probe_inplace(ctx, 0, stream)
+    b.record()
+    b.synchronize()
+    probe_gbps = 4.0 * wl.w_elements() / (a.elapsed_time(b) / 3 * 1e-3) / 1e9
     L.lsw_destroy(ctx)
     del stack
     torch.cuda.empty_cache()
@@ -201,6 +212,10 @@ def other_config(torch, L, I, name, factor_dtype, steps, warmup, traffic_table, 
     roofline, achieved = switch_roofline(wl, stats["terms"], stats["kernels"], stats["launch_bytes"], stats["avg_ms"], bf16_factors,
                                          traffic_table.get(key))
     extra = {}
+    if roofline["bound"] == "hbm":
+        extra["inplace_probe"] = {"switch_pattern_GBps": round(probe_gbps, 1), "switch_over_probe": round(achieved / probe_gbps, 4),
+                                  "note": "lsw_probe_inplace(ctx, 0): the streaming matrix-core switch launch (4 terms) on the same weights with "
+                                          "operand loads and matrix instructions taken out: 4 bytes per weight, nothing else"}
     if roofline["bound"] == "mfma":
         # what the bare inner loop of this kernel sustains on this part (power-limited clock under matrix load):
         # a wave's 32 x 256 tile needs K / 4 groups of six matrix instructions, the chip runs 1024 waves at once

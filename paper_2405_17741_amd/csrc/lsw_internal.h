@@ -119,6 +119,7 @@ LSW_HD inline int32_t walk_pool_item(int32_t n_items, int32_t per, int32_t pool_
 }
 
 constexpr int kResidentLdsBytes = 128 * 1024;   // LDS the resident-Q matrix-core kernel may use for one item's Q
+constexpr int kProbeLdsBytes = 96 * 1024;       // LDS the switch-pattern probe reserves: more than half of a CU's 160 KB
 
 // Tile shapes of the two switch kernels (rows x columns of one work item).
 constexpr int kValuTileRows = 64,  kValuTileCols = 128;

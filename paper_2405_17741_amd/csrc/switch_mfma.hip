@@ -185,7 +185,9 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma(LaunchPlan p, Ter
 
 template <int NKS, int QP, bool PROBE = false>
 static hipError_t launch_wg(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int grid, hipStream_t s) {
-  const size_t lds = size_t(2) * NKS * 8 * QP * 64 * sizeof(u32x4);     // 16 KB per k-step and Q part, two buffers
+  // 16 KB per k-step and Q part, two buffers; the probe (few registers, no LDS use) asks for more than half a CU's LDS so
+  // that, like the kernels it stands in for, exactly one workgroup runs per CU
+  const size_t lds = PROBE ? size_t(kProbeLdsBytes) : size_t(2) * NKS * 8 * QP * 64 * sizeof(u32x4);
   // once per process (function-local statics are initialised exactly once, also under concurrent first calls)
   static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_switch_mfma<NKS, QP, PROBE>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));

@@ -255,8 +255,11 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_switch_mfma_res(LaunchPlan p,
 
 template <int NKS, int QP, bool PROBE = false>
 static hipError_t launch_res(const LaunchPlan& p, const Terms& t, const Terms* t_dev, int r, int grid, hipStream_t s) {
-  const size_t lds = size_t(p.tile_cols / MT_STEP) * NKS * 8 * QP * 64 * sizeof(u32x4);     // 8 KB per column step, k-step and Q part
+  size_t lds = size_t(p.tile_cols / MT_STEP) * NKS * 8 * QP * 64 * sizeof(u32x4);     // 8 KB per column step, k-step and Q part
   if (lds > size_t(kResidentLdsBytes) || p.Z != nullptr) return hipErrorInvalidValue;
+  // the probe uses few registers and no LDS: it asks for more than half a CU's LDS so that, like the kernels it stands in
+  // for, exactly one workgroup runs per CU (two on one CU would leave another CU idle)
+  if (PROBE) lds = std::max(lds, size_t(kProbeLdsBytes));
   // once per process (function-local statics are initialised exactly once, also under concurrent first calls)
   static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_switch_mfma_res<NKS, QP, PROBE>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, kResidentLdsBytes);

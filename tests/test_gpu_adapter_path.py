@@ -257,3 +257,58 @@ def test_whole_layer_in_three_launches_equals_the_per_linear_calls(E, r, T):
         L.lsw_adapter_forward_layer(ds.ctx, layer, [16] * 6 + [0], T, idd.data_ptr(), gd.data_ptr(), k, [16] * 7, ws.data_ptr(), stream)
     assert e.value.status == L.LSW_ERR_ARG
     ds.close()
+
+
+@pytest.mark.parametrize("T", [2048, 8200])
+def test_full_size_layer_prompt_on_sampled_tokens(T):
+    """The launch configuration bench.py times: one layer of the 7B-shaped stack (4096 / 11008, 8 experts of rank 8, top-2),
+    a prompt of 2048 tokens (and a longer, ragged one) through lsw_adapter_forward_layer with the activations grouped as a
+    decoder layer hands them out (q, k, v read one tensor, gate and up another).  Tokens are independent, so a sample of
+    them (the first and last ones, the edges of a 128-token tile, random ones) is compared over ALL output columns of all
+    seven linears with the oracle; every token NOT sampled is checked to have changed (no tile was skipped)."""
+    wl = I.scaled(I.WORKLOADS["7b"], 1)
+    shapes = wl.linear_shapes()
+    stack = I.device_stack(wl)
+    ds = DeviceStack(stack, shapes, wl.experts, wl.rank)
+    L.lsw_enable_adapter_path(ds.ctx)
+    stream = torch.cuda.current_stream().cuda_stream
+    gen = torch.Generator(device="cuda").manual_seed(4100 + T)
+    draw = lambda n, std: (torch.randn(T, n, device="cuda", generator=gen) * std).to(torch.bfloat16)
+    x_attn, x_o, x_mlp, x_down = draw(wl.hidden, 1.0), draw(wl.hidden, 1.0), draw(wl.hidden, 1.0), draw(wl.ffn, 1.0)
+    Xs = [x_attn, x_attn, x_attn, x_o, x_mlp, x_mlp, x_down]                  # q, k, v, o, gate, up, down
+    Y0 = [draw(o, 0.5) for _, _, o, _ in shapes]
+    Ys = [y.clone() for y in Y0]
+    k = wl.top_k
+    logits = torch.randn(T, wl.experts, device="cuda", generator=gen)
+    ids_d = torch.zeros(T, k, dtype=torch.int32, device="cuda")
+    gates_d = torch.zeros(T, k, dtype=torch.float32, device="cuda")
+    L.lsw_route_batch_dev(ds.ctx, logits.data_ptr(), T, k, ids_d.data_ptr(), gates_d.data_ptr(), stream)
+    ws = torch.full((L.lsw_adapter_layer_workspace_bytes(ds.ctx, 0, T) // 4 + 64,), float("nan"), dtype=torch.float32, device="cuda")
+    L.lsw_adapter_forward_layer(ds.ctx, 0, [x.data_ptr() for x in Xs], T, ids_d.data_ptr(), gates_d.data_ptr(), k,
+                                [y.data_ptr() for y in Ys], ws.data_ptr(), stream)
+    torch.cuda.synchronize()
+    assert torch.isnan(ws[-64:]).all() and L.lsw_dev_status(ds.ctx) == 0
+    rng = np.random.default_rng(T)
+    tok = np.unique(np.concatenate([[0, 1, 127, 128, 255, 256, T - 129, T - 2, T - 1], rng.choice(T, 23, replace=False)]))
+    sel = torch.as_tensor(tok, device="cuda")
+    ids, gates = ids_d[sel].cpu().numpy(), gates_d[sel].cpu().numpy()
+    host_logits = logits[sel].cpu().numpy()
+    for j in range(len(tok)):                        # the selection is the oracle's, bit for bit; the gates within 1 fp32 ulp
+        want_ids, want_g = O.route(host_logits[j], k)
+        assert ids[j].tolist() == want_ids.tolist()
+        assert np.all(np.abs(gates[j] - want_g) <= np.spacing(np.maximum(np.abs(want_g), np.float32(1e-30)).astype(np.float32)))
+    reports = []
+    for p, (_, A, B) in enumerate(stack):
+        got, y0, x = device_to_bits(Ys[p][sel]), device_to_bits(Y0[p][sel]), device_to_bits(Xs[p][sel])
+        Ah, Bh = A.float().cpu().numpy(), B.float().cpu().numpy()
+        rep = C.switch_parity(got, O.adapter_forward(y0, x, Ah, Bh, ids, gates, 1.0), y0, O.adapter_magnitude(x, Ah, Bh, ids, gates, 1.0))
+        assert rep["fail"] == 0, (p, {k_: v for k_, v in rep.items() if k_ != "fail_mask"})
+        reports.append(rep)
+        changed = (Ys[p] != Y0[p]).float().mean(dim=1)
+        assert float(changed.min()) > 0.2, (p, "a token's row was left (nearly) unchanged", int(changed.argmin()))
+    n = sum(r["n"] for r in reports)
+    exact, c2 = sum(r["exact"] for r in reports), sum(r["needed_clause2"] for r in reports)
+    print(f"[prompt layer T={T}] tokens={len(tok)} n={n} exact_frac={exact / n:.6f} clause2={c2} max_dist={max(r['max_dist'] for r in reports)}", flush=True)
+    assert exact >= 0.998 * n - 6 * (0.002 * n) ** 0.5 - 2
+    assert c2 <= 2e-4 * n + 6 * (2e-4 * n) ** 0.5 + 2
+    ds.close()

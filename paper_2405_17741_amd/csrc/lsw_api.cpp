@@ -812,17 +812,10 @@ static lsw_status adapter_run(lsw_ctx* c, const int32_t* lin_idx, int n, const v
   const int n_groups = c->E * (c->r / 8);
   const bool bigk = n_groups > 8;
   // Up-projection items: 128 tokens x some output columns.  The row operand (a token block's rows of Z, split) is set up
-  // once per item, so wide items are cheaper per byte.  Fused ranks up to 64: the work is numbered in single column steps
-  // and every workgroup takes one contiguous, equally long range of it (LaunchPlan::flat), cut into items only where a
-  // row of steps ends.  Above: items of a fixed width, the widest that still leaves every workgroup three items or more.
+  // once per item, so wide items are cheaper per byte: the work is numbered in single column steps and every workgroup
+  // takes one contiguous, equally long range of it (LaunchPlan::flat), cut into items only where a row of steps ends.
   const int grid = std::max(8, (c->n_cu / 8) * 8);
-  int tc = bigk ? 512 : kApkBlockCols;
-  if (bigk)
-    for (int cand : {2048, 1024}) {
-      int64_t items = 0;
-      for (int i = 0; i < n; ++i) items += int64_t(ceil_div(T, kMfmaTileRows)) * ceil_div(c->lin[size_t(lin_idx[i])].out, cand);
-      if (items >= 3 * int64_t(grid)) { tc = cand; break; }
-    }
+  const int tc = kApkBlockCols;
   AdJobs jobs{};
   jobs.n = n;
   jobs.T = T;
@@ -830,7 +823,7 @@ static lsw_status adapter_run(lsw_ctx* c, const int32_t* lin_idx, int n, const v
   lp.n_sel = n;
   lp.tile_cols = tc;
   lp.xcd_remap = c->opt_xcd ? 1 : 0;
-  lp.flat = bigk ? 0 : 1;
+  lp.flat = 1;
   lp.z_stride = zs;
   char* ws = static_cast<char*>(workspace);
   int64_t n_items = 0;

@@ -150,7 +150,7 @@ struct LaunchPlan {             // device pointers + counts for one launch
   int32_t z_stride;
   LinDesc ad[kAdMaxLin];
   int32_t ad_first[kAdMaxLin + 1];
-  int32_t flat;                 // 1 (adapter mode of k_switch_mfma): the items are numbered in units of one column step
+  int32_t flat;                 // 1 (adapter mode of k_switch_mfma and k_switch_mfma_bigk): the items are numbered in units of one column step
                                 // (tile_cols = kApkBlockCols) and every workgroup takes ONE contiguous range of the numbering,
                                 // all ranges equal to within a step; a range is worked off as items that each run to the end of
                                 // their row of units or of the range (walk_init_flat, mfma_load_item)

@@ -306,9 +306,18 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
   w.coeff_last = H ? __builtin_bit_cast(float, uniform(__builtin_bit_cast(int, s_tc[n_terms - 1]))) : 1.0f;
 
   const int grid = gridDim.x;
-  const int first_item = p.xcd_remap ? xcd_contiguous_block(blockIdx.x, grid) : int(blockIdx.x);
+  // Items of a fixed width, workgroup b taking b', b' + grid, ...; or (LaunchPlan::flat, adapter mode) the numbering is in single
+  // column steps and the workgroup works off ONE contiguous range of it, every item running to the end of its row of steps
+  // or of the range
+  int first_item = p.xcd_remap ? xcd_contiguous_block(blockIdx.x, grid) : int(blockIdx.x);
+  int item_end = p.n_items, advance = grid;
+  if (p.flat) {
+    const long long place = (long long)(blockIdx.x & 7) * (grid >> 3) + (blockIdx.x >> 3);
+    first_item = int((long long)p.n_items * place / grid);
+    item_end = int((long long)p.n_items * (place + 1) / grid);
+  }
   int buf = 0;
-  for (int item = first_item; item < p.n_items; item += grid) {       // uniform over the workgroup
+  for (int item = first_item; item < item_end; item += advance) {       // uniform over the workgroup
     const bool adapter = p.Z != nullptr;
     LinDesc L;
     int local = item;
@@ -339,7 +348,11 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
     int row0, col0;
     decode_item(local, out, in, kMfmaTileRows, p.tile_cols, 0, &row0, &col0);
     row0 += 32 * wave;
-    const int col_end = min(in, col0 + p.tile_cols);
+    int col_end = min(in, col0 + p.tile_cols);
+    if (p.flat) {
+      advance = min(ceil_div(in - col0, MT_STEP), item_end - item);
+      col_end = min(in, col0 + MT_STEP * advance);
+    }
     const int ncb = ceil_div(in, MT_STEP);
     w.W = L.W;
     w.Wsrc = p.from_base ? L.Wbase : w.W;

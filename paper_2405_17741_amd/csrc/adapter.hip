@@ -39,7 +39,7 @@ hipError_t adapter_static_scratch(int device, void** ptr) {
 // ---------------------------------------------------------------------------
 // Un-merged adapter path for many tokens (Eq. 2: y = f(x) + sum_i G(x1)_i E_i(x), E_i(x) = W_up (W_down x)).
 //
-// Three launches per linear.  (1) k_adapter_down: U = X A_all^T on the matrix cores, all E*r down-projection rows of
+// Three launches per call, whether the call covers one linear or all linears of a layer.  (1) k_adapter_down: U = X A_all^T on the matrix cores, all E*r down-projection rows of
 // all experts at once (N = E*r is at most 256, so computing the unselected experts too costs nothing next to the
 // traffic), the long contraction over `in` cut into slices whose partial sums go to Upart[slice][T][N].
 // (2) k_adapter_gate: Z[t][e*r+rho] = scale * g(t,e) * sum_slices Upart (zero for experts token t did not select):
@@ -47,9 +47,10 @@ hipError_t adapter_static_scratch(int device, void** ptr) {
 // kernels in adapter mode: Y[T,out] <- rne(Y + Z B_all^T), rows = tokens, the row operand read from Z, the shared
 // operand B^T packed like A (k_pack_A, transposed source).
 //
-// k_adapter_down.  X is bf16 and needs no split; A is split into bf16 high + low (two passes).  The contraction index inside a 64-column chunk u is laid out so that a
-// lane reads 64 contiguous bytes of its token's row: k-step s (0..3), lane half h, element i  <->  column
-// 64u + 32h + 8s + i.  The A operand comes from a re-laid-out copy built once (k_pack_Atk):
+// k_adapter_down.  X is bf16 and needs no split; A is split into bf16 high + low (two passes).  Inside a 64-column chunk u
+// the contraction index is ordered  k-step s (0..3), lane half h, element i  <->  column 64u + 32h + 8s + i  (a lane's four
+// k-steps are four consecutive 16-byte pieces of its token's row).  The A operand comes from a re-laid-out copy built once
+// (k_pack_Atk):
 //   Atk bf16 [N/32 blocks][in/64 chunks][4 k-steps][parts][64 lanes][8]
 // holding for lane (h, n) the 8 values A_all[32*block + n][64u + 32h + 8s + i]: one operand load of a wave is 1 KB
 // contiguous.  Rows of A_all past E*r and columns past `in` hold zeros.

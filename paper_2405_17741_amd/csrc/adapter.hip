@@ -66,8 +66,11 @@ int64_t adapter_atk_elems(int E, int r, int in, int qp) {
   return int64_t(adapter_blocks(E * r)) * ceil_div(in, AD_CHUNK) * 4 * qp * 64 * 8;
 }
 
-// Token blocks of 32 per wave (RB): 2 for a prompt, 1 for a handful of tokens (more workgroups).
-int adapter_token_blocks(int T, int N) { (void)N; return T < 256 ? 1 : 2; }
+// Token blocks of 32 per wave (RB).  1: a workgroup covers 128 tokens and keeps two LDS stages (64 KB at 64 down-projection
+// rows), so two workgroups share a CU; 2: 256 tokens and three stages, one workgroup per CU, half the L2 traffic for A.
+// Measured per 7B layer: 512 tokens equal, 1024: 76 against 82 us, 2048: 118 against 125, 4096: 200 against 221, 8192: 401
+// against 404, 16384: 810 against 822, and one call per linear at 16384 tokens 1,297 against 1,105 us: small tiles up to 8192.
+int adapter_token_blocks(int T, int N) { (void)N; return T <= 8192 ? 1 : 2; }
 
 // 64-column chunks one workgroup contracts: about 128 workgroups per linear (a call usually covers the linears of a
 // layer), at least 8 chunks each unless the matrix has fewer (every slice costs a set of partial sums)
@@ -117,7 +120,7 @@ hipError_t launch_pack_Atk(const void* A, uint16_t* Atk, int E, int r, int in, i
 // k_adapter_down.  A workgroup = 4 waves x RB blocks of 32 tokens x one slice of `in` (cps chunks of 64 columns).  Every
 // wave owns its tokens and accumulates over the slice's chunks, so there is nothing to reduce across waves.
 //
-// Both operands reach the matrix cores through LDS, copied there by LDS-DMA (no registers), kStages chunks deep:
+// Both operands reach the matrix cores through LDS, copied there by LDS-DMA (no registers), kAdStages chunks deep:
 //   A: the chunk's NB * 4 * QP pieces of 1 KB are the same for all tokens; the four waves copy a quarter each, all read
 //      them, so a chunk of A leaves L2 once per 128 * RB tokens.
 //   X: a wave's 32 * RB token rows of the chunk (128 bytes each).  The matrix-core operand wants a lane to hold 16 bytes
@@ -133,7 +136,7 @@ hipError_t launch_pack_Atk(const void* A, uint16_t* Atk, int E, int r, int in, i
 template <int NB, int QP, int RB>
 constexpr int kAdStageSlots = NB * 4 * QP * 64 + 4 * RB * 256;       // 16-byte slots of one stage: A pieces, then the waves' X tiles
 template <int NB, int QP, int RB>
-constexpr int kAdStages = (3 * kAdStageSlots<NB, QP, RB> * 16 <= 144 * 1024) ? 3 : 2;
+constexpr int kAdStages = (RB > 1 && 3 * kAdStageSlots<NB, QP, RB> * 16 <= 144 * 1024) ? 3 : 2;     // RB = 1: two, so that two workgroups fit a CU
 
 template <int NB, int QP, int RB>
 __global__ __launch_bounds__(256) void k_adapter_down(AdJobs jobs, int N) {

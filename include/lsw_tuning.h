@@ -96,6 +96,20 @@ lsw_status lsw_worklist_item_grouped(const int32_t* out, const int32_t* in, int3
 lsw_status lsw_walk_share(int32_t n_items, int32_t grid, int32_t block, int32_t pool_div, int32_t share[5]);
 int32_t    lsw_walk_pool_item(int32_t n_items, int32_t grid, int32_t pool_div, int32_t claim);
 
+/*
+ * The work decomposition of the up-projection of the prompt path (lsw_adapter_forward*), as a pure host function; the
+ * kernels use the same routines.  The matrices are the outputs Y of the call's linears, rows[i] = tokens, cols[i] = out
+ * features; the work is numbered in units of 128 rows x 256 columns, matrix by matrix, rows outermost.  Workgroup `block`
+ * of `grid` takes ONE contiguous range of the numbering (all ranges equal to within a unit; XCD x = workgroups x, x + 8,
+ * ... the x-th eighth) and works it off as items that each run to the end of their row of units or of the range.
+ * unit < 0 asks for the workgroup's first item, otherwise `unit` must be a next_unit this function returned for the
+ * same arguments.  Outputs: the item's matrix, first row, first column and width in columns, and the unit its successor
+ * starts at (-1 = the range ends here; an empty range answers mat = -1 at once).
+ * LSW_ERR_ARG: a bad shape, grid not a positive multiple of 8, block outside 0..grid-1, a null pointer.
+ */
+lsw_status lsw_flat_item(const int32_t* rows, const int32_t* cols, int32_t n_mat, int32_t grid, int32_t block,
+                         int64_t unit, int32_t* mat, int32_t* row0, int32_t* col0, int32_t* n_cols, int64_t* next_unit);
+
 #ifdef __cplusplus
 }
 #endif

@@ -26,7 +26,7 @@ EXPORTS = (
     "lsw_route_dev", "lsw_switch_dev", "lsw_dev_status", "lsw_gemv_bf16", "lsw_create_adapters_ex",
     "lsw_set_base", "lsw_rebase", "lsw_enable_adapter_path", "lsw_adapter_workspace_bytes", "lsw_route_batch_dev",
     "lsw_adapter_forward", "lsw_drop_subset_tables", "lsw_adapter_forward_static",
-    "lsw_adapter_layer_workspace_bytes", "lsw_adapter_forward_layer", "lsw_probe_matrix_loop",
+    "lsw_adapter_layer_workspace_bytes", "lsw_adapter_forward_layer", "lsw_probe_matrix_loop", "lsw_flat_item",
 )
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblsw.so")
@@ -322,6 +322,17 @@ def lsw_walk_share(n_items: int, grid: int, block: int, pool_div: int):
 
 def lsw_walk_pool_item(n_items: int, grid: int, pool_div: int, claim: int) -> int:
     return int(lib().lsw_walk_pool_item(n_items, grid, pool_div, claim))
+
+
+def lsw_flat_item(rows, cols, grid: int, block: int, unit: int = -1):
+    """One item of workgroup `block`'s range in the flat order of the prompt path's up-projection:
+    (matrix, row0, col0, n_cols, next_unit); matrix = -1 for an empty range, next_unit = -1 at the range's end."""
+    n = len(rows)
+    r, c = (C.c_int32 * n)(*rows), (C.c_int32 * n)(*cols)
+    mat, row0, col0, n_cols, nxt = C.c_int32(), C.c_int32(), C.c_int32(), C.c_int32(), C.c_int64()
+    _check(lib().lsw_flat_item(r, c, n, grid, block, C.c_int64(unit), C.byref(mat), C.byref(row0), C.byref(col0), C.byref(n_cols),
+                               C.byref(nxt)))
+    return mat.value, row0.value, col0.value, n_cols.value, nxt.value
 
 
 def lsw_probe_inplace(ctx: int, waves_per_cu: int, stream: int = 0) -> None:

@@ -257,6 +257,35 @@ extern "C" int32_t lsw_walk_pool_item(int32_t n_items, int32_t grid, int32_t poo
   return walk_pool_item(n_items, w.per, w.pool_len, claim);
 }
 
+extern "C" lsw_status lsw_flat_item(const int32_t* rows, const int32_t* cols, int32_t n_mat, int32_t grid, int32_t block,
+                                    int64_t unit, int32_t* mat, int32_t* row0, int32_t* col0, int32_t* n_cols, int64_t* next_unit) {
+  if (!shapes_ok(rows, cols, n_mat, kMfmaTileRows, kApkBlockCols) || grid <= 0 || grid % 8 != 0 || block < 0 || block >= grid ||
+      !mat || !row0 || !col0 || !n_cols || !next_unit)
+    return fail(LSW_ERR_ARG, "lsw_flat_item: bad argument");
+  std::vector<int32_t> first(size_t(n_mat) + 1, 0);
+  int64_t total = 0;
+  for (int32_t i = 0; i < n_mat; ++i) {
+    first[size_t(i)] = int32_t(total);
+    total += int64_t(ceil_div(rows[i], kMfmaTileRows)) * ceil_div(cols[i], kApkBlockCols);
+    if (total > INT32_MAX) return fail(LSW_ERR_SHAPE, "lsw_flat_item: more than 2^31 - 1 units");
+  }
+  first[size_t(n_mat)] = int32_t(total);
+  int32_t lo, hi;
+  flat_range(int32_t(total), grid, block, &lo, &hi);
+  if (unit < 0) unit = lo;                                 // the range's first item
+  if (unit < lo || unit >= hi) { *next_unit = -1; *mat = -1; *row0 = *col0 = *n_cols = 0; return LSW_OK; }   // empty range, or past its end
+  const int32_t seg = find_segment(first.data(), n_mat, int32_t(unit));
+  int32_t r0, c0;
+  decode_item(int32_t(unit) - first[size_t(seg)], rows[seg], cols[seg], kMfmaTileRows, kApkBlockCols, 0, &r0, &c0);
+  const int32_t len = flat_item_units(cols[seg], c0, int32_t(unit), hi);
+  *mat = seg;
+  *row0 = r0;
+  *col0 = c0;
+  *n_cols = std::min(cols[seg], c0 + kApkBlockCols * len) - c0;
+  *next_unit = unit + len < hi ? unit + len : -1;
+  return LSW_OK;
+}
+
 extern "C" lsw_status lsw_worklist_item(const int32_t* out, const int32_t* in, int32_t n_lin,
                                         int32_t tile_rows, int32_t tile_cols, int64_t item,
                                         int32_t* lin, int32_t* row0, int32_t* n_rows, int32_t* col0,

@@ -128,6 +128,21 @@ constexpr int kMfmaBigkTileCols = 4096;                     // default item widt
 constexpr int kGemvRows = 4;                                // rows of one wave's block in the merged-decode kernels
 constexpr int kApkBlockCols = 256;   // column block of the packed A layout = columns per matrix-core step
 
+// Flat order (LaunchPlan::flat): the work is numbered in units of one column step; the workgroup at place i of the
+// XCD-contiguous order (XCD x = workgroups x, x + 8, ...: place = (block % 8) * (grid / 8) + block / 8) takes the units
+// [n * i / grid, n * (i + 1) / grid): all ranges equal to within one unit, XCD x on the x-th eighth of the numbering.
+LSW_HD inline void flat_range(int32_t n_units, int32_t grid, int32_t block, int32_t* first, int32_t* end) {
+  const long long place = (long long)(block & 7) * (grid >> 3) + (block >> 3);
+  *first = int32_t((long long)n_units * place / grid);
+  *end = int32_t((long long)n_units * (place + 1) / grid);
+}
+// A range is worked off as items: the item that starts at unit `unit` (column col0 of a matrix with `in` columns) takes
+// every unit up to the end of its row of units or of the range, whichever comes first.  Returns its length in units.
+LSW_HD inline int32_t flat_item_units(int32_t in, int32_t col0, int32_t unit, int32_t range_end) {
+  const int32_t to_row_end = ceil_div(in - col0, kApkBlockCols), to_range_end = range_end - unit;
+  return to_row_end < to_range_end ? to_row_end : to_range_end;
+}
+
 constexpr int kAdMaxLin = 8;    // linears one launch of the adapter path (lsw_adapter_forward_layer) covers at most
 
 struct LaunchPlan {             // device pointers + counts for one launch

@@ -75,7 +75,7 @@ __device__ __forceinline__ void mfma_load_item(const LaunchPlan& p, int item, in
   it.col_end = min(L.in, col0 + p.tile_cols);
   // flat numbering (flat_end = end of the workgroup's range): the item takes every unit up to the end of its row of units
   // or of the range, whichever comes first
-  if (flat_end > 0) it.col_end = min(L.in, col0 + MT_STEP * min(ceil_div(L.in - col0, MT_STEP), flat_end - item));
+  if (flat_end > 0) it.col_end = min(L.in, col0 + MT_STEP * flat_item_units(L.in, col0, item, flat_end));
   it.stride_byte = uint32_t(L.ld) * 2u;
   it.row0_byte = uint32_t(row0) * it.stride_byte;
   const int prow = min(row0 + n, L.out - 1);
@@ -291,9 +291,8 @@ __device__ __forceinline__ int walk_init(const LaunchPlan& p, bool per_xcd, Item
   return sh.first;
 }
 
-// Flat numbering (LaunchPlan::flat): workgroup b takes the units [n * i / grid, n * (i + 1) / grid) where i is its place in the
-// XCD-contiguous order (XCD x = workgroups x, x + 8, ... works on one contiguous eighth of the numbering).  w.step is the
-// length of the item loaded last (mfma_item_units), set by the caller after every load.  Returns the first unit.
+// Flat numbering (LaunchPlan::flat): the workgroup takes the units of flat_range.  w.step is the length of the item loaded
+// last (mfma_item_units), set by the caller after every load.  Returns the first unit.
 __device__ __forceinline__ int walk_init_flat(const LaunchPlan& p, ItemWalk& w) {
   w.n_items = p.n_items;
   w.pool = nullptr;
@@ -303,9 +302,9 @@ __device__ __forceinline__ int walk_init_flat(const LaunchPlan& p, ItemWalk& w) 
   w.slot = 0;
   w.per = p.n_items;
   w.step = 1;
-  const long long g = gridDim.x, i = (long long)(blockIdx.x & 7) * (g >> 3) + (blockIdx.x >> 3);
-  w.static_end = int((long long)p.n_items * (i + 1) / g);
-  return int((long long)p.n_items * i / g);
+  int first;
+  flat_range(p.n_items, int(gridDim.x), int(blockIdx.x), &first, &w.static_end);
+  return first;
 }
 
 template <int NKS>

@@ -311,11 +311,7 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
   // or of the range
   int first_item = p.xcd_remap ? xcd_contiguous_block(blockIdx.x, grid) : int(blockIdx.x);
   int item_end = p.n_items, advance = grid;
-  if (p.flat) {
-    const long long place = (long long)(blockIdx.x & 7) * (grid >> 3) + (blockIdx.x >> 3);
-    first_item = int((long long)p.n_items * place / grid);
-    item_end = int((long long)p.n_items * (place + 1) / grid);
-  }
+  if (p.flat) flat_range(p.n_items, grid, int(blockIdx.x), &first_item, &item_end);
   int buf = 0;
   for (int item = first_item; item < item_end; item += advance) {       // uniform over the workgroup
     const bool adapter = p.Z != nullptr;
@@ -350,7 +346,7 @@ __global__ __launch_bounds__(256) void k_switch_mfma_bigk(LaunchPlan p, Terms t,
     row0 += 32 * wave;
     int col_end = min(in, col0 + p.tile_cols);
     if (p.flat) {
-      advance = min(ceil_div(in - col0, MT_STEP), item_end - item);
+      advance = flat_item_units(in, col0, item, item_end);
       col_end = min(in, col0 + MT_STEP * advance);
     }
     const int ncb = ceil_div(in, MT_STEP);

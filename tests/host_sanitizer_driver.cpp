@@ -110,6 +110,10 @@ int main() {
     EXPECT(lsw_rebase(nullptr, nullptr, 0, nullptr, nullptr, 0, nullptr) == LSW_ERR_ARG);
     EXPECT(lsw_set_base(nullptr, nullptr, 0) == LSW_ERR_ARG);
     EXPECT(lsw_drop_subset_tables(nullptr) == LSW_ERR_ARG);
+    { int32_t rr[2] = {300, 5}, cc[2] = {520, 264}, m, r0, c0, nc; int64_t nx;
+      EXPECT(lsw_flat_item(rr, cc, 2, 16, 3, -1, &m, &r0, &c0, &nc, &nx) == LSW_OK);
+      EXPECT(lsw_flat_item(rr, cc, 2, 12, 3, -1, &m, &r0, &c0, &nc, &nx) == LSW_ERR_ARG);
+      EXPECT(lsw_flat_item(rr, cc, 2, 16, 3, -1, nullptr, &r0, &c0, &nc, &nx) == LSW_ERR_ARG); }
     { double ns = 0; EXPECT(lsw_probe_matrix_loop(0, 1, 0, 0, &ns) == LSW_ERR_ARG); EXPECT(lsw_probe_matrix_loop(1, 1, 3, 0, &ns) == LSW_ERR_ARG);
       EXPECT(lsw_probe_matrix_loop(1, 1, 0, 0, nullptr) == LSW_ERR_ARG); }
     EXPECT(lsw_enable_adapter_path(nullptr) == LSW_ERR_ARG);

@@ -248,3 +248,46 @@ def test_null_context_calls_fail_cleanly():
     k = ctypes.c_int32(0)
     assert lib.lsw_get_state(None, 0, None, None, ctypes.byref(k)) == L.LSW_ERR_ARG
     lib.lsw_destroy(None)
+
+
+@pytest.mark.parametrize("rows,cols,grid", [
+    ((2048,) * 7, (4096, 4096, 4096, 4096, 11008, 11008, 4096), 256),       # the 7B layer at 2048 tokens
+    ((1,), (8,), 256),                                                       # one unit: 255 empty ranges
+    ((300, 300, 300), (264, 520, 136), 64), ((37,), (11000,), 8), ((129, 1), (256, 257), 16), ((130,) * 8, (72,) * 8, 256),
+])
+def test_flat_order_of_the_prompt_path_covers_every_cell_once_in_equal_ranges(rows, cols, grid):
+    """The up-projection of the prompt path: every workgroup's items together cover every cell of every output exactly
+    once, an item never leaves its row block or its matrix, its columns start and end on 256-column steps (or at the edge),
+    and no workgroup has more than one unit (128 rows x 256 columns) more than another."""
+    cover = [np.zeros(((r + 127) // 128, (c + 255) // 256), np.int32) for r, c in zip(rows, cols)]
+    per_block = []
+    for block in range(grid):
+        units, unit = 0, -1
+        while True:
+            mat, row0, col0, n_cols, nxt = L.lsw_flat_item(rows, cols, grid, block, unit)
+            if mat < 0:
+                assert unit == -1 and nxt == -1                # an empty range says so at once
+                break
+            assert 0 <= mat < len(rows) and row0 % 128 == 0 and row0 < rows[mat] and col0 % 256 == 0 and n_cols > 0
+            assert col0 + n_cols <= cols[mat] and ((col0 + n_cols) % 256 == 0 or col0 + n_cols == cols[mat])
+            n = (n_cols + 255) // 256
+            cover[mat][row0 // 128, col0 // 256: col0 // 256 + n] += 1
+            units += n
+            if nxt < 0:
+                break
+            unit = nxt
+        per_block.append(units)
+    assert all((c == 1).all() for c in cover)
+    assert max(per_block) - min(per_block) <= 1
+    # each XCD (blocks x, x + 8, ...) works on one contiguous eighth: its blocks' first units rise with the block number
+    firsts = {}
+    for block in range(grid):
+        mat, row0, col0, _, _ = L.lsw_flat_item(rows, cols, grid, block)
+        if mat >= 0:
+            firsts.setdefault(block % 8, []).append((mat, row0, col0))
+    assert all(v == sorted(v) for v in firsts.values())
+    with pytest.raises(L.LswError):
+        L.lsw_flat_item(rows, cols, grid + 1, 0)
+    with pytest.raises(L.LswError):
+        L.lsw_flat_item(rows, cols, grid, grid)
+

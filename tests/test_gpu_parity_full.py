@@ -21,13 +21,13 @@ NONE = (np.zeros(0, np.int32), np.zeros(0, np.float32))
 
 
 def _run_sampled(wl, check_steps, full_linears=(), n_random_rows=61, kernel=L.KERNEL_AUTO, factor_dtype=torch.float32,
-                 device_routed=False):
+                 device_routed=False, ld_of=None):
     """factor_dtype bf16: the factors are stored as bf16 (the oracle gets exactly those values).  device_routed: every
     token's (ids, gates) comes from lsw_route_dev and stays on the device, the switch is lsw_switch_dev (term list built
     on the device, launches sized for k_old + k_new terms); ids must equal the oracle router's, the gates it produced are
     what the oracle's switch is given."""
     shapes = wl.linear_shapes()
-    stack = I.device_stack(wl, factor_dtype=factor_dtype)
+    stack = I.device_stack(wl, factor_dtype=factor_dtype, ld_of=ld_of)      # ld_of: weights stored at a leading dimension > in
     ds = DeviceStack(stack, shapes, wl.experts, wl.rank, kernel=kernel)
     rng = np.random.default_rng(wl.seed + 1)
     rows = [I.sample_rows(rng, o, n_random_rows) for _, _, o, _ in shapes]
@@ -78,6 +78,10 @@ def _run_sampled(wl, check_steps, full_linears=(), n_random_rows=61, kernel=L.KE
         old = new
     if device_routed:
         assert L.lsw_dev_status(ds.ctx) == 0
+    torch.cuda.synchronize()
+    for (W, _, _), (_, _, _, n_cols) in zip(stack, shapes):          # padding columns (if any) still hold their guard value
+        if W._base is not None and W._base.shape[1] > n_cols:
+            assert bool((W._base[:, n_cols:] == I.PAD_GUARD).all()), "padding columns were written"
     ds.close()
     return reports, kernels
 
@@ -98,6 +102,17 @@ def test_7b_full_size_factors_stored_as_bf16():
     reports, kernels = _run_sampled(wl, {1, 2, 8}, n_random_rows=13, factor_dtype=torch.bfloat16)
     assert kernels == {L.KERNEL_MFMA}
     assert len(reports) == 3
+
+
+def test_7b_full_size_at_a_fast_row_pitch():
+    """The launch configuration of bench.py's 7b_pitch_padded entry: every weight whose rows are not 4, 8, 16 or 32 KB apart
+    (the 32 `down` matrices, 11008 columns) stored at the next such leading dimension; sampled rows of every linear against
+    the oracle, and every padding column untouched at the end."""
+    wl = I.Workload(**{**I.WORKLOADS["7b"].__dict__, "steps": 8})
+    pitch = lambda n: next(p for p in (2048, 4096, 8192, 16384) if p >= n) if n <= 16384 else n
+    reports, kernels = _run_sampled(wl, {1, 2, 3, 8}, n_random_rows=13, ld_of=pitch)
+    assert kernels == {L.KERNEL_MFMA}
+    assert len(reports) == 4
 
 
 def test_7b_full_size_device_routed_token_steps():

@@ -246,8 +246,8 @@ def other_config(torch, L, I, name, factor_dtype, steps, warmup, traffic_table, 
     }
 
 
-OTHER_CONFIGS = (("7b_r64", "fp32", 16, False), ("7b_r64", "bf16", 16, False), ("13b", "fp32", 16, False), ("70b", "fp32", 8, False),
-                 ("7b", "fp32", 16, True), ("13b", "fp32", 16, True))
+OTHER_CONFIGS = (("7b_r64", "fp32", 32, False), ("7b_r64", "bf16", 32, False), ("13b", "fp32", 32, False), ("70b", "fp32", 16, False),
+                 ("7b", "fp32", 32, True), ("13b", "fp32", 32, True))
 
 
 def main():

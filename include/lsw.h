@@ -256,7 +256,10 @@ lsw_status lsw_gemv_bf16(const void* W_bf16, const void* x_bf16, float* y_fp32, 
  * lsw_enable_adapter_path  builds, once, the two re-laid-out operand copies the path needs for every linear (A for
  *                          the down-projection, B^T for the up-projection, E*r*(in+out)*4 bytes per linear for fp32
  *                          factors, half for bf16).  Needs r % 8 == 0, E*r <= 256 and every out % 8 == 0
- *                          (LSW_ERR_SHAPE otherwise); synchronises the device.
+ *                          (LSW_ERR_SHAPE otherwise); synchronises the device.  The path computes the down-projection
+ *                          of ALL E*r rows for every token and selects with a gate table, so its matrix work grows with
+ *                          E*r, not k*r: it moves a prompt at about half of the HBM rate for E*r = 64 and becomes bound by
+ *                          the matrix cores beyond (measured: a quarter of the HBM rate at E*r = 256).
  * lsw_route_batch_dev      G = Softmax(TopK(.)) for n_tokens rows of logits at once (the router of Eq. 2 over a prompt):
  *                          logits_dev DEVICE fp32 [n_tokens, E]; ids_dev DEVICE int32 [n_tokens, k]; gates_dev DEVICE
  *                          fp32 [n_tokens, k]; per row exactly what lsw_route_dev computes.

@@ -540,7 +540,7 @@ static lsw_status launch_switch(lsw_ctx* c, const std::vector<int32_t>& sel_laye
   c->last_grid = 0;
   if (t.n > 0) {
     DevicePlan* dp = nullptr;
-    const int tc = kernel >= 2 ? (bigk ? c->opt_tile_cols_bigk : c->opt_tile_cols) : kValuTileCols;
+    int tc = kernel >= 2 ? (bigk ? c->opt_tile_cols_bigk : c->opt_tile_cols) : kValuTileCols;
     int grid = c->opt_grid;
     if (grid <= 0) grid = (kernel == 2) ? c->n_cu : c->n_cu * 2;   // matrix-core: one workgroup per CU
     grid = std::max(8, (grid / 8) * 8);     // a multiple of the 8 XCDs (the kernels' block remap assumes it)
@@ -558,24 +558,37 @@ static lsw_status launch_switch(lsw_ctx* c, const std::vector<int32_t>& sel_laye
     // 0.8 % slower) and not in the round-wise order (13B: 2-4 % slower).
     bool per_xcd = false;
     int panel_group = 0;
-    if (kernel == 2 && !bigk) {
-      int64_t reuse = 0, total = 0, widest_q = 0;
+    int64_t widest_q = 0;
+    auto per_xcd_at = [&](int cols) {
+      int64_t reuse = 0, total = 0;
+      widest_q = 0;
       for (const lsw_linear& L : c->lin) {
         if (!sel_layers.empty() && !std::binary_search(sel_layers.begin(), sel_layers.end(), L.layer)) continue;
         const int64_t w = int64_t(L.out) * L.in;
         total += w;
-        if ((grid / 8) % ceil_div(L.in, tc) == 0) reuse += w;
+        if ((grid / 8) % ceil_div(L.in, cols) == 0) reuse += w;
         widest_q = std::max(widest_q, int64_t(n_groups) * 8 * L.in * 2 * c->qp);
       }
-      per_xcd = 2 * reuse >= total;
-      panel_group = c->opt_panel_group >= 0 ? c->opt_panel_group : (per_xcd && widest_q > (3 << 19)) ? 4 : 0;
-    }
+      return 2 * reuse >= total;
+    };
+    auto q_fits = [&](int cols) { return (cols / kApkBlockCols) * ((n_groups + 1) / 2) * 8 * c->qp * 1024 <= kResidentLdsBytes; };
+    if (kernel == 2 && !bigk) per_xcd = per_xcd_at(tc);
     // The resident-Q kernel on top of that where the Q of one item (8 KB per 256 columns, k-step and Q part) fits LDS.
-    // fp32-stored factors only: with bf16-stored ones (half the Q bytes) the streaming kernel is as fast or faster; and
-    // not at half the item width to make K = 48-64 fit: on the 70B shape that gained 1.4 % on 3-term launches and lost
-    // 11 % on 4-term ones (the kernel spills registers at 4 k-steps).
-    const bool resident = per_xcd && c->opt_resident && c->qp == 2 &&
-                          (tc / kApkBlockCols) * ((n_groups + 1) / 2) * 8 * c->qp * 1024 <= kResidentLdsBytes;
+    // fp32-stored factors only: with bf16-stored ones (half the Q bytes) the streaming kernel is as fast or faster.
+    // At 3 k-steps (fused ranks 40-48) the Q of a full-width item does not fit but that of a half-width one does:
+    // measured on the 70B shape 44.5 against 45.5 ms for the streaming kernel, so those launches run at half width.  Not
+    // at 4 k-steps: there the resident kernel spills registers (52.9, or 50.5 with the B rows of the next item loaded
+    // after the tile update, against 48.5 ms).
+    bool resident = per_xcd && c->opt_resident && c->qp == 2 && q_fits(tc);
+    if (kernel == 2 && !bigk && !resident && c->opt_resident && c->qp == 2 && (n_groups + 1) / 2 == 3 && tc % (2 * kApkBlockCols) == 0 &&
+        q_fits(tc / 2) && per_xcd_at(tc / 2)) {
+      tc /= 2;
+      per_xcd = resident = true;
+    } else if (kernel == 2 && !bigk) {
+      per_xcd = per_xcd_at(tc);       // (widest_q of the width in use)
+    }
+    if (kernel == 2 && !bigk)
+      panel_group = c->opt_panel_group >= 0 ? c->opt_panel_group : (per_xcd && widest_q > (3 << 19)) ? 4 : 0;
     // LSW_OPT_XCD_REMAP: 3 = automatic
     const int xcd_mode = c->opt_xcd == 3 ? (bigk || kernel != 2 ? 1 : per_xcd ? 2 : 1) : c->opt_xcd;
     lsw_status st = get_plan(c, kernel, tc, sel_layers, &dp);

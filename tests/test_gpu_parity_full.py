@@ -199,6 +199,16 @@ def test_13b_full_size_sampled_rows_every_linear():
     assert len(reports) == 3
 
 
+def test_13b_full_size_at_a_fast_row_pitch():
+    """bench.py's 13b_pitch_padded entry: all 40 layers with every weight at a leading dimension of 8192 or 16384 elements (38 GB
+    allocated for 25 GB of weights); sampled rows against the oracle, every padding column untouched."""
+    wl = I.Workload(**{**I.WORKLOADS["13b"].__dict__, "steps": 3})
+    pitch = lambda n: next(p for p in (2048, 4096, 8192, 16384) if p >= n) if n <= 16384 else n
+    reports, kernels = _run_sampled(wl, {1, 2, 3}, n_random_rows=13, ld_of=pitch)
+    assert kernels == {L.KERNEL_MFMA}
+    assert len(reports) == 3
+
+
 def test_7b_rank64_full_size_sampled_rows_every_linear():
     """All 32 layers with rank-64 experts: the chunked matrix-core kernel over the whole stack."""
     wl = I.Workload(**{**I.WORKLOADS["7b_r64"].__dict__, "steps": 3})

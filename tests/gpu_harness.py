@@ -93,7 +93,7 @@ def gate_quality(tot, label, rank=8, exact_min=None, clause2_max=None):
     its accumulation error of a rounding boundary, and needs the second clause only where the result cancels to within
     2^8 times that error of zero; both rates follow from the arithmetic (three-pass split-bf16 products: about 2^-18
     relative per product, so the error of the sum grows like sqrt(K) with the fused rank K).  Measured on the full-size
-    stacks: 0.99983-0.99994 bit-equal and 5e-6 - 1.2e-5 on the second clause at ranks 8 and 16 (K = 24-64), 0.99963-0.99974
+    stacks: 0.99982-0.99994 bit-equal and 5e-6 - 1.2e-5 on the second clause at ranks 8 and 16 (K = 24-64), 0.99963-0.99974
     and 1.6e-5 - 2.1e-5 at rank 64 (K = 192-256).  The gates sit a factor of about two beyond those; a kernel with
     bf16-rounded factors in a single pass (97 % bit-equal) or a systematic error near zero fails them.
     Small samples get an absolute allowance of a few elements on top (Poisson noise)."""
